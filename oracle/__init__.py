@@ -1,0 +1,121 @@
+"""CPU oracle for CommVQ decode attention -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes binding over ``commvq_oracle.c`` (plain C, fp64), which writes out
+the paper's naive decode-then-attend definition (Sec. 3.1, Eq. v1_formula).
+Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this package; the product path (``paper_2506_18879_amd``) never does and
+shares no code with it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "commvq_oracle.c")
+_LIB = os.path.join(_HERE, "libcommvq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math) into this directory."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-pthread", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.commvq_oracle_rope.argtypes = [dp, ctypes.c_int, ctypes.c_double, ctypes.c_double]
+        lib.commvq_oracle_rope.restype = None
+        lib.commvq_oracle_decode.argtypes = [ctypes.c_void_p, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
+        lib.commvq_oracle_decode.restype = None
+        lib.commvq_oracle_decode_attn.argtypes = (
+            [ctypes.c_int] * 7 + [ctypes.c_void_p] * 8 + [ctypes.c_double] * 2 + [ctypes.c_void_p] * 4 + [ctypes.c_int]
+        )
+        lib.commvq_oracle_decode_attn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def rope(u, pos, rope_base):
+    """Return u R_pos (Sec. 3.2, Eq. rope_ri) for a 1-D vector of even length."""
+    u = _f64(u).copy()
+    _load().commvq_oracle_rope(u.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), u.size, float(pos), float(rope_base))
+    return u
+
+
+def decode(codes, codebooks):
+    """Return s C: the sum of the selected codeword rows (Eq. vanilla_decode).
+
+    codes: uint8[M]; codebooks: [M][K][d].
+    """
+    cb = _f64(codebooks)
+    M, K, d = cb.shape
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    assert codes.shape == (M,)
+    out = np.empty(d, dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    _load().commvq_oracle_decode(_ptr(codes), cb.ctypes.data_as(dp), M, K, d, out.ctypes.data_as(dp))
+    return out
+
+
+def decode_attn(q, key_codes, val_codes, key_codebooks, val_codebooks, cu_seqlens, q_pos,
+                key_pos=None, rope_base=500000.0, scale=None, unit_mask=None, n_threads=1,
+                return_intermediates=False):
+    """Naive decode-then-attend attention in fp64 (Sec. 3.1, Eq. v1_formula).
+
+    q [B][Hq][d]; key_codes/val_codes flat uint8, per sequence [Hkv][L_b][M];
+    codebooks [Hkv][M][K][d]; cu_seqlens int32[B+1]; q_pos int32[B];
+    key_pos int32[T] or None (token i at position i).  Float inputs of any
+    width are widened exactly to fp64.  unit_mask (bool [B][Hkv]) restricts the
+    work to some (sequence, KV head) units; other output rows are NaN.
+    Returns out [B][Hq][d], or (out, scores, weights) with the ragged
+    [T*Hq] intermediates (sequence b, head h, token i at cu[b]*Hq + h*L_b + i).
+    """
+    q = _f64(q)
+    kcb, vcb = _f64(key_codebooks), _f64(val_codebooks)
+    B, Hq, d = q.shape
+    Hkv, Mk, K, d2 = kcb.shape
+    Mv = vcb.shape[1]
+    assert d2 == d and vcb.shape == (Hkv, Mv, K, d)
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    qp = np.ascontiguousarray(q_pos, dtype=np.int32)
+    assert cu.shape == (B + 1,) and qp.shape == (B,) and cu[0] == 0
+    T = int(cu[-1])
+    kc = np.ascontiguousarray(key_codes, dtype=np.uint8).reshape(-1)
+    vc = np.ascontiguousarray(val_codes, dtype=np.uint8).reshape(-1)
+    assert kc.size == T * Hkv * Mk and vc.size == T * Hkv * Mv
+    kp = None if key_pos is None else np.ascontiguousarray(key_pos, dtype=np.int32)
+    assert kp is None or kp.shape == (T,)
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.full((B, Hq, d), np.nan, dtype=np.float64)
+    scores = np.full(T * Hq, np.nan, dtype=np.float64) if return_intermediates else None
+    weights = np.full(T * Hq, np.nan, dtype=np.float64) if return_intermediates else None
+    um = None if unit_mask is None else np.ascontiguousarray(unit_mask, dtype=np.uint8).reshape(B * Hkv)
+    rc = _load().commvq_oracle_decode_attn(
+        B, Hq, Hkv, d, Mk, Mv, K, _ptr(q), _ptr(kc), _ptr(vc), _ptr(kcb), _ptr(vcb), _ptr(cu), _ptr(qp), _ptr(kp),
+        float(rope_base), float(scale), _ptr(out), _ptr(scores), _ptr(weights), _ptr(um), int(n_threads))
+    if rc != 0:
+        raise ValueError(f"commvq_oracle_decode_attn failed with code {rc}")
+    if return_intermediates:
+        return out, scores, weights
+    return out

@@ -1,0 +1,176 @@
+"""Seeded synthetic workloads shaped like the paper's LLaMA-3.1-8B long-context runs.
+
+This module only *generates inputs* (codes, codebooks, queries, positions) and
+converts storage formats; it holds none of the method's arithmetic, so both the
+HIP path and the CPU oracle may be fed from it.  The paper evaluates on
+LLaMA-3.1-8B-Instruct (Sec. 5.1) at 8K-128K context (Table "speedup"); those
+weights, caches and trained codebooks are not available, so these stand in for
+them with the same layer shapes.
+
+Storage conventions
+  * bf16 tensors are carried as ``uint16`` bit patterns (numpy has no bf16).
+  * key/value codes: flat ``uint8``; sequence ``b`` holds ``[Hkv][L_b][M]``,
+    sequences concatenated in batch order.
+  * codebooks: ``[Hkv][M][K][d]``; a key codeword row is the sequence of first
+    rows ``(x, y)`` of its d/2 RoPE-commuting blocks ``[[x, y], [-y, x]]``
+    (Property 1, Eq. C_struct), so the free parameters are exactly the row.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+BASE_SEED = 250618879
+ROPE_BASE = 500000.0
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (round-to-nearest-even) and return the uint16 bit patterns."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns exactly to fp32."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+@dataclass
+class Workload:
+    name: str
+    B: int
+    Hq: int
+    Hkv: int
+    d: int
+    Mk: int
+    Mv: int
+    K: int
+    dtype: str  # "f32" or "bf16": storage type of q and of both codebooks
+    rope_base: float
+    q: np.ndarray  # [B][Hq][d] float32, or uint16 bf16 bits
+    key_codes: np.ndarray  # uint8 flat
+    val_codes: np.ndarray  # uint8 flat
+    key_codebooks: np.ndarray  # [Hkv][Mk][K][d]
+    val_codebooks: np.ndarray  # [Hkv][Mv][K][d]
+    cu_seqlens: np.ndarray  # int32 [B+1]
+    q_pos: np.ndarray  # int32 [B]
+    key_pos: Optional[np.ndarray] = None  # int32 [T] or None (token i at position i)
+    seed: int = 0
+    code_dist: str = "uniform"
+    extras: dict = field(default_factory=dict)
+
+    @property
+    def total_tokens(self) -> int:
+        return int(self.cu_seqlens[-1])
+
+    @property
+    def max_seqlen(self) -> int:
+        return int(np.max(np.diff(self.cu_seqlens)))
+
+    def as_f64(self, name: str) -> np.ndarray:
+        """Exact fp64 widening of q / key_codebooks / val_codebooks (for the oracle)."""
+        a = getattr(self, name)
+        if a.dtype == np.uint16:
+            a = bf16_bits_to_f32(a)
+        return a.astype(np.float64)
+
+    def seq_codes(self, which: str, b: int) -> np.ndarray:
+        """View of one sequence's codes as [Hkv][L_b][M]."""
+        M = self.Mk if which == "key" else self.Mv
+        flat = self.key_codes if which == "key" else self.val_codes
+        o, e = int(self.cu_seqlens[b]), int(self.cu_seqlens[b + 1])
+        return flat[o * self.Hkv * M:e * self.Hkv * M].reshape(self.Hkv, e - o, M)
+
+
+def _zipf_codes(rng: np.random.Generator, Hkv: int, L: int, M: int, K: int, s: float) -> np.ndarray:
+    """Codes with P(rank r) proportional to (r+1)^-s, r < K; rank -> codeword id by an
+    independent random permutation per (KV head, codebook) so hot codewords differ."""
+    p = (np.arange(1, K + 1, dtype=np.float64)) ** (-s)
+    cdf = np.cumsum(p / p.sum())
+    cdf[-1] = 1.0
+    out = np.empty((Hkv, L, M), dtype=np.uint8)
+    for g in range(Hkv):
+        ranks = np.searchsorted(cdf, rng.random((L, M)), side="right").astype(np.int64)
+        np.clip(ranks, 0, K - 1, out=ranks)
+        perms = np.stack([rng.permutation(K) for _ in range(M)], axis=0)  # [M][K]
+        out[g] = perms[np.arange(M)[None, :], ranks].astype(np.uint8)
+    return out
+
+
+def make_workload(name: str, *, B: int, Hq: int, Hkv: int, seqlens, Mk: int, Mv: int, dtype: str,
+                  seed: int, d: int = 128, K: int = 256, code_dist: str = "uniform",
+                  zipf_s: float = 1.1, rope_base: float = ROPE_BASE) -> Workload:
+    """Generate every tensor of one workload from a single seed."""
+    assert dtype in ("f32", "bf16") and Hq % Hkv == 0 and d % 2 == 0
+    rng = np.random.Generator(np.random.PCG64(seed))
+    seqlens = np.asarray(seqlens, dtype=np.int64)
+    assert seqlens.shape == (B,) and np.all(seqlens >= 1)
+    cu = np.zeros(B + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(seqlens)
+
+    def codebook(M):
+        # block parameters (x, y) ~ N(0, M^-1/2): decoded coordinates have unit variance
+        params = rng.standard_normal((Hkv, M, K, d // 2, 2), dtype=np.float32) * np.float32(M ** -0.5)
+        cb = params.reshape(Hkv, M, K, d)
+        return f32_to_bf16_bits(cb) if dtype == "bf16" else cb
+
+    key_cb = codebook(Mk)
+    val_cb = codebook(Mv)
+    q = rng.standard_normal((B, Hq, d), dtype=np.float32)
+    if dtype == "bf16":
+        q = f32_to_bf16_bits(q)
+
+    def codes(M):
+        parts = []
+        for L in seqlens:
+            if code_dist == "uniform":
+                parts.append(rng.integers(0, K, size=(Hkv, int(L), M), dtype=np.uint8 if K == 256 else np.int64)
+                             .astype(np.uint8).reshape(-1))
+            elif code_dist == "zipf":
+                parts.append(_zipf_codes(rng, Hkv, int(L), M, K, zipf_s).reshape(-1))
+            else:
+                raise ValueError(code_dist)
+        return np.concatenate(parts)
+
+    key_codes = codes(Mk)
+    val_codes = codes(Mv)
+    q_pos = (seqlens - 1).astype(np.int32)  # the query's own key is the last cached row
+    return Workload(name=name, B=B, Hq=Hq, Hkv=Hkv, d=d, Mk=Mk, Mv=Mv, K=K, dtype=dtype, rope_base=rope_base,
+                    q=q, key_codes=key_codes, val_codes=val_codes, key_codebooks=key_cb, val_codebooks=val_cb,
+                    cu_seqlens=cu, q_pos=q_pos, key_pos=None, seed=seed, code_dist=code_dist)
+
+
+def config(idx: int, *, seed: Optional[int] = None, max_len: Optional[int] = None) -> Workload:
+    """The five benchmark configurations (1-based ``idx``).
+
+    ``max_len`` shrinks every context length to at most that many tokens (ragged
+    lengths are scaled down proportionally) so parity tests can run the same
+    shapes at sizes the oracle finishes quickly; the full sizes are the default.
+    """
+    s = BASE_SEED + (idx - 1) if seed is None else seed
+
+    def cap(L):
+        return int(L) if max_len is None else int(min(L, max_len))
+
+    if idx == 1:  # single head, fp32, 2-bit
+        return make_workload("c1_1head_f32_L4096_2bit", B=1, Hq=1, Hkv=1, seqlens=[cap(4096)], Mk=32, Mv=32,
+                             dtype="f32", seed=s)
+    if idx == 2:  # 8B-shaped layer, 32K, 2-bit
+        return make_workload("c2_8b_L32768_2bit", B=1, Hq=32, Hkv=8, seqlens=[cap(32768)], Mk=32, Mv=32,
+                             dtype="bf16", seed=s)
+    if idx == 3:  # 8B-shaped layer, 128K, 1-bit, skewed code usage
+        return make_workload("c3_8b_L131072_1bit_zipf", B=1, Hq=32, Hkv=8, seqlens=[cap(131072)], Mk=16, Mv=16,
+                             dtype="bf16", seed=s, code_dist="zipf")
+    if idx == 4:  # batch of 8 ragged sequences, 2-bit
+        lens = np.random.Generator(np.random.PCG64(s ^ 0x5EED)).integers(8192, 65536, size=8, endpoint=True)
+        if max_len is not None:
+            lens = np.maximum(1, (lens.astype(np.float64) * (max_len / 65536.0)).astype(np.int64))
+        return make_workload("c4_8b_B8_ragged_2bit", B=8, Hq=32, Hkv=8, seqlens=lens, Mk=32, Mv=32,
+                             dtype="bf16", seed=s)
+    if idx == 5:  # 70B-shaped layer, batch 4, 128K, 2-bit keys / 1-bit values
+        return make_workload("c5_70b_B4_L131072_k2v1", B=4, Hq=64, Hkv=8, seqlens=[cap(131072)] * 4, Mk=32, Mv=16,
+                             dtype="bf16", seed=s)
+    raise ValueError(f"config index {idx} not in 1..5")
