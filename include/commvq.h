@@ -1,0 +1,160 @@
+/*
+ * libcommvq -- single-token decode attention computed directly on a
+ * CommVQ-compressed KV cache, for AMD MI355X (gfx950).
+ *
+ * Every cached key and value is stored as M uint8 code indices into learned
+ * codebooks (additive quantization, paper Sec. 4.1, Eq. vanilla_decode).  The
+ * library never decompresses the cache.  Scores follow the commutative
+ * reformulation of Sec. 4.2 (Eq. new_attention): the selected key codewords are
+ * gather-summed, rotated once by the RoPE matrix of the relative position and
+ * contracted with the query.  Values follow the re-association of
+ * Eq. optimized_v: softmax weights are accumulated into per-codeword bins
+ * (Softmax(A) S_V) and the bins are multiplied by the value codebook once.
+ * The result equals Eq. v1_formula (decode, RoPE, dense softmax attention) up
+ * to fp32 rounding.
+ *
+ * Conventions
+ *   - Pointers are DEVICE pointers unless a comment says "host".  The caller
+ *     owns every buffer; the library only allocates its RoPE phase tables (in
+ *     commvq_create) and frees them in commvq_destroy.
+ *   - All work is enqueued on the caller's stream; nothing synchronises.
+ *   - Functions return a commvq_status; nothing throws or aborts.  Arguments
+ *     that can be checked from host values are checked before any launch.
+ *   - RoPE is the paper's (Sec. 3.2, Eq. rope_ri): adjacent pairs (2j, 2j+1),
+ *     row vector times [[cos, -sin], [sin, cos]], theta_j = rope_base^(-2j/d).
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ */
+#ifndef COMMVQ_H
+#define COMMVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    COMMVQ_OK = 0,
+    COMMVQ_ERR_NULL = 1,      /* a required pointer is NULL */
+    COMMVQ_ERR_CONFIG = 2,    /* unsupported head_dim / M / K / dtype / head counts */
+    COMMVQ_ERR_SHAPE = 3,     /* batch, total_tokens or max_seqlen inconsistent or < 1 */
+    COMMVQ_ERR_WORKSPACE = 4, /* workspace NULL, misaligned or too small */
+    COMMVQ_ERR_LAUNCH = 5,    /* the HIP runtime reported an error (allocation, launch) */
+    COMMVQ_ERR_NO_DEVICE = 6  /* no usable gfx950 device */
+} commvq_status;
+
+typedef enum { COMMVQ_F32 = 0, COMMVQ_BF16 = 1 } commvq_dtype;
+
+/* Host struct, copied by commvq_create. */
+typedef struct {
+    int32_t n_q_heads;       /* Hq */
+    int32_t n_kv_heads;      /* Hkv; Hq / Hkv must be 1, 2, 4 or 8 */
+    int32_t head_dim;        /* d; must be 128 */
+    int32_t m_key;           /* M_k: key codebooks per KV head; 16 or 32 */
+    int32_t m_val;           /* M_v: value codebooks per KV head; 16 or 32 */
+    int32_t k;               /* K: codewords per codebook; must be 256 (one byte per code) */
+    int32_t q_dtype;         /* commvq_dtype of q */
+    int32_t codebook_dtype;  /* commvq_dtype of both codebooks */
+    double rope_base;        /* > 1; 500000 for LLaMA-3.1 */
+    double softmax_scale;    /* 0 selects 1/sqrt(head_dim) (Eq. v1_formula) */
+    int32_t max_position;    /* largest |q_pos - key position| that will occur; sizes the phase tables */
+} commvq_config;
+
+/* Host struct of device pointers: where the tokens sit (ragged batch). */
+typedef struct {
+    int32_t batch;             /* B >= 1 */
+    const int32_t *cu_seqlens; /* device [B+1]: prefix sums of the context lengths L_b, L_b >= 1 */
+    const int32_t *q_pos;      /* device [B]: position t of the query token (q <- q R_t) */
+    const int32_t *key_pos;    /* device [T] or NULL; NULL means token i of a sequence sits at position i */
+    int64_t total_tokens;      /* T = cu_seqlens[B] (host copy, sizes grids without a sync) */
+    int32_t max_seqlen;        /* host copy of max_b L_b */
+} commvq_positions;
+
+/* How one call is cut into workgroups (host struct, filled by commvq_plan_query). */
+typedef struct {
+    int32_t score_split_len;  /* context tokens per score workgroup */
+    int32_t score_splits;     /* score workgroups per (sequence, KV head) for max_seqlen */
+    int32_t value_split_len;  /* context tokens per value workgroup */
+    int32_t value_splits;     /* value workgroups per (sequence, KV head) for max_seqlen */
+    int32_t out_chunks;       /* codebook-row chunks per (sequence, KV head) in the bins x codebook product */
+    int32_t reserved;
+} commvq_plan;
+
+typedef struct commvq_handle commvq_handle;
+
+/* Validates the config and builds the RoPE phase tables on the current device.
+ * *out is set only on COMMVQ_OK. */
+commvq_status commvq_create(const commvq_config *config, commvq_handle **out);
+commvq_status commvq_destroy(commvq_handle *handle);
+
+/* Host-only check of a config (what commvq_create checks before touching the device). */
+commvq_status commvq_validate_config(const commvq_config *config);
+
+/* Host-only: work decomposition and workspace size for a batch shape. */
+commvq_status commvq_plan_query(const commvq_handle *handle, int32_t batch, int64_t total_tokens,
+                                int32_t max_seqlen, commvq_plan *plan);
+commvq_status commvq_workspace_bytes(const commvq_handle *handle, int32_t batch, int64_t total_tokens,
+                                     int32_t max_seqlen, size_t *bytes);
+
+/*
+ * Decode attention over the compressed cache (Eq. new_attention + Eq. optimized_v;
+ * equals Eq. v1_formula).  For every sequence b and query head h:
+ *     out[b][h] = Softmax_i( (q[b][h] R_t) . (k_hat_i R_{p_i}) * scale ) . v_hat_i
+ * with k_hat_i / v_hat_i the sums of the M_k / M_v codeword rows that the codes of
+ * token i select in the codebooks of KV head h / G.
+ *
+ *   q              [B][Hq][d], q_dtype
+ *   key_codes      uint8; sequence b holds [Hkv][L_b][M_k], sequences concatenated
+ *                  (byte offset of sequence b = cu_seqlens[b] * Hkv * M_k); 16-byte aligned
+ *   val_codes      uint8; same with M_v
+ *   key_codebooks  [Hkv][M_k][K][d], codebook_dtype, row-major; a key codeword row is the
+ *                  sequence of (x, y) first rows of its RoPE-commuting 2x2 blocks (Eq. C_struct)
+ *   val_codebooks  [Hkv][M_v][K][d]
+ *   positions      host struct, see above; |q_pos - key position| must not exceed max_position
+ *                  (larger distances are clamped: no fault, wrong rotation)
+ *   out            [B][Hq][d] fp32, fully overwritten
+ *   workspace      >= commvq_workspace_bytes(...) bytes, 256-byte aligned, contents undefined after
+ *   stream         a hipStream_t (NULL = the default stream)
+ * Inputs are never written.  Concurrent calls need distinct workspaces.
+ */
+commvq_status commvq_decode_attn(commvq_handle *handle, const void *q, const uint8_t *key_codes,
+                                 const uint8_t *val_codes, const void *key_codebooks, const void *val_codebooks,
+                                 const commvq_positions *positions, float *out, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/*
+ * The three stages of commvq_decode_attn, callable on their own (tests and profiling).
+ * They read/write the same workspace; run them in this order on one stream.
+ *   commvq_stage_scores  Eq. new_attention: scaled logits for every (b, h, token) and the
+ *                        per-split maxima.  If scores_out is not NULL it receives a copy of the
+ *                        logits, fp32 [T*Hq], (b, h, i) at cu_seqlens[b]*Hq + h*L_b + i.
+ *   commvq_stage_bins    Softmax(A) S_V of Eq. optimized_v, unnormalised: exp(score - max)
+ *                        accumulated per (head, value codebook, codeword), plus the exp sums.
+ *   commvq_stage_output  (bins C_V) / sum of Eq. optimized_v -> out.
+ */
+commvq_status commvq_stage_scores(commvq_handle *handle, const void *q, const uint8_t *key_codes,
+                                  const void *key_codebooks, const commvq_positions *positions,
+                                  void *workspace, size_t workspace_bytes, float *scores_out, void *stream);
+commvq_status commvq_stage_bins(commvq_handle *handle, const uint8_t *val_codes,
+                                const commvq_positions *positions, void *workspace, size_t workspace_bytes,
+                                void *stream);
+commvq_status commvq_stage_output(commvq_handle *handle, const void *val_codebooks,
+                                  const commvq_positions *positions, float *out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
+ * Per-stage timing.  When enabled, commvq_decode_attn brackets each stage with HIP events on
+ * the caller's stream (a ring of 64 calls).  commvq_profile_read synchronises on the recorded
+ * events and returns the mean duration in milliseconds of [scores, bins, output] over the calls
+ * recorded since the last read (host array of 3 floats) and their count.
+ */
+commvq_status commvq_profile_enable(commvq_handle *handle, int32_t enable);
+commvq_status commvq_profile_read(commvq_handle *handle, float *mean_ms /* host [3] */, int32_t *n_calls /* host */);
+
+const char *commvq_status_string(commvq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMMVQ_H */

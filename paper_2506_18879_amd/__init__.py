@@ -1,1 +1,30 @@
-"""MI355X-native decode attention over a CommVQ-compressed KV cache (libcommvq binding)."""
+"""MI355X-native decode attention over a CommVQ-compressed KV cache.
+
+Thin ctypes binding over ``libcommvq.so`` (hand-written HIP for gfx950).  The
+functions carry the names of the C entry points in ``include/commvq.h`` and only
+marshal arguments; every step of the path runs in the library's kernels.  There
+is no CPU fallback: without the built library, or without a GPU, calls raise.
+"""
+from .binding import (  # noqa: F401
+    COMMVQ_BF16,
+    COMMVQ_F32,
+    CommVQError,
+    Config,
+    Handle,
+    Plan,
+    Positions,
+    commvq_create,
+    commvq_decode_attn,
+    commvq_destroy,
+    commvq_plan_query,
+    commvq_profile_enable,
+    commvq_profile_read,
+    commvq_stage_bins,
+    commvq_stage_output,
+    commvq_stage_scores,
+    commvq_status_string,
+    commvq_validate_config,
+    commvq_workspace_bytes,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,907 @@
+// libcommvq: decode attention over a CommVQ-compressed KV cache, hand-written for gfx950.
+//
+// Pipeline of one call (all on the caller's stream):
+//   k_score     Eq. new_attention: per (token, KV head) gather-sum the M_k selected key
+//               codewords, rotate once by the RoPE matrix of the relative position, contract
+//               with the G query heads of the group -> scaled logits + per-split maxima.
+//   k_bins      Softmax(A) S_V of Eq. optimized_v (unnormalised): exp(logit - max) is
+//               scatter-added into LDS bins [G][M_v][K], one bin set per context split.
+//   k_out_part  (bins C_V): split reduction + bins x value-codebook product, per row chunk.
+//   k_out_final sum of the chunks, division by the softmax denominator.
+//
+// RoPE algebra used by k_score (Sec. 3.2, Eq. rope_ri).  Writing a 2-D sub-vector (x, y) as
+// z = x + iy, the paper's row-vector product (x, y) R_m^j is z * exp(-i m theta_j).  The dot
+// product of two sub-vectors is Re(a conj(b)), so
+//     (q^j R_t^j) . (k^j R_p^j) = Re( q^j conj(k^j) exp(-i (t - p) theta_j) ),
+// i.e. only the relative position t - p enters, and the rotation can be applied to the
+// gather-summed codewords once per token (commutativity, Property 1).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "commvq.h"
+
+namespace {
+
+constexpr int kD = 128;         // head_dim
+constexpr int kJ = 64;          // 2-D sub-spaces = lanes of a wavefront
+constexpr int kK = 256;         // codewords per codebook
+constexpr int kLoBits = 8;      // relative position = hi * 256 + lo
+constexpr int kLo = 1 << kLoBits;
+constexpr int kScoreThreads = 256;
+constexpr int kBinsThreads = 512;
+constexpr int kOutThreads = 256;
+constexpr int kOutRows = 128;   // codebook rows per k_out_part workgroup
+constexpr int kProfRing = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct commvq_handle {
+    commvq_config cfg;
+    int G;
+    float scale;
+    int n_hi;
+    int device;
+    float2 *tbl_hi;  // [n_hi][64]  exp(i * theta_j * 256 * hi)
+    float2 *tbl_lo;  // [256][64]   exp(i * theta_j * lo)
+    int prof_on;
+    int prof_head, prof_count;
+    hipEvent_t prof_ev[kProfRing][4];
+    bool prof_ev_made;
+};
+
+namespace {
+
+struct Workspace {
+    float *scores;   // [T * Hq]
+    float *smax;     // [B * Hq * score_splits]
+    float *lsum;     // [B * Hq * value_splits]
+    float *bins;     // [B * Hkv * value_splits][G * Mv * K]
+    float *partial;  // [B * Hq * out_chunks][d]
+    size_t bytes;
+};
+
+void make_plan(const commvq_handle *h, int B, int max_seqlen, commvq_plan *p)
+{
+    const int units = B * h->cfg.n_kv_heads;
+    int len = 1024;
+    while (len > 256 && (long)units * ((max_seqlen + len - 1) / len) < 1024) len /= 2;
+    p->score_split_len = len;
+    p->score_splits = (max_seqlen + len - 1) / len;
+    int nv = 512 / units;
+    if (nv < 1) nv = 1;
+    int vlen = (max_seqlen + nv - 1) / nv;
+    vlen = (vlen + 255) / 256 * 256;
+    if (vlen < 512) vlen = 512;
+    p->value_split_len = vlen;
+    p->value_splits = (max_seqlen + vlen - 1) / vlen;
+    p->out_chunks = h->cfg.m_val * kK / kOutRows;
+    p->reserved = 0;
+}
+
+void carve(const commvq_handle *h, const commvq_plan &p, int B, int64_t T, void *base, Workspace *w)
+{
+    const commvq_config &c = h->cfg;
+    size_t off = 0;
+    auto take = [&](size_t n_floats) {
+        float *ptr = base ? reinterpret_cast<float *>(static_cast<char *>(base) + off) : nullptr;
+        off += align_up(n_floats * sizeof(float), 256);
+        return ptr;
+    };
+    w->scores = take((size_t)T * c.n_q_heads);
+    w->smax = take((size_t)B * c.n_q_heads * p.score_splits);
+    w->lsum = take((size_t)B * c.n_q_heads * p.value_splits);
+    w->bins = take((size_t)B * c.n_kv_heads * p.value_splits * h->G * c.m_val * kK);
+    w->partial = take((size_t)B * c.n_q_heads * p.out_chunks * kD);
+    w->bytes = off;
+}
+
+// ------------------------------------------------------------------ device helpers
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 64 lanes of a wavefront; every lane receives the total.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);  // row_half_mirror
+    v += dpp_mov<0x140>(v);  // row_mirror: every lane now holds its 16-lane row sum
+    unsigned u = __builtin_bit_cast(unsigned, v);
+    auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    v = __builtin_bit_cast(float, (unsigned)r16[0]) + __builtin_bit_cast(float, (unsigned)r16[1]);
+    u = __builtin_bit_cast(unsigned, v);
+    auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (unsigned)r32[0]) + __builtin_bit_cast(float, (unsigned)r32[1]);
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, dpp_mov<0xB1>(v));
+    v = fmaxf(v, dpp_mov<0x4E>(v));
+    v = fmaxf(v, dpp_mov<0x141>(v));
+    v = fmaxf(v, dpp_mov<0x140>(v));
+    unsigned u = __builtin_bit_cast(unsigned, v);
+    auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    v = fmaxf(__builtin_bit_cast(float, (unsigned)r16[0]), __builtin_bit_cast(float, (unsigned)r16[1]));
+    u = __builtin_bit_cast(unsigned, v);
+    auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (unsigned)r32[0]), __builtin_bit_cast(float, (unsigned)r32[1]));
+}
+
+__device__ __forceinline__ float bf16_lo(unsigned v) { return __builtin_bit_cast(float, v << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned v) { return __builtin_bit_cast(float, v & 0xffff0000u); }
+
+// acc + low / high bf16 half of a packed pair, in one v_dot2c_f32_bf16 each:
+// the other half is multiplied by zero, so this is an exact fp32 add of the widened value.
+__device__ __forceinline__ float add_bf16_lo(unsigned v, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v), __builtin_bit_cast(bf16x2_t, 0x00003f80u), acc,
+                                           false);
+}
+__device__ __forceinline__ float add_bf16_hi(unsigned v, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v), __builtin_bit_cast(bf16x2_t, 0x3f800000u), acc,
+                                           false);
+}
+
+// ------------------------------------------------------------------ k_score
+struct ScoreDims {
+    int Hq, Hkv, nsplit, split_len, n_hi, q_bf16;
+    float scale;
+};
+
+typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
+
+// Raw buffer descriptor over [base, base + bytes): loads take a per-lane byte offset plus a
+// wave-uniform (scalar) byte offset, and reads past the end return zero instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// Sums four per-lane values over the 64 lanes at once: on return every lane of 16-lane row r
+// holds the wavefront total of value r.  Two cross-half swaps fold lanes 32..63 onto 0..31,
+// one row swap folds odd rows onto even rows, then four DPP steps finish inside the rows.
+__device__ __forceinline__ float wave_sum4(float v0, float v1, float v2, float v3)
+{
+    auto a = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v0), __builtin_bit_cast(unsigned, v2), false, false);
+    auto c = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v1), __builtin_bit_cast(unsigned, v3), false, false);
+    // lanes 0..31: v0 (resp. v1) folded, lanes 32..63: v2 (resp. v3) folded
+    const float r02 = __builtin_bit_cast(float, (unsigned)a[0]) + __builtin_bit_cast(float, (unsigned)a[1]);
+    const float r13 = __builtin_bit_cast(float, (unsigned)c[0]) + __builtin_bit_cast(float, (unsigned)c[1]);
+    auto e = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, r02), __builtin_bit_cast(unsigned, r13), false, false);
+    float r = __builtin_bit_cast(float, (unsigned)e[0]) + __builtin_bit_cast(float, (unsigned)e[1]);  // rows: v0 v1 v2 v3
+    r += dpp_mov<0xB1>(r);
+    r += dpp_mov<0x4E>(r);
+    r += dpp_mov<0x141>(r);
+    r += dpp_mov<0x140>(r);
+    return r;
+}
+
+__device__ __forceinline__ float row_max16(float v)
+{
+    v = fmaxf(v, dpp_mov<0xB1>(v));
+    v = fmaxf(v, dpp_mov<0x4E>(v));
+    v = fmaxf(v, dpp_mov<0x141>(v));
+    return fmaxf(v, dpp_mov<0x140>(v));
+}
+
+template <int G> struct ScoreTok { static constexpr int value = G == 1 ? 4 : (G == 8 ? 1 : 2); };
+
+// One wavefront walks a run of tokens; lane j owns sub-space j (elements 2j, 2j+1), so a
+// codeword row is one fully coalesced 256-byte (bf16) or 512-byte (fp32) load whose row
+// index is wave-uniform: codes come through scalar loads (prefetched one iteration ahead)
+// and the row offset is formed on the scalar unit and passed as the buffer load's scalar
+// offset, leaving the vector ALUs to the additions.  blockIdx.x % Hkv selects the KV head:
+// consecutive workgroups go to consecutive XCDs, so with 8 KV heads each XCD's L2 serves one
+// head's codebook.  TOK tokens are in flight per iteration; their TOK*G partial dot products
+// are reduced four at a time (wave_sum4) and parked in a lane until 16 iterations are done,
+// then written as 64-byte runs.
+template <int M, int G, bool BF16>
+__global__ __launch_bounds__(kScoreThreads) void k_score(
+    const void *__restrict__ q, const uint8_t *__restrict__ key_codes, const void *__restrict__ key_cb,
+    const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const int32_t *__restrict__ key_pos,
+    const float2 *__restrict__ tbl_hi, const float2 *__restrict__ tbl_lo, float *__restrict__ scores,
+    float *__restrict__ smax, const ScoreDims a)
+{
+    constexpr int TOK = ScoreTok<G>::value;
+    constexpr int NV = TOK * G, NQ = NV / 4, CW = M / 4;
+    constexpr unsigned ROWB = BF16 ? kD * 2 : kD * 4;
+    static_assert(NV % 4 == 0, "values are reduced four at a time");
+    int id = blockIdx.x;
+    const int g = id % a.Hkv;
+    id /= a.Hkv;
+    const int split = id % a.nsplit;
+    const int b = id / a.nsplit;
+    const int cu0 = cu[b];
+    const int L = cu[b + 1] - cu0;
+    const int s0 = split * a.split_len;
+    if (s0 >= L) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wlen = a.split_len / (kScoreThreads / 64);  // multiple of 64
+    const int t0 = s0 + wave * wlen;
+    const int t1 = min(min(t0 + wlen, s0 + a.split_len), L);
+    const int n_it = t1 > t0 ? (t1 - t0 + TOK - 1) / TOK : 0;
+    const int qpos = q_pos[b];
+
+    float2 qv[G], qr[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        const size_t qo = ((size_t)b * a.Hq + (size_t)g * G + hh) * kD + 2 * lane;
+        if (a.q_bf16) {
+            const unsigned v = *reinterpret_cast<const unsigned *>(static_cast<const uint16_t *>(q) + qo);
+            qv[hh] = make_float2(bf16_lo(v) * a.scale, bf16_hi(v) * a.scale);
+        } else {
+            const float2 v = *reinterpret_cast<const float2 *>(static_cast<const float *>(q) + qo);
+            qv[hh] = make_float2(v.x * a.scale, v.y * a.scale);
+        }
+        qr[hh] = qv[hh];
+    }
+
+    const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
+    const __amdgpu_buffer_rsrc_t cb_rs =
+        make_rsrc(static_cast<const char *>(key_cb) + (size_t)g * M * kK * ROWB, (unsigned)(M * kK) * ROWB);
+    const __amdgpu_buffer_rsrc_t hi_rs = make_rsrc(tbl_hi, (unsigned)a.n_hi * kJ * 8u);
+    const __amdgpu_buffer_rsrc_t lo_rs = make_rsrc(tbl_lo, (unsigned)kLo * kJ * 8u);
+    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+
+    float keep[NQ], vmax[NQ];
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) { keep[k] = 0.f; vmax[k] = -INFINITY; }
+    int cur_key = -1;  // (hi << 1 | negative) whose phase is folded into qr
+
+    unsigned cwn[TOK][CW];
+    auto load_codes = [&](int i, unsigned(&dst)[TOK][CW]) {
+#pragma unroll
+        for (int u = 0; u < TOK; ++u) {
+            const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)min(i + u, L - 1) * M);
+#pragma unroll
+            for (int v = 0; v < M / 16; ++v) {
+                const uint4 c4 = cp[v];
+                dst[u][4 * v + 0] = c4.x; dst[u][4 * v + 1] = c4.y; dst[u][4 * v + 2] = c4.z; dst[u][4 * v + 3] = c4.w;
+            }
+        }
+    };
+    if (n_it > 0) load_codes(t0, cwn);
+
+    for (int it = 0; it < n_it; ++it) {
+        const int i = t0 + it * TOK;
+        unsigned cw[TOK][CW];
+#pragma unroll
+        for (int u = 0; u < TOK; ++u)
+#pragma unroll
+            for (int v = 0; v < CW; ++v) cw[u][v] = cwn[u][v];
+        if (it + 1 < n_it) load_codes(i + TOK, cwn);
+
+        // A = sum of the M selected codeword rows (Eq. commute_decode), this lane's sub-space
+        float ax[TOK], ay[TOK];
+#pragma unroll
+        for (int u = 0; u < TOK; ++u) {
+            ax[u] = 0.f; ay[u] = 0.f;
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const unsigned c = (cw[u][m / 4] >> (8 * (m % 4))) & 0xffu;
+                const unsigned soff = ((unsigned)m * kK + c) * ROWB;
+                if (BF16) {
+                    const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(cb_rs, lane * 4, soff, 0);
+                    ax[u] = add_bf16_lo(v, ax[u]);
+                    ay[u] = add_bf16_hi(v, ay[u]);
+                } else {
+                    const uint2_t v = __builtin_amdgcn_raw_buffer_load_b64(cb_rs, lane * 8, soff, 0);
+                    ax[u] += __builtin_bit_cast(float, (unsigned)v[0]);
+                    ay[u] += __builtin_bit_cast(float, (unsigned)v[1]);
+                }
+            }
+        }
+
+        float val[NV];
+#pragma unroll
+        for (int u = 0; u < TOK; ++u) {
+            const int tok = min(i + u, L - 1);
+            const int pos = key_pos ? key_pos[cu0 + tok] : tok;
+            const int dl = qpos - pos;
+            const int neg = dl < 0;
+            const int ad = neg ? -dl : dl;
+            const int hi = min(ad >> kLoBits, a.n_hi - 1);
+            const int lo = ad & (kLo - 1);
+            const uint2_t plu = __builtin_amdgcn_raw_buffer_load_b64(lo_rs, lane * 8, (unsigned)lo * (kJ * 8u), 0);
+            if (((hi << 1) | neg) != cur_key) {  // fold the coarse phase into the queries (rare)
+                cur_key = (hi << 1) | neg;
+                const uint2_t phu = __builtin_amdgcn_raw_buffer_load_b64(hi_rs, lane * 8, (unsigned)hi * (kJ * 8u), 0);
+                const float hc = __builtin_bit_cast(float, (unsigned)phu[0]);
+                float hs = __builtin_bit_cast(float, (unsigned)phu[1]);
+                hs = neg ? -hs : hs;
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh)  // q' = q conj(E_hi) for t >= p, q E_hi otherwise
+                    qr[hh] = make_float2(qv[hh].x * hc + qv[hh].y * hs, qv[hh].y * hc - qv[hh].x * hs);
+            }
+            const float lc = __builtin_bit_cast(float, (unsigned)plu[0]);
+            float lsn = __builtin_bit_cast(float, (unsigned)plu[1]);
+            lsn = neg ? -lsn : lsn;
+            // B = A E_lo; score_h = sum_j Re(q'_h conj(B))
+            const float bx = ax[u] * lc - ay[u] * lsn;
+            const float by = ax[u] * lsn + ay[u] * lc;
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) val[u * G + hh] = qr[hh].x * bx + qr[hh].y * by;
+        }
+
+        const bool mine = (lane & 15) == (it & 15);
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) {
+            const float r = wave_sum4(val[4 * k], val[4 * k + 1], val[4 * k + 2], val[4 * k + 3]);
+            keep[k] = mine ? r : keep[k];
+        }
+        if ((it & 15) == 15 || it == n_it - 1) {  // flush 16 iterations' logits as 64-byte runs
+            const int itc = (it & ~15) + (lane & 15);
+#pragma unroll
+            for (int k = 0; k < NQ; ++k) {
+                const int idx = 4 * k + (lane >> 4);
+                const int u = idx / G, hh = idx % G;
+                const int tok = t0 + itc * TOK + u;
+                if (itc <= it && tok < t1) {
+                    srow[(size_t)hh * L + tok] = keep[k];
+                    vmax[k] = fmaxf(vmax[k], keep[k]);
+                }
+            }
+        }
+    }
+
+    __shared__ float wmax[kScoreThreads / 64][NV];
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) {
+        const float m = row_max16(vmax[k]);
+        if ((lane & 15) == 0) wmax[wave][4 * k + (lane >> 4)] = m;
+    }
+    __syncthreads();
+    if (threadIdx.x < G) {
+        float m = -INFINITY;
+        for (int w = 0; w < kScoreThreads / 64; ++w)
+            for (int u = 0; u < TOK; ++u) m = fmaxf(m, wmax[w][u * G + threadIdx.x]);
+        smax[((size_t)b * a.Hq + (size_t)g * G + threadIdx.x) * a.nsplit + split] = m;
+    }
+}
+
+// ------------------------------------------------------------------ k_bins
+struct BinsArgs {
+    const uint8_t *val_codes;
+    const int32_t *cu;
+    const float *scores, *smax;
+    float *bins, *lsum;
+    int Hq, Hkv, nsplit, split_len;  // score-stage split geometry (for the maxima)
+    int nvsplit, vsplit_len;
+};
+
+// One thread per token: exp(logit - max) for the G heads of the group, then M_v * G fp32
+// atomic adds into LDS bins indexed by the token's value codes (index form of Softmax(A) S_V).
+template <int M, int G>
+__global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
+{
+    extern __shared__ float bins[];  // [G][M][K]
+    __shared__ float red[kBinsThreads / 64][G];
+    __shared__ float mx_s[G];
+    int id = blockIdx.x;
+    const int g = id % a.Hkv;
+    id /= a.Hkv;
+    const int vs = id % a.nvsplit;
+    const int b = id / a.nvsplit;
+    const int cu0 = a.cu[b];
+    const int L = a.cu[b + 1] - cu0;
+    const int v0 = vs * a.vsplit_len;
+    if (v0 >= L) return;
+    const int v1 = min(v0 + a.vsplit_len, L);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NB = G * M * kK;
+
+    for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0.f;
+    if (wave < G) {  // global maximum of head (g*G + wave) over this sequence's score splits
+        const int ns = (L + a.split_len - 1) / a.split_len;
+        const float *sm = a.smax + ((size_t)b * a.Hq + (size_t)g * G + wave) * a.nsplit;
+        float m = -INFINITY;
+        for (int s = lane; s < ns; s += 64) m = fmaxf(m, sm[s]);
+        m = wave_max(m);
+        if (lane == 0) mx_s[wave] = m;
+    }
+    __syncthreads();
+    float mx[G], ls[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) { mx[hh] = mx_s[hh] * kLog2e; ls[hh] = 0.f; }
+
+    const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
+    const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    for (int i = v0 + tid; i < v1; i += kBinsThreads) {
+        unsigned cw[M / 4];
+        const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)i * M);
+#pragma unroll
+        for (int v = 0; v < M / 16; ++v) {
+            const uint4 c4 = cp[v];
+            cw[4 * v + 0] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
+        }
+        float p[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            p[hh] = __builtin_amdgcn_exp2f(srow[(size_t)hh * L + i] * kLog2e - mx[hh]);
+            ls[hh] += p[hh];
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) atomicAdd(&bins[(hh * M + m) * kK + c], p[hh]);
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        const float s = wave_sum(ls[hh]);
+        if (lane == 0) red[wave][hh] = s;
+    }
+    __syncthreads();
+    if (tid < G) {
+        float s = 0.f;
+        for (int w = 0; w < kBinsThreads / 64; ++w) s += red[w][tid];
+        a.lsum[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nvsplit + vs] = s;
+    }
+    float *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB;
+    for (int x = tid; x < NB; x += kBinsThreads) dst[x] = bins[x];
+}
+
+// ------------------------------------------------------------------ k_out_part / k_out_final
+struct OutArgs {
+    const void *val_cb;
+    const int32_t *cu;
+    const float *bins, *lsum;
+    float *partial, *out;
+    int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
+};
+
+// Workgroup = (sequence, KV head, chunk of 128 codebook rows): sums the chunk's bins over the
+// context splits, then multiplies them with the chunk's value-codebook rows (Eq. optimized_v).
+template <int G, bool BF16>
+__global__ __launch_bounds__(kOutThreads) void k_out_part(OutArgs a)
+{
+    __shared__ float wsum[G][kOutRows];
+    __shared__ float red[kOutThreads / 64][G][kD];
+    int id = blockIdx.x;
+    const int chunk = id % a.nchunk;
+    id /= a.nchunk;
+    const int g = id % a.Hkv;
+    const int b = id / a.Hkv;
+    const int L = a.cu[b + 1] - a.cu[b];
+    const int nvs = (L + a.vsplit_len - 1) / a.vsplit_len;
+    const int MK = a.Mv * kK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    for (int x = tid; x < G * kOutRows; x += kOutThreads) {
+        const int hh = x / kOutRows, r = x % kOutRows;
+        const float *src = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit * G + hh) * MK + chunk * kOutRows + r;
+        float s = 0.f;
+        for (int v = 0; v < nvs; ++v) s += src[(size_t)v * G * MK];
+        wsum[hh][r] = s;
+    }
+    __syncthreads();
+    float2 acc[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) acc[hh] = make_float2(0.f, 0.f);
+    const size_t row0 = (size_t)g * MK + (size_t)chunk * kOutRows;
+    for (int r = wave; r < kOutRows; r += kOutThreads / 64) {
+        float2 c;
+        if (BF16) {
+            const unsigned v = static_cast<const unsigned *>(a.val_cb)[(row0 + r) * kJ + lane];
+            c = make_float2(bf16_lo(v), bf16_hi(v));
+        } else {
+            c = static_cast<const float2 *>(a.val_cb)[(row0 + r) * kJ + lane];
+        }
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            const float w = wsum[hh][r];
+            acc[hh].x += w * c.x;
+            acc[hh].y += w * c.y;
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        red[wave][hh][2 * lane] = acc[hh].x;
+        red[wave][hh][2 * lane + 1] = acc[hh].y;
+    }
+    __syncthreads();
+    for (int x = tid; x < G * kD; x += kOutThreads) {
+        const int hh = x / kD, e = x % kD;
+        float s = 0.f;
+        for (int w = 0; w < kOutThreads / 64; ++w) s += red[w][hh][e];
+        a.partial[(((size_t)b * a.Hq + (size_t)g * G + hh) * a.nchunk + chunk) * kD + e] = s;
+    }
+}
+
+__global__ __launch_bounds__(kD) void k_out_final(OutArgs a)
+{
+    const int bh = blockIdx.x;
+    const int b = bh / a.Hq;
+    const int L = a.cu[b + 1] - a.cu[b];
+    const int nvs = (L + a.vsplit_len - 1) / a.vsplit_len;
+    float l = 0.f;
+    for (int v = 0; v < nvs; ++v) l += a.lsum[(size_t)bh * a.nvsplit + v];
+    float s = 0.f;
+    for (int c = 0; c < a.nchunk; ++c) s += a.partial[((size_t)bh * a.nchunk + c) * kD + threadIdx.x];
+    a.out[(size_t)bh * kD + threadIdx.x] = s / l;
+}
+
+// ------------------------------------------------------------------ host side
+commvq_status check_positions(const commvq_positions *p)
+{
+    if (!p) return COMMVQ_ERR_NULL;
+    if (!p->cu_seqlens || !p->q_pos) return COMMVQ_ERR_NULL;
+    if (p->batch < 1 || p->max_seqlen < 1) return COMMVQ_ERR_SHAPE;
+    if (p->total_tokens < p->batch || p->total_tokens < p->max_seqlen) return COMMVQ_ERR_SHAPE;
+    if (p->total_tokens > (int64_t)p->batch * p->max_seqlen) return COMMVQ_ERR_SHAPE;
+    if (p->total_tokens > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
+    return COMMVQ_OK;
+}
+
+commvq_status prep(const commvq_handle *h, const commvq_positions *pos, void *workspace, size_t workspace_bytes,
+                   commvq_plan *plan, Workspace *w)
+{
+    if (!h) return COMMVQ_ERR_NULL;
+    commvq_status st = check_positions(pos);
+    if (st != COMMVQ_OK) return st;
+    make_plan(h, pos->batch, pos->max_seqlen, plan);
+    carve(h, *plan, pos->batch, pos->total_tokens, workspace, w);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < w->bytes)
+        return COMMVQ_ERR_WORKSPACE;
+    return COMMVQ_OK;
+}
+
+struct ScoreArgs {
+    const void *q;
+    const uint8_t *key_codes;
+    const void *key_cb;
+    const int32_t *cu, *q_pos, *key_pos;
+    const float2 *tbl_hi, *tbl_lo;
+    float *scores, *smax;
+    ScoreDims d;
+};
+
+template <int M, int G>
+hipError_t launch_score_mg(const ScoreArgs &a, bool bf16, int grid, hipStream_t s)
+{
+    if (bf16)
+        hipLaunchKernelGGL((k_score<M, G, true>), dim3(grid), dim3(kScoreThreads), 0, s, a.q, a.key_codes, a.key_cb, a.cu,
+                           a.q_pos, a.key_pos, a.tbl_hi, a.tbl_lo, a.scores, a.smax, a.d);
+    else
+        hipLaunchKernelGGL((k_score<M, G, false>), dim3(grid), dim3(kScoreThreads), 0, s, a.q, a.key_codes, a.key_cb, a.cu,
+                           a.q_pos, a.key_pos, a.tbl_hi, a.tbl_lo, a.scores, a.smax, a.d);
+    return hipGetLastError();
+}
+template <int M>
+hipError_t launch_score_m(const ScoreArgs &a, int G, bool bf16, int grid, hipStream_t s)
+{
+    switch (G) {
+    case 1: return launch_score_mg<M, 1>(a, bf16, grid, s);
+    case 2: return launch_score_mg<M, 2>(a, bf16, grid, s);
+    case 4: return launch_score_mg<M, 4>(a, bf16, grid, s);
+    default: return launch_score_mg<M, 8>(a, bf16, grid, s);
+    }
+}
+
+template <int M, int G>
+hipError_t launch_bins_mg(const BinsArgs &a, int grid, hipStream_t s)
+{
+    const size_t lds = (size_t)G * M * kK * sizeof(float);
+    static bool attr_set = false;  // per instantiation; raising the limit is idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bins<M, G>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_bins<M, G>), dim3(grid), dim3(kBinsThreads), lds, s, a);
+    return hipGetLastError();
+}
+template <int M>
+hipError_t launch_bins_m(const BinsArgs &a, int G, int grid, hipStream_t s)
+{
+    switch (G) {
+    case 1: return launch_bins_mg<M, 1>(a, grid, s);
+    case 2: return launch_bins_mg<M, 2>(a, grid, s);
+    case 4: return launch_bins_mg<M, 4>(a, grid, s);
+    default: return launch_bins_mg<M, 8>(a, grid, s);
+    }
+}
+
+template <int G>
+hipError_t launch_out_g(const OutArgs &a, bool bf16, int grid, hipStream_t s)
+{
+    if (bf16) hipLaunchKernelGGL((k_out_part<G, true>), dim3(grid), dim3(kOutThreads), 0, s, a);
+    else hipLaunchKernelGGL((k_out_part<G, false>), dim3(grid), dim3(kOutThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_codes, const void *key_cb,
+                         const commvq_positions *pos, const commvq_plan &plan, const Workspace &w, hipStream_t s)
+{
+    const commvq_config &c = h->cfg;
+    ScoreArgs a;
+    a.q = q; a.key_codes = key_codes; a.key_cb = key_cb;
+    a.cu = pos->cu_seqlens; a.q_pos = pos->q_pos; a.key_pos = pos->key_pos;
+    a.tbl_hi = h->tbl_hi; a.tbl_lo = h->tbl_lo;
+    a.scores = w.scores; a.smax = w.smax;
+    a.d.Hq = c.n_q_heads; a.d.Hkv = c.n_kv_heads; a.d.nsplit = plan.score_splits; a.d.split_len = plan.score_split_len;
+    a.d.n_hi = h->n_hi; a.d.q_bf16 = c.q_dtype == COMMVQ_BF16; a.d.scale = h->scale;
+    const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
+    const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
+    hipError_t e = c.m_key == 16 ? launch_score_m<16>(a, h->G, bf16, grid, s) : launch_score_m<32>(a, h->G, bf16, grid, s);
+    return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+}
+
+commvq_status run_bins(commvq_handle *h, const uint8_t *val_codes, const commvq_positions *pos,
+                       const commvq_plan &plan, const Workspace &w, hipStream_t s)
+{
+    const commvq_config &c = h->cfg;
+    BinsArgs a;
+    a.val_codes = val_codes; a.cu = pos->cu_seqlens; a.scores = w.scores; a.smax = w.smax;
+    a.bins = w.bins; a.lsum = w.lsum;
+    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = plan.score_splits; a.split_len = plan.score_split_len;
+    a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
+    const int grid = pos->batch * c.n_kv_heads * plan.value_splits;
+    hipError_t e = c.m_val == 16 ? launch_bins_m<16>(a, h->G, grid, s) : launch_bins_m<32>(a, h->G, grid, s);
+    return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+}
+
+commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_positions *pos, const commvq_plan &plan,
+                         const Workspace &w, float *out, hipStream_t s)
+{
+    const commvq_config &c = h->cfg;
+    OutArgs a;
+    a.val_cb = val_cb; a.cu = pos->cu_seqlens; a.bins = w.bins; a.lsum = w.lsum; a.partial = w.partial; a.out = out;
+    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
+    a.nchunk = plan.out_chunks; a.Mv = c.m_val;
+    const int grid = pos->batch * c.n_kv_heads * plan.out_chunks;
+    const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
+    hipError_t e;
+    switch (h->G) {
+    case 1: e = launch_out_g<1>(a, bf16, grid, s); break;
+    case 2: e = launch_out_g<2>(a, bf16, grid, s); break;
+    case 4: e = launch_out_g<4>(a, bf16, grid, s); break;
+    default: e = launch_out_g<8>(a, bf16, grid, s); break;
+    }
+    if (e != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_out_final, dim3(pos->batch * c.n_q_heads), dim3(kD), 0, s, a);
+    return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+extern "C" {
+
+const char *commvq_status_string(commvq_status s)
+{
+    switch (s) {
+    case COMMVQ_OK: return "ok";
+    case COMMVQ_ERR_NULL: return "required pointer is NULL";
+    case COMMVQ_ERR_CONFIG: return "unsupported configuration";
+    case COMMVQ_ERR_SHAPE: return "inconsistent batch shape";
+    case COMMVQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case COMMVQ_ERR_LAUNCH: return "HIP runtime error";
+    case COMMVQ_ERR_NO_DEVICE: return "no usable gfx950 device";
+    }
+    return "unknown status";
+}
+
+commvq_status commvq_validate_config(const commvq_config *c)
+{
+    if (!c) return COMMVQ_ERR_NULL;
+    if (c->head_dim != kD || c->k != kK) return COMMVQ_ERR_CONFIG;
+    if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return COMMVQ_ERR_CONFIG;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return COMMVQ_ERR_CONFIG;
+    if ((c->m_key != 16 && c->m_key != 32) || (c->m_val != 16 && c->m_val != 32)) return COMMVQ_ERR_CONFIG;
+    if (c->q_dtype != COMMVQ_F32 && c->q_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    if (c->codebook_dtype != COMMVQ_F32 && c->codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    if (!(c->rope_base > 1.0) || !(c->softmax_scale >= 0.0)) return COMMVQ_ERR_CONFIG;
+    if (c->max_position < 0 || c->max_position > (1 << 24)) return COMMVQ_ERR_CONFIG;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_create(const commvq_config *config, commvq_handle **out)
+{
+    if (!out) return COMMVQ_ERR_NULL;
+    commvq_status st = commvq_validate_config(config);
+    if (st != COMMVQ_OK) return st;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return COMMVQ_ERR_NO_DEVICE; }
+    commvq_handle *h = new (std::nothrow) commvq_handle();
+    if (!h) return COMMVQ_ERR_LAUNCH;
+    h->cfg = *config;
+    h->G = config->n_q_heads / config->n_kv_heads;
+    h->scale = (float)(config->softmax_scale > 0.0 ? config->softmax_scale : 1.0 / std::sqrt((double)kD));
+    h->n_hi = (config->max_position >> kLoBits) + 1;
+    h->device = dev;
+    h->tbl_hi = h->tbl_lo = nullptr;
+    h->prof_on = 0; h->prof_head = h->prof_count = 0; h->prof_ev_made = false;
+    // exact phases in fp64, rounded once to fp32
+    std::vector<float2> hi((size_t)h->n_hi * kJ), lo((size_t)kLo * kJ);
+    for (int j = 0; j < kJ; ++j) {
+        const double theta = std::pow(config->rope_base, -2.0 * j / kD);
+        for (int a = 0; a < h->n_hi; ++a) {
+            const double ang = theta * (double)((int64_t)a << kLoBits);
+            hi[(size_t)a * kJ + j] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+        }
+        for (int a = 0; a < kLo; ++a) {
+            const double ang = theta * (double)a;
+            lo[(size_t)a * kJ + j] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+        }
+    }
+    bool ok = hipMalloc(reinterpret_cast<void **>(&h->tbl_hi), hi.size() * sizeof(float2)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&h->tbl_lo), lo.size() * sizeof(float2)) == hipSuccess &&
+              hipMemcpy(h->tbl_hi, hi.data(), hi.size() * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(h->tbl_lo, lo.data(), lo.size() * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (h->tbl_hi) (void)hipFree(h->tbl_hi);
+        if (h->tbl_lo) (void)hipFree(h->tbl_lo);
+        delete h;
+        return COMMVQ_ERR_LAUNCH;
+    }
+    *out = h;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_destroy(commvq_handle *h)
+{
+    if (!h) return COMMVQ_ERR_NULL;
+    if (h->prof_ev_made)
+        for (int i = 0; i < kProfRing; ++i)
+            for (int k = 0; k < 4; ++k) (void)hipEventDestroy(h->prof_ev[i][k]);
+    (void)hipFree(h->tbl_hi);
+    (void)hipFree(h->tbl_lo);
+    delete h;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_plan_query(const commvq_handle *h, int32_t batch, int64_t total_tokens, int32_t max_seqlen,
+                                commvq_plan *plan)
+{
+    if (!h || !plan) return COMMVQ_ERR_NULL;
+    if (batch < 1 || max_seqlen < 1 || total_tokens < batch || total_tokens < max_seqlen ||
+        total_tokens > (int64_t)batch * max_seqlen)
+        return COMMVQ_ERR_SHAPE;
+    make_plan(h, batch, max_seqlen, plan);
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_workspace_bytes(const commvq_handle *h, int32_t batch, int64_t total_tokens, int32_t max_seqlen,
+                                     size_t *bytes)
+{
+    if (!bytes) return COMMVQ_ERR_NULL;
+    commvq_plan plan;
+    commvq_status st = commvq_plan_query(h, batch, total_tokens, max_seqlen, &plan);
+    if (st != COMMVQ_OK) return st;
+    Workspace w;
+    carve(h, plan, batch, total_tokens, nullptr, &w);
+    *bytes = w.bytes;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_stage_scores(commvq_handle *h, const void *q, const uint8_t *key_codes, const void *key_cb,
+                                  const commvq_positions *pos, void *workspace, size_t workspace_bytes,
+                                  float *scores_out, void *stream)
+{
+    if (!h || !q || !key_codes || !key_cb) return COMMVQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(key_codes) & 15u) return COMMVQ_ERR_SHAPE;
+    commvq_plan plan;
+    Workspace w;
+    commvq_status st = prep(h, pos, workspace, workspace_bytes, &plan, &w);
+    if (st != COMMVQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = run_scores(h, q, key_codes, key_cb, pos, plan, w, s);
+    if (st != COMMVQ_OK) return st;
+    if (scores_out &&
+        hipMemcpyAsync(scores_out, w.scores, (size_t)pos->total_tokens * h->cfg.n_q_heads * sizeof(float),
+                       hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return COMMVQ_ERR_LAUNCH;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_stage_bins(commvq_handle *h, const uint8_t *val_codes, const commvq_positions *pos,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!h || !val_codes) return COMMVQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(val_codes) & 15u) return COMMVQ_ERR_SHAPE;
+    commvq_plan plan;
+    Workspace w;
+    commvq_status st = prep(h, pos, workspace, workspace_bytes, &plan, &w);
+    if (st != COMMVQ_OK) return st;
+    return run_bins(h, val_codes, pos, plan, w, static_cast<hipStream_t>(stream));
+}
+
+commvq_status commvq_stage_output(commvq_handle *h, const void *val_cb, const commvq_positions *pos, float *out,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!h || !val_cb || !out) return COMMVQ_ERR_NULL;
+    commvq_plan plan;
+    Workspace w;
+    commvq_status st = prep(h, pos, workspace, workspace_bytes, &plan, &w);
+    if (st != COMMVQ_OK) return st;
+    return run_output(h, val_cb, pos, plan, w, out, static_cast<hipStream_t>(stream));
+}
+
+commvq_status commvq_decode_attn(commvq_handle *h, const void *q, const uint8_t *key_codes, const uint8_t *val_codes,
+                                 const void *key_cb, const void *val_cb, const commvq_positions *pos, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!h || !q || !key_codes || !val_codes || !key_cb || !val_cb || !out) return COMMVQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(key_codes) | reinterpret_cast<uintptr_t>(val_codes)) & 15u) return COMMVQ_ERR_SHAPE;
+    commvq_plan plan;
+    Workspace w;
+    commvq_status st = prep(h, pos, workspace, workspace_bytes, &plan, &w);
+    if (st != COMMVQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t *ev = nullptr;
+    if (h->prof_on) {
+        if (!h->prof_ev_made) {
+            for (int i = 0; i < kProfRing; ++i)
+                for (int k = 0; k < 4; ++k)
+                    if (hipEventCreate(&h->prof_ev[i][k]) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+            h->prof_ev_made = true;
+        }
+        ev = h->prof_ev[h->prof_head];
+        if (hipEventRecord(ev[0], s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    }
+    st = run_scores(h, q, key_codes, key_cb, pos, plan, w, s);
+    if (st != COMMVQ_OK) return st;
+    if (ev && hipEventRecord(ev[1], s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    st = run_bins(h, val_codes, pos, plan, w, s);
+    if (st != COMMVQ_OK) return st;
+    if (ev && hipEventRecord(ev[2], s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    st = run_output(h, val_cb, pos, plan, w, out, s);
+    if (st != COMMVQ_OK) return st;
+    if (ev) {
+        if (hipEventRecord(ev[3], s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+        h->prof_head = (h->prof_head + 1) % kProfRing;
+        if (h->prof_count < kProfRing) ++h->prof_count;
+    }
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_profile_enable(commvq_handle *h, int32_t enable)
+{
+    if (!h) return COMMVQ_ERR_NULL;
+    h->prof_on = enable ? 1 : 0;
+    h->prof_head = h->prof_count = 0;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_profile_read(commvq_handle *h, float *mean_ms, int32_t *n_calls)
+{
+    if (!h || !mean_ms || !n_calls) return COMMVQ_ERR_NULL;
+    double acc[3] = {0, 0, 0};
+    const int n = h->prof_count;
+    for (int k = 0; k < n; ++k) {
+        const int i = (h->prof_head - 1 - k + 2 * kProfRing) % kProfRing;
+        if (hipEventSynchronize(h->prof_ev[i][3]) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+        for (int st = 0; st < 3; ++st) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, h->prof_ev[i][st], h->prof_ev[i][st + 1]) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+            acc[st] += ms;
+        }
+    }
+    for (int st = 0; st < 3; ++st) mean_ms[st] = n ? (float)(acc[st] / n) : 0.f;
+    *n_calls = n;
+    h->prof_head = h->prof_count = 0;
+    return COMMVQ_OK;
+}
+
+}  // extern "C"

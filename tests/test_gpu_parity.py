@@ -1,0 +1,219 @@
+"""GPU parity: libcommvq (through its C ABI) against the fp64 CPU oracle, element by element.
+
+Bar: per (sequence, head) row, max |out - ref| / max |ref| <= 2e-3 on the attention output;
+logits from the score stage within 2e-5 absolute (fp32 accumulation of ~4k terms of order 1).
+"""
+import numpy as np
+import pytest
+
+from paper_2506_18879_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL_OUT = 2e-3
+TOL_SCORE = 2e-5
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2506_18879_amd as cv
+    cv.load_library()
+    from paper_2506_18879_amd import device
+    return device
+
+
+def oracle_out(oracle, w, **kw):
+    return oracle.decode_attn(w.as_f64("q"), w.key_codes, w.val_codes, w.as_f64("key_codebooks"),
+                              w.as_f64("val_codebooks"), w.cu_seqlens, w.q_pos, key_pos=w.key_pos,
+                              rope_base=w.rope_base, n_threads=16, **kw)
+
+
+def row_err(got, ref):
+    got = np.asarray(got, np.float64)
+    return np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+
+
+def run_gpu(gpu, w, staged=False, **kw):
+    import torch
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w, **kw)
+    out = op.staged(dw) if staged else op(dw)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    op.close()
+    return res
+
+
+def check(gpu, oracle, w, tol=TOL_OUT, **kw):
+    print(f"case {w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} Mk={w.Mk} Mv={w.Mv} lens={np.diff(w.cu_seqlens)[:8]}", flush=True)
+    got = run_gpu(gpu, w, **kw)
+    ref = oracle_out(oracle, w)
+    assert np.isfinite(got).all()
+    err = row_err(got, ref)
+    print(f"  max row error {err.max():.3e}", flush=True)
+    assert err.max() <= tol, (w.name, err.max())
+    return got, ref
+
+
+# ---------------------------------------------------------------- the score stage on its own
+@pytest.mark.parametrize("idx,L", [(1, 777), (2, 1500), (3, 1100), (5, 900)])
+def test_scores_match_oracle_logits(gpu, oracle, idx, L):
+    import torch
+    w = synth.config(idx, max_len=L)
+    print(f"scores case config {idx} L={L}", flush=True)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    s = op.scores(dw)
+    torch.cuda.synchronize()
+    got = s.cpu().numpy().astype(np.float64)
+    op.close()
+    _, ref, _ = oracle_out(oracle, w, return_intermediates=True)
+    assert np.abs(got - ref).max() <= TOL_SCORE, np.abs(got - ref).max()
+
+
+# ---------------------------------------------------------------- the five configurations, reduced lengths
+@pytest.mark.parametrize("idx,L", [(1, 4096), (2, 3000), (3, 5001), (4, 4099), (5, 2500)])
+def test_configs_reduced(gpu, oracle, idx, L):
+    # several score/value splits and a ragged tail (lengths are not multiples of 64)
+    check(gpu, oracle, synth.config(idx, max_len=L))
+
+
+def test_staged_entry_points_equal_fused_call(gpu):
+    w = synth.config(3, max_len=3000)
+    a = run_gpu(gpu, w)
+    b = run_gpu(gpu, w, staged=True)
+    # same kernels, same order; LDS float atomics reorder additions inside the bins
+    assert np.abs(a - b).max() <= 1e-6 * np.abs(a).max()
+
+
+# ---------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025])
+def test_lengths_around_tile_boundaries(gpu, oracle, L):
+    w = synth.make_workload(f"edge_L{L}", B=1, Hq=8, Hkv=2, seqlens=[L], Mk=16, Mv=32, dtype="bf16", seed=100 + L)
+    check(gpu, oracle, w)
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 3), (2, 2), (4, 1), (8, 1)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_group_sizes_and_dtypes(gpu, oracle, G, Hkv, dtype):
+    w = synth.make_workload(f"g{G}_{dtype}", B=2, Hq=G * Hkv, Hkv=Hkv, seqlens=[700, 333], Mk=32, Mv=16, dtype=dtype,
+                            seed=7 * G + Hkv)
+    check(gpu, oracle, w)
+
+
+def test_ragged_batch_with_length_one_sequence(gpu, oracle):
+    w = synth.make_workload("ragged", B=5, Hq=8, Hkv=2, seqlens=[1, 2100, 64, 1, 517], Mk=32, Mv=32, dtype="bf16", seed=5)
+    got, ref = check(gpu, oracle, w)
+    # L = 1: the output is the decoded value of the only token
+    assert row_err(got[0], ref[0]).max() <= 1e-6
+
+
+def test_explicit_positions_and_negative_distances(gpu, oracle):
+    rng = np.random.default_rng(3)
+    w = synth.make_workload("pos", B=2, Hq=8, Hkv=2, seqlens=[900, 450], Mk=16, Mv=16, dtype="bf16", seed=11)
+    w.key_pos = rng.integers(0, 131072, w.total_tokens).astype(np.int32)
+    w.q_pos = np.array([131071, 40000], np.int32)  # second sequence sees keys on both sides of the query
+    check(gpu, oracle, w, max_position=131072)
+
+
+def test_shift_invariance_on_gpu(gpu):
+    # scores depend on t - p only (Eq. attention): shifting every position leaves the output unchanged
+    w = synth.make_workload("shift", B=1, Hq=4, Hkv=1, seqlens=[1200], Mk=16, Mv=16, dtype="bf16", seed=12)
+    w.key_pos = np.arange(1200, dtype=np.int32)
+    a = run_gpu(gpu, w, max_position=70000)
+    w.key_pos = w.key_pos + 60000
+    w.q_pos = w.q_pos + 60000
+    b = run_gpu(gpu, w, max_position=70000)
+    assert np.abs(a - b).max() <= 1e-6 * np.abs(a).max()
+
+
+def test_equal_positions_scalar_lut_case(gpu, oracle):
+    # the paper's hypothetical "R_i independent of i": RoPE cancels
+    w = synth.make_workload("nope", B=1, Hq=4, Hkv=1, seqlens=[800], Mk=32, Mv=32, dtype="bf16", seed=13)
+    w.key_pos = np.full(800, 4242, np.int32)
+    w.q_pos = np.array([4242], np.int32)
+    check(gpu, oracle, w)
+
+
+def test_zero_query_histogram_closed_form(gpu):
+    # q = 0 => uniform weights => out = hist C_V / L (Eq. optimized_v)
+    w = synth.make_workload("q0", B=1, Hq=4, Hkv=1, seqlens=[1500], Mk=16, Mv=16, dtype="bf16", seed=14)
+    w.q[...] = 0
+    got = run_gpu(gpu, w)
+    vc = w.seq_codes("val", 0)[0]
+    cb = w.as_f64("val_codebooks")[0]
+    want = sum(np.bincount(vc[:, m], minlength=256) @ cb[m] for m in range(16)) / 1500
+    for h in range(4):
+        assert np.abs(got[0, h] - want).max() <= 1e-5 * np.abs(want).max()
+
+
+def test_peaked_softmax_large_logits(gpu, oracle):
+    # logits of order 1e2: max-subtraction must hold on the GPU too
+    w = synth.make_workload("peak", B=1, Hq=4, Hkv=1, seqlens=[2000], Mk=16, Mv=16, dtype="f32", seed=15)
+    w.q *= 25.0
+    check(gpu, oracle, w)
+
+
+def test_run_to_run_spread(gpu):
+    w = synth.config(3, max_len=4000)
+    a, b, c = run_gpu(gpu, w), run_gpu(gpu, w), run_gpu(gpu, w)
+    scale = np.abs(a).max()
+    assert max(np.abs(a - b).max(), np.abs(a - c).max()) <= 1e-5 * scale  # atomics reorder, nothing more
+
+
+# ---------------------------------------------------------------- argument checking through the C ABI
+def test_error_statuses(gpu):
+    import torch
+    import paper_2506_18879_amd as cv
+    w = synth.make_workload("err", B=1, Hq=4, Hkv=1, seqlens=[100], Mk=16, Mv=16, dtype="bf16", seed=16)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    args = (dw.q, dw.key_codes, dw.val_codes, dw.key_codebooks, dw.val_codebooks)
+
+    def status(fn):
+        with pytest.raises(cv.CommVQError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: cv.commvq_decode_attn(op.handle, None, *args[1:], dw.positions, op.out, op.workspace,
+                                                op.workspace_bytes)) == 1
+    assert status(lambda: cv.commvq_decode_attn(op.handle, *args, dw.positions, op.out, op.workspace,
+                                                op.workspace_bytes - 1)) == 4
+    assert status(lambda: cv.commvq_decode_attn(op.handle, *args, dw.positions, op.out,
+                                                op.workspace.data_ptr() + 16, op.workspace_bytes)) == 4
+    assert status(lambda: cv.commvq_decode_attn(op.handle, dw.q, dw.key_codes.data_ptr() + 1, *args[2:], dw.positions,
+                                                op.out, op.workspace, op.workspace_bytes)) == 3
+    bad = cv.binding.make_positions(1, dw.cu_seqlens, dw.q_pos, None, 0, 100)
+    assert status(lambda: cv.commvq_decode_attn(op.handle, *args, bad, op.out, op.workspace, op.workspace_bytes)) == 3
+    bad = cv.binding.make_positions(1, None, dw.q_pos, None, 100, 100)
+    assert status(lambda: cv.commvq_decode_attn(op.handle, *args, bad, op.out, op.workspace, op.workspace_bytes)) == 1
+    # and the handle still works afterwards
+    op(dw)
+    torch.cuda.synchronize()
+    assert torch.isfinite(op.out).all()
+    op.close()
+
+
+# ---------------------------------------------------------------- full benchmark sizes, sampled units
+@pytest.mark.parametrize("idx,units", [(2, 8), (3, 2), (4, 3), (5, 2)])
+def test_full_size_sampled_units(gpu, oracle, idx, units):
+    """The configurations at their full sizes (the launch shapes bench.py times); the oracle
+    computes `units` sampled (sequence, KV head) units, i.e. all G heads of each."""
+    w = synth.config(idx)
+    print(f"full-size case {w.name} T={w.total_tokens}", flush=True)
+    got = run_gpu(gpu, w)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(idx)
+    mask = np.zeros(w.B * w.Hkv, bool)
+    mask[rng.choice(w.B * w.Hkv, size=units, replace=False)] = True
+    ref = oracle_out(oracle, w, unit_mask=mask.reshape(w.B, w.Hkv))
+    G = w.Hq // w.Hkv
+    worst = 0.0
+    for u in np.flatnonzero(mask):
+        b, g = divmod(int(u), w.Hkv)
+        e = row_err(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G]).max()
+        worst = max(worst, e)
+    print(f"  worst row error over {units} units: {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT
