@@ -144,17 +144,18 @@ __device__ __forceinline__ float wave_max(float v)
 __device__ __forceinline__ float bf16_lo(unsigned v) { return __builtin_bit_cast(float, v << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned v) { return __builtin_bit_cast(float, v & 0xffff0000u); }
 
-// acc + low / high bf16 half of a packed pair, in one v_dot2c_f32_bf16 each:
-// the other half is multiplied by zero, so this is an exact fp32 add of the widened value.
-__device__ __forceinline__ float add_bf16_lo(unsigned v, float acc)
+// acc + low / high bf16 half of a packed pair, in one v_dot2c_f32_bf16 each: the other half
+// is multiplied by zero, so this is an exact fp32 add of the widened value.  The selector
+// (1.0 in one half, 0 in the other) is passed through an opaque register so that it is never
+// encoded as an inline constant, whose meaning for packed bf16 operands is ambiguous.
+__device__ __forceinline__ unsigned opaque_sgpr(unsigned v)
 {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v), __builtin_bit_cast(bf16x2_t, 0x00003f80u), acc,
-                                           false);
+    asm volatile("" : "+s"(v));
+    return v;
 }
-__device__ __forceinline__ float add_bf16_hi(unsigned v, float acc)
+__device__ __forceinline__ float add_bf16_sel(unsigned v, unsigned sel, float acc)
 {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v), __builtin_bit_cast(bf16x2_t, 0x3f800000u), acc,
-                                           false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v), __builtin_bit_cast(bf16x2_t, sel), acc, false);
 }
 
 // ------------------------------------------------------------------ k_score
@@ -263,6 +264,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
 #pragma unroll
     for (int k = 0; k < NQ; ++k) { keep[k] = 0.f; vmax[k] = -INFINITY; }
     int cur_key = -1;  // (hi << 1 | negative) whose phase is folded into qr
+    const unsigned sel_lo = opaque_sgpr(0x00003f80u), sel_hi = opaque_sgpr(0x3f800000u);
 
     unsigned cwn[TOK][CW];
     auto load_codes = [&](int i, unsigned(&dst)[TOK][CW]) {
@@ -298,8 +300,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
                 const unsigned soff = ((unsigned)m * kK + c) * ROWB;
                 if (BF16) {
                     const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(cb_rs, lane * 4, soff, 0);
-                    ax[u] = add_bf16_lo(v, ax[u]);
-                    ay[u] = add_bf16_hi(v, ay[u]);
+                    ax[u] = add_bf16_sel(v, sel_lo, ax[u]);
+                    ay[u] = add_bf16_sel(v, sel_hi, ay[u]);
                 } else {
                     const uint2_t v = __builtin_amdgcn_raw_buffer_load_b64(cb_rs, lane * 8, soff, 0);
                     ax[u] += __builtin_bit_cast(float, (unsigned)v[0]);
