@@ -5,7 +5,10 @@
 //               codewords, rotate once by the RoPE matrix of the relative position, contract
 //               with the G query heads of the group -> scaled logits + per-split maxima.
 //   k_bins      Softmax(A) S_V of Eq. optimized_v (unnormalised): exp(logit - max) is
-//               scatter-added into LDS bins [G][M_v][K], one bin set per context split.
+//               scatter-added into LDS bins [G][M_v][K], one bin set per context split.  The
+//               bins are 32-bit fixed point (integer LDS atomics run ~20x faster than fp32 ones
+//               on gfx950); the scale of each split is chosen from its known exp-sum so that
+//               no bin can overflow and the worst-case error is (tokens per split) * 2^-32.
 //   k_out_part  (bins C_V): split reduction + bins x value-codebook product, per row chunk.
 //   k_out_final sum of the chunks, division by the softmax denominator.
 //
@@ -35,7 +38,7 @@ constexpr int kLo = 1 << kLoBits;
 constexpr int kScoreThreads = 256;
 constexpr int kBinsThreads = 512;
 constexpr int kOutThreads = 256;
-constexpr int kOutRows = 128;   // codebook rows per k_out_part workgroup
+constexpr int kOutRows = 64;    // codebook rows per k_out_part workgroup
 constexpr int kProfRing = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -62,11 +65,11 @@ struct commvq_handle {
 namespace {
 
 struct Workspace {
-    float *scores;   // [T * Hq]
-    float *smax;     // [B * Hq * score_splits]
-    float *lsum;     // [B * Hq * value_splits]
-    float *bins;     // [B * Hkv * value_splits][G * Mv * K]
-    float *partial;  // [B * Hq * out_chunks][d]
+    float *scores;    // [T * Hq] scaled logits
+    float2 *sstat;    // [B * Hq * score_splits] (max, sum of exp(logit - max)) of each score split
+    float *vscale;    // [B * Hq * value_splits] 2^-S: value of one fixed-point unit of that split's bins
+    unsigned *bins;   // [B * Hkv * value_splits][G * Mv * K] fixed-point bins
+    float *partial;   // [B * Hq * out_chunks][d]
     size_t bytes;
 };
 
@@ -74,14 +77,13 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, commvq_plan *p)
 {
     const int units = B * h->cfg.n_kv_heads;
     int len = 1024;
-    while (len > 256 && (long)units * ((max_seqlen + len - 1) / len) < 1024) len /= 2;
+    while (len > 256 && (long)units * ((max_seqlen + len - 1) / len) < 2048) len /= 2;
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
     int nv = 512 / units;
     if (nv < 1) nv = 1;
     int vlen = (max_seqlen + nv - 1) / nv;
-    vlen = (vlen + 255) / 256 * 256;
-    if (vlen < 512) vlen = 512;
+    vlen = (vlen + 1023) / 1024 * 1024;  // whole score splits, so their statistics can be summed
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
     p->out_chunks = h->cfg.m_val * kK / kOutRows;
@@ -98,9 +100,9 @@ void carve(const commvq_handle *h, const commvq_plan &p, int B, int64_t T, void 
         return ptr;
     };
     w->scores = take((size_t)T * c.n_q_heads);
-    w->smax = take((size_t)B * c.n_q_heads * p.score_splits);
-    w->lsum = take((size_t)B * c.n_q_heads * p.value_splits);
-    w->bins = take((size_t)B * c.n_kv_heads * p.value_splits * h->G * c.m_val * kK);
+    w->sstat = reinterpret_cast<float2 *>(take((size_t)B * c.n_q_heads * p.score_splits * 2));
+    w->vscale = take((size_t)B * c.n_q_heads * p.value_splits);
+    w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * p.value_splits * h->G * c.m_val * kK));
     w->partial = take((size_t)B * c.n_q_heads * p.out_chunks * kD);
     w->bytes = off;
 }
@@ -200,6 +202,14 @@ __device__ __forceinline__ float row_max16(float v)
     return fmaxf(v, dpp_mov<0x140>(v));
 }
 
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += dpp_mov<0xB1>(v);
+    v += dpp_mov<0x4E>(v);
+    v += dpp_mov<0x141>(v);
+    return v + dpp_mov<0x140>(v);
+}
+
 template <int G> struct ScoreTok { static constexpr int value = G == 1 ? 4 : (G == 8 ? 1 : 2); };
 
 // One wavefront walks a run of tokens; lane j owns sub-space j (elements 2j, 2j+1), so a
@@ -216,7 +226,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     const void *__restrict__ q, const uint8_t *__restrict__ key_codes, const void *__restrict__ key_cb,
     const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const int32_t *__restrict__ key_pos,
     const float2 *__restrict__ tbl_hi, const float2 *__restrict__ tbl_lo, float *__restrict__ scores,
-    float *__restrict__ smax, const ScoreDims a)
+    float2 *__restrict__ sstat, const ScoreDims a)
 {
     constexpr int TOK = ScoreTok<G>::value;
     constexpr int NV = TOK * G, NQ = NV / 4, CW = M / 4;
@@ -260,9 +270,10 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     const __amdgpu_buffer_rsrc_t lo_rs = make_rsrc(tbl_lo, (unsigned)kLo * kJ * 8u);
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
 
-    float keep[NQ], vmax[NQ];
+    // per lane: parked logits, and the running (max, sum exp) of the logits this lane flushed
+    float keep[NQ], vmax[NQ], vsum[NQ];
 #pragma unroll
-    for (int k = 0; k < NQ; ++k) { keep[k] = 0.f; vmax[k] = -INFINITY; }
+    for (int k = 0; k < NQ; ++k) { keep[k] = 0.f; vmax[k] = -INFINITY; vsum[k] = 0.f; }
     int cur_key = -1;  // (hi << 1 | negative) whose phase is folded into qr
     const unsigned sel_lo = opaque_sgpr(0x00003f80u), sel_hi = opaque_sgpr(0x3f800000u);
 
@@ -356,24 +367,35 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
                 const int tok = t0 + itc * TOK + u;
                 if (itc <= it && tok < t1) {
                     srow[(size_t)hh * L + tok] = keep[k];
-                    vmax[k] = fmaxf(vmax[k], keep[k]);
+                    const float mn = fmaxf(vmax[k], keep[k]);
+                    vsum[k] = vsum[k] * __builtin_amdgcn_exp2f((vmax[k] - mn) * kLog2e) +
+                              __builtin_amdgcn_exp2f((keep[k] - mn) * kLog2e);
+                    vmax[k] = mn;
                 }
             }
         }
     }
 
-    __shared__ float wmax[kScoreThreads / 64][NV];
+    // (max, sum exp) of the split: lanes of a row -> waves and token slots -> one pair per head
+    __shared__ float2 wstat[kScoreThreads / 64][NV];
 #pragma unroll
     for (int k = 0; k < NQ; ++k) {
         const float m = row_max16(vmax[k]);
-        if ((lane & 15) == 0) wmax[wave][4 * k + (lane >> 4)] = m;
+        const float l = row_sum16(vmax[k] == -INFINITY ? 0.f : vsum[k] * __builtin_amdgcn_exp2f((vmax[k] - m) * kLog2e));
+        if ((lane & 15) == 0) wstat[wave][4 * k + (lane >> 4)] = make_float2(m, l);
     }
     __syncthreads();
     if (threadIdx.x < G) {
         float m = -INFINITY;
         for (int w = 0; w < kScoreThreads / 64; ++w)
-            for (int u = 0; u < TOK; ++u) m = fmaxf(m, wmax[w][u * G + threadIdx.x]);
-        smax[((size_t)b * a.Hq + (size_t)g * G + threadIdx.x) * a.nsplit + split] = m;
+            for (int u = 0; u < TOK; ++u) m = fmaxf(m, wstat[w][u * G + threadIdx.x].x);
+        float l = 0.f;
+        for (int w = 0; w < kScoreThreads / 64; ++w)
+            for (int u = 0; u < TOK; ++u) {
+                const float2 st = wstat[w][u * G + threadIdx.x];
+                if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+            }
+        sstat[((size_t)b * a.Hq + (size_t)g * G + threadIdx.x) * a.nsplit + split] = make_float2(m, l);
     }
 }
 
@@ -381,20 +403,26 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
 struct BinsArgs {
     const uint8_t *val_codes;
     const int32_t *cu;
-    const float *scores, *smax;
-    float *bins, *lsum;
-    int Hq, Hkv, nsplit, split_len;  // score-stage split geometry (for the maxima)
+    const float *scores;
+    const float2 *sstat;
+    unsigned *bins;
+    float *vscale;
+    int Hq, Hkv, nsplit, split_len;  // score-stage split geometry (for the statistics)
     int nvsplit, vsplit_len;
 };
 
-// One thread per token: exp(logit - max) for the G heads of the group, then M_v * G fp32
-// atomic adds into LDS bins indexed by the token's value codes (index form of Softmax(A) S_V).
+// One thread per token: w = exp(logit - max) for the G heads of the group, then M_v * G
+// integer atomic adds into LDS bins indexed by the token's value codes (index form of
+// Softmax(A) S_V).  w is added as round(w * 2^S): the score stage already produced the
+// exp-sum l of this split (relative to the sequence maximum), every bin is bounded by it, so
+// S = 30 - floor(log2 l) keeps every bin below 2^31 while the rounding error of the whole
+// split stays below (tokens in split) * 2^-32 of its weight.  Integer adds commute, so the
+// result does not depend on the order in which wavefronts arrive.
 template <int M, int G>
 __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 {
-    extern __shared__ float bins[];  // [G][M][K]
-    __shared__ float red[kBinsThreads / 64][G];
-    __shared__ float mx_s[G];
+    extern __shared__ unsigned bins[];  // [G][M][K]
+    __shared__ float eoff_s[G];
     int id = blockIdx.x;
     const int g = id % a.Hkv;
     id /= a.Hkv;
@@ -408,19 +436,28 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NB = G * M * kK;
 
-    for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0.f;
-    if (wave < G) {  // global maximum of head (g*G + wave) over this sequence's score splits
-        const int ns = (L + a.split_len - 1) / a.split_len;
-        const float *sm = a.smax + ((size_t)b * a.Hq + (size_t)g * G + wave) * a.nsplit;
-        float m = -INFINITY;
-        for (int s = lane; s < ns; s += 64) m = fmaxf(m, sm[s]);
-        m = wave_max(m);
-        if (lane == 0) mx_s[wave] = m;
+    for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0u;
+    if (wave < G) {
+        const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
+        const float2 *st = a.sstat + ((size_t)b * a.Hq + (size_t)g * G + wave) * a.nsplit;
+        float mx = -INFINITY;  // maximum logit of head (g*G + wave) over the whole sequence
+        for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, st[s].x);
+        mx = wave_max(mx);
+        const int sa = v0 / a.split_len, sb = min((v1 + a.split_len - 1) / a.split_len, ns);
+        float l = 0.f;  // sum of exp(logit - mx) over this value split
+        for (int s = sa + lane; s < sb; s += 64) l += st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
+        l = wave_sum(l);
+        int S = 0;
+        if (l >= 1e-30f) S = min(30 - ilogbf(l), 120);
+        if (lane == 0) {
+            eoff_s[wave] = (float)S - mx * kLog2e;
+            a.vscale[((size_t)b * a.Hq + (size_t)g * G + wave) * a.nvsplit + vs] = ldexpf(1.f, -S);
+        }
     }
     __syncthreads();
-    float mx[G], ls[G];
+    float eoff[G];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) { mx[hh] = mx_s[hh] * kLog2e; ls[hh] = 0.f; }
+    for (int hh = 0; hh < G; ++hh) eoff[hh] = eoff_s[hh];
 
     const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
@@ -432,12 +469,10 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
             const uint4 c4 = cp[v];
             cw[4 * v + 0] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
         }
-        float p[G];
+        unsigned p[G];
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            p[hh] = __builtin_amdgcn_exp2f(srow[(size_t)hh * L + i] * kLog2e - mx[hh]);
-            ls[hh] += p[hh];
-        }
+        for (int hh = 0; hh < G; ++hh)
+            p[hh] = (unsigned)(__builtin_amdgcn_exp2f(srow[(size_t)hh * L + i] * kLog2e + eoff[hh]) + 0.5f);
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
@@ -445,18 +480,8 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
             for (int hh = 0; hh < G; ++hh) atomicAdd(&bins[(hh * M + m) * kK + c], p[hh]);
         }
     }
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        const float s = wave_sum(ls[hh]);
-        if (lane == 0) red[wave][hh] = s;
-    }
     __syncthreads();
-    if (tid < G) {
-        float s = 0.f;
-        for (int w = 0; w < kBinsThreads / 64; ++w) s += red[w][tid];
-        a.lsum[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nvsplit + vs] = s;
-    }
-    float *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB;
+    unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB;
     for (int x = tid; x < NB; x += kBinsThreads) dst[x] = bins[x];
 }
 
@@ -464,13 +489,16 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 struct OutArgs {
     const void *val_cb;
     const int32_t *cu;
-    const float *bins, *lsum;
+    const unsigned *bins;
+    const float *vscale;
+    const float2 *sstat;
     float *partial, *out;
-    int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
+    int Hq, Hkv, nsplit, split_len, nvsplit, vsplit_len, nchunk, Mv;
 };
 
-// Workgroup = (sequence, KV head, chunk of 128 codebook rows): sums the chunk's bins over the
-// context splits, then multiplies them with the chunk's value-codebook rows (Eq. optimized_v).
+// Workgroup = (sequence, KV head, chunk of codebook rows): sums the chunk's bins over the
+// context splits (fixed point -> fp32 with each split's unit), then multiplies them with the
+// chunk's value-codebook rows (Eq. optimized_v).
 template <int G, bool BF16>
 __global__ __launch_bounds__(kOutThreads) void k_out_part(OutArgs a)
 {
@@ -482,15 +510,17 @@ __global__ __launch_bounds__(kOutThreads) void k_out_part(OutArgs a)
     const int g = id % a.Hkv;
     const int b = id / a.Hkv;
     const int L = a.cu[b + 1] - a.cu[b];
-    const int nvs = (L + a.vsplit_len - 1) / a.vsplit_len;
+    const int nvs = min((L + a.vsplit_len - 1) / a.vsplit_len, a.nvsplit);
     const int MK = a.Mv * kK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     for (int x = tid; x < G * kOutRows; x += kOutThreads) {
         const int hh = x / kOutRows, r = x % kOutRows;
-        const float *src = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit * G + hh) * MK + chunk * kOutRows + r;
+        const unsigned *src = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit * G + hh) * MK + chunk * kOutRows + r;
+        const float *sc = a.vscale + ((size_t)b * a.Hq + (size_t)g * G + hh) * a.nvsplit;
         float s = 0.f;
-        for (int v = 0; v < nvs; ++v) s += src[(size_t)v * G * MK];
+#pragma unroll 8
+        for (int v = 0; v < nvs; ++v) s += (float)src[(size_t)v * G * MK] * sc[v];
         wsum[hh][r] = s;
     }
     __syncthreads();
@@ -527,14 +557,30 @@ __global__ __launch_bounds__(kOutThreads) void k_out_part(OutArgs a)
     }
 }
 
+// One workgroup per (sequence, head): softmax denominator from the split statistics, sum of
+// the chunk partials, division.
 __global__ __launch_bounds__(kD) void k_out_final(OutArgs a)
 {
+    __shared__ float red[2];
     const int bh = blockIdx.x;
     const int b = bh / a.Hq;
     const int L = a.cu[b + 1] - a.cu[b];
-    const int nvs = (L + a.vsplit_len - 1) / a.vsplit_len;
+    const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
+    const float2 *st = a.sstat + (size_t)bh * a.nsplit;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float mx = -INFINITY;
+    for (int s = threadIdx.x; s < ns; s += kD) mx = fmaxf(mx, st[s].x);
+    mx = wave_max(mx);
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(red[0], red[1]);
+    __syncthreads();
     float l = 0.f;
-    for (int v = 0; v < nvs; ++v) l += a.lsum[(size_t)bh * a.nvsplit + v];
+    for (int s = threadIdx.x; s < ns; s += kD) l += st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
+    l = wave_sum(l);
+    if (lane == 0) red[wave] = l;
+    __syncthreads();
+    l = red[0] + red[1];
     float s = 0.f;
     for (int c = 0; c < a.nchunk; ++c) s += a.partial[((size_t)bh * a.nchunk + c) * kD + threadIdx.x];
     a.out[(size_t)bh * kD + threadIdx.x] = s / l;
@@ -571,7 +617,8 @@ struct ScoreArgs {
     const void *key_cb;
     const int32_t *cu, *q_pos, *key_pos;
     const float2 *tbl_hi, *tbl_lo;
-    float *scores, *smax;
+    float *scores;
+    float2 *sstat;
     ScoreDims d;
 };
 
@@ -580,10 +627,10 @@ hipError_t launch_score_mg(const ScoreArgs &a, bool bf16, int grid, hipStream_t 
 {
     if (bf16)
         hipLaunchKernelGGL((k_score<M, G, true>), dim3(grid), dim3(kScoreThreads), 0, s, a.q, a.key_codes, a.key_cb, a.cu,
-                           a.q_pos, a.key_pos, a.tbl_hi, a.tbl_lo, a.scores, a.smax, a.d);
+                           a.q_pos, a.key_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
     else
         hipLaunchKernelGGL((k_score<M, G, false>), dim3(grid), dim3(kScoreThreads), 0, s, a.q, a.key_codes, a.key_cb, a.cu,
-                           a.q_pos, a.key_pos, a.tbl_hi, a.tbl_lo, a.scores, a.smax, a.d);
+                           a.q_pos, a.key_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
     return hipGetLastError();
 }
 template <int M>
@@ -600,7 +647,7 @@ hipError_t launch_score_m(const ScoreArgs &a, int G, bool bf16, int grid, hipStr
 template <int M, int G>
 hipError_t launch_bins_mg(const BinsArgs &a, int grid, hipStream_t s)
 {
-    const size_t lds = (size_t)G * M * kK * sizeof(float);
+    const size_t lds = (size_t)G * M * kK * sizeof(unsigned);
     static bool attr_set = false;  // per instantiation; raising the limit is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bins<M, G>),
@@ -638,7 +685,7 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
     a.q = q; a.key_codes = key_codes; a.key_cb = key_cb;
     a.cu = pos->cu_seqlens; a.q_pos = pos->q_pos; a.key_pos = pos->key_pos;
     a.tbl_hi = h->tbl_hi; a.tbl_lo = h->tbl_lo;
-    a.scores = w.scores; a.smax = w.smax;
+    a.scores = w.scores; a.sstat = w.sstat;
     a.d.Hq = c.n_q_heads; a.d.Hkv = c.n_kv_heads; a.d.nsplit = plan.score_splits; a.d.split_len = plan.score_split_len;
     a.d.n_hi = h->n_hi; a.d.q_bf16 = c.q_dtype == COMMVQ_BF16; a.d.scale = h->scale;
     const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
@@ -652,8 +699,8 @@ commvq_status run_bins(commvq_handle *h, const uint8_t *val_codes, const commvq_
 {
     const commvq_config &c = h->cfg;
     BinsArgs a;
-    a.val_codes = val_codes; a.cu = pos->cu_seqlens; a.scores = w.scores; a.smax = w.smax;
-    a.bins = w.bins; a.lsum = w.lsum;
+    a.val_codes = val_codes; a.cu = pos->cu_seqlens; a.scores = w.scores; a.sstat = w.sstat;
+    a.bins = w.bins; a.vscale = w.vscale;
     a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = plan.score_splits; a.split_len = plan.score_split_len;
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
     const int grid = pos->batch * c.n_kv_heads * plan.value_splits;
@@ -666,8 +713,10 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
 {
     const commvq_config &c = h->cfg;
     OutArgs a;
-    a.val_cb = val_cb; a.cu = pos->cu_seqlens; a.bins = w.bins; a.lsum = w.lsum; a.partial = w.partial; a.out = out;
-    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
+    a.val_cb = val_cb; a.cu = pos->cu_seqlens; a.bins = w.bins; a.vscale = w.vscale; a.sstat = w.sstat;
+    a.partial = w.partial; a.out = out;
+    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = plan.score_splits; a.split_len = plan.score_split_len;
+    a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
     a.nchunk = plan.out_chunks; a.Mv = c.m_val;
     const int grid = pos->batch * c.n_kv_heads * plan.out_chunks;
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
