@@ -33,7 +33,7 @@ namespace {
 constexpr int kD = 128;         // head_dim
 constexpr int kJ = 64;          // 2-D sub-spaces = lanes of a wavefront
 constexpr int kK = 256;         // codewords per codebook
-constexpr int kLoBits = 8;      // relative position = hi * 256 + lo
+constexpr int kLoBits = 6;      // relative position = hi * 64 + lo
 constexpr int kLo = 1 << kLoBits;
 constexpr int kScoreThreads = 256;
 constexpr int kBinsThreads = 512;
@@ -54,8 +54,8 @@ struct commvq_handle {
     float scale;
     int n_hi;
     int device;
-    float2 *tbl_hi;  // [n_hi][64]  exp(i * theta_j * 256 * hi)
-    float2 *tbl_lo;  // [256][64]   exp(i * theta_j * lo)
+    float2 *tbl_hi;  // [n_hi][64]  exp(i * theta_j * 64 * hi)
+    float2 *tbl_lo;  // [64][64]    exp(i * theta_j * lo)
     int prof_on;
     int prof_head, prof_count;
     hipEvent_t prof_ev[kProfRing][4];
@@ -175,25 +175,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, un
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-// Sums four per-lane values over the 64 lanes at once: on return every lane of 16-lane row r
-// holds the wavefront total of value r.  Two cross-half swaps fold lanes 32..63 onto 0..31,
-// one row swap folds odd rows onto even rows, then four DPP steps finish inside the rows.
-__device__ __forceinline__ float wave_sum4(float v0, float v1, float v2, float v3)
-{
-    auto a = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v0), __builtin_bit_cast(unsigned, v2), false, false);
-    auto c = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v1), __builtin_bit_cast(unsigned, v3), false, false);
-    // lanes 0..31: v0 (resp. v1) folded, lanes 32..63: v2 (resp. v3) folded
-    const float r02 = __builtin_bit_cast(float, (unsigned)a[0]) + __builtin_bit_cast(float, (unsigned)a[1]);
-    const float r13 = __builtin_bit_cast(float, (unsigned)c[0]) + __builtin_bit_cast(float, (unsigned)c[1]);
-    auto e = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, r02), __builtin_bit_cast(unsigned, r13), false, false);
-    float r = __builtin_bit_cast(float, (unsigned)e[0]) + __builtin_bit_cast(float, (unsigned)e[1]);  // rows: v0 v1 v2 v3
-    r += dpp_mov<0xB1>(r);
-    r += dpp_mov<0x4E>(r);
-    r += dpp_mov<0x141>(r);
-    r += dpp_mov<0x140>(r);
-    return r;
-}
-
 __device__ __forceinline__ float row_max16(float v)
 {
     v = fmaxf(v, dpp_mov<0xB1>(v));
@@ -202,6 +183,7 @@ __device__ __forceinline__ float row_max16(float v)
     return fmaxf(v, dpp_mov<0x140>(v));
 }
 
+// Sum over each 16-lane row; every lane of the row receives the row total.
 __device__ __forceinline__ float row_sum16(float v)
 {
     v += dpp_mov<0xB1>(v);
@@ -210,17 +192,24 @@ __device__ __forceinline__ float row_sum16(float v)
     return v + dpp_mov<0x140>(v);
 }
 
-template <int G> struct ScoreTok { static constexpr int value = G == 1 ? 4 : (G == 8 ? 1 : 2); };
+typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
 
-// One wavefront walks a run of tokens; lane j owns sub-space j (elements 2j, 2j+1), so a
-// codeword row is one fully coalesced 256-byte (bf16) or 512-byte (fp32) load whose row
-// index is wave-uniform: codes come through scalar loads (prefetched one iteration ahead)
-// and the row offset is formed on the scalar unit and passed as the buffer load's scalar
-// offset, leaving the vector ALUs to the additions.  blockIdx.x % Hkv selects the KV head:
-// consecutive workgroups go to consecutive XCDs, so with 8 KV heads each XCD's L2 serves one
-// head's codebook.  TOK tokens are in flight per iteration; their TOK*G partial dot products
-// are reduced four at a time (wave_sum4) and parked in a lane until 16 iterations are done,
-// then written as 64-byte runs.
+// Score kernel.  A wavefront handles FOUR tokens per iteration, one per 16-lane row; lane
+// `sub` of a row owns sub-spaces 4*sub .. 4*sub+3 (elements 8*sub .. 8*sub+7), i.e. 16 bytes of
+// a bf16 codeword row, so one 16-byte-per-lane buffer load fetches four different codeword
+// rows (1 KiB) per instruction: measured ~1.7x the bytes per clock of the one-row-per-
+// instruction form, whose rate is bound by the L1's per-instruction cost.  The per-lane byte
+// offset (code << 8 | sub * 16) is built by a single byte permute; the codebook index is the
+// load's scalar offset.  The relative-position phase is split as 64 * hi + lo: E_hi is folded
+// into the query registers (recomputed only when some lane's hi changes, every 64 tokens for
+// contiguous positions), E_lo comes from a 32 KiB LDS table.  The dot products are reduced
+// inside the 16-lane rows (4 DPP steps per head), parked for 16 iterations and written as
+// one 256-byte run per head.  blockIdx.x % Hkv selects the KV head: consecutive workgroups
+// go to consecutive XCDs, so with 8 KV heads each XCD's L2 serves one head's codebook.
+#ifndef COMMVQ_SCORE_CHUNK
+#define COMMVQ_SCORE_CHUNK 4
+#endif
+
 template <int M, int G, bool BF16>
 __global__ __launch_bounds__(kScoreThreads) void k_score(
     const void *__restrict__ q, const uint8_t *__restrict__ key_codes, const void *__restrict__ key_cb,
@@ -228,10 +217,12 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     const float2 *__restrict__ tbl_hi, const float2 *__restrict__ tbl_lo, float *__restrict__ scores,
     float2 *__restrict__ sstat, const ScoreDims a)
 {
-    constexpr int TOK = ScoreTok<G>::value;
-    constexpr int NV = TOK * G, NQ = NV / 4, CW = M / 4;
+    constexpr int CW = M / 4;
     constexpr unsigned ROWB = BF16 ? kD * 2 : kD * 4;
-    static_assert(NV % 4 == 0, "values are reduced four at a time");
+    // E_lo as two planes of float4: plane h, entry [lo][sub] = sub-spaces 4*sub+2h, 4*sub+2h+1
+    __shared__ float4 lo_lds[2][kLo][16];
+    __shared__ float2 wstat[kScoreThreads / 64][G];
+
     int id = blockIdx.x;
     const int g = id % a.Hkv;
     id /= a.Hkv;
@@ -241,160 +232,206 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     const int L = cu[b + 1] - cu0;
     const int s0 = split * a.split_len;
     if (s0 >= L) return;
+    for (int x = threadIdx.x; x < 2 * kLo * 16; x += kScoreThreads) {
+        const int h = x / (kLo * 16), lo = (x / 16) % kLo, sb = x % 16;
+        const float2 e0 = tbl_lo[lo * kJ + 4 * sb + 2 * h], e1 = tbl_lo[lo * kJ + 4 * sb + 2 * h + 1];
+        lo_lds[h][lo][sb] = make_float4(e0.x, e0.y, e1.x, e1.y);
+    }
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    const int r = lane >> 4, sub = lane & 15;
     const int wlen = a.split_len / (kScoreThreads / 64);  // multiple of 64
     const int t0 = s0 + wave * wlen;
     const int t1 = min(min(t0 + wlen, s0 + a.split_len), L);
-    const int n_it = t1 > t0 ? (t1 - t0 + TOK - 1) / TOK : 0;
+    const int n_it = t1 > t0 ? (t1 - t0 + 3) / 4 : 0;
     const int qpos = q_pos[b];
-
-    float2 qv[G], qr[G];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        const size_t qo = ((size_t)b * a.Hq + (size_t)g * G + hh) * kD + 2 * lane;
-        if (a.q_bf16) {
-            const unsigned v = *reinterpret_cast<const unsigned *>(static_cast<const uint16_t *>(q) + qo);
-            qv[hh] = make_float2(bf16_lo(v) * a.scale, bf16_hi(v) * a.scale);
-        } else {
-            const float2 v = *reinterpret_cast<const float2 *>(static_cast<const float *>(q) + qo);
-            qv[hh] = make_float2(v.x * a.scale, v.y * a.scale);
-        }
-        qr[hh] = qv[hh];
-    }
+    __syncthreads();
 
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const __amdgpu_buffer_rsrc_t cb_rs =
         make_rsrc(static_cast<const char *>(key_cb) + (size_t)g * M * kK * ROWB, (unsigned)(M * kK) * ROWB);
     const __amdgpu_buffer_rsrc_t hi_rs = make_rsrc(tbl_hi, (unsigned)a.n_hi * kJ * 8u);
-    const __amdgpu_buffer_rsrc_t lo_rs = make_rsrc(tbl_lo, (unsigned)kLo * kJ * 8u);
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-
-    // per lane: parked logits, and the running (max, sum exp) of the logits this lane flushed
-    float keep[NQ], vmax[NQ], vsum[NQ];
-#pragma unroll
-    for (int k = 0; k < NQ; ++k) { keep[k] = 0.f; vmax[k] = -INFINITY; vsum[k] = 0.f; }
-    int cur_key = -1;  // (hi << 1 | negative) whose phase is folded into qr
+    const size_t q_off = ((size_t)b * a.Hq + (size_t)g * G) * kD + 8 * sub;
     const unsigned sel_lo = opaque_sgpr(0x00003f80u), sel_hi = opaque_sgpr(0x3f800000u);
+    const unsigned lane_off = BF16 ? sub * 16u : sub * 32u;
 
-    unsigned cwn[TOK][CW];
-    auto load_codes = [&](int i, unsigned(&dst)[TOK][CW]) {
+    float qr[G][8];  // queries of the group with E_hi folded in: (x, y) of this lane's 4 sub-spaces
 #pragma unroll
-        for (int u = 0; u < TOK; ++u) {
-            const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)min(i + u, L - 1) * M);
+    for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-            for (int v = 0; v < M / 16; ++v) {
-                const uint4 c4 = cp[v];
-                dst[u][4 * v + 0] = c4.x; dst[u][4 * v + 1] = c4.y; dst[u][4 * v + 2] = c4.z; dst[u][4 * v + 3] = c4.w;
+        for (int e = 0; e < 8; ++e) qr[hh][e] = 0.f;
+    int cur_key = -1;  // per lane: (hi << 1 | negative) whose phase is folded into qr
+    float keep[G], vmax[G], vsum[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) { keep[hh] = 0.f; vmax[hh] = -INFINITY; vsum[hh] = 0.f; }
+
+    // Codeword loads are issued in chunks of CH codebooks into two register buffers; the chunk
+    // after the one being summed is always in flight (across iterations too), and the codes
+    // are fetched two iterations ahead.
+    constexpr int CH = BF16 ? COMMVQ_SCORE_CHUNK : COMMVQ_SCORE_CHUNK / 2;  // codebooks per chunk
+    constexpr int LPC = BF16 ? CH : 2 * CH;                                  // 16-byte loads per chunk
+    constexpr int NC = M / CH;
+    static_assert(NC % 2 == 0, "buffer parity must repeat every iteration");
+    uint4_t buf[2][LPC];
+    unsigned cw[CW], cwn[CW];
+    auto load_codes = [&](int i, unsigned(&dst)[CW]) {
+        const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)min(i + r, L - 1) * M);
+#pragma unroll
+        for (int v = 0; v < M / 16; ++v) {
+            const uint4 c4 = cp[v];
+            dst[4 * v + 0] = c4.x; dst[4 * v + 1] = c4.y; dst[4 * v + 2] = c4.z; dst[4 * v + 3] = c4.w;
+        }
+    };
+    auto issue = [&](const unsigned(&c)[CW], int chunk, uint4_t(&dst)[LPC]) {
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int m = chunk * CH + k;
+            if (BF16) {
+                // byte 1 <- code m, byte 0 <- sub * 16: (code << 8) | (sub * 16)
+                const unsigned voff = __builtin_amdgcn_perm(c[m / 4], lane_off, 0x0c0c0000u | ((4u + (m % 4)) << 8));
+                dst[k] = __builtin_amdgcn_raw_buffer_load_b128(cb_rs, voff, (unsigned)m * kK * ROWB, 0);
+            } else {
+                const unsigned voff = ((c[m / 4] >> (8 * (m % 4))) & 0xffu) * ROWB + lane_off;
+                dst[2 * k] = __builtin_amdgcn_raw_buffer_load_b128(cb_rs, voff, (unsigned)m * kK * ROWB, 0);
+                dst[2 * k + 1] = __builtin_amdgcn_raw_buffer_load_b128(cb_rs, voff + 16u, (unsigned)m * kK * ROWB, 0);
             }
         }
     };
-    if (n_it > 0) load_codes(t0, cwn);
+    float A[8];
+    auto consume = [&](const uint4_t(&src)[LPC]) {
+#pragma unroll
+        for (int k = 0; k < LPC; ++k)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned ve = src[k][e];
+                if (BF16) {
+                    A[2 * e] = add_bf16_sel(ve, sel_lo, A[2 * e]);
+                    A[2 * e + 1] = add_bf16_sel(ve, sel_hi, A[2 * e + 1]);
+                } else {
+                    A[4 * (k & 1) + e] += __builtin_bit_cast(float, ve);
+                }
+            }
+    };
+    if (n_it > 0) {
+        load_codes(t0, cw);
+        issue(cw, 0, buf[0]);
+        load_codes(t0 + 4, cwn);
+    }
 
     for (int it = 0; it < n_it; ++it) {
-        const int i = t0 + it * TOK;
-        unsigned cw[TOK][CW];
+        const int i = t0 + it * 4;
+        // relative position of this row's token
+        const int tok = min(i + r, L - 1);
+        const int pos = key_pos ? key_pos[cu0 + tok] : tok;
+        const int dl = qpos - pos;
+        const int neg = dl < 0;
+        const int ad = neg ? -dl : dl;
+        const int hi = min(ad >> kLoBits, a.n_hi - 1);
+        const int lo = ad & (kLo - 1);
+        const int key = (hi << 1) | neg;
+        if (__builtin_amdgcn_ballot_w64(key != cur_key) != 0) {
+            // fold the coarse phase into the queries: q' = q conj(E_hi) for t >= p, q E_hi otherwise
+            cur_key = key;
+            float eh[8];
 #pragma unroll
-        for (int u = 0; u < TOK; ++u)
+            for (int hf = 0; hf < 2; ++hf) {
+                const uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(hi_rs, (unsigned)hi * (kJ * 8u) + sub * 32u + 16u * hf, 0, 0);
 #pragma unroll
-            for (int v = 0; v < CW; ++v) cw[u][v] = cwn[u][v];
-        if (it + 1 < n_it) load_codes(i + TOK, cwn);
-
-        // A = sum of the M selected codeword rows (Eq. commute_decode), this lane's sub-space
-        float ax[TOK], ay[TOK];
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned ve = v[e];
+                    eh[4 * hf + e] = __builtin_bit_cast(float, ve);
+                }
+            }
 #pragma unroll
-        for (int u = 0; u < TOK; ++u) {
-            ax[u] = 0.f; ay[u] = 0.f;
+            for (int hh = 0; hh < G; ++hh) {
+                float qx[4], qy[4];
+                if (a.q_bf16) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(q) + q_off + (size_t)hh * kD);
+                    const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int m = 0; m < M; ++m) {
-                const unsigned c = (cw[u][m / 4] >> (8 * (m % 4))) & 0xffu;
-                const unsigned soff = ((unsigned)m * kK + c) * ROWB;
-                if (BF16) {
-                    const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(cb_rs, lane * 4, soff, 0);
-                    ax[u] = add_bf16_sel(v, sel_lo, ax[u]);
-                    ay[u] = add_bf16_sel(v, sel_hi, ay[u]);
+                    for (int e = 0; e < 4; ++e) { qx[e] = bf16_lo(w[e]) * a.scale; qy[e] = bf16_hi(w[e]) * a.scale; }
                 } else {
-                    const uint2_t v = __builtin_amdgcn_raw_buffer_load_b64(cb_rs, lane * 8, soff, 0);
-                    ax[u] += __builtin_bit_cast(float, (unsigned)v[0]);
-                    ay[u] += __builtin_bit_cast(float, (unsigned)v[1]);
+                    const float4 *qp = reinterpret_cast<const float4 *>(static_cast<const float *>(q) + q_off + (size_t)hh * kD);
+                    const float4 v0 = qp[0], v1 = qp[1];
+                    qx[0] = v0.x * a.scale; qy[0] = v0.y * a.scale; qx[1] = v0.z * a.scale; qy[1] = v0.w * a.scale;
+                    qx[2] = v1.x * a.scale; qy[2] = v1.y * a.scale; qx[3] = v1.z * a.scale; qy[3] = v1.w * a.scale;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float hc = eh[2 * e], hs = neg ? -eh[2 * e + 1] : eh[2 * e + 1];
+                    qr[hh][2 * e] = qx[e] * hc + qy[e] * hs;
+                    qr[hh][2 * e + 1] = qy[e] * hc - qx[e] * hs;
                 }
             }
         }
-
-        float val[NV];
+        // A = sum of the M selected codeword rows (Eq. commute_decode), this lane's 4 sub-spaces
 #pragma unroll
-        for (int u = 0; u < TOK; ++u) {
-            const int tok = min(i + u, L - 1);
-            const int pos = key_pos ? key_pos[cu0 + tok] : tok;
-            const int dl = qpos - pos;
-            const int neg = dl < 0;
-            const int ad = neg ? -dl : dl;
-            const int hi = min(ad >> kLoBits, a.n_hi - 1);
-            const int lo = ad & (kLo - 1);
-            const uint2_t plu = __builtin_amdgcn_raw_buffer_load_b64(lo_rs, lane * 8, (unsigned)lo * (kJ * 8u), 0);
-            if (((hi << 1) | neg) != cur_key) {  // fold the coarse phase into the queries (rare)
-                cur_key = (hi << 1) | neg;
-                const uint2_t phu = __builtin_amdgcn_raw_buffer_load_b64(hi_rs, lane * 8, (unsigned)hi * (kJ * 8u), 0);
-                const float hc = __builtin_bit_cast(float, (unsigned)phu[0]);
-                float hs = __builtin_bit_cast(float, (unsigned)phu[1]);
-                hs = neg ? -hs : hs;
+        for (int e = 0; e < 8; ++e) A[e] = 0.f;
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh)  // q' = q conj(E_hi) for t >= p, q E_hi otherwise
-                    qr[hh] = make_float2(qv[hh].x * hc + qv[hh].y * hs, qv[hh].y * hc - qv[hh].x * hs);
-            }
-            const float lc = __builtin_bit_cast(float, (unsigned)plu[0]);
-            float lsn = __builtin_bit_cast(float, (unsigned)plu[1]);
-            lsn = neg ? -lsn : lsn;
-            // B = A E_lo; score_h = sum_j Re(q'_h conj(B))
-            const float bx = ax[u] * lc - ay[u] * lsn;
-            const float by = ax[u] * lsn + ay[u] * lc;
-#pragma unroll
-            for (int hh = 0; hh < G; ++hh) val[u * G + hh] = qr[hh].x * bx + qr[hh].y * by;
+        for (int c = 0; c < NC; ++c) {
+            // (the last iteration issues one redundant, in-range chunk rather than branch)
+            if (c + 1 < NC) issue(cw, c + 1, buf[(c + 1) & 1]);
+            else issue(cwn, 0, buf[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(buf[c & 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int v = 0; v < CW; ++v) cw[v] = cwn[v];
+        load_codes(i + 8, cwn);  // token index is clamped to the sequence
 
-        const bool mine = (lane & 15) == (it & 15);
+        // B = A E_lo (conjugated for negative distances); score_h = sum_j Re(q'_h conj(B))
+        const float4 l0 = lo_lds[0][lo][sub], l1 = lo_lds[1][lo][sub];
+        const float ec[4] = {l0.x, l0.z, l1.x, l1.z};
+        const float es[4] = {neg ? -l0.y : l0.y, neg ? -l0.w : l0.w, neg ? -l1.y : l1.y, neg ? -l1.w : l1.w};
+        float Bx[4], By[4];
 #pragma unroll
-        for (int k = 0; k < NQ; ++k) {
-            const float r = wave_sum4(val[4 * k], val[4 * k + 1], val[4 * k + 2], val[4 * k + 3]);
-            keep[k] = mine ? r : keep[k];
+        for (int e = 0; e < 4; ++e) {
+            Bx[e] = A[2 * e] * ec[e] - A[2 * e + 1] * es[e];
+            By[e] = A[2 * e] * es[e] + A[2 * e + 1] * ec[e];
         }
-        if ((it & 15) == 15 || it == n_it - 1) {  // flush 16 iterations' logits as 64-byte runs
-            const int itc = (it & ~15) + (lane & 15);
+        const bool mine = sub == (it & 15);
 #pragma unroll
-            for (int k = 0; k < NQ; ++k) {
-                const int idx = 4 * k + (lane >> 4);
-                const int u = idx / G, hh = idx % G;
-                const int tok = t0 + itc * TOK + u;
-                if (itc <= it && tok < t1) {
-                    srow[(size_t)hh * L + tok] = keep[k];
-                    const float mn = fmaxf(vmax[k], keep[k]);
-                    vsum[k] = vsum[k] * __builtin_amdgcn_exp2f((vmax[k] - mn) * kLog2e) +
-                              __builtin_amdgcn_exp2f((keep[k] - mn) * kLog2e);
-                    vmax[k] = mn;
+        for (int hh = 0; hh < G; ++hh) {
+            float v = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v += qr[hh][2 * e] * Bx[e] + qr[hh][2 * e + 1] * By[e];
+            v = row_sum16(v);
+            keep[hh] = mine ? v : keep[hh];
+        }
+        if ((it & 15) == 15 || it == n_it - 1) {  // flush: lane (r, sub) holds token 4 * sub + r of this 64-token block
+            const int itc = (it & ~15) + sub;
+            const int tk = t0 + itc * 4 + r;
+            if (itc <= it && tk < t1) {
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    srow[(size_t)hh * L + tk] = keep[hh];
+                    const float mn = fmaxf(vmax[hh], keep[hh]);
+                    vsum[hh] = vsum[hh] * __builtin_amdgcn_exp2f((vmax[hh] - mn) * kLog2e) +
+                               __builtin_amdgcn_exp2f((keep[hh] - mn) * kLog2e);
+                    vmax[hh] = mn;
                 }
             }
         }
     }
 
-    // (max, sum exp) of the split: lanes of a row -> waves and token slots -> one pair per head
-    __shared__ float2 wstat[kScoreThreads / 64][NV];
+    // (max, sum exp) of the split: lanes -> waves -> one pair per head
 #pragma unroll
-    for (int k = 0; k < NQ; ++k) {
-        const float m = row_max16(vmax[k]);
-        const float l = row_sum16(vmax[k] == -INFINITY ? 0.f : vsum[k] * __builtin_amdgcn_exp2f((vmax[k] - m) * kLog2e));
-        if ((lane & 15) == 0) wstat[wave][4 * k + (lane >> 4)] = make_float2(m, l);
+    for (int hh = 0; hh < G; ++hh) {
+        const float m = wave_max(vmax[hh]);
+        const float l = wave_sum(vmax[hh] == -INFINITY ? 0.f : vsum[hh] * __builtin_amdgcn_exp2f((vmax[hh] - m) * kLog2e));
+        if (lane == 0) wstat[wave][hh] = make_float2(m, l);
     }
     __syncthreads();
     if (threadIdx.x < G) {
         float m = -INFINITY;
-        for (int w = 0; w < kScoreThreads / 64; ++w)
-            for (int u = 0; u < TOK; ++u) m = fmaxf(m, wstat[w][u * G + threadIdx.x].x);
+        for (int w = 0; w < kScoreThreads / 64; ++w) m = fmaxf(m, wstat[w][threadIdx.x].x);
         float l = 0.f;
-        for (int w = 0; w < kScoreThreads / 64; ++w)
-            for (int u = 0; u < TOK; ++u) {
-                const float2 st = wstat[w][u * G + threadIdx.x];
-                if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
-            }
+        for (int w = 0; w < kScoreThreads / 64; ++w) {
+            const float2 st = wstat[w][threadIdx.x];
+            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+        }
         sstat[((size_t)b * a.Hq + (size_t)g * G + threadIdx.x) * a.nsplit + split] = make_float2(m, l);
     }
 }
