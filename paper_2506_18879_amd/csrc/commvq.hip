@@ -498,6 +498,8 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 
     const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    constexpr int CW = M / 4;
+    const unsigned rot = lane & (M - 1);
     for (int i = v0 + tid; i < v1; i += kBinsThreads) {
         unsigned cw[M / 4];
         const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)i * M);
@@ -510,11 +512,27 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
             p[hh] = (unsigned)(__builtin_amdgcn_exp2f(srow[(size_t)hh * L + i] * kLog2e + eoff[hh]) + 0.5f);
+        // Lane l walks the codebooks in the order (l + k) % M, so that at every step the 64
+        // lanes spread over all M codebooks: skewed code usage (one codeword taking ~20 % of the
+        // tokens) would otherwise put a dozen lanes on the same LDS address in one instruction.
+        // The code vector is rotated by `rot` bytes once per token (dword selects + alignbyte).
 #pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
+        for (int st = 1; st < CW; st <<= 1) {
+            unsigned t[CW];
 #pragma unroll
-            for (int hh = 0; hh < G; ++hh) atomicAdd(&bins[(hh * M + m) * kK + c], p[hh]);
+            for (int j = 0; j < CW; ++j) t[j] = ((rot >> 2) & st) ? cw[(j + st) % CW] : cw[j];
+#pragma unroll
+            for (int j = 0; j < CW; ++j) cw[j] = t[j];
+        }
+        unsigned rv[CW];
+#pragma unroll
+        for (int j = 0; j < CW; ++j) rv[j] = __builtin_amdgcn_alignbyte(cw[(j + 1) % CW], cw[j], rot & 3u);
+#pragma unroll
+        for (int k = 0; k < M; ++k) {
+            const unsigned c = (rv[k / 4] >> (8 * (k % 4))) & 0xffu;
+            const unsigned idx = ((((unsigned)k << 8) + (rot << 8)) & ((unsigned)(M - 1) << 8)) | c;  // m * K + c
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) atomicAdd(&bins[hh * M * kK + idx], p[hh]);
         }
     }
     __syncthreads();
