@@ -29,6 +29,7 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = 8B-shaped layer, 128K context, 1-bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-resident numbers)")
+    ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
     return ap.parse_args()
 
 
@@ -68,7 +69,7 @@ def main():
     for i in range(args.warmup):
         op(copies[i % n_copies])
     torch.cuda.synchronize()
-    B.commvq_profile_enable(op.handle, True)
+    B.commvq_profile_enable(op.handle, not args.no_stage_events)
     t0 = time.perf_counter()
     for i in range(args.steps):
         op(copies[i % n_copies])

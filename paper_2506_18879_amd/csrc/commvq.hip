@@ -9,8 +9,8 @@
 //               bins are 32-bit fixed point (integer LDS atomics run ~20x faster than fp32 ones
 //               on gfx950); the scale of each split is chosen from its known exp-sum so that
 //               no bin can overflow and the worst-case error is (tokens per split) * 2^-32.
-//   k_out_part  (bins C_V): split reduction + bins x value-codebook product, per row chunk.
-//   k_out_final sum of the chunks, division by the softmax denominator.
+//   k_out       (bins C_V): split reduction + bins x value-codebook product, per chunk of rows.
+//   k_out_final sum of the per-chunk products, division by the softmax denominator.
 //
 // RoPE algebra used by k_score (Sec. 3.2, Eq. rope_ri).  Writing a 2-D sub-vector (x, y) as
 // z = x + iy, the paper's row-vector product (x, y) R_m^j is z * exp(-i m theta_j).  The dot
@@ -38,7 +38,7 @@ constexpr int kLo = 1 << kLoBits;
 constexpr int kScoreThreads = 256;
 constexpr int kBinsThreads = 512;
 constexpr int kOutThreads = 256;
-constexpr int kOutRows = 64;    // codebook rows per k_out_part workgroup
+constexpr int kOutRows = 64;    // codebook rows per k_out workgroup
 constexpr int kProfRing = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -68,6 +68,7 @@ struct Workspace {
     float *scores;    // [T * Hq] scaled logits
     float2 *sstat;    // [B * Hq * score_splits] (max, sum of exp(logit - max)) of each score split
     float *vscale;    // [B * Hq * value_splits] 2^-S: value of one fixed-point unit of that split's bins
+    float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over that value split
     unsigned *bins;   // [B * Hkv * value_splits][G * Mv * K] fixed-point bins
     float *partial;   // [B * Hq * out_chunks][d]
     size_t bytes;
@@ -80,7 +81,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, commvq_plan *p)
     while (len > 256 && (long)units * ((max_seqlen + len - 1) / len) < 2048) len /= 2;
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
-    int nv = 512 / units;
+    int nv = 256 / units;  // about one value workgroup per compute unit
     if (nv < 1) nv = 1;
     int vlen = (max_seqlen + nv - 1) / nv;
     vlen = (vlen + 1023) / 1024 * 1024;  // whole score splits, so their statistics can be summed
@@ -102,6 +103,7 @@ void carve(const commvq_handle *h, const commvq_plan &p, int B, int64_t T, void 
     w->scores = take((size_t)T * c.n_q_heads);
     w->sstat = reinterpret_cast<float2 *>(take((size_t)B * c.n_q_heads * p.score_splits * 2));
     w->vscale = take((size_t)B * c.n_q_heads * p.value_splits);
+    w->lsum = take((size_t)B * c.n_q_heads * p.value_splits);
     w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * p.value_splits * h->G * c.m_val * kK));
     w->partial = take((size_t)B * c.n_q_heads * p.out_chunks * kD);
     w->bytes = off;
@@ -443,7 +445,7 @@ struct BinsArgs {
     const float *scores;
     const float2 *sstat;
     unsigned *bins;
-    float *vscale;
+    float *vscale, *lsum;
     int Hq, Hkv, nsplit, split_len;  // score-stage split geometry (for the statistics)
     int nvsplit, vsplit_len;
 };
@@ -489,6 +491,7 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         if (lane == 0) {
             eoff_s[wave] = (float)S - mx * kLog2e;
             a.vscale[((size_t)b * a.Hq + (size_t)g * G + wave) * a.nvsplit + vs] = ldexpf(1.f, -S);
+            a.lsum[((size_t)b * a.Hq + (size_t)g * G + wave) * a.nvsplit + vs] = l;
         }
     }
     __syncthreads();
@@ -540,22 +543,21 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     for (int x = tid; x < NB; x += kBinsThreads) dst[x] = bins[x];
 }
 
-// ------------------------------------------------------------------ k_out_part / k_out_final
+// ------------------------------------------------------------------ k_out
 struct OutArgs {
     const void *val_cb;
     const int32_t *cu;
     const unsigned *bins;
-    const float *vscale;
-    const float2 *sstat;
+    const float *vscale, *lsum;
     float *partial, *out;
-    int Hq, Hkv, nsplit, split_len, nvsplit, vsplit_len, nchunk, Mv;
+    int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
 };
 
 // Workgroup = (sequence, KV head, chunk of codebook rows): sums the chunk's bins over the
 // context splits (fixed point -> fp32 with each split's unit), then multiplies them with the
 // chunk's value-codebook rows (Eq. optimized_v).
 template <int G, bool BF16>
-__global__ __launch_bounds__(kOutThreads) void k_out_part(OutArgs a)
+__global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
 {
     __shared__ float wsum[G][kOutRows];
     __shared__ float red[kOutThreads / 64][G][kD];
@@ -612,33 +614,29 @@ __global__ __launch_bounds__(kOutThreads) void k_out_part(OutArgs a)
     }
 }
 
-// One workgroup per (sequence, head): softmax denominator from the split statistics, sum of
-// the chunk partials, division.
+// One workgroup per (sequence, head): sum of the chunk partials in a fixed order, division
+// by the softmax denominator (sum of the value splits' exp-sums).  Measured: finishing inside
+// k_out by a last-arriving workgroup costs more than this launch, because the device-scope
+// release/acquire it needs writes back and invalidates L2.
 __global__ __launch_bounds__(kD) void k_out_final(OutArgs a)
 {
-    __shared__ float red[2];
+    __shared__ float l_s;
     const int bh = blockIdx.x;
     const int b = bh / a.Hq;
-    const int L = a.cu[b + 1] - a.cu[b];
-    const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
-    const float2 *st = a.sstat + (size_t)bh * a.nsplit;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float mx = -INFINITY;
-    for (int s = threadIdx.x; s < ns; s += kD) mx = fmaxf(mx, st[s].x);
-    mx = wave_max(mx);
-    if (lane == 0) red[wave] = mx;
-    __syncthreads();
-    mx = fmaxf(red[0], red[1]);
-    __syncthreads();
-    float l = 0.f;
-    for (int s = threadIdx.x; s < ns; s += kD) l += st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
-    l = wave_sum(l);
-    if (lane == 0) red[wave] = l;
-    __syncthreads();
-    l = red[0] + red[1];
+    const float *pp = a.partial + (size_t)bh * a.nchunk * kD + threadIdx.x;
     float s = 0.f;
-    for (int c = 0; c < a.nchunk; ++c) s += a.partial[((size_t)bh * a.nchunk + c) * kD + threadIdx.x];
-    a.out[(size_t)bh * kD + threadIdx.x] = s / l;
+#pragma unroll 8
+    for (int c = 0; c < a.nchunk; ++c) s += pp[(size_t)c * kD];
+    if (threadIdx.x < 64) {
+        const int L = a.cu[b + 1] - a.cu[b];
+        const int nvs = min((L + a.vsplit_len - 1) / a.vsplit_len, a.nvsplit);
+        float l = 0.f;
+        for (int v = threadIdx.x; v < nvs; v += 64) l += a.lsum[(size_t)bh * a.nvsplit + v];
+        l = wave_sum(l);
+        if (threadIdx.x == 0) l_s = l;
+    }
+    __syncthreads();
+    a.out[(size_t)bh * kD + threadIdx.x] = s / l_s;
 }
 
 // ------------------------------------------------------------------ host side
@@ -727,8 +725,8 @@ hipError_t launch_bins_m(const BinsArgs &a, int G, int grid, hipStream_t s)
 template <int G>
 hipError_t launch_out_g(const OutArgs &a, bool bf16, int grid, hipStream_t s)
 {
-    if (bf16) hipLaunchKernelGGL((k_out_part<G, true>), dim3(grid), dim3(kOutThreads), 0, s, a);
-    else hipLaunchKernelGGL((k_out_part<G, false>), dim3(grid), dim3(kOutThreads), 0, s, a);
+    if (bf16) hipLaunchKernelGGL((k_out<G, true>), dim3(grid), dim3(kOutThreads), 0, s, a);
+    else hipLaunchKernelGGL((k_out<G, false>), dim3(grid), dim3(kOutThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -755,7 +753,7 @@ commvq_status run_bins(commvq_handle *h, const uint8_t *val_codes, const commvq_
     const commvq_config &c = h->cfg;
     BinsArgs a;
     a.val_codes = val_codes; a.cu = pos->cu_seqlens; a.scores = w.scores; a.sstat = w.sstat;
-    a.bins = w.bins; a.vscale = w.vscale;
+    a.bins = w.bins; a.vscale = w.vscale; a.lsum = w.lsum;
     a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = plan.score_splits; a.split_len = plan.score_split_len;
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
     const int grid = pos->batch * c.n_kv_heads * plan.value_splits;
@@ -768,9 +766,9 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
 {
     const commvq_config &c = h->cfg;
     OutArgs a;
-    a.val_cb = val_cb; a.cu = pos->cu_seqlens; a.bins = w.bins; a.vscale = w.vscale; a.sstat = w.sstat;
+    a.val_cb = val_cb; a.cu = pos->cu_seqlens; a.bins = w.bins; a.vscale = w.vscale; a.lsum = w.lsum;
     a.partial = w.partial; a.out = out;
-    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = plan.score_splits; a.split_len = plan.score_split_len;
+    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
     a.nchunk = plan.out_chunks; a.Mv = c.m_val;
     const int grid = pos->batch * c.n_kv_heads * plan.out_chunks;
