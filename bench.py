@@ -18,6 +18,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 vector peak (packed FMA counted as 2 flop)
+L1_PEAK_TBS = 39.3          # 256 CUs x 64 B/clk vector L1 data path x 2.4 GHz
+L1_MEASURED_TBS = 30.3      # four random 256-byte rows per 16-byte-per-lane load (profiles/microbenchmarks__*.md)
 COLD_FOOTPRINT = 640 << 20  # rotate through at least this many bytes of codes + codebooks
 
 
@@ -96,9 +98,14 @@ def main():
         except Exception:
             traffic = None
     key_stream_gbs = T * w.Hkv * w.Mk / score_s / 1e9 if score_s > 0 else 0.0
+    # the resource the kernel actually saturates: codeword rows gathered through the L1 data path
+    gather_tbs = units * w.Mk * w.d * esz / score_s / 1e12 if score_s > 0 else 0.0
     roofline = {"kernel": "k_score", "bound": "alu", "achieved": round(achieved_tflops, 3), "peak": FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved_tflops / FP32_PEAK_TFLOPS, 4), "traffic": traffic,
                 "kernel_ms": round(stage_ms[0], 5), "launches_averaged": n_prof,
+                "l1_gather_view": {"codeword_bytes_TBs": round(gather_tbs, 2), "peak_TBs": L1_PEAK_TBS,
+                                   "frac": round(gather_tbs / L1_PEAK_TBS, 4),
+                                   "measured_ceiling_TBs": L1_MEASURED_TBS},
                 "hbm_view": {"key_code_stream_GBs": round(key_stream_gbs, 1),
                              "frac_of_hbm_peak": round(key_stream_gbs / HBM_PEAK_GBS, 4)}}
 

@@ -11,7 +11,7 @@
  * Eq. optimized_v: softmax weights are accumulated into per-codeword bins
  * (Softmax(A) S_V) and the bins are multiplied by the value codebook once.
  * The result equals Eq. v1_formula (decode, RoPE, dense softmax attention) up
- * to fp32 rounding.
+ * to fp32 rounding.  Results are bit-reproducible from call to call.
  *
  * Conventions
  *   - Pointers are DEVICE pointers unless a comment says "host".  The caller
@@ -130,7 +130,9 @@ commvq_status commvq_decode_attn(commvq_handle *handle, const void *q, const uin
  *                        per-split maxima.  If scores_out is not NULL it receives a copy of the
  *                        logits, fp32 [T*Hq], (b, h, i) at cu_seqlens[b]*Hq + h*L_b + i.
  *   commvq_stage_bins    Softmax(A) S_V of Eq. optimized_v, unnormalised: exp(score - max)
- *                        accumulated per (head, value codebook, codeword), plus the exp sums.
+ *                        accumulated per (head, value codebook, codeword) in 32-bit fixed point
+ *                        (unit chosen per context split from its exp-sum; error below
+ *                        tokens-per-split * 2^-32 of the split's weight), plus the exp sums.
  *   commvq_stage_output  (bins C_V) / sum of Eq. optimized_v -> out.
  */
 commvq_status commvq_stage_scores(commvq_handle *handle, const void *q, const uint8_t *key_codes,

@@ -35,7 +35,13 @@ constexpr int kJ = 64;          // 2-D sub-spaces = lanes of a wavefront
 constexpr int kK = 256;         // codewords per codebook
 constexpr int kLoBits = 6;      // relative position = hi * 64 + lo
 constexpr int kLo = 1 << kLoBits;
-constexpr int kScoreThreads = 256;
+#ifndef COMMVQ_SCORE_MIN_WGS
+#define COMMVQ_SCORE_MIN_WGS 2048
+#endif
+#ifndef COMMVQ_SCORE_THREADS
+#define COMMVQ_SCORE_THREADS 256
+#endif
+constexpr int kScoreThreads = COMMVQ_SCORE_THREADS;
 constexpr int kBinsThreads = 512;
 constexpr int kOutThreads = 256;
 constexpr int kOutRows = 64;    // codebook rows per k_out workgroup
@@ -78,7 +84,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, commvq_plan *p)
 {
     const int units = B * h->cfg.n_kv_heads;
     int len = 1024;
-    while (len > 256 && (long)units * ((max_seqlen + len - 1) / len) < 2048) len /= 2;
+    while (len > kScoreThreads && (long)units * ((max_seqlen + len - 1) / len) < COMMVQ_SCORE_MIN_WGS) len /= 2;
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
     int nv = 256 / units;  // about one value workgroup per compute unit

@@ -84,8 +84,8 @@ def test_staged_entry_points_equal_fused_call(gpu):
     w = synth.config(3, max_len=3000)
     a = run_gpu(gpu, w)
     b = run_gpu(gpu, w, staged=True)
-    # same kernels, same order; LDS float atomics reorder additions inside the bins
-    assert np.abs(a - b).max() <= 1e-6 * np.abs(a).max()
+    # same kernels, same order; the bins are integer, so even the atomics are order-independent
+    assert np.array_equal(a, b)
 
 
 # ---------------------------------------------------------------- edge cases
@@ -159,8 +159,8 @@ def test_peaked_softmax_large_logits(gpu, oracle):
 def test_run_to_run_spread(gpu):
     w = synth.config(3, max_len=4000)
     a, b, c = run_gpu(gpu, w), run_gpu(gpu, w), run_gpu(gpu, w)
-    scale = np.abs(a).max()
-    assert max(np.abs(a - b).max(), np.abs(a - c).max()) <= 1e-5 * scale  # atomics reorder, nothing more
+    # fixed-point bins and fixed-order reductions: bit-reproducible
+    assert np.array_equal(a, b) and np.array_equal(a, c)
 
 
 # ---------------------------------------------------------------- argument checking through the C ABI
