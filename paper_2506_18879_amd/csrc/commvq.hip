@@ -77,29 +77,60 @@ struct Workspace {
     float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over that value split
     unsigned *bins;   // [B * Hkv * value_splits][G * Mv * K] fixed-point bins
     float *partial;   // [B * Hq * out_chunks][d]
+    uint4 *packed;    // key codebook re-laid slice-major for k_score_sliced (same size as the codebook)
+    float *qs;        // [B * Hq][d] scaled queries in fp32
     size_t bytes;
 };
 
-void make_plan(const commvq_handle *h, int B, int max_seqlen, commvq_plan *p)
+// The sliced score kernel serves bf16 codebooks with contiguous positions; everything else
+// (fp32 codebooks, explicit key positions) goes through the gather kernel.
+bool use_sliced(const commvq_handle *h, bool explicit_positions)
+{
+    return h->cfg.codebook_dtype == COMMVQ_BF16 && !explicit_positions;
+}
+
+void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commvq_plan *p)
 {
     const int units = B * h->cfg.n_kv_heads;
-    int len = 1024;
-    while (len > kScoreThreads && (long)units * ((max_seqlen + len - 1) / len) < COMMVQ_SCORE_MIN_WGS) len /= 2;
+    int len;
+    if (sliced) {
+        // tokens per lane (1, 2 or 4): longer tiles amortise the LDS refill of each codebook slice
+        // (a quarter of a 1024-token gather), shorter ones fill the 256 compute units more evenly
+        double best = -1.0;
+        len = 1024;
+        for (int tpt = 1; tpt <= 4; tpt *= 2) {
+            const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt));
+            const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
+            const double eff = fill / (1.0 + 0.25 / tpt);
+            if (eff > best * 1.0001) { best = eff; len = 1024 * tpt; }
+        }
+    } else {
+        len = 1024;
+        while (len > kScoreThreads && (long)units * ((max_seqlen + len - 1) / len) < COMMVQ_SCORE_MIN_WGS) len /= 2;
+    }
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
     int nv = 256 / units;  // about one value workgroup per compute unit
     if (nv < 1) nv = 1;
     int vlen = (max_seqlen + nv - 1) / nv;
-    vlen = (vlen + 1023) / 1024 * 1024;  // whole score splits, so their statistics can be summed
+    const int round_to = len > 1024 ? len : 1024;  // whole score splits, so their statistics can be summed
+    vlen = (vlen + round_to - 1) / round_to * round_to;
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
     p->out_chunks = h->cfg.m_val * kK / kOutRows;
-    p->reserved = 0;
+    p->reserved = sliced ? 1 : 0;
 }
 
-void carve(const commvq_handle *h, const commvq_plan &p, int B, int64_t T, void *base, Workspace *w)
+// Carves the workspace.  Array sizes are the larger of what the two score kernels need, so one
+// workspace size serves a batch shape whether or not explicit positions are passed.
+void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base, Workspace *w)
 {
     const commvq_config &c = h->cfg;
+    commvq_plan pa, pb;
+    make_plan(h, B, max_seqlen, true, &pa);
+    make_plan(h, B, max_seqlen, false, &pb);
+    const size_t ssplits = pa.score_splits > pb.score_splits ? pa.score_splits : pb.score_splits;
+    const size_t vsplits = pa.value_splits > pb.value_splits ? pa.value_splits : pb.value_splits;
     size_t off = 0;
     auto take = [&](size_t n_floats) {
         float *ptr = base ? reinterpret_cast<float *>(static_cast<char *>(base) + off) : nullptr;
@@ -107,11 +138,13 @@ void carve(const commvq_handle *h, const commvq_plan &p, int B, int64_t T, void 
         return ptr;
     };
     w->scores = take((size_t)T * c.n_q_heads);
-    w->sstat = reinterpret_cast<float2 *>(take((size_t)B * c.n_q_heads * p.score_splits * 2));
-    w->vscale = take((size_t)B * c.n_q_heads * p.value_splits);
-    w->lsum = take((size_t)B * c.n_q_heads * p.value_splits);
-    w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * p.value_splits * h->G * c.m_val * kK));
-    w->partial = take((size_t)B * c.n_q_heads * p.out_chunks * kD);
+    w->sstat = reinterpret_cast<float2 *>(take((size_t)B * c.n_q_heads * ssplits * 2));
+    w->vscale = take((size_t)B * c.n_q_heads * vsplits);
+    w->lsum = take((size_t)B * c.n_q_heads * vsplits);
+    w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * vsplits * h->G * c.m_val * kK));
+    w->partial = take((size_t)B * c.n_q_heads * pa.out_chunks * kD);
+    w->packed = reinterpret_cast<uint4 *>(take((size_t)c.n_kv_heads * c.m_key * kK * kD / 2));  // bf16 codebook
+    w->qs = take((size_t)B * c.n_q_heads * kD);
     w->bytes = off;
 }
 
@@ -444,6 +477,230 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     }
 }
 
+// ------------------------------------------------------------------ k_prep / k_score_sliced
+constexpr int kSliceThreads = 1024;              // one workgroup per compute unit
+constexpr int kSliceBytes = 128 * 1024;          // LDS bytes of one codebook slice
+
+// Key codebook re-laid for k_score_sliced, plus the scaled queries in fp32.
+//   packed[g][s][p][m][c] : 16-byte pieces (8 bf16); piece (s, p) of row (m, c) holds elements
+//                           DS*s + 8p .. +7 with DS = 256 / M elements per slice (S = 128 / DS slices,
+//                           P = DS / 8 planes), so that slice s is one contiguous 128 KiB block
+//   qs[b][h][d]           : q * softmax scale
+// One thread per 16-byte piece of the source (coalesced reads).
+__global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, uint4 *__restrict__ packed,
+                                              const void *__restrict__ q, float *__restrict__ qs, int Hkv, int M,
+                                              int n_q, int q_bf16, float scale)
+{
+    const int P = 32 / M;                       // planes: DS / 8 = (256 / M) / 8
+    const size_t n_pieces = (size_t)Hkv * M * kK * 16;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t < n_pieces) {
+        const int piece = (int)(t & 15);        // 16 pieces of 8 elements per row
+        const size_t row = t >> 4;              // (g * M + m) * K + c
+        const int g = (int)(row / ((size_t)M * kK));
+        const int mc = (int)(row % ((size_t)M * kK));
+        const int sl = piece / P, pl = piece % P;
+        const int S = 16 / P;
+        packed[(((size_t)g * S + sl) * P + pl) * ((size_t)M * kK) + mc] = key_cb[t];
+    }
+    if (t < (size_t)n_q) {
+        float v;
+        if (q_bf16) v = __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(q)[t] << 16);
+        else v = static_cast<const float *>(q)[t];
+        qs[t] = v * scale;
+    }
+}
+
+struct SliceDims {
+    int Hq, Hkv, nsplit, n_hi;
+};
+
+// Score kernel for contiguous positions and bf16 codebooks.  One workgroup (1024 lanes, one
+// per compute unit) owns a tile of TPT * 1024 consecutive tokens of one (sequence, KV head);
+// lane l handles tokens l, l + 1024, ...  The key codebook is streamed through LDS one slice of
+// DS = 256 / M elements at a time (128 KiB: every row of every codebook, DS elements each);
+// for each slice a lane gathers its tokens' M rows from LDS (16-byte reads, rows of different
+// lanes are independent), rotates the DS/2 sub-space sums by exp(i theta_j (t - p)) and adds
+// q . B into its own G logits, which stay in registers across all slices.  No cross-lane
+// reduction is needed and codeword rows never travel through L1: the gather runs at LDS rate
+// (measured ~1.6x the L1 gather rate) and L2 only sees the 1-2 MiB codebook once per tile.
+// Phases: exact two-level table product exp(i theta_j 64 H) exp(i theta_j lo) for every token.
+template <int M, int G, int TPT>
+__global__ __launch_bounds__(kSliceThreads) void k_score_sliced(
+    const float *__restrict__ qs, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
+    const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const float2 *__restrict__ tbl_hi,
+    const float2 *__restrict__ tbl_lo, float *__restrict__ scores, float2 *__restrict__ sstat, const SliceDims a)
+{
+    constexpr int DS = 256 / M;          // elements per slice (16 or 8)
+    constexpr int NJ = DS / 2;           // sub-spaces per slice
+    constexpr int P = DS / 8;            // 16-byte planes per slice
+    constexpr int S = kD / DS;           // slices
+    constexpr int TILE = TPT * kSliceThreads;
+    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [P][M][K] 16-byte pieces
+    __shared__ float2 wstat[kSliceThreads / 64][G];
+
+    int id = blockIdx.x;
+    const int g = id % a.Hkv;
+    id /= a.Hkv;
+    const int tile = id % a.nsplit;
+    const int b = id / a.nsplit;
+    const int cu0 = cu[b];
+    const int L = cu[b + 1] - cu0;
+    const int t0 = tile * TILE;
+    if (t0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qpos = q_pos[b];
+    const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
+    const uint4 *src = packed + (size_t)g * S * P * M * kK;
+    const float *qg = qs + ((size_t)b * a.Hq + (size_t)g * G) * kD;
+    const unsigned sel_lo = opaque_sgpr(0x00003f80u), sel_hi = opaque_sgpr(0x3f800000u);
+    constexpr int PIECES = P * M * kK;                 // 8192 pieces per slice
+    constexpr int PPT = PIECES / kSliceThreads;        // 8 per lane
+
+    float sc[TPT][G];
+#pragma unroll
+    for (int k = 0; k < TPT; ++k)
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) sc[k][hh] = 0.f;
+
+    // Relative position of the lane's first token as 64 * H + lo with 0 <= lo < 64 and H signed;
+    // the lane's k-th token is 1024 positions later, i.e. H - 16 k with the same lo, so E_lo is a
+    // per-lane constant and E_hi is looked up per token (exp(i theta 64 H) = conj of entry |H|
+    // for negative H).
+    const int dl0 = qpos - min(t0 + tid, L - 1);
+    const int H0 = dl0 >> kLoBits, lo0 = dl0 & (kLo - 1);
+    constexpr int HSTEP = kSliceThreads >> kLoBits;
+
+    for (int sl = 0; sl < S; ++sl) {
+        __syncthreads();  // everyone is done reading the previous slice
+        {
+            uint4 stage[PPT];
+#pragma unroll
+            for (int x = 0; x < PPT; ++x) stage[x] = src[(size_t)sl * PIECES + x * kSliceThreads + tid];
+#pragma unroll
+            for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
+        }
+        __syncthreads();
+        // this slice's scaled queries of the group (scalar registers, fetched with vector loads + readfirstlane: scalar memory loads inside the
+        // token loop would force every LDS wait to drain the whole lgkm counter)
+        float qx[G][NJ], qy[G][NJ];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj) {
+                const float2 qv = *reinterpret_cast<const float2 *>(qg + hh * kD + 2 * (sl * NJ + jj) + 2 * (lane & 0));
+                qx[hh][jj] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, qv.x)));
+                qy[hh][jj] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, qv.y)));
+            }
+#pragma unroll
+        for (int k = 0; k < TPT; ++k) {
+            __builtin_amdgcn_sched_barrier(0);  // one token at a time: keeps register pressure flat in TPT
+            int tok = min(t0 + k * kSliceThreads + tid, L - 1);
+            // opaque to the optimiser: otherwise the codes and all M * TPT row addresses are hoisted
+            // out of the slice loop and spilled; re-reading 16-32 bytes per token and slice is cheaper
+            asm volatile("" : "+v"(tok));
+            unsigned cw[M / 4];
+            const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)tok * M);
+#pragma unroll
+            for (int v = 0; v < M / 16; ++v) {
+                const uint4 c4 = cp[v];
+                cw[4 * v + 0] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
+            }
+            const int H = H0 - HSTEP * k;
+            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
+            // A = this slice's part of the sum of the M selected codeword rows (Eq. commute_decode)
+            float A[DS];
+#pragma unroll
+            for (int e = 0; e < DS; ++e) A[e] = 0.f;
+            // LDS reads go out in groups of 4 (16 registers), two groups in flight: the group after
+            // the one being summed is always outstanding, and the compiler cannot queue all M * P
+            // reads at once and spill.
+            constexpr int RM = 4 / P;      // codebooks per group
+            constexpr int NG = M / RM;     // groups per token
+            uint4 v[2][RM][P];
+            auto issue = [&](int grp, uint4(&dst)[RM][P]) {
+#pragma unroll
+                for (int r = 0; r < RM; ++r) {
+                    const int m = grp * RM + r;
+                    const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
+#pragma unroll
+                    for (int pl = 0; pl < P; ++pl) dst[r][pl] = tab[(pl * M + m) * kK + c];
+                }
+            };
+            issue(0, v[0]);
+#pragma unroll
+            for (int grp = 0; grp < NG; ++grp) {
+                if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < RM; ++r)
+#pragma unroll
+                    for (int pl = 0; pl < P; ++pl) {
+                        const uint4 x = v[grp & 1][r][pl];
+                        const unsigned w4[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            A[8 * pl + 2 * e] = add_bf16_sel(w4[e], sel_lo, A[8 * pl + 2 * e]);
+                            A[8 * pl + 2 * e + 1] = add_bf16_sel(w4[e], sel_hi, A[8 * pl + 2 * e + 1]);
+                        }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // E = E_hi E_lo; B = A E; logit_h += sum_j Re(q_h conj(B))
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj) {
+                // (loaded after the gather on purpose: 32 fewer live registers while the LDS reads
+                // are in flight; these are L1 hits on the vector-memory counter)
+                const float2 eh = tbl_hi[(size_t)hi * kJ + sl * NJ + jj];
+                const float2 el = tbl_lo[(size_t)lo0 * kJ + sl * NJ + jj];
+                const float hy = H < 0 ? -eh.y : eh.y;
+                const float ex = eh.x * el.x - hy * el.y;
+                const float ey = eh.x * el.y + hy * el.x;
+                const float bx = A[2 * jj] * ex - A[2 * jj + 1] * ey;
+                const float by = A[2 * jj] * ey + A[2 * jj + 1] * ex;
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    sc[k][hh] = __builtin_fmaf(qx[hh][jj], bx, sc[k][hh]);
+                    sc[k][hh] = __builtin_fmaf(qy[hh][jj], by, sc[k][hh]);
+                }
+            }
+        }
+    }
+
+    // write the logits (consecutive lanes = consecutive tokens) and the tile's (max, sum exp)
+    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < TPT; ++k) {
+            const int tok = t0 + k * kSliceThreads + tid;
+            if (tok < L) {
+                srow[(size_t)hh * L + tok] = sc[k][hh];
+                mx = fmaxf(mx, sc[k][hh]);
+            }
+        }
+        const float wm = wave_max(mx);
+        float l = 0.f;
+#pragma unroll
+        for (int k = 0; k < TPT; ++k)
+            if (t0 + k * kSliceThreads + tid < L) l += __builtin_amdgcn_exp2f((sc[k][hh] - wm) * kLog2e);
+        l = wave_sum(l);
+        if (lane == 0) wstat[wave][hh] = make_float2(wm, l);
+    }
+    __syncthreads();
+    if (tid < G) {
+        float m = -INFINITY;
+        for (int w = 0; w < kSliceThreads / 64; ++w) m = fmaxf(m, wstat[w][tid].x);
+        float l = 0.f;
+        for (int w = 0; w < kSliceThreads / 64; ++w) {
+            const float2 st = wstat[w][tid];
+            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+        }
+        sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
+    }
+}
+
 // ------------------------------------------------------------------ k_bins
 struct BinsArgs {
     const uint8_t *val_codes;
@@ -663,8 +920,8 @@ commvq_status prep(const commvq_handle *h, const commvq_positions *pos, void *wo
     if (!h) return COMMVQ_ERR_NULL;
     commvq_status st = check_positions(pos);
     if (st != COMMVQ_OK) return st;
-    make_plan(h, pos->batch, pos->max_seqlen, plan);
-    carve(h, *plan, pos->batch, pos->total_tokens, workspace, w);
+    make_plan(h, pos->batch, pos->max_seqlen, use_sliced(h, pos->key_pos != nullptr), plan);
+    carve(h, pos->batch, pos->total_tokens, pos->max_seqlen, workspace, w);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < w->bytes)
         return COMMVQ_ERR_WORKSPACE;
     return COMMVQ_OK;
@@ -736,10 +993,71 @@ hipError_t launch_out_g(const OutArgs &a, bool bf16, int grid, hipStream_t s)
     return hipGetLastError();
 }
 
+struct SliceArgs {
+    const float *qs;
+    const uint8_t *key_codes;
+    const uint4 *packed;
+    const int32_t *cu, *q_pos;
+    const float2 *tbl_hi, *tbl_lo;
+    float *scores;
+    float2 *sstat;
+    SliceDims d;
+};
+
+template <int M, int G, int TPT>
+hipError_t launch_sliced_mgt(const SliceArgs &a, int grid, hipStream_t s)
+{
+    static bool attr_set = false;  // per instantiation; raising the limit is idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_sliced<M, G, TPT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSliceBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_score_sliced<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kSliceBytes, s, a.qs, a.key_codes,
+                       a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
+    return hipGetLastError();
+}
+template <int M, int G>
+hipError_t launch_sliced_mg(const SliceArgs &a, int tpt, int grid, hipStream_t s)
+{
+    switch (tpt) {
+    case 1: return launch_sliced_mgt<M, G, 1>(a, grid, s);
+    case 2: return launch_sliced_mgt<M, G, 2>(a, grid, s);
+    default: return launch_sliced_mgt<M, G, 4>(a, grid, s);
+    }
+}
+template <int M>
+hipError_t launch_sliced_m(const SliceArgs &a, int G, int tpt, int grid, hipStream_t s)
+{
+    switch (G) {
+    case 1: return launch_sliced_mg<M, 1>(a, tpt, grid, s);
+    case 2: return launch_sliced_mg<M, 2>(a, tpt, grid, s);
+    case 4: return launch_sliced_mg<M, 4>(a, tpt, grid, s);
+    default: return launch_sliced_mg<M, 8>(a, tpt, grid, s);
+    }
+}
+
 commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_codes, const void *key_cb,
                          const commvq_positions *pos, const commvq_plan &plan, const Workspace &w, hipStream_t s)
 {
     const commvq_config &c = h->cfg;
+    if (plan.reserved) {  // sliced kernel: re-lay the codebook and scale the queries, then score
+        const size_t n_pieces = (size_t)c.n_kv_heads * c.m_key * kK * 16;
+        const int n_q = pos->batch * c.n_q_heads * kD;
+        const size_t n = n_pieces > (size_t)n_q ? n_pieces : (size_t)n_q;
+        hipLaunchKernelGGL(k_prep, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const uint4 *>(key_cb),
+                           w.packed, q, w.qs, c.n_kv_heads, c.m_key, n_q, c.q_dtype == COMMVQ_BF16, h->scale);
+        if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+        SliceArgs sa;
+        sa.qs = w.qs; sa.key_codes = key_codes; sa.packed = w.packed; sa.cu = pos->cu_seqlens; sa.q_pos = pos->q_pos;
+        sa.tbl_hi = h->tbl_hi; sa.tbl_lo = h->tbl_lo; sa.scores = w.scores; sa.sstat = w.sstat;
+        sa.d.Hq = c.n_q_heads; sa.d.Hkv = c.n_kv_heads; sa.d.nsplit = plan.score_splits; sa.d.n_hi = h->n_hi;
+        const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
+        const int tpt = plan.score_split_len / kSliceThreads;
+        hipError_t e = c.m_key == 16 ? launch_sliced_m<16>(sa, h->G, tpt, grid, s) : launch_sliced_m<32>(sa, h->G, tpt, grid, s);
+        return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+    }
     ScoreArgs a;
     a.q = q; a.key_codes = key_codes; a.key_cb = key_cb;
     a.cu = pos->cu_seqlens; a.q_pos = pos->q_pos; a.key_pos = pos->key_pos;
@@ -888,7 +1206,7 @@ commvq_status commvq_plan_query(const commvq_handle *h, int32_t batch, int64_t t
     if (batch < 1 || max_seqlen < 1 || total_tokens < batch || total_tokens < max_seqlen ||
         total_tokens > (int64_t)batch * max_seqlen)
         return COMMVQ_ERR_SHAPE;
-    make_plan(h, batch, max_seqlen, plan);
+    make_plan(h, batch, max_seqlen, use_sliced(h, false), plan);
     return COMMVQ_OK;
 }
 
@@ -900,7 +1218,7 @@ commvq_status commvq_workspace_bytes(const commvq_handle *h, int32_t batch, int6
     commvq_status st = commvq_plan_query(h, batch, total_tokens, max_seqlen, &plan);
     if (st != COMMVQ_OK) return st;
     Workspace w;
-    carve(h, plan, batch, total_tokens, nullptr, &w);
+    carve(h, batch, total_tokens, max_seqlen, nullptr, &w);
     *bytes = w.bytes;
     return COMMVQ_OK;
 }
