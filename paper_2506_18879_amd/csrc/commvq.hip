@@ -701,6 +701,273 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_sliced(
     }
 }
 
+// ------------------------------------------------------------------ k_score_mfma
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+// Max / sum over the lanes that hold the same query heads: all 64 lanes for G <= 4; for G = 8 the
+// 16-lane rows 0 and 2 hold heads 0..3 and rows 1 and 3 hold heads 4..7.
+template <int G>
+__device__ __forceinline__ float heads_max(float v)
+{
+    if (G < 8) return wave_max(v);
+    v = row_max16(v);
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (unsigned)r32[0]), __builtin_bit_cast(float, (unsigned)r32[1]));
+}
+template <int G>
+__device__ __forceinline__ float heads_sum(float v)
+{
+    if (G < 8) return wave_sum(v);
+    v = row_sum16(v);
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (unsigned)r32[0]) + __builtin_bit_cast(float, (unsigned)r32[1]);
+}
+
+// Slice-streaming score kernel with both contractions on the matrix cores (Eq. new_attention,
+// re-bracketed: gather-sum the codeword blocks first, rotate once, contract with the G queries).
+// Works on the key codebook repacked by k_prep: slice sl (DS = 256 / M consecutive elements of
+// every codeword) sits in LDS as tab[P][M][K] 16-byte pieces while all tokens of the tile pass by.
+//
+//  1. Gather-sum: v_mfma_f32_16x16x32_bf16 with a constant 0/1 selection matrix as first operand
+//     and 64 gathered pieces as second (lane n + 16 g supplies the 8 elements of its piece as rows
+//     8g .. 8g+7 of column n).  Products with 1.0 are exact, so this is the plain fp32 sum of the
+//     M codeword slices.  Row i of the result is element (i mod 8) of k-groups {0,1} (i < 8) or
+//     {2,3} (i >= 8):
+//       M = 16 (two planes): a pass covers 16 tokens; k-groups = plane x (even | odd codebook);
+//               lane (n, g) receives elements 4g .. 4g+3 of the slice for token n;
+//       M = 32 (one plane):  a pass covers 32 tokens in two sets; k-groups = set x (even | odd
+//               codebook); lane (n, g) receives elements 4 (g & 1) .. +3 for token n + 16 (g >> 1).
+//  2. Each lane rotates its two (x, y) sub-spaces by the token's relative position (two-level
+//     phase tables) -- the only per-token vector arithmetic left on the vector ALUs.
+//  3. Contraction with the queries: v_mfma_f32_16x16x4_f32, first operand = scaled queries (row i
+//     = head i mod G, column k = the k-group's r-th element), second = the rotated r-th element of
+//     every lane.  Rows outside the current "row group" are zeroed, so that 16 / G consecutive
+//     16-token sets accumulate into disjoint rows of one accumulator: lane (n, g) register r of
+//     accumulator a ends up with head (4g + r) mod G of token n of set a (16 / G) + (4g + r) / G.
+template <int M, int G, int TPT>
+__global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
+    const float *__restrict__ qs, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
+    const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const float2 *__restrict__ tbl_hi,
+    const float2 *__restrict__ tbl_lo, float *__restrict__ scores, float2 *__restrict__ sstat, const SliceDims a)
+{
+    constexpr int DS = 256 / M;          // elements per slice (16 or 8)
+    constexpr int NJ = DS / 2;           // sub-spaces per slice
+    constexpr int P = DS / 8;            // 16-byte planes per slice
+    constexpr int S = kD / DS;           // slices
+    constexpr int TILE = TPT * kSliceThreads;
+    constexpr int NW = kSliceThreads / 64;
+    constexpr int SETS = M == 16 ? 1 : 2;                     // 16-token sets per wavefront pass
+    constexpr int NPASS = TILE / (16 * SETS * NW);
+    constexpr int NVP = NPASS * SETS;                         // 16-token sets per wavefront and tile
+    constexpr int NPG = 16 / G;                               // sets per accumulator (row groups)
+    constexpr int NACC = (NVP + NPG - 1) / NPG;
+    constexpr int NS = M / 2;                                 // gather MFMAs per pass and slice
+    constexpr int CW = M / 4;
+    constexpr int HL = G < 4 ? G : 4;                         // distinct heads among a lane's 4 registers
+    static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
+    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [P][M][K] 16-byte pieces
+    __shared__ float2 wstat[NW][G];
+
+    int id = blockIdx.x;
+    const int g = id % a.Hkv;
+    id /= a.Hkv;
+    const int tile = id % a.nsplit;
+    const int b = id / a.nsplit;
+    const int cu0 = cu[b];
+    const int L = cu[b + 1] - cu0;
+    const int t0 = tile * TILE;
+    if (t0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gk = lane >> 4;
+    const int par = gk & 1;                                   // odd / even codebook of a gather step
+    const int set = gk >> 1;                                  // M = 32: which 16-token set the lane gathers for
+    const int plane = M == 16 ? (gk >> 1) : 0;
+    const int el = M == 16 ? 4 * gk : 4 * par;                // first of the lane's 4 slice elements
+    const int qpos = q_pos[b];
+    const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
+    const uint4 *src = packed + (size_t)g * S * P * M * kK;
+    const __amdgpu_buffer_rsrc_t cd_rs = make_rsrc(codes, (unsigned)L * M);
+    const __amdgpu_buffer_rsrc_t hi_rs = make_rsrc(tbl_hi, (unsigned)a.n_hi * kJ * 8u);
+    const __amdgpu_buffer_rsrc_t lo_rs = make_rsrc(tbl_lo, (unsigned)kLo * kJ * 8u);
+    const __amdgpu_buffer_rsrc_t q_rs = make_rsrc(qs + ((size_t)b * a.Hq + (size_t)g * G) * kD, (unsigned)G * kD * 4u);
+    constexpr int PIECES = P * M * kK;
+    constexpr int PPT = PIECES / kSliceThreads;
+
+    // selection matrix operand: lane (i = n, k-group gk) holds row i, columns 8 gk .. 8 gk + 7:
+    // one-hot at e = i - 8 (gk >> 1) when that lies in 0..7
+    uint4_t sel = {0u, 0u, 0u, 0u};
+    {
+        const int e = n - 8 * (gk >> 1);
+        if (e >= 0 && e < 8) sel[e >> 1] = (e & 1) ? 0x3f800000u : 0x00003f80u;
+    }
+    const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
+    // as first operand of the query contraction the lane is row n (head n mod G, row group n / G), column gk
+    const int rowgrp = n / G;
+    const unsigned q_off = (unsigned)(n % G) * (kD * 4u) + (unsigned)el * 4u;
+
+    floatx4_t dacc[NACC];
+#pragma unroll
+    for (int x = 0; x < NACC; ++x) dacc[x] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+    // byte offset of the lane's first piece: ((plane * M + par) * K) * 16
+    const unsigned lane_base = (unsigned)((plane * M + par) * kK) * 16u;
+    // bit offsets of the lane's code inside a code dword for even / odd steps (codebook 2 st + par)
+    const unsigned boff0 = 8u * par, boff2 = 16u + 8u * par;
+
+    // Codes are fetched one pass ahead (the fetch for pass 0 of the next slice rides on the last
+    // pass of this one), so that their latency hides behind a whole pass of gather work.  tb is the
+    // lane's first token; it is re-read through an opaque copy in every slice so that nothing that
+    // depends on a token index (code loads, table offsets) is hoisted out of the slice loop.
+    int tb = t0 + wave * (16 * SETS) + n + 16 * (M == 16 ? 0 : set);
+    unsigned cw[2][CW];
+    auto fetch_codes = [&](int p, unsigned(&dst)[CW]) {
+        const int tok = min(tb + p * NW * 16 * SETS, L - 1);
+#pragma unroll
+        for (int v = 0; v < M / 16; ++v) {
+            const uint4_t c4 = __builtin_amdgcn_raw_buffer_load_b128(cd_rs, (unsigned)tok * M + 16u * v, 0, 0);
+            dst[4 * v + 0] = c4[0]; dst[4 * v + 1] = c4[1]; dst[4 * v + 2] = c4[2]; dst[4 * v + 3] = c4[3];
+        }
+    };
+    fetch_codes(0, cw[0]);
+
+    for (int sl = 0; sl < S; ++sl) {
+        __syncthreads();  // everyone is done reading the previous slice
+        {
+            uint4 stage[PPT];
+#pragma unroll
+            for (int x = 0; x < PPT; ++x) stage[x] = src[(size_t)sl * PIECES + x * kSliceThreads + tid];
+#pragma unroll
+            for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
+        }
+        __syncthreads();
+        asm volatile("" : "+v"(tb));
+        // scaled queries of this slice as seen by the lane in its role as row n, column gk
+        const uint4_t qraw = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off, (unsigned)sl * DS * 4u, 0);
+        float qrow[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const unsigned u = qraw[r];
+            qrow[r] = __builtin_bit_cast(float, u);
+        }
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure flat
+            const int tok = min(tb + p * NW * 16 * SETS, L - 1);
+            const int dl = qpos - tok;
+            const int H = dl >> kLoBits, lo = dl & (kLo - 1);
+            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
+            // phase factors first (older than the code prefetch, so waiting for them does not wait for it)
+            const unsigned soff = (unsigned)(sl * NJ) * 8u;
+            const uint4_t ehr = __builtin_amdgcn_raw_buffer_load_b128(hi_rs, (unsigned)hi * (kJ * 8u) + (unsigned)el * 4u, soff, 0);
+            const uint4_t elr = __builtin_amdgcn_raw_buffer_load_b128(lo_rs, (unsigned)lo * (kJ * 8u) + (unsigned)el * 4u, soff, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned(&cc)[CW] = cw[p & 1];
+
+            // 1. gather-sum on the matrix cores; LDS reads in groups of RG, two groups in flight
+            floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+            constexpr int RG = 4, NG = NS / RG;
+            uint4 v[2][RG];
+            auto issue = [&](int grp, uint4(&dst)[RG]) {
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    const int st = grp * RG + r;  // codebooks 2 st, 2 st + 1
+                    const unsigned c = __builtin_amdgcn_ubfe(cc[st / 2], (st & 1) ? boff2 : boff0, 8u);
+                    dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + lane_base +
+                                                              (unsigned)st * (2u * kK * 16u) + c * 16u);
+                }
+            };
+            issue(0, v[0]);
+#pragma unroll
+            for (int grp = 0; grp < NG; ++grp) {
+                if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    const uint4 x = v[grp & 1][r];
+                    const uint4_t xv = {x.x, x.y, x.z, x.w};
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, xv), acc, 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // 2. E = E_hi E_lo for the lane's two sub-spaces; rotated block = A E
+            float val[4];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const unsigned hxr = ehr[2 * u], hyr = ehr[2 * u + 1], lxr = elr[2 * u], lyr = elr[2 * u + 1];
+                const float hx = __builtin_bit_cast(float, hxr);
+                const float hy0 = __builtin_bit_cast(float, hyr);
+                const float hy = H < 0 ? -hy0 : hy0;
+                const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
+                const float ex = hx * lx - hy * ly;
+                const float ey = hx * ly + hy * lx;
+                const float ax = acc[2 * u], ay = acc[2 * u + 1];
+                val[2 * u] = ax * ex - ay * ey;
+                val[2 * u + 1] = ax * ey + ay * ex;
+            }
+            // 3. logits += queries x rotated blocks; only the rows of this set's row group are live
+#pragma unroll
+            for (int sx = 0; sx < SETS; ++sx) {
+                const int vp = p * SETS + sx;
+                const bool on = rowgrp == vp % NPG && (SETS == 1 || set == sx);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    dacc[vp / NPG] = __builtin_amdgcn_mfma_f32_16x16x4f32(on ? qrow[r] : 0.f, val[r], dacc[vp / NPG], 0, 0, 0);
+            }
+        }
+    }
+
+    // logits to memory and the tile's (max, sum of exp) per head
+    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    auto token_of = [&](int vp) {
+        return M == 16 ? t0 + (vp * NW + wave) * 16 + n : t0 + ((vp / 2) * NW + wave) * 32 + 16 * (vp % 2) + n;
+    };
+    float mx[HL];
+#pragma unroll
+    for (int hl = 0; hl < HL; ++hl) mx[hl] = -INFINITY;
+#pragma unroll
+    for (int x = 0; x < NACC; ++x)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * gk + r;
+            const int vp = x * NPG + row / G;
+            const int tok = token_of(vp);
+            if (vp < NVP && tok < L) {
+                srow[(size_t)(row % G) * L + tok] = dacc[x][r];
+                mx[r % HL] = fmaxf(mx[r % HL], dacc[x][r]);
+            }
+        }
+#pragma unroll
+    for (int hl = 0; hl < HL; ++hl) {
+        const float wm = heads_max<G>(mx[hl]);
+        float l = 0.f;
+#pragma unroll
+        for (int x = 0; x < NACC; ++x)
+#pragma unroll
+            for (int r = hl; r < 4; r += HL) {
+                const int vp = x * NPG + (4 * gk + r) / G;
+                if (vp < NVP && token_of(vp) < L) l += __builtin_amdgcn_exp2f((dacc[x][r] - wm) * kLog2e);
+            }
+        l = heads_sum<G>(l);
+        if (n == 0 && gk < (G + 3) / 4) wstat[wave][(4 * gk + hl) % G] = make_float2(wm, l);
+    }
+    __syncthreads();
+    if (tid < G) {
+        float m = -INFINITY;
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
+        float l = 0.f;
+        for (int w = 0; w < NW; ++w) {
+            const float2 st = wstat[w][tid];
+            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+        }
+        sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
+    }
+}
+
 // ------------------------------------------------------------------ k_bins
 struct BinsArgs {
     const uint8_t *val_codes;
@@ -1009,13 +1276,23 @@ hipError_t launch_sliced_mgt(const SliceArgs &a, int grid, hipStream_t s)
 {
     static bool attr_set = false;  // per instantiation; raising the limit is idempotent
     if (!attr_set) {
+#ifdef COMMVQ_SCORE_VALU_SLICED
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_sliced<M, G, TPT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kSliceBytes);
+#else
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_mfma<M, G, TPT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSliceBytes);
+#endif
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+#ifdef COMMVQ_SCORE_VALU_SLICED
     hipLaunchKernelGGL((k_score_sliced<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kSliceBytes, s, a.qs, a.key_codes,
                        a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
+#else
+    hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kSliceBytes, s, a.qs, a.key_codes,
+                       a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
+#endif
     return hipGetLastError();
 }
 template <int M, int G>
