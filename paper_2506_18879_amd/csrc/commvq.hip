@@ -477,15 +477,18 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     }
 }
 
-// ------------------------------------------------------------------ k_prep / k_score_sliced
+// ------------------------------------------------------------------ k_prep
 constexpr int kSliceThreads = 1024;              // one workgroup per compute unit
 constexpr int kSliceBytes = 128 * 1024;          // LDS bytes of one codebook slice
 
-// Key codebook re-laid for k_score_sliced, plus the scaled queries in fp32.
-//   packed[g][s][p][m][c] : 16-byte pieces (8 bf16); piece (s, p) of row (m, c) holds elements
-//                           DS*s + 8p .. +7 with DS = 256 / M elements per slice (S = 128 / DS slices,
-//                           P = DS / 8 planes), so that slice s is one contiguous 128 KiB block
-//   qs[b][h][d]           : q * softmax scale
+// Key codebook re-laid for k_score_mfma, plus the scaled queries in fp32.
+//   packed[g][s][c][x] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of every
+//                        codeword (DS = 256 / M, S = 128 / DS slices) as one contiguous 128 KiB block
+//                        of 256 rows (one per code value c) x 32 pieces: x = 16 * plane + m for M = 16
+//                        (plane = which 8 of the 16 elements), x = m for M = 32.  A row spans all 64
+//                        LDS banks twice, so piece x lives in bank column x mod 16 whatever its code:
+//                        lanes that read different columns never conflict.
+//   qs[b][h][d]        : q * softmax scale
 // One thread per 16-byte piece of the source (coalesced reads).
 __global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, uint4 *__restrict__ packed,
                                               const void *__restrict__ q, float *__restrict__ qs, int Hkv, int M,
@@ -499,9 +502,10 @@ __global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, 
         const size_t row = t >> 4;              // (g * M + m) * K + c
         const int g = (int)(row / ((size_t)M * kK));
         const int mc = (int)(row % ((size_t)M * kK));
+        const int m = mc / kK, c = mc % kK;
         const int sl = piece / P, pl = piece % P;
         const int S = 16 / P;
-        packed[(((size_t)g * S + sl) * P + pl) * ((size_t)M * kK) + mc] = key_cb[t];
+        packed[(((size_t)g * S + sl) * kK + c) * 32 + pl * 16 + m] = key_cb[t];
     }
     if (t < (size_t)n_q) {
         float v;
@@ -514,192 +518,6 @@ __global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, 
 struct SliceDims {
     int Hq, Hkv, nsplit, n_hi;
 };
-
-// Score kernel for contiguous positions and bf16 codebooks.  One workgroup (1024 lanes, one
-// per compute unit) owns a tile of TPT * 1024 consecutive tokens of one (sequence, KV head);
-// lane l handles tokens l, l + 1024, ...  The key codebook is streamed through LDS one slice of
-// DS = 256 / M elements at a time (128 KiB: every row of every codebook, DS elements each);
-// for each slice a lane gathers its tokens' M rows from LDS (16-byte reads, rows of different
-// lanes are independent), rotates the DS/2 sub-space sums by exp(i theta_j (t - p)) and adds
-// q . B into its own G logits, which stay in registers across all slices.  No cross-lane
-// reduction is needed and codeword rows never travel through L1: the gather runs at LDS rate
-// (measured ~1.6x the L1 gather rate) and L2 only sees the 1-2 MiB codebook once per tile.
-// Phases: exact two-level table product exp(i theta_j 64 H) exp(i theta_j lo) for every token.
-template <int M, int G, int TPT>
-__global__ __launch_bounds__(kSliceThreads) void k_score_sliced(
-    const float *__restrict__ qs, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
-    const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const float2 *__restrict__ tbl_hi,
-    const float2 *__restrict__ tbl_lo, float *__restrict__ scores, float2 *__restrict__ sstat, const SliceDims a)
-{
-    constexpr int DS = 256 / M;          // elements per slice (16 or 8)
-    constexpr int NJ = DS / 2;           // sub-spaces per slice
-    constexpr int P = DS / 8;            // 16-byte planes per slice
-    constexpr int S = kD / DS;           // slices
-    constexpr int TILE = TPT * kSliceThreads;
-    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [P][M][K] 16-byte pieces
-    __shared__ float2 wstat[kSliceThreads / 64][G];
-
-    int id = blockIdx.x;
-    const int g = id % a.Hkv;
-    id /= a.Hkv;
-    const int tile = id % a.nsplit;
-    const int b = id / a.nsplit;
-    const int cu0 = cu[b];
-    const int L = cu[b + 1] - cu0;
-    const int t0 = tile * TILE;
-    if (t0 >= L) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qpos = q_pos[b];
-    const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
-    const uint4 *src = packed + (size_t)g * S * P * M * kK;
-    const float *qg = qs + ((size_t)b * a.Hq + (size_t)g * G) * kD;
-    const unsigned sel_lo = opaque_sgpr(0x00003f80u), sel_hi = opaque_sgpr(0x3f800000u);
-    constexpr int PIECES = P * M * kK;                 // 8192 pieces per slice
-    constexpr int PPT = PIECES / kSliceThreads;        // 8 per lane
-
-    float sc[TPT][G];
-#pragma unroll
-    for (int k = 0; k < TPT; ++k)
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) sc[k][hh] = 0.f;
-
-    // Relative position of the lane's first token as 64 * H + lo with 0 <= lo < 64 and H signed;
-    // the lane's k-th token is 1024 positions later, i.e. H - 16 k with the same lo, so E_lo is a
-    // per-lane constant and E_hi is looked up per token (exp(i theta 64 H) = conj of entry |H|
-    // for negative H).
-    const int dl0 = qpos - min(t0 + tid, L - 1);
-    const int H0 = dl0 >> kLoBits, lo0 = dl0 & (kLo - 1);
-    constexpr int HSTEP = kSliceThreads >> kLoBits;
-
-    for (int sl = 0; sl < S; ++sl) {
-        __syncthreads();  // everyone is done reading the previous slice
-        {
-            uint4 stage[PPT];
-#pragma unroll
-            for (int x = 0; x < PPT; ++x) stage[x] = src[(size_t)sl * PIECES + x * kSliceThreads + tid];
-#pragma unroll
-            for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
-        }
-        __syncthreads();
-        // this slice's scaled queries of the group (scalar registers, fetched with vector loads + readfirstlane: scalar memory loads inside the
-        // token loop would force every LDS wait to drain the whole lgkm counter)
-        float qx[G][NJ], qy[G][NJ];
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh)
-#pragma unroll
-            for (int jj = 0; jj < NJ; ++jj) {
-                const float2 qv = *reinterpret_cast<const float2 *>(qg + hh * kD + 2 * (sl * NJ + jj) + 2 * (lane & 0));
-                qx[hh][jj] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, qv.x)));
-                qy[hh][jj] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, qv.y)));
-            }
-#pragma unroll
-        for (int k = 0; k < TPT; ++k) {
-            __builtin_amdgcn_sched_barrier(0);  // one token at a time: keeps register pressure flat in TPT
-            int tok = min(t0 + k * kSliceThreads + tid, L - 1);
-            // opaque to the optimiser: otherwise the codes and all M * TPT row addresses are hoisted
-            // out of the slice loop and spilled; re-reading 16-32 bytes per token and slice is cheaper
-            asm volatile("" : "+v"(tok));
-            unsigned cw[M / 4];
-            const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)tok * M);
-#pragma unroll
-            for (int v = 0; v < M / 16; ++v) {
-                const uint4 c4 = cp[v];
-                cw[4 * v + 0] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
-            }
-            const int H = H0 - HSTEP * k;
-            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
-            // A = this slice's part of the sum of the M selected codeword rows (Eq. commute_decode)
-            float A[DS];
-#pragma unroll
-            for (int e = 0; e < DS; ++e) A[e] = 0.f;
-            // LDS reads go out in groups of 4 (16 registers), two groups in flight: the group after
-            // the one being summed is always outstanding, and the compiler cannot queue all M * P
-            // reads at once and spill.
-            constexpr int RM = 4 / P;      // codebooks per group
-            constexpr int NG = M / RM;     // groups per token
-            uint4 v[2][RM][P];
-            auto issue = [&](int grp, uint4(&dst)[RM][P]) {
-#pragma unroll
-                for (int r = 0; r < RM; ++r) {
-                    const int m = grp * RM + r;
-                    const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
-#pragma unroll
-                    for (int pl = 0; pl < P; ++pl) dst[r][pl] = tab[(pl * M + m) * kK + c];
-                }
-            };
-            issue(0, v[0]);
-#pragma unroll
-            for (int grp = 0; grp < NG; ++grp) {
-                if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int r = 0; r < RM; ++r)
-#pragma unroll
-                    for (int pl = 0; pl < P; ++pl) {
-                        const uint4 x = v[grp & 1][r][pl];
-                        const unsigned w4[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            A[8 * pl + 2 * e] = add_bf16_sel(w4[e], sel_lo, A[8 * pl + 2 * e]);
-                            A[8 * pl + 2 * e + 1] = add_bf16_sel(w4[e], sel_hi, A[8 * pl + 2 * e + 1]);
-                        }
-                    }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // E = E_hi E_lo; B = A E; logit_h += sum_j Re(q_h conj(B))
-#pragma unroll
-            for (int jj = 0; jj < NJ; ++jj) {
-                // (loaded after the gather on purpose: 32 fewer live registers while the LDS reads
-                // are in flight; these are L1 hits on the vector-memory counter)
-                const float2 eh = tbl_hi[(size_t)hi * kJ + sl * NJ + jj];
-                const float2 el = tbl_lo[(size_t)lo0 * kJ + sl * NJ + jj];
-                const float hy = H < 0 ? -eh.y : eh.y;
-                const float ex = eh.x * el.x - hy * el.y;
-                const float ey = eh.x * el.y + hy * el.x;
-                const float bx = A[2 * jj] * ex - A[2 * jj + 1] * ey;
-                const float by = A[2 * jj] * ey + A[2 * jj + 1] * ex;
-#pragma unroll
-                for (int hh = 0; hh < G; ++hh) {
-                    sc[k][hh] = __builtin_fmaf(qx[hh][jj], bx, sc[k][hh]);
-                    sc[k][hh] = __builtin_fmaf(qy[hh][jj], by, sc[k][hh]);
-                }
-            }
-        }
-    }
-
-    // write the logits (consecutive lanes = consecutive tokens) and the tile's (max, sum exp)
-    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        float mx = -INFINITY;
-#pragma unroll
-        for (int k = 0; k < TPT; ++k) {
-            const int tok = t0 + k * kSliceThreads + tid;
-            if (tok < L) {
-                srow[(size_t)hh * L + tok] = sc[k][hh];
-                mx = fmaxf(mx, sc[k][hh]);
-            }
-        }
-        const float wm = wave_max(mx);
-        float l = 0.f;
-#pragma unroll
-        for (int k = 0; k < TPT; ++k)
-            if (t0 + k * kSliceThreads + tid < L) l += __builtin_amdgcn_exp2f((sc[k][hh] - wm) * kLog2e);
-        l = wave_sum(l);
-        if (lane == 0) wstat[wave][hh] = make_float2(wm, l);
-    }
-    __syncthreads();
-    if (tid < G) {
-        float m = -INFINITY;
-        for (int w = 0; w < kSliceThreads / 64; ++w) m = fmaxf(m, wstat[w][tid].x);
-        float l = 0.f;
-        for (int w = 0; w < kSliceThreads / 64; ++w) {
-            const float2 st = wstat[w][tid];
-            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
-        }
-        sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
-    }
-}
 
 // ------------------------------------------------------------------ k_score_mfma
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -765,10 +583,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     constexpr int NPG = 16 / G;                               // sets per accumulator (row groups)
     constexpr int NACC = (NVP + NPG - 1) / NPG;
     constexpr int NS = M / 2;                                 // gather MFMAs per pass and slice
-    constexpr int CW = M / 4;
+    constexpr int CW = M / 8;                                 // code dwords a lane needs per token
     constexpr int HL = G < 4 ? G : 4;                         // distinct heads among a lane's 4 registers
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
-    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [P][M][K] 16-byte pieces
+    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [K][32] 16-byte pieces
     __shared__ float2 wstat[NW][G];
 
     int id = blockIdx.x;
@@ -812,10 +630,19 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 #pragma unroll
     for (int x = 0; x < NACC; ++x) dacc[x] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-    // byte offset of the lane's first piece: ((plane * M + par) * K) * 16
-    const unsigned lane_base = (unsigned)((plane * M + par) * kK) * 16u;
-    // bit offsets of the lane's code inside a code dword for even / odd steps (codebook 2 st + par)
-    const unsigned boff0 = 8u * par, boff2 = 16u + 8u * par;
+    // The lane gathers the 8 codebooks 8 par .. 8 par + 7 (M = 32: and 16 more) of its token, in the
+    // rotated order (n + st) mod 8: in every group of lanes that the LDS checks against each other
+    // for bank conflicts the 16 pieces then come from 16 different bank columns, whatever the codes.
+    unsigned xofs[8];  // byte offset of the piece column read at step st (row stride 512 bytes)
+#pragma unroll
+    for (int st = 0; st < 8; ++st) xofs[st] = (unsigned)(16 * plane + 8 * par + ((n + st) & 7)) * 16u;
+    // byte selectors that rotate the lane's 8 code bytes by n mod 8, so that step st finds its code at byte st
+    unsigned rsel_lo = 0u, rsel_hi = 0u;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        rsel_lo |= (unsigned)((x + n) & 7) << (8 * x);
+        rsel_hi |= (unsigned)((x + 4 + n) & 7) << (8 * x);
+    }
 
     // Codes are fetched one pass ahead (the fetch for pass 0 of the next slice rides on the last
     // pass of this one), so that their latency hides behind a whole pass of gather work.  tb is the
@@ -826,9 +653,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     auto fetch_codes = [&](int p, unsigned(&dst)[CW]) {
         const int tok = min(tb + p * NW * 16 * SETS, L - 1);
 #pragma unroll
-        for (int v = 0; v < M / 16; ++v) {
-            const uint4_t c4 = __builtin_amdgcn_raw_buffer_load_b128(cd_rs, (unsigned)tok * M + 16u * v, 0, 0);
-            dst[4 * v + 0] = c4[0]; dst[4 * v + 1] = c4[1]; dst[4 * v + 2] = c4[2]; dst[4 * v + 3] = c4[3];
+        for (int v = 0; v < M / 16; ++v) {  // bytes 16 v + 8 par .. + 7 of the token's codes
+            const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * M + 8u * par + 16u * v, 0, 0);
+            dst[2 * v + 0] = c2[0]; dst[2 * v + 1] = c2[1];
         }
     };
     fetch_codes(0, cw[0]);
@@ -866,7 +693,12 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             __builtin_amdgcn_sched_barrier(0);
             fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
-            const unsigned(&cc)[CW] = cw[p & 1];
+            unsigned cc[CW];
+#pragma unroll
+            for (int v = 0; v < M / 16; ++v) {
+                cc[2 * v + 0] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_lo);
+                cc[2 * v + 1] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_hi);
+            }
 
             // 1. gather-sum on the matrix cores; LDS reads in groups of RG, two groups in flight
             floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -875,10 +707,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             auto issue = [&](int grp, uint4(&dst)[RG]) {
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
-                    const int st = grp * RG + r;  // codebooks 2 st, 2 st + 1
-                    const unsigned c = __builtin_amdgcn_ubfe(cc[st / 2], (st & 1) ? boff2 : boff0, 8u);
-                    dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + lane_base +
-                                                              (unsigned)st * (2u * kK * 16u) + c * 16u);
+                    const int st = grp * RG + r;  // step st reads codebook 16 (st / 8) + 8 par + (n + st) mod 8
+                    const unsigned c = __builtin_amdgcn_ubfe(cc[st / 4], 8u * (st % 4), 8u);
+                    dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + (st / 8) * 256 +
+                                                              (xofs[st % 8] + c * 512u));
                 }
             };
             issue(0, v[0]);
@@ -1276,23 +1108,13 @@ hipError_t launch_sliced_mgt(const SliceArgs &a, int grid, hipStream_t s)
 {
     static bool attr_set = false;  // per instantiation; raising the limit is idempotent
     if (!attr_set) {
-#ifdef COMMVQ_SCORE_VALU_SLICED
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_sliced<M, G, TPT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSliceBytes);
-#else
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_mfma<M, G, TPT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kSliceBytes);
-#endif
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-#ifdef COMMVQ_SCORE_VALU_SLICED
-    hipLaunchKernelGGL((k_score_sliced<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kSliceBytes, s, a.qs, a.key_codes,
-                       a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
-#else
     hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kSliceBytes, s, a.qs, a.key_codes,
                        a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
-#endif
     return hipGetLastError();
 }
 template <int M, int G>
