@@ -482,12 +482,13 @@ constexpr int kSliceThreads = 1024;              // one workgroup per compute un
 constexpr int kSliceBytes = 128 * 1024;          // LDS bytes of one codebook slice
 
 // Key codebook re-laid for k_score_mfma, plus the scaled queries in fp32.
-//   packed[g][s][c][x] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of every
-//                        codeword (DS = 256 / M, S = 128 / DS slices) as one contiguous 128 KiB block
-//                        of 256 rows (one per code value c) x 32 pieces: x = 16 * plane + m for M = 16
-//                        (plane = which 8 of the 16 elements), x = m for M = 32.  A row spans all 64
-//                        LDS banks twice, so piece x lives in bank column x mod 16 whatever its code:
-//                        lanes that read different columns never conflict.
+//   packed[g][s][blk][c][col] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of
+//                        every codeword (DS = 256 / M, S = 128 / DS slices) as one contiguous 128 KiB
+//                        image of two 64 KiB blocks of 256 rows (one per code value c) x 16 pieces:
+//                        piece x = 16 blk + col with x = 16 * plane + m for M = 16 (plane = which 8 of
+//                        the 16 elements) and x = m for M = 32.  A 256-byte row spans all 64 LDS banks,
+//                        so a piece lives in bank column col whatever its code: lanes that read
+//                        different columns never conflict.
 //   qs[b][h][d]        : q * softmax scale
 // One thread per 16-byte piece of the source (coalesced reads).
 __global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, uint4 *__restrict__ packed,
@@ -505,7 +506,8 @@ __global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, 
         const int m = mc / kK, c = mc % kK;
         const int sl = piece / P, pl = piece % P;
         const int S = 16 / P;
-        packed[(((size_t)g * S + sl) * kK + c) * 32 + pl * 16 + m] = key_cb[t];
+        const int x = pl * 16 + m;              // 0..31: block x / 16, bank column x % 16
+        packed[((((size_t)g * S + sl) * 2 + x / 16) * kK + c) * 16 + x % 16] = key_cb[t];
     }
     if (t < (size_t)n_q) {
         float v;
@@ -586,7 +588,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     constexpr int CW = M / 8;                                 // code dwords a lane needs per token
     constexpr int HL = G < 4 ? G : 4;                         // distinct heads among a lane's 4 registers
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
-    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [K][32] 16-byte pieces
+    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces
     __shared__ float2 wstat[NW][G];
 
     int id = blockIdx.x;
@@ -633,9 +635,12 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     // The lane gathers the 8 codebooks 8 par .. 8 par + 7 (M = 32: and 16 more) of its token, in the
     // rotated order (n + st) mod 8: in every group of lanes that the LDS checks against each other
     // for bank conflicts the 16 pieces then come from 16 different bank columns, whatever the codes.
-    unsigned xofs[8];  // byte offset of the piece column read at step st (row stride 512 bytes)
+    // xreg[st]: byte 0 = 16 * column read at step st, byte 2 = 64 KiB block of the lane (M = 16: its
+    // plane), byte 3 = 1; a byte permute splices the code in as byte 1, which yields the LDS byte
+    // address 65536 blk + 256 c + 16 col in one instruction.
+    unsigned xreg[8];
 #pragma unroll
-    for (int st = 0; st < 8; ++st) xofs[st] = (unsigned)(16 * plane + 8 * par + ((n + st) & 7)) * 16u;
+    for (int st = 0; st < 8; ++st) xreg[st] = (unsigned)(8 * par + ((n + st) & 7)) * 16u | (unsigned)plane << 16 | 1u << 24;
     // byte selectors that rotate the lane's 8 code bytes by n mod 8, so that step st finds its code at byte st
     unsigned rsel_lo = 0u, rsel_hi = 0u;
 #pragma unroll
@@ -708,9 +713,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
                     const int st = grp * RG + r;  // step st reads codebook 16 (st / 8) + 8 par + (n + st) mod 8
-                    const unsigned c = __builtin_amdgcn_ubfe(cc[st / 4], 8u * (st % 4), 8u);
-                    dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + (st / 8) * 256 +
-                                                              (xofs[st % 8] + c * 512u));
+                    // address bytes: [0] column, [1] code byte st % 4 of its dword, [2] block (M = 32: st / 8), [3] zero
+                    const unsigned sel = 0x0c000000u | (unsigned)(M == 16 ? 2 : 2 + st / 8) << 16 | (unsigned)(4 + st % 4) << 8;
+                    const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], sel);
+                    dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + addr);
                 }
             };
             issue(0, v[0]);
