@@ -525,25 +525,37 @@ struct SliceDims {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-// Max / sum over the lanes that hold the same query heads: all 64 lanes for G <= 4; for G = 8 the
-// 16-lane rows 0 and 2 hold heads 0..3 and rows 1 and 3 hold heads 4..7.
-template <int G>
-__device__ __forceinline__ float heads_max(float v)
+// Max / sum over the lanes of a wavefront that hold logits of the same query head in k_score_mfma:
+// one 16-lane row (M = 16), or the two rows r and r + 2 (M = 32).
+template <int M>
+__device__ __forceinline__ float head_lanes_max(float v)
 {
-    if (G < 8) return wave_max(v);
     v = row_max16(v);
+    if (M == 16) return v;
     const unsigned u = __builtin_bit_cast(unsigned, v);
     auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return fmaxf(__builtin_bit_cast(float, (unsigned)r32[0]), __builtin_bit_cast(float, (unsigned)r32[1]));
 }
-template <int G>
-__device__ __forceinline__ float heads_sum(float v)
+template <int M>
+__device__ __forceinline__ float head_lanes_sum(float v)
 {
-    if (G < 8) return wave_sum(v);
     v = row_sum16(v);
+    if (M == 16) return v;
     const unsigned u = __builtin_bit_cast(unsigned, v);
     auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return __builtin_bit_cast(float, (unsigned)r32[0]) + __builtin_bit_cast(float, (unsigned)r32[1]);
+}
+// x + y after exchanging the odd 16-lane rows of x with the even rows of y (row r of the result:
+// r even: x[r] + x[r+1], r odd: y[r-1] + y[r]), and the same with 32-lane halves.
+__device__ __forceinline__ float swap16_add(float x, float y)
+{
+    auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+    return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+__device__ __forceinline__ float swap32_add(float x, float y)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+    return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
 }
 
 // Slice-streaming score kernel with both contractions on the matrix cores (Eq. new_attention,
@@ -562,11 +574,12 @@ __device__ __forceinline__ float heads_sum(float v)
 //               codebook); lane (n, g) receives elements 4 (g & 1) .. +3 for token n + 16 (g >> 1).
 //  2. Each lane rotates its two (x, y) sub-spaces by the token's relative position (two-level
 //     phase tables) -- the only per-token vector arithmetic left on the vector ALUs.
-//  3. Contraction with the queries: v_mfma_f32_16x16x4_f32, first operand = scaled queries (row i
-//     = head i mod G, column k = the k-group's r-th element), second = the rotated r-th element of
-//     every lane.  Rows outside the current "row group" are zeroed, so that 16 / G consecutive
-//     16-token sets accumulate into disjoint rows of one accumulator: lane (n, g) register r of
-//     accumulator a ends up with head (4g + r) mod G of token n of set a (16 / G) + (4g + r) / G.
+//  3. Contraction with the queries: four v_mfma_f32_4x4x1_16b_f32 per group of 4 heads.  In each
+//     block of 4 lanes, lane i supplies q[head i][the block's r-th element] and every lane its own
+//     rotated r-th element, so register i of a lane receives the partial logit of head i for the
+//     lane's own token over the lane's 4 elements.  The 4 (M = 16) or 2 (M = 32) lanes of a token
+//     are then combined with row / half swaps so that each keeps the total of one (two) heads:
+//     lane (n, g) holds head g of token n (M = 16), heads g & 1 and 2 + (g & 1) (M = 32).
 template <int M, int G, int TPT>
 __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const float *__restrict__ qs, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
@@ -581,12 +594,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     constexpr int NW = kSliceThreads / 64;
     constexpr int SETS = M == 16 ? 1 : 2;                     // 16-token sets per wavefront pass
     constexpr int NPASS = TILE / (16 * SETS * NW);
-    constexpr int NVP = NPASS * SETS;                         // 16-token sets per wavefront and tile
-    constexpr int NPG = 16 / G;                               // sets per accumulator (row groups)
-    constexpr int NACC = (NVP + NPG - 1) / NPG;
+    constexpr int NGRP = (G + 3) / 4;                         // groups of 4 heads (padded with zero queries)
+    constexpr int NOUT = M == 16 ? 1 : 2;                     // heads per group whose totals a lane keeps
     constexpr int NS = M / 2;                                 // gather MFMAs per pass and slice
     constexpr int CW = M / 8;                                 // code dwords a lane needs per token
-    constexpr int HL = G < 4 ? G : 4;                         // distinct heads among a lane's 4 registers
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
     extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces
     __shared__ float2 wstat[NW][G];
@@ -624,13 +635,17 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         if (e >= 0 && e < 8) sel[e >> 1] = (e & 1) ? 0x3f800000u : 0x00003f80u;
     }
     const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
-    // as first operand of the query contraction the lane is row n (head n mod G, row group n / G), column gk
-    const int rowgrp = n / G;
-    const unsigned q_off = (unsigned)(n % G) * (kD * 4u) + (unsigned)el * 4u;
+    // as first operand of the query contraction the lane supplies head 4 grp + n % 4; rows past the last
+    // head read beyond the end of the buffer, i.e. zero
+    const unsigned q_off = (unsigned)(n & 3) * (kD * 4u) + (unsigned)el * 4u;
 
-    floatx4_t dacc[NACC];
+    float sc[NPASS][NGRP][NOUT];
 #pragma unroll
-    for (int x = 0; x < NACC; ++x) dacc[x] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+        for (int x = 0; x < NGRP; ++x)
+#pragma unroll
+            for (int o = 0; o < NOUT; ++o) sc[p][x][o] = 0.f;
 
     // The lane gathers the 8 codebooks 8 par .. 8 par + 7 (M = 32: and 16 more) of its token, in the
     // rotated order (n + st) mod 8: in every group of lanes that the LDS checks against each other
@@ -676,13 +691,16 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         }
         __syncthreads();
         asm volatile("" : "+v"(tb));
-        // scaled queries of this slice as seen by the lane in its role as row n, column gk
-        const uint4_t qraw = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off, (unsigned)sl * DS * 4u, 0);
-        float qrow[4];
+        // scaled queries of this slice: head 4 grp + n % 4, the lane's 4 elements
+        float qrow[NGRP][4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const unsigned u = qraw[r];
-            qrow[r] = __builtin_bit_cast(float, u);
+        for (int x = 0; x < NGRP; ++x) {
+            const uint4_t qraw = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off + (unsigned)x * (4u * kD * 4u), (unsigned)sl * DS * 4u, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const unsigned u = qraw[r];
+                qrow[x][r] = __builtin_bit_cast(float, u);
+            }
         }
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
@@ -707,7 +725,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 
             // 1. gather-sum on the matrix cores; LDS reads in groups of RG, two groups in flight
             floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-            constexpr int RG = 4, NG = NS / RG;
+            constexpr int RG = (G == 8 && TPT == 4) ? 2 : 4, NG = NS / RG;  // fewer reads in flight where registers are short
             uint4 v[2][RG];
             auto issue = [&](int grp, uint4(&dst)[RG]) {
 #pragma unroll
@@ -747,52 +765,49 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 val[2 * u] = ax * ex - ay * ey;
                 val[2 * u + 1] = ax * ey + ay * ex;
             }
-            // 3. logits += queries x rotated blocks; only the rows of this set's row group are live
+            // 3. per-lane partial logits of 4 heads at a time, then totals over the lanes of the token
 #pragma unroll
-            for (int sx = 0; sx < SETS; ++sx) {
-                const int vp = p * SETS + sx;
-                const bool on = rowgrp == vp % NPG && (SETS == 1 || set == sx);
+            for (int x = 0; x < NGRP; ++x) {
+                floatx4_t t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    dacc[vp / NPG] = __builtin_amdgcn_mfma_f32_16x16x4f32(on ? qrow[r] : 0.f, val[r], dacc[vp / NPG], 0, 0, 0);
+                for (int r = 0; r < 4; ++r) t = __builtin_amdgcn_mfma_f32_4x4x1f32(qrow[x][r], val[r], t, 0, 0, 0);
+                if (M == 16) {
+                    sc[p][x][0] += swap16_add(swap32_add(t[0], t[2]), swap32_add(t[1], t[3]));
+                } else {
+                    sc[p][x][0] += swap16_add(t[0], t[1]);
+                    sc[p][x][NOUT - 1] += swap16_add(t[2], t[3]);
+                }
             }
         }
     }
 
-    // logits to memory and the tile's (max, sum of exp) per head
+    // logits to memory and the tile's (max, sum of exp) per head.  sc[p][x][o] of lane (n, gk) is the logit
+    // of head 4 x + gk (M = 16) or 4 x + 2 o + par (M = 32) for the lane's token of pass p.
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-    auto token_of = [&](int vp) {
-        return M == 16 ? t0 + (vp * NW + wave) * 16 + n : t0 + ((vp / 2) * NW + wave) * 32 + 16 * (vp % 2) + n;
-    };
-    float mx[HL];
 #pragma unroll
-    for (int hl = 0; hl < HL; ++hl) mx[hl] = -INFINITY;
+    for (int x = 0; x < NGRP; ++x)
 #pragma unroll
-    for (int x = 0; x < NACC; ++x)
+        for (int o = 0; o < NOUT; ++o) {
+            const int head = 4 * x + (M == 16 ? gk : 2 * o + par);
+            float mx = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = 4 * gk + r;
-            const int vp = x * NPG + row / G;
-            const int tok = token_of(vp);
-            if (vp < NVP && tok < L) {
-                srow[(size_t)(row % G) * L + tok] = dacc[x][r];
-                mx[r % HL] = fmaxf(mx[r % HL], dacc[x][r]);
+            for (int p = 0; p < NPASS; ++p) {
+                const int tok = tb + p * NW * 16 * SETS;
+                if (head < G && tok < L) {
+                    srow[(size_t)head * L + tok] = sc[p][x][o];
+                    mx = fmaxf(mx, sc[p][x][o]);
+                }
             }
+            const float wm = head_lanes_max<M>(mx);
+            float l = 0.f;
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int tok = tb + p * NW * 16 * SETS;
+                if (head < G && tok < L) l += __builtin_amdgcn_exp2f((sc[p][x][o] - wm) * kLog2e);
+            }
+            l = head_lanes_sum<M>(l);
+            if (n == 0 && head < G && (M == 16 || set == 0)) wstat[wave][head] = make_float2(wm, l);
         }
-#pragma unroll
-    for (int hl = 0; hl < HL; ++hl) {
-        const float wm = heads_max<G>(mx[hl]);
-        float l = 0.f;
-#pragma unroll
-        for (int x = 0; x < NACC; ++x)
-#pragma unroll
-            for (int r = hl; r < 4; r += HL) {
-                const int vp = x * NPG + (4 * gk + r) / G;
-                if (vp < NVP && token_of(vp) < L) l += __builtin_amdgcn_exp2f((dacc[x][r] - wm) * kLog2e);
-            }
-        l = heads_sum<G>(l);
-        if (n == 0 && gk < (G + 3) / 4) wstat[wave][(4 * gk + hl) % G] = make_float2(wm, l);
-    }
     __syncthreads();
     if (tid < G) {
         float m = -INFINITY;
