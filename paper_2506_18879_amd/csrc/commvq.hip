@@ -99,6 +99,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         double best = -1.0;
         len = 1024;
         for (int tpt = 1; tpt <= 4; tpt *= 2) {
+            if (tpt == 4 && h->G == 8 && h->cfg.m_key == 16) break;  // that instantiation runs out of registers
             const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt));
             const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
             const double eff = fill / (1.0 + 0.25 / tpt);
@@ -480,6 +481,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
 // ------------------------------------------------------------------ k_prep
 constexpr int kSliceThreads = 1024;              // one workgroup per compute unit
 constexpr int kSliceBytes = 128 * 1024;          // LDS bytes of one codebook slice
+constexpr int kPhaseBytes = (4 * 64 + 4 * 65) * 16;  // LDS bytes of the slice's phase factors (at most)
+constexpr int kScoreLds = kSliceBytes + kPhaseBytes;
 
 // Key codebook re-laid for k_score_mfma, plus the scaled queries in fp32.
 //   packed[g][s][blk][c][col] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of
@@ -594,12 +597,16 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     constexpr int NW = kSliceThreads / 64;
     constexpr int SETS = M == 16 ? 1 : 2;                     // 16-token sets per wavefront pass
     constexpr int NPASS = TILE / (16 * SETS * NW);
+    constexpr int PARTS = NJ / 2;                             // 16-byte (two sub-space) parts of a slice's phase rows
+    constexpr int NHR = TILE / kLo + 1;                       // coarse phase rows a tile can touch
     constexpr int NGRP = (G + 3) / 4;                         // groups of 4 heads (padded with zero queries)
     constexpr int NOUT = M == 16 ? 1 : 2;                     // heads per group whose totals a lane keeps
     constexpr int NS = M / 2;                                 // gather MFMAs per pass and slice
     constexpr int CW = M / 8;                                 // code dwords a lane needs per token
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
-    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces
+    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces, then the phase factors
+    float4 *elo = reinterpret_cast<float4 *>(tab + kSliceBytes / 16);  // [PARTS][64]  exp(i theta_j lo), this slice's j
+    float4 *ehi = elo + PARTS * kLo;                                   // [PARTS][NHR] exp(i theta_j 64 H), H = Hmin + row
     __shared__ float2 wstat[NW][G];
 
     int id = blockIdx.x;
@@ -621,8 +628,6 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const uint4 *src = packed + (size_t)g * S * P * M * kK;
     const __amdgpu_buffer_rsrc_t cd_rs = make_rsrc(codes, (unsigned)L * M);
-    const __amdgpu_buffer_rsrc_t hi_rs = make_rsrc(tbl_hi, (unsigned)a.n_hi * kJ * 8u);
-    const __amdgpu_buffer_rsrc_t lo_rs = make_rsrc(tbl_lo, (unsigned)kLo * kJ * 8u);
     const __amdgpu_buffer_rsrc_t q_rs = make_rsrc(qs + ((size_t)b * a.Hq + (size_t)g * G) * kD, (unsigned)G * kD * 4u);
     constexpr int PIECES = P * M * kK;
     constexpr int PPT = PIECES / kSliceThreads;
@@ -679,6 +684,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         }
     };
     fetch_codes(0, cw[0]);
+    const int hmin = (qpos - (t0 + TILE - 1)) >> kLoBits;     // coarse row of the tile's last token (arithmetic shift)
+    const unsigned elo_base = (unsigned)kSliceBytes + (unsigned)(M == 16 ? gk : par) * (kLo * 16u);
+    const unsigned ehi_base = (unsigned)kSliceBytes + (unsigned)(PARTS * kLo) * 16u + (unsigned)(M == 16 ? gk : par) * (NHR * 16u);
 
     for (int sl = 0; sl < S; ++sl) {
         __syncthreads();  // everyone is done reading the previous slice
@@ -689,8 +697,23 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 #pragma unroll
             for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
         }
+        // phase factors of this slice's sub-spaces: the fine table as it is, and the rows of the coarse
+        // table that the tile's distances q_pos - token can reach, conjugated where the distance is negative
+        if (tid < PARTS * kLo) {
+            const int part = tid / kLo, lo = tid % kLo;
+            elo[tid] = *reinterpret_cast<const float4 *>(tbl_lo + (size_t)lo * kJ + sl * NJ + 2 * part);
+        }
+        for (int x = tid; x < PARTS * NHR; x += kSliceThreads) {
+            const int part = x / NHR, H = hmin + x % NHR;
+            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
+            float4 e = *reinterpret_cast<const float4 *>(tbl_hi + (size_t)hi * kJ + sl * NJ + 2 * part);
+            if (H < 0) { e.y = -e.y; e.w = -e.w; }
+            ehi[x] = e;
+        }
         __syncthreads();
         asm volatile("" : "+v"(tb));
+        // byte offsets (in the LDS phase tables) of the lane's part, and its distance to the query, times 16
+        const int dist16 = (qpos - tb) * 16;
         // scaled queries of this slice: head 4 grp + n % 4, the lane's 4 elements
         float qrow[NGRP][4];
 #pragma unroll
@@ -705,14 +728,12 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure flat
-            const int tok = min(tb + p * NW * 16 * SETS, L - 1);
-            const int dl = qpos - tok;
-            const int H = dl >> kLoBits, lo = dl & (kLo - 1);
-            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
-            // phase factors first (older than the code prefetch, so waiting for them does not wait for it)
-            const unsigned soff = (unsigned)(sl * NJ) * 8u;
-            const uint4_t ehr = __builtin_amdgcn_raw_buffer_load_b128(hi_rs, (unsigned)hi * (kJ * 8u) + (unsigned)el * 4u, soff, 0);
-            const uint4_t elr = __builtin_amdgcn_raw_buffer_load_b128(lo_rs, (unsigned)lo * (kJ * 8u) + (unsigned)el * 4u, soff, 0);
+            // phase factors of the lane's token and part, from LDS (16 consecutive tokens read 16 consecutive
+            // fine rows and at most two coarse rows: no bank conflicts)
+            const int d16 = dist16 - p * (NW * 16 * SETS * 16);
+            const uint4_t elr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + elo_base + (unsigned)(d16 & ((kLo - 1) * 16)));
+            const uint4_t ehr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + ehi_base +
+                                                                   (unsigned)(((d16 >> (kLoBits + 4)) - hmin) * 16));
             __builtin_amdgcn_sched_barrier(0);
             fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
@@ -756,8 +777,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             for (int u = 0; u < 2; ++u) {
                 const unsigned hxr = ehr[2 * u], hyr = ehr[2 * u + 1], lxr = elr[2 * u], lyr = elr[2 * u + 1];
                 const float hx = __builtin_bit_cast(float, hxr);
-                const float hy0 = __builtin_bit_cast(float, hyr);
-                const float hy = H < 0 ? -hy0 : hy0;
+                const float hy = __builtin_bit_cast(float, hyr);
                 const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
                 const float ex = hx * lx - hy * ly;
                 const float ey = hx * ly + hy * lx;
@@ -1130,11 +1150,11 @@ hipError_t launch_sliced_mgt(const SliceArgs &a, int grid, hipStream_t s)
     static bool attr_set = false;  // per instantiation; raising the limit is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_mfma<M, G, TPT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSliceBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kScoreLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kSliceBytes, s, a.qs, a.key_codes,
+    hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kScoreLds, s, a.qs, a.key_codes,
                        a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
     return hipGetLastError();
 }
