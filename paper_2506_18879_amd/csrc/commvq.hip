@@ -482,7 +482,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
 constexpr int kSliceThreads = 1024;              // one workgroup per compute unit
 constexpr int kSliceBytes = 128 * 1024;          // LDS bytes of one codebook slice
 constexpr int kPhaseBytes = (4 * 64 + 4 * 65) * 16;  // LDS bytes of the slice's phase factors (at most)
-constexpr int kScoreLds = kSliceBytes + kPhaseBytes;
+constexpr int kStatBytes = (kSliceThreads / 64) * 8 * 8;  // per-wavefront (max, sum) of up to 8 heads
+constexpr int kScoreLds = kSliceBytes + kPhaseBytes + kStatBytes;
 
 // Key codebook re-laid for k_score_mfma, plus the scaled queries in fp32.
 //   packed[g][s][blk][c][col] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of
@@ -607,7 +608,8 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces, then the phase factors
     float4 *elo = reinterpret_cast<float4 *>(tab + kSliceBytes / 16);  // [PARTS][64]  exp(i theta_j lo), this slice's j
     float4 *ehi = elo + PARTS * kLo;                                   // [PARTS][NHR] exp(i theta_j 64 H), H = Hmin + row
-    __shared__ float2 wstat[NW][G];
+    // the slice sits at LDS address 0 (no static LDS in this kernel), so gather addresses need no base added
+    float2(*wstat)[G] = reinterpret_cast<float2(*)[G]>(reinterpret_cast<char *>(tab) + kSliceBytes + kPhaseBytes);  // [NW][G]
 
     int id = blockIdx.x;
     const int g = id % a.Hkv;
