@@ -690,15 +690,21 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const unsigned elo_base = (unsigned)kSliceBytes + (unsigned)(M == 16 ? gk : par) * (kLo * 16u);
     const unsigned ehi_base = (unsigned)kSliceBytes + (unsigned)(PARTS * kLo) * 16u + (unsigned)(M == 16 ? gk : par) * (NHR * 16u);
 
+    // The next slice is fetched into registers while the last pass of the current one finishes (its
+    // gather registers are dead by then).
+    const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(src, (unsigned)S * PIECES * 16u);
+    uint4_t stage[PPT];
+    auto fetch_slice = [&](int sl) {
+#pragma unroll
+        for (int x = 0; x < PPT; ++x)
+            stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, (unsigned)sl * (PIECES * 16u), 0);
+    };
+    fetch_slice(0);
+
     for (int sl = 0; sl < S; ++sl) {
         __syncthreads();  // everyone is done reading the previous slice
-        {
-            uint4 stage[PPT];
 #pragma unroll
-            for (int x = 0; x < PPT; ++x) stage[x] = src[(size_t)sl * PIECES + x * kSliceThreads + tid];
-#pragma unroll
-            for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
-        }
+        for (int x = 0; x < PPT; ++x) reinterpret_cast<uint4_t *>(tab)[x * kSliceThreads + tid] = stage[x];
         // phase factors of this slice's sub-spaces: the fine table as it is, and the rows of the coarse
         // table that the tile's distances q_pos - token can reach, conjugated where the distance is negative
         if (tid < PARTS * kLo) {
@@ -773,6 +779,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (p == NPASS - 1) fetch_slice(min(sl + 1, S - 1));  // after the last slice: a harmless re-read
             // 2. E = E_hi E_lo for the lane's two sub-spaces; rotated block = A E
             float val[4];
 #pragma unroll
