@@ -103,6 +103,26 @@ def test_group_sizes_and_dtypes(gpu, oracle, G, Hkv, dtype):
     check(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (8, 1)])
+@pytest.mark.parametrize("L", [900, 2600, 5000])
+def test_one_bit_keys_group_sizes_and_tile_lengths(gpu, oracle, G, Hkv, L):
+    # M_k = 16 with every group size, at lengths that select 1024-, 2048- and 4096-token score tiles
+    w = synth.make_workload(f"m16_g{G}_L{L}", B=1, Hq=G * Hkv, Hkv=Hkv, seqlens=[L], Mk=16, Mv=16, dtype="bf16",
+                            seed=31 * G + L)
+    check(gpu, oracle, w)
+
+
+@pytest.mark.parametrize("Mk", [16, 32])
+@pytest.mark.parametrize("qpos", [0, 1234, 70000])
+def test_contiguous_keys_with_query_inside_or_far_beyond_the_context(gpu, oracle, Mk, qpos):
+    # implicit key positions 0..L-1 with the query at the start, in the middle (distances of both
+    # signs inside one tile) and far past the end (large coarse phase index)
+    w = synth.make_workload(f"qpos{qpos}_m{Mk}", B=2, Hq=8, Hkv=2, seqlens=[2500, 1300], Mk=Mk, Mv=16, dtype="bf16",
+                            seed=17 + qpos + Mk)
+    w.q_pos = np.array([qpos, qpos // 2], np.int32)
+    check(gpu, oracle, w, max_position=80000)
+
+
 def test_ragged_batch_with_length_one_sequence(gpu, oracle):
     w = synth.make_workload("ragged", B=5, Hq=8, Hkv=2, seqlens=[1, 2100, 64, 1, 517], Mk=32, Mv=32, dtype="bf16", seed=5)
     got, ref = check(gpu, oracle, w)
