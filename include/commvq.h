@@ -124,6 +124,24 @@ commvq_status commvq_decode_attn(commvq_handle *handle, const void *q, const uin
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * Optional one-time preparation of static key codebooks (they are per-layer constants, Sec. 4.1).
+ * The score kernel for bf16 codebooks streams the key codebook through LDS in slices of
+ * 256 / M_k elements (Eq. new_attention is evaluated slice by slice) and wants it in that order.
+ * Without preparation every commvq_decode_attn call re-lays the codebook into its workspace
+ * first (one extra read + write of the codebook).  commvq_pack_key_codebooks does it once:
+ *   key_codebooks  [Hkv][M_k][K][d] bf16, as for commvq_decode_attn
+ *   packed         device buffer of commvq_packed_key_codebook_bytes() bytes, 16-byte aligned,
+ *                  owned by the caller; must stay alive and unchanged while registered
+ * and remembers the pair in the handle: later calls that pass the same key_codebooks pointer
+ * use `packed` instead of re-laying (the caller vouches that the contents did not change).
+ * Results are bit-identical either way.  commvq_forget_packed_key_codebooks drops one pair
+ * (or all, with NULL).  COMMVQ_ERR_CONFIG for fp32 codebooks (they take another kernel).
+ */
+commvq_status commvq_packed_key_codebook_bytes(const commvq_handle *handle, size_t *bytes);
+commvq_status commvq_pack_key_codebooks(commvq_handle *handle, const void *key_codebooks, void *packed, void *stream);
+commvq_status commvq_forget_packed_key_codebooks(commvq_handle *handle, const void *key_codebooks);
+
+/*
  * The three stages of commvq_decode_attn, callable on their own (tests and profiling).
  * They read/write the same workspace; run them in this order on one stream.
  *   commvq_stage_scores  Eq. new_attention: scaled logits for every (b, h, token) and the

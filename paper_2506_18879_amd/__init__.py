@@ -16,6 +16,9 @@ from .binding import (  # noqa: F401
     commvq_create,
     commvq_decode_attn,
     commvq_destroy,
+    commvq_forget_packed_key_codebooks,
+    commvq_pack_key_codebooks,
+    commvq_packed_key_codebook_bytes,
     commvq_plan_query,
     commvq_profile_enable,
     commvq_profile_read,

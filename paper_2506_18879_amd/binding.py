@@ -37,6 +37,7 @@ Handle = c_void_p
 
 EXPORTS = ("commvq_create", "commvq_destroy", "commvq_validate_config", "commvq_plan_query", "commvq_workspace_bytes",
            "commvq_decode_attn", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
+           "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
            "commvq_profile_enable", "commvq_profile_read", "commvq_status_string")
 
 
@@ -65,6 +66,9 @@ def load_library():
                                         c_void_p, c_void_p]
     lib.commvq_stage_bins.argtypes = [c_void_p, c_void_p, POINTER(Positions), c_void_p, c_size_t, c_void_p]
     lib.commvq_stage_output.argtypes = [c_void_p, c_void_p, POINTER(Positions), c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.commvq_packed_key_codebook_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
+    lib.commvq_pack_key_codebooks.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.commvq_forget_packed_key_codebooks.argtypes = [c_void_p, c_void_p]
     lib.commvq_profile_enable.argtypes = [c_void_p, c_int32]
     lib.commvq_profile_read.argtypes = [c_void_p, POINTER(c_float), POINTER(c_int32)]
     for name in EXPORTS:
@@ -128,6 +132,22 @@ def commvq_decode_attn(handle, q, key_codes, val_codes, key_codebooks, val_codeb
     _check(load_library().commvq_decode_attn(handle, _ptr(q), _ptr(key_codes), _ptr(val_codes), _ptr(key_codebooks),
                                              _ptr(val_codebooks), byref(positions), _ptr(out), _ptr(workspace),
                                              int(workspace_bytes), stream or None), "commvq_decode_attn")
+
+
+def commvq_packed_key_codebook_bytes(handle) -> int:
+    n = c_size_t()
+    _check(load_library().commvq_packed_key_codebook_bytes(handle, byref(n)), "commvq_packed_key_codebook_bytes")
+    return int(n.value)
+
+
+def commvq_pack_key_codebooks(handle, key_codebooks, packed, stream: int = 0) -> None:
+    _check(load_library().commvq_pack_key_codebooks(handle, _ptr(key_codebooks), _ptr(packed), stream or None),
+           "commvq_pack_key_codebooks")
+
+
+def commvq_forget_packed_key_codebooks(handle, key_codebooks=None) -> None:
+    _check(load_library().commvq_forget_packed_key_codebooks(handle, _ptr(key_codebooks)),
+           "commvq_forget_packed_key_codebooks")
 
 
 def commvq_stage_scores(handle, q, key_codes, key_codebooks, positions: Positions, workspace, workspace_bytes: int,

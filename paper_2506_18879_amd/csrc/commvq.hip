@@ -1,9 +1,13 @@
 // libcommvq: decode attention over a CommVQ-compressed KV cache, hand-written for gfx950.
 //
 // Pipeline of one call (all on the caller's stream):
-//   k_score     Eq. new_attention: per (token, KV head) gather-sum the M_k selected key
+//   score stage Eq. new_attention: per (token, KV head) gather-sum the M_k selected key
 //               codewords, rotate once by the RoPE matrix of the relative position, contract
-//               with the G query heads of the group -> scaled logits + per-split maxima.
+//               with the G query heads of the group -> scaled logits + per-split (max, sum exp).
+//               bf16 codebooks with contiguous key positions: k_prep (codebook re-laid in
+//               LDS-image order, queries scaled) + k_score_mfma (codebook slices streamed
+//               through LDS, gather-sum and query contraction on the matrix cores);
+//               fp32 codebooks or explicit key positions: k_score (rows gathered through L1).
 //   k_bins      Softmax(A) S_V of Eq. optimized_v (unnormalised): exp(logit - max) is
 //               scatter-added into LDS bins [G][M_v][K], one bin set per context split.  The
 //               bins are 32-bit fixed point (integer LDS atomics run ~20x faster than fp32 ones
@@ -24,6 +28,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "commvq.h"
@@ -35,6 +40,9 @@ constexpr int kJ = 64;          // 2-D sub-spaces = lanes of a wavefront
 constexpr int kK = 256;         // codewords per codebook
 constexpr int kLoBits = 6;      // relative position = hi * 64 + lo
 constexpr int kLo = 1 << kLoBits;
+#ifndef COMMVQ_SCORE_MAX_TPT
+#define COMMVQ_SCORE_MAX_TPT 4
+#endif
 #ifndef COMMVQ_SCORE_MIN_WGS
 #define COMMVQ_SCORE_MIN_WGS 2048
 #endif
@@ -66,6 +74,8 @@ struct commvq_handle {
     int prof_head, prof_count;
     hipEvent_t prof_ev[kProfRing][4];
     bool prof_ev_made;
+    // key codebooks that the caller has had re-laid once (commvq_pack_key_codebooks): source pointer -> packed copy
+    std::vector<std::pair<const void *, const uint4 *>> packed_keys;
 };
 
 namespace {
@@ -77,12 +87,11 @@ struct Workspace {
     float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over that value split
     unsigned *bins;   // [B * Hkv * value_splits][G * Mv * K] fixed-point bins
     float *partial;   // [B * Hq * out_chunks][d]
-    uint4 *packed;    // key codebook re-laid slice-major for k_score_sliced (same size as the codebook)
-    float *qs;        // [B * Hq][d] scaled queries in fp32
+    uint4 *packed;    // key codebook re-laid slice-major for k_score_mfma (same size as the codebook)
     size_t bytes;
 };
 
-// The sliced score kernel serves bf16 codebooks with contiguous positions; everything else
+// The slice-streaming score kernel (k_score_mfma) serves bf16 codebooks with contiguous positions; everything else
 // (fp32 codebooks, explicit key positions) goes through the gather kernel.
 bool use_sliced(const commvq_handle *h, bool explicit_positions)
 {
@@ -94,11 +103,11 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
     const int units = B * h->cfg.n_kv_heads;
     int len;
     if (sliced) {
-        // tokens per lane (1, 2 or 4): longer tiles amortise the LDS refill of each codebook slice
-        // (a quarter of a 1024-token gather), shorter ones fill the 256 compute units more evenly
+        // tile = 1024, 2048 or 4096 tokens: longer tiles amortise the LDS refill of each codebook slice
+        // (about a quarter of the work of 1024 tokens), shorter ones fill the 256 compute units more evenly
         double best = -1.0;
         len = 1024;
-        for (int tpt = 1; tpt <= 4; tpt *= 2) {
+        for (int tpt = 1; tpt <= COMMVQ_SCORE_MAX_TPT; tpt *= 2) {
             if (tpt == 4 && h->G == 8 && h->cfg.m_key == 16) break;  // that instantiation runs out of registers
             const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt));
             const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
@@ -145,7 +154,6 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * vsplits * h->G * c.m_val * kK));
     w->partial = take((size_t)B * c.n_q_heads * pa.out_chunks * kD);
     w->packed = reinterpret_cast<uint4 *>(take((size_t)c.n_kv_heads * c.m_key * kK * kD / 2));  // bf16 codebook
-    w->qs = take((size_t)B * c.n_q_heads * kD);
     w->bytes = off;
 }
 
@@ -485,7 +493,7 @@ constexpr int kPhaseBytes = (4 * 64 + 4 * 65) * 16;  // LDS bytes of the slice's
 constexpr int kStatBytes = (kSliceThreads / 64) * 8 * 8;  // per-wavefront (max, sum) of up to 8 heads
 constexpr int kScoreLds = kSliceBytes + kPhaseBytes + kStatBytes;
 
-// Key codebook re-laid for k_score_mfma, plus the scaled queries in fp32.
+// Key codebook re-laid for k_score_mfma.
 //   packed[g][s][blk][c][col] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of
 //                        every codeword (DS = 256 / M, S = 128 / DS slices) as one contiguous 128 KiB
 //                        image of two 64 KiB blocks of 256 rows (one per code value c) x 16 pieces:
@@ -493,36 +501,27 @@ constexpr int kScoreLds = kSliceBytes + kPhaseBytes + kStatBytes;
 //                        the 16 elements) and x = m for M = 32.  A 256-byte row spans all 64 LDS banks,
 //                        so a piece lives in bank column col whatever its code: lanes that read
 //                        different columns never conflict.
-//   qs[b][h][d]        : q * softmax scale
 // One thread per 16-byte piece of the source (coalesced reads).
-__global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, uint4 *__restrict__ packed,
-                                              const void *__restrict__ q, float *__restrict__ qs, int Hkv, int M,
-                                              int n_q, int q_bf16, float scale)
+__global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, uint4 *__restrict__ packed, int Hkv, int M)
 {
     const int P = 32 / M;                       // planes: DS / 8 = (256 / M) / 8
     const size_t n_pieces = (size_t)Hkv * M * kK * 16;
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (t < n_pieces) {
-        const int piece = (int)(t & 15);        // 16 pieces of 8 elements per row
-        const size_t row = t >> 4;              // (g * M + m) * K + c
-        const int g = (int)(row / ((size_t)M * kK));
-        const int mc = (int)(row % ((size_t)M * kK));
-        const int m = mc / kK, c = mc % kK;
-        const int sl = piece / P, pl = piece % P;
-        const int S = 16 / P;
-        const int x = pl * 16 + m;              // 0..31: block x / 16, bank column x % 16
-        packed[((((size_t)g * S + sl) * 2 + x / 16) * kK + c) * 16 + x % 16] = key_cb[t];
-    }
-    if (t < (size_t)n_q) {
-        float v;
-        if (q_bf16) v = __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(q)[t] << 16);
-        else v = static_cast<const float *>(q)[t];
-        qs[t] = v * scale;
-    }
+    if (t >= n_pieces) return;
+    const int piece = (int)(t & 15);            // 16 pieces of 8 elements per row
+    const size_t row = t >> 4;                  // (g * M + m) * K + c
+    const int g = (int)(row / ((size_t)M * kK));
+    const int mc = (int)(row % ((size_t)M * kK));
+    const int m = mc / kK, c = mc % kK;
+    const int sl = piece / P, pl = piece % P;
+    const int S = 16 / P;
+    const int x = pl * 16 + m;                  // 0..31: block x / 16, bank column x % 16
+    packed[((((size_t)g * S + sl) * 2 + x / 16) * kK + c) * 16 + x % 16] = key_cb[t];
 }
 
 struct SliceDims {
-    int Hq, Hkv, nsplit, n_hi;
+    int Hq, Hkv, nsplit, n_hi, q_bf16;
+    float scale;
 };
 
 // ------------------------------------------------------------------ k_score_mfma
@@ -586,7 +585,7 @@ __device__ __forceinline__ float swap32_add(float x, float y)
 //     lane (n, g) holds head g of token n (M = 16), heads g & 1 and 2 + (g & 1) (M = 32).
 template <int M, int G, int TPT>
 __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
-    const float *__restrict__ qs, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
+    const void *__restrict__ q, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
     const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const float2 *__restrict__ tbl_hi,
     const float2 *__restrict__ tbl_lo, float *__restrict__ scores, float2 *__restrict__ sstat, const SliceDims a)
 {
@@ -630,7 +629,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const uint4 *src = packed + (size_t)g * S * P * M * kK;
     const __amdgpu_buffer_rsrc_t cd_rs = make_rsrc(codes, (unsigned)L * M);
-    const __amdgpu_buffer_rsrc_t q_rs = make_rsrc(qs + ((size_t)b * a.Hq + (size_t)g * G) * kD, (unsigned)G * kD * 4u);
+    const unsigned qesz = a.q_bf16 ? 2u : 4u;
+    const __amdgpu_buffer_rsrc_t q_rs =
+        make_rsrc(static_cast<const char *>(q) + ((size_t)b * a.Hq + (size_t)g * G) * kD * qesz, (unsigned)G * kD * qesz);
     constexpr int PIECES = P * M * kK;
     constexpr int PPT = PIECES / kSliceThreads;
 
@@ -644,7 +645,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
     // as first operand of the query contraction the lane supplies head 4 grp + n % 4; rows past the last
     // head read beyond the end of the buffer, i.e. zero
-    const unsigned q_off = (unsigned)(n & 3) * (kD * 4u) + (unsigned)el * 4u;
+    const unsigned q_off = (unsigned)(n & 3) * kD + (unsigned)el;  // in elements
 
     float sc[NPASS][NGRP][NOUT];
 #pragma unroll
@@ -699,9 +700,11 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         for (int x = 0; x < PPT; ++x)
             stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, (unsigned)sl * (PIECES * 16u), 0);
     };
-    fetch_slice(0);
+    constexpr bool PREFETCH = !(M == 32 && G == 8 && TPT == 4);  // that instantiation has no registers to spare
+    if (PREFETCH) fetch_slice(0);
 
     for (int sl = 0; sl < S; ++sl) {
+        if (!PREFETCH) fetch_slice(sl);
         __syncthreads();  // everyone is done reading the previous slice
 #pragma unroll
         for (int x = 0; x < PPT; ++x) reinterpret_cast<uint4_t *>(tab)[x * kSliceThreads + tid] = stage[x];
@@ -726,11 +729,18 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         float qrow[NGRP][4];
 #pragma unroll
         for (int x = 0; x < NGRP; ++x) {
-            const uint4_t qraw = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off + (unsigned)x * (4u * kD * 4u), (unsigned)sl * DS * 4u, 0);
+            const unsigned off = q_off + (unsigned)x * (4u * kD);
+            if (a.q_bf16) {
+                const uint2_t qraw = __builtin_amdgcn_raw_buffer_load_b64(q_rs, off * 2u, (unsigned)sl * DS * 2u, 0);
+                qrow[x][0] = bf16_lo(qraw[0]) * a.scale; qrow[x][1] = bf16_hi(qraw[0]) * a.scale;
+                qrow[x][2] = bf16_lo(qraw[1]) * a.scale; qrow[x][3] = bf16_hi(qraw[1]) * a.scale;
+            } else {
+                const uint4_t qraw = __builtin_amdgcn_raw_buffer_load_b128(q_rs, off * 4u, (unsigned)sl * DS * 4u, 0);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const unsigned u = qraw[r];
-                qrow[x][r] = __builtin_bit_cast(float, u);
+                for (int r = 0; r < 4; ++r) {
+                    const unsigned u = qraw[r];
+                    qrow[x][r] = __builtin_bit_cast(float, u) * a.scale;
+                }
             }
         }
 #pragma unroll
@@ -779,7 +789,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (p == NPASS - 1) fetch_slice(min(sl + 1, S - 1));  // after the last slice: a harmless re-read
+            if (PREFETCH && p == NPASS - 1) fetch_slice(min(sl + 1, S - 1));  // after the last slice: a harmless re-read
             // 2. E = E_hi E_lo for the lane's two sub-spaces; rotated block = A E
             float val[4];
 #pragma unroll
@@ -1143,7 +1153,7 @@ hipError_t launch_out_g(const OutArgs &a, bool bf16, int grid, hipStream_t s)
 }
 
 struct SliceArgs {
-    const float *qs;
+    const void *q;
     const uint8_t *key_codes;
     const uint4 *packed;
     const int32_t *cu, *q_pos;
@@ -1163,7 +1173,7 @@ hipError_t launch_sliced_mgt(const SliceArgs &a, int grid, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kScoreLds, s, a.qs, a.key_codes,
+    hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kScoreLds, s, a.q, a.key_codes,
                        a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
     return hipGetLastError();
 }
@@ -1191,17 +1201,22 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
                          const commvq_positions *pos, const commvq_plan &plan, const Workspace &w, hipStream_t s)
 {
     const commvq_config &c = h->cfg;
-    if (plan.reserved) {  // sliced kernel: re-lay the codebook and scale the queries, then score
-        const size_t n_pieces = (size_t)c.n_kv_heads * c.m_key * kK * 16;
-        const int n_q = pos->batch * c.n_q_heads * kD;
-        const size_t n = n_pieces > (size_t)n_q ? n_pieces : (size_t)n_q;
-        hipLaunchKernelGGL(k_prep, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const uint4 *>(key_cb),
-                           w.packed, q, w.qs, c.n_kv_heads, c.m_key, n_q, c.q_dtype == COMMVQ_BF16, h->scale);
-        if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    if (plan.reserved) {  // slice-streaming kernel: needs the codebook in LDS-image order
+        const uint4 *packed = nullptr;
+        for (const auto &e : h->packed_keys)
+            if (e.first == key_cb) packed = e.second;
+        if (!packed) {  // not packed ahead of time: re-lay it into the workspace on every call
+            const size_t n_pieces = (size_t)c.n_kv_heads * c.m_key * kK * 16;
+            hipLaunchKernelGGL(k_prep, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, s,
+                               static_cast<const uint4 *>(key_cb), w.packed, c.n_kv_heads, c.m_key);
+            if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+            packed = w.packed;
+        }
         SliceArgs sa;
-        sa.qs = w.qs; sa.key_codes = key_codes; sa.packed = w.packed; sa.cu = pos->cu_seqlens; sa.q_pos = pos->q_pos;
+        sa.q = q; sa.key_codes = key_codes; sa.packed = packed; sa.cu = pos->cu_seqlens; sa.q_pos = pos->q_pos;
         sa.tbl_hi = h->tbl_hi; sa.tbl_lo = h->tbl_lo; sa.scores = w.scores; sa.sstat = w.sstat;
         sa.d.Hq = c.n_q_heads; sa.d.Hkv = c.n_kv_heads; sa.d.nsplit = plan.score_splits; sa.d.n_hi = h->n_hi;
+        sa.d.q_bf16 = c.q_dtype == COMMVQ_BF16; sa.d.scale = h->scale;
         const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
         const int tpt = plan.score_split_len / kSliceThreads;
         hipError_t e = c.m_key == 16 ? launch_sliced_m<16>(sa, h->G, tpt, grid, s) : launch_sliced_m<32>(sa, h->G, tpt, grid, s);
@@ -1369,6 +1384,47 @@ commvq_status commvq_workspace_bytes(const commvq_handle *h, int32_t batch, int6
     Workspace w;
     carve(h, batch, total_tokens, max_seqlen, nullptr, &w);
     *bytes = w.bytes;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_packed_key_codebook_bytes(const commvq_handle *h, size_t *bytes)
+{
+    if (!h || !bytes) return COMMVQ_ERR_NULL;
+    if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    *bytes = (size_t)h->cfg.n_kv_heads * h->cfg.m_key * kK * kD * 2;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_pack_key_codebooks(commvq_handle *h, const void *key_cb, void *packed, void *stream)
+{
+    if (!h || !key_cb || !packed) return COMMVQ_ERR_NULL;
+    if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    if ((reinterpret_cast<uintptr_t>(key_cb) | reinterpret_cast<uintptr_t>(packed)) & 15u) return COMMVQ_ERR_SHAPE;
+    const size_t n_pieces = (size_t)h->cfg.n_kv_heads * h->cfg.m_key * kK * 16;
+    hipLaunchKernelGGL(k_prep, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(key_cb), static_cast<uint4 *>(packed), h->cfg.n_kv_heads, h->cfg.m_key);
+    if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    for (auto &e : h->packed_keys)
+        if (e.first == key_cb) {
+            e.second = static_cast<const uint4 *>(packed);
+            return COMMVQ_OK;
+        }
+    try {
+        h->packed_keys.emplace_back(key_cb, static_cast<const uint4 *>(packed));
+    } catch (...) {
+        return COMMVQ_ERR_LAUNCH;
+    }
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_forget_packed_key_codebooks(commvq_handle *h, const void *key_cb)
+{
+    if (!h) return COMMVQ_ERR_NULL;
+    for (size_t i = 0; i < h->packed_keys.size(); ++i)
+        if (!key_cb || h->packed_keys[i].first == key_cb) {
+            h->packed_keys.erase(h->packed_keys.begin() + (long)i);
+            --i;
+        }
     return COMMVQ_OK;
 }
 

@@ -59,6 +59,14 @@ class DecodeAttention:
         assert self.workspace.data_ptr() % 256 == 0
         self.out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
         self.n_scores = w.total_tokens * w.Hq
+        self._packed = {}
+
+    def pack_key_codebooks(self, dw: DeviceWorkload):
+        """One-time re-layout of dw's (static) key codebooks; later calls with dw skip the per-call re-layout."""
+        torch = _torch()
+        buf = torch.empty(B.commvq_packed_key_codebook_bytes(self.handle), dtype=torch.uint8, device="cuda")
+        B.commvq_pack_key_codebooks(self.handle, dw.key_codebooks, buf, self.stream_ptr())
+        self._packed[dw.key_codebooks.data_ptr()] = (buf, dw.key_codebooks)  # keep both alive while registered
 
     def close(self):
         if self.handle is not None:

@@ -88,6 +88,29 @@ def test_staged_entry_points_equal_fused_call(gpu):
     assert np.array_equal(a, b)
 
 
+def test_prepacked_key_codebooks_give_identical_bits(gpu):
+    import torch
+    w = synth.config(3, max_len=5000)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    a = op(dw).clone()
+    op.pack_key_codebooks(dw)
+    b = op(dw).clone()
+    import paper_2506_18879_amd as cv
+    cv.commvq_forget_packed_key_codebooks(op.handle, dw.key_codebooks)
+    c = op(dw).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    # fp32 codebooks go through the other score kernel: packing is refused, nothing is registered
+    w32 = synth.config(1, max_len=600)
+    op32 = gpu.DecodeAttention(w32)
+    with pytest.raises(cv.CommVQError) as e:
+        cv.commvq_packed_key_codebook_bytes(op32.handle)
+    assert e.value.status == 2
+    op.close()
+    op32.close()
+
+
 # ---------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025])
 def test_lengths_around_tile_boundaries(gpu, oracle, L):
