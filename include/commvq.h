@@ -46,6 +46,17 @@ typedef enum {
 
 typedef enum { COMMVQ_F32 = 0, COMMVQ_BF16 = 1 } commvq_dtype;
 
+/*
+ * How the keys are stored.
+ *   COMMVQ_KEYS_INDEXED  m_key independent codebooks of K = 256 codewords, one uint8 index per codebook.
+ *   COMMVQ_KEYS_PAIRED   the paper's own key format (Sec. 4.2 with all 64 sub-spaces in one group, App. A.1):
+ *                        key_levels = R residual levels; a token stores R pairs (a_r, b_r) of 6-bit indices into
+ *                        ONE table of N_c' = 64 centres per level, and decodes to sum_r C[r][a_r] + i C[r][b_r],
+ *                        i.e. per 2-D sub-space (x_a - y_b, y_a + x_b) (Eq. def_center).  12 R bits per token and
+ *                        KV head: R = 11 is the paper's 1-bit setting, R = 21 its 2-bit setting.
+ */
+typedef enum { COMMVQ_KEYS_INDEXED = 0, COMMVQ_KEYS_PAIRED = 1 } commvq_key_format;
+
 /* Host struct, copied by commvq_create. */
 typedef struct {
     int32_t n_q_heads;       /* Hq */
@@ -59,6 +70,8 @@ typedef struct {
     double rope_base;        /* > 1; 500000 for LLaMA-3.1 */
     double softmax_scale;    /* 0 selects 1/sqrt(head_dim) (Eq. v1_formula) */
     int32_t max_position;    /* largest |q_pos - key position| that will occur; sizes the phase tables */
+    int32_t key_format;      /* commvq_key_format; 0 (indexed) keeps every field above as described */
+    int32_t key_levels;      /* R, 1..21; COMMVQ_KEYS_PAIRED only (m_key is then ignored; bf16 tables, implicit key positions) */
 } commvq_config;
 
 /* Host struct of device pointers: where the tokens sit (ragged batch). */
@@ -106,10 +119,14 @@ commvq_status commvq_workspace_bytes(const commvq_handle *handle, int32_t batch,
  *
  *   q              [B][Hq][d], q_dtype
  *   key_codes      uint8; sequence b holds [Hkv][L_b][M_k], sequences concatenated
- *                  (byte offset of sequence b = cu_seqlens[b] * Hkv * M_k); 16-byte aligned
+ *                  (byte offset of sequence b = cu_seqlens[b] * Hkv * M_k); 16-byte aligned.
+ *                  COMMVQ_KEYS_PAIRED: [Hkv][L_b][PB] with PB = ceil(12 R / 8) bytes per record; pair r of a
+ *                  token is bits 12 r .. 12 r + 11 of its record (little endian), a_r the low 6 bits, b_r the
+ *                  high 6 bits; sequence offset cu_seqlens[b] * Hkv * PB
  *   val_codes      uint8; same with M_v
  *   key_codebooks  [Hkv][M_k][K][d], codebook_dtype, row-major; a key codeword row is the
- *                  sequence of (x, y) first rows of its RoPE-commuting 2x2 blocks (Eq. C_struct)
+ *                  sequence of (x, y) first rows of its RoPE-commuting 2x2 blocks (Eq. C_struct).
+ *                  COMMVQ_KEYS_PAIRED: the tied table [Hkv][R][64][d] bf16, same row convention
  *   val_codebooks  [Hkv][M_v][K][d]
  *   positions      host struct, see above; |q_pos - key position| must not exceed max_position
  *                  (larger distances are clamped: no fault, wrong rotation)
@@ -136,6 +153,8 @@ commvq_status commvq_decode_attn(commvq_handle *handle, const void *q, const uin
  * use `packed` instead of re-laying (the caller vouches that the contents did not change).
  * Results are bit-identical either way.  commvq_forget_packed_key_codebooks drops one pair
  * (or all, with NULL).  COMMVQ_ERR_CONFIG for fp32 codebooks (they take another kernel).
+ * COMMVQ_KEYS_PAIRED: key_codebooks is the tied table; `packed` then holds it padded to blocks of
+ * 16 levels, in LDS-image order.
  */
 commvq_status commvq_packed_key_codebook_bytes(const commvq_handle *handle, size_t *bytes);
 commvq_status commvq_pack_key_codebooks(commvq_handle *handle, const void *key_codebooks, void *packed, void *stream);

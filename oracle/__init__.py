@@ -119,3 +119,46 @@ def decode_attn(q, key_codes, val_codes, key_codebooks, val_codebooks, cu_seqlen
     if return_intermediates:
         return out, scores, weights
     return out
+
+
+def unpack_key_pairs(records, R):
+    """Paired key format (App. A.1): records uint8 [..., ceil(12 R / 8)] -> (a, b), each uint8 [..., R].
+
+    Pair r of a record is its bits 12 r .. 12 r + 11 (little endian); a_r is the low 6 bits, b_r the high 6.
+    """
+    rec = np.ascontiguousarray(records, dtype=np.uint8)
+    pb = (12 * R + 7) // 8
+    assert rec.shape[-1] == pb
+    bits = np.unpackbits(rec, axis=-1, bitorder="little")[..., :12 * R].reshape(rec.shape[:-1] + (R, 12))
+    w = (1 << np.arange(6)).astype(np.uint8)
+    a = (bits[..., :6] * w).sum(axis=-1).astype(np.uint8)
+    b = (bits[..., 6:] * w).sum(axis=-1).astype(np.uint8)
+    return a, b
+
+
+def tied_table_as_codebooks(table, K=None):
+    """Tied pair table [Hkv][R][N][d] -> index-form codebooks [Hkv][2R][K][d] (Eq. def_center).
+
+    Level r decodes to C[r][a] + (second rows of the blocks of C[r][b]); a block [[x, y], [-y, x]] has second
+    row (-y, x).  So codebook 2r holds the rows themselves and codebook 2r + 1 the same rows with every
+    (x, y) replaced by (-y, x).  Rows N .. K-1 (never selected) are zero.
+    """
+    t = _f64(table)
+    Hkv, R, N, d = t.shape
+    K = N if K is None else K
+    out = np.zeros((Hkv, 2 * R, K, d), dtype=np.float64)
+    out[:, 0::2, :N, :] = t
+    out[:, 1::2, :N, 0::2] = -t[..., 1::2]
+    out[:, 1::2, :N, 1::2] = t[..., 0::2]
+    return out
+
+
+def paired_as_indexed(records, R, cu_seqlens, Hkv):
+    """Flat packed records (per sequence [Hkv][L_b][PB]) -> flat index-form codes (per sequence [Hkv][L_b][2R]),
+    index 2r = a_r, index 2r + 1 = b_r, matching tied_table_as_codebooks."""
+    pb = (12 * R + 7) // 8
+    rec = np.ascontiguousarray(records, dtype=np.uint8).reshape(-1, pb)
+    a, b = unpack_key_pairs(rec, R)
+    out = np.empty((rec.shape[0], 2 * R), dtype=np.uint8)
+    out[:, 0::2], out[:, 1::2] = a, b
+    return out.reshape(-1)

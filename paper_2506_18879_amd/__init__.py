@@ -8,6 +8,8 @@ is no CPU fallback: without the built library, or without a GPU, calls raise.
 from .binding import (  # noqa: F401
     COMMVQ_BF16,
     COMMVQ_F32,
+    COMMVQ_KEYS_INDEXED,
+    COMMVQ_KEYS_PAIRED,
     CommVQError,
     Config,
     Handle,

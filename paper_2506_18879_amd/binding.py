@@ -8,6 +8,7 @@ from ctypes import POINTER, Structure, byref, c_double, c_float, c_int32, c_int6
 from . import build as _build
 
 COMMVQ_F32, COMMVQ_BF16 = 0, 1
+COMMVQ_KEYS_INDEXED, COMMVQ_KEYS_PAIRED = 0, 1
 _lib = None
 
 
@@ -20,7 +21,8 @@ class CommVQError(RuntimeError):
 class Config(Structure):
     _fields_ = [("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32), ("m_key", c_int32),
                 ("m_val", c_int32), ("k", c_int32), ("q_dtype", c_int32), ("codebook_dtype", c_int32),
-                ("rope_base", c_double), ("softmax_scale", c_double), ("max_position", c_int32)]
+                ("rope_base", c_double), ("softmax_scale", c_double), ("max_position", c_int32),
+                ("key_format", c_int32), ("key_levels", c_int32)]
 
 
 class Positions(Structure):

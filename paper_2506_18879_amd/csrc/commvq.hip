@@ -87,7 +87,8 @@ struct Workspace {
     float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over that value split
     unsigned *bins;   // [B * Hkv * value_splits][G * Mv * K] fixed-point bins
     float *partial;   // [B * Hq * out_chunks][d]
-    uint4 *packed;    // key codebook re-laid slice-major for k_score_mfma (same size as the codebook)
+    uint4 *packed;    // key codebook re-laid slice-major for k_score_mfma / k_score_pair
+    uint8_t *pair_bytes;  // paired-code keys: one byte per index, [T * Hkv][32 * blocks]
     size_t bytes;
 };
 
@@ -96,6 +97,16 @@ struct Workspace {
 bool use_sliced(const commvq_handle *h, bool explicit_positions)
 {
     return h->cfg.codebook_dtype == COMMVQ_BF16 && !explicit_positions;
+}
+
+// Paired-code key format: blocks of 16 levels, bytes of one packed record, bytes of the unpacked indices of a token.
+inline bool pair_keys(const commvq_config &c) { return c.key_format == COMMVQ_KEYS_PAIRED; }
+inline int pair_blocks(const commvq_config &c) { return (c.key_levels + 15) / 16; }
+inline int pair_record_bytes(const commvq_config &c) { return (12 * c.key_levels + 7) / 8; }
+inline size_t packed_key_bytes(const commvq_config &c)
+{
+    if (pair_keys(c)) return (size_t)c.n_kv_heads * 16 * pair_blocks(c) * 64 * 256;  // 16 planes x blocks x 16 KiB
+    return (size_t)c.n_kv_heads * c.m_key * kK * kD * 2;
 }
 
 void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commvq_plan *p)
@@ -108,7 +119,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         double best = -1.0;
         len = 1024;
         for (int tpt = 1; tpt <= COMMVQ_SCORE_MAX_TPT; tpt *= 2) {
-            if (tpt == 4 && h->G == 8 && h->cfg.m_key == 16) break;  // that instantiation runs out of registers
+            if (tpt == 4 && h->G == 8 && (h->cfg.m_key == 16 || pair_keys(h->cfg))) break;  // those instantiations run out of registers
             const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt));
             const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
             const double eff = fill / (1.0 + 0.25 / tpt);
@@ -153,7 +164,8 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     w->lsum = take((size_t)B * c.n_q_heads * vsplits);
     w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * vsplits * h->G * c.m_val * kK));
     w->partial = take((size_t)B * c.n_q_heads * pa.out_chunks * kD);
-    w->packed = reinterpret_cast<uint4 *>(take((size_t)c.n_kv_heads * c.m_key * kK * kD / 2));  // bf16 codebook
+    w->packed = reinterpret_cast<uint4 *>(take(packed_key_bytes(c) / 4));
+    w->pair_bytes = pair_keys(c) ? reinterpret_cast<uint8_t *>(take((size_t)T * c.n_kv_heads * 8 * pair_blocks(c))) : nullptr;
     w->bytes = off;
 }
 
@@ -860,6 +872,328 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     }
 }
 
+// ------------------------------------------------------------------ paired-code keys (App. A.1)
+// The paper's own key format: per token and KV head R residual levels, each a pair (a, b) of 6-bit
+// indices into ONE table of N_c' = 64 centres per level; level r contributes C[r][a] + i C[r][b]
+// (Eq. def_center: per 2-D sub-space (x_a - y_b, y_a + x_b)), i.e. index form with 2R tied codebooks.
+constexpr int kPairK = 64;       // centres per level
+constexpr int kPairPlanes = 4;   // 8-element planes per LDS slice (4 slices cover the 16 planes of d = 128)
+constexpr int kPairBlock = kPairK * 256;  // bytes of one (plane, block of 16 levels): 64 rows x 16 pieces
+
+// Packed 12-bit pairs -> one byte per index, in the order the score kernel wants.
+//   pairs : per (sequence, KV head) L records of PB = ceil(12 R / 8) bytes; pair r of a token is bits
+//           12 r .. 12 r + 11 of its record (little endian), a_r = low 6 bits, b_r = high 6 bits
+//   bytes : [token-unit][blk][t][16]: level 16 blk + col of type t (0 = a, 1 = b); 0 for levels >= R
+// One workgroup = 256 consecutive tokens of one (sequence, KV head); their records are contiguous and
+// are staged through LDS with aligned dword loads.
+__global__ __launch_bounds__(256) void k_unpack_pairs(const uint8_t *__restrict__ pairs, uint8_t *__restrict__ bytes,
+                                                      const int32_t *__restrict__ cu, int Hkv, int R, int PB, int NB)
+{
+    __shared__ unsigned stage[256 * 32 / 4 + 2];
+    const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
+    const int cu0 = cu[b], L = cu[b + 1] - cu0;
+    const int i0 = blockIdx.x * 256;
+    if (i0 >= L) return;
+    const int cnt = min(256, L - i0);
+    const size_t first = ((size_t)cu0 * Hkv + (size_t)g * L + i0) * PB;  // byte offset of the first record
+    const size_t lo = first & ~(size_t)3, hi = first + (size_t)cnt * PB;  // hi never passes the end of the (b, g) stream
+    const unsigned skew = (unsigned)(first - lo);
+    const unsigned ndw = (unsigned)((hi - lo + 3) / 4);
+    for (unsigned x = threadIdx.x; x < ndw; x += 256) {
+        // the last dword may reach past the stream: read it byte by byte
+        const size_t at = lo + (size_t)x * 4;
+        unsigned v = 0;
+        if (at + 4 <= hi) v = *reinterpret_cast<const unsigned *>(pairs + at);
+        else for (unsigned k = 0; at + k < hi; ++k) v |= (unsigned)pairs[at + k] << (8 * k);
+        stage[x] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x >= cnt) return;
+    const uint8_t *rec = reinterpret_cast<const uint8_t *>(stage) + skew + threadIdx.x * PB;
+    uint4 *dst = reinterpret_cast<uint4 *>(bytes + ((size_t)cu0 * Hkv + (size_t)g * L + i0 + threadIdx.x) * (32 * NB));
+    for (int blk = 0; blk < NB; ++blk) {
+        unsigned wa[4] = {0, 0, 0, 0}, wb[4] = {0, 0, 0, 0};
+        for (int col = 0; col < 16; ++col) {
+            const int r = 16 * blk + col;
+            if (r < R) {
+                const int at = (3 * r) >> 1;
+                const unsigned pr = (((unsigned)rec[at] | (unsigned)rec[at + 1] << 8) >> (4 * (r & 1))) & 0xfffu;
+                wa[col >> 2] |= (pr & 63u) << (8 * (col & 3));
+                wb[col >> 2] |= (pr >> 6) << (8 * (col & 3));
+            }
+        }
+        dst[2 * blk] = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+        dst[2 * blk + 1] = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+    }
+}
+
+// Tied table [Hkv][R][64][d] bf16 -> LDS images for k_score_pair:
+//   packed[g][slice][plane][blk][c][col] 16-byte pieces = elements 8 (4 slice + plane) .. +7 of centre c of
+//   level 16 blk + col (zeros for levels >= R).  One thread per piece of the output.
+__global__ __launch_bounds__(256) void k_prep_pairs(const uint4 *__restrict__ table, uint4 *__restrict__ packed, int Hkv,
+                                                    int R, int NB)
+{
+    const size_t n = (size_t)Hkv * 16 * NB * kPairK * 16;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n) return;
+    const int col = (int)(t & 15);
+    const int c = (int)((t >> 4) % kPairK);
+    size_t rest = (t >> 4) / kPairK;
+    const int blk = (int)(rest % NB);
+    rest /= NB;
+    const int plane16 = (int)(rest % 16);  // 4 slice + plane
+    const int g = (int)(rest / 16);
+    const int r = 16 * blk + col;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < R) v = table[(((size_t)g * R + r) * kPairK + c) * 16 + plane16];
+    packed[t] = v;
+}
+
+// Score kernel for paired-code keys: same scheme as k_score_mfma (codebook streamed through LDS in
+// slices, gather-sum and query product on the matrix cores), with
+//   * a slice = 4 planes of 8 elements of every centre of every level (NB blocks of 16 levels, one
+//     bank column per level, 64 rows = centre index): 64 KiB (R <= 16) or 128 KiB (R <= 32);
+//   * k-groups = (a | b) x (levels 8h .. 8h + 7): lane (n, g) gathers the centres that the a (g < 2) or
+//     b (g >= 2) indices of token n select in levels 8 (g & 1) + (n + step) mod 8 of every block;
+//   * a selection matrix that routes the a-sum and the b-sum of sub-space g of the plane to rows
+//     4g .. 4g + 3, so that lane (n, g) receives (SA_x, SA_y, SB_x, SB_y) and forms the decoded block
+//     (SA_x - SB_y, SA_y + SB_x) of Eq. def_center locally;
+//   * one cross-lane head total per slice: the 4x4x1 query MFMAs of the slice's 4 planes chain into
+//     one accumulator before the row / half swaps.
+template <int NB, int G, int TPT>
+__global__ __launch_bounds__(kSliceThreads) void k_score_pair(
+    const void *__restrict__ q, const uint8_t *__restrict__ codes_all, const uint4 *__restrict__ packed,
+    const int32_t *__restrict__ cu, const int32_t *__restrict__ q_pos, const float2 *__restrict__ tbl_hi,
+    const float2 *__restrict__ tbl_lo, float *__restrict__ scores, float2 *__restrict__ sstat, const SliceDims a)
+{
+    constexpr int PL = kPairPlanes;
+    constexpr int S = 16 / PL;
+    constexpr int CB = 32 * NB;                      // code bytes per token
+    constexpr int SLICE = PL * NB * kPairBlock;      // LDS bytes of one slice
+    constexpr int TILE = TPT * kSliceThreads;
+    constexpr int NW = kSliceThreads / 64;
+    constexpr int NPASS = TILE / (16 * NW);
+    constexpr int NHR = TILE / kLo + 1;
+    constexpr int NGRP = (G + 3) / 4;
+    constexpr int PARTS = 8;                          // (sub-space of a plane) x (planes 0,1 | 2,3)
+    static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
+    extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [PL][NB][64][16] pieces, then the phase factors
+    float4 *elo = reinterpret_cast<float4 *>(reinterpret_cast<char *>(tab) + SLICE);  // [PARTS][64]
+    float4 *ehi = elo + PARTS * kLo;                                                   // [PARTS][NHR]
+    float2(*wstat)[G] = reinterpret_cast<float2(*)[G]>(ehi + PARTS * NHR);            // [NW][G]
+
+    int id = blockIdx.x;
+    const int g = id % a.Hkv;
+    id /= a.Hkv;
+    const int tile = id % a.nsplit;
+    const int b = id / a.nsplit;
+    const int cu0 = cu[b];
+    const int L = cu[b + 1] - cu0;
+    const int t0 = tile * TILE;
+    if (t0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gk = lane >> 4;
+    const int type = gk >> 1;                         // 0: the a indices, 1: the b indices
+    const int half = gk & 1;                          // levels 8 half .. 8 half + 7 of every block
+    const int qpos = q_pos[b];
+    const uint8_t *codes = codes_all + ((size_t)cu0 * a.Hkv + (size_t)g * L) * CB;
+    const uint4 *src = packed + (size_t)g * S * (SLICE / 16);
+    const __amdgpu_buffer_rsrc_t cd_rs = make_rsrc(codes, (unsigned)L * CB);
+    const unsigned qesz = a.q_bf16 ? 2u : 4u;
+    const __amdgpu_buffer_rsrc_t q_rs =
+        make_rsrc(static_cast<const char *>(q) + ((size_t)b * a.Hq + (size_t)g * G) * kD * qesz, (unsigned)G * kD * qesz);
+    constexpr int PPT = SLICE / 16 / kSliceThreads;
+
+    // selection matrix operand: row i = n takes, from the k-groups of its type (i >> 1) & 1, element 2 (i >> 2) + (i & 1)
+    uint4_t sel = {0u, 0u, 0u, 0u};
+    if (type == ((n >> 1) & 1)) {
+        const int e = 2 * (n >> 2) + (n & 1);
+        sel[e >> 1] = (e & 1) ? 0x3f800000u : 0x00003f80u;
+    }
+    const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
+
+    float sc[NPASS][NGRP];
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+        for (int x = 0; x < NGRP; ++x) sc[p][x] = 0.f;
+
+    // xreg[st]: byte 0 = 16 * bank column (= level within the block) read at step st, byte 2 = 0, byte 3 = 1;
+    // a byte permute splices the centre index in as byte 1: address = 256 c + 16 col (+ 65536 via byte 3)
+    unsigned xreg[8];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) xreg[st] = (unsigned)(8 * half + ((n + st) & 7)) * 16u | 1u << 24;
+    unsigned rsel_lo = 0u, rsel_hi = 0u;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        rsel_lo |= (unsigned)((x + n) & 7) << (8 * x);
+        rsel_hi |= (unsigned)((x + 4 + n) & 7) << (8 * x);
+    }
+
+    int tb = t0 + wave * 16 + n;
+    unsigned cw[2][2 * NB];
+    auto fetch_codes = [&](int p, unsigned(&dst)[2 * NB]) {
+        const int tok = min(tb + p * NW * 16, L - 1);
+#pragma unroll
+        for (int v = 0; v < NB; ++v) {  // bytes 32 v + 16 type + 8 half .. + 7 of the token's indices
+            const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * CB + 32u * v + 16u * type + 8u * half, 0, 0);
+            dst[2 * v + 0] = c2[0]; dst[2 * v + 1] = c2[1];
+        }
+    };
+    fetch_codes(0, cw[0]);
+    const int hmin = (qpos - (t0 + TILE - 1)) >> kLoBits;
+    const unsigned elo_base = (unsigned)SLICE + (unsigned)(2 * gk) * (kLo * 16u);
+    const unsigned ehi_base = (unsigned)SLICE + (unsigned)(PARTS * kLo) * 16u + (unsigned)(2 * gk) * (NHR * 16u);
+
+    for (int sl = 0; sl < S; ++sl) {
+        __syncthreads();  // everyone is done reading the previous slice
+        {
+            uint4 stage[PPT];
+#pragma unroll
+            for (int x = 0; x < PPT; ++x) stage[x] = src[(size_t)sl * (SLICE / 16) + x * kSliceThreads + tid];
+#pragma unroll
+            for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
+        }
+        // phase factors of this slice's 16 sub-spaces: part (s, h) holds sub-space s of planes 2h and 2h + 1
+        if (tid < PARTS * kLo) {
+            const int part = tid / kLo, lo = tid % kLo;
+            const int j0 = 16 * sl + 8 * (part & 1) + (part >> 1);
+            const float2 e0 = tbl_lo[(size_t)lo * kJ + j0], e1 = tbl_lo[(size_t)lo * kJ + j0 + 4];
+            elo[tid] = make_float4(e0.x, e0.y, e1.x, e1.y);
+        }
+        for (int x = tid; x < PARTS * NHR; x += kSliceThreads) {
+            const int part = x / NHR, H = hmin + x % NHR;
+            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
+            const int j0 = 16 * sl + 8 * (part & 1) + (part >> 1);
+            const float2 e0 = tbl_hi[(size_t)hi * kJ + j0], e1 = tbl_hi[(size_t)hi * kJ + j0 + 4];
+            const float sg = H < 0 ? -1.f : 1.f;
+            ehi[x] = make_float4(e0.x, sg * e0.y, e1.x, sg * e1.y);
+        }
+        __syncthreads();
+        asm volatile("" : "+v"(tb));
+        const int dist16 = (qpos - tb) * 16;
+        // scaled queries of this slice: head 4 grp + n % 4, sub-space gk of each of the 4 planes
+        float qrow[NGRP][PL][2];
+#pragma unroll
+        for (int x = 0; x < NGRP; ++x)
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl) {
+                const unsigned off = (unsigned)(4 * x + (n & 3)) * kD + 2u * (unsigned)(16 * sl + 4 * pl + gk);  // elements
+                if (a.q_bf16) {
+                    const unsigned qraw = __builtin_amdgcn_raw_buffer_load_b32(q_rs, off * 2u, 0, 0);
+                    qrow[x][pl][0] = bf16_lo(qraw) * a.scale; qrow[x][pl][1] = bf16_hi(qraw) * a.scale;
+                } else {
+                    const uint2_t qraw = __builtin_amdgcn_raw_buffer_load_b64(q_rs, off * 4u, 0, 0);
+                    const unsigned u0 = qraw[0], u1 = qraw[1];
+                    qrow[x][pl][0] = __builtin_bit_cast(float, u0) * a.scale; qrow[x][pl][1] = __builtin_bit_cast(float, u1) * a.scale;
+                }
+            }
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure flat
+            const int d16 = dist16 - p * (NW * 16 * 16);
+            const unsigned lo_off = elo_base + (unsigned)(d16 & ((kLo - 1) * 16));
+            const unsigned hi_off = ehi_base + (unsigned)(((d16 >> (kLoBits + 4)) - hmin) * 16);
+            fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            unsigned cc[2 * NB];
+#pragma unroll
+            for (int v = 0; v < NB; ++v) {
+                cc[2 * v + 0] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_lo);
+                cc[2 * v + 1] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_hi);
+            }
+            floatx4_t t[NGRP];
+#pragma unroll
+            for (int x = 0; x < NGRP; ++x) t[x] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl) {
+                // 1. gather-sum of the plane: 8 NB pieces per lane, in groups of 4 reads
+                floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+                constexpr int NS = 8 * NB, RG = 4, NG = NS / RG;
+                uint4 v[2][RG];
+                auto issue = [&](int grp, uint4(&dst)[RG]) {
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) {
+                        const int st = grp * RG + r;       // level 16 (st / 8) + 8 half + (n + st) mod 8
+                        const int idx = pl * NB + st / 8;  // (plane, block) image of 16 KiB
+                        const unsigned selb = 0x0c000000u | (unsigned)(2 + idx / 4) << 16 | (unsigned)(4 + st % 4) << 8;
+                        const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], selb);
+                        dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + (idx % 4) * kPairBlock + addr);
+                    }
+                };
+                issue(0, v[0]);
+#pragma unroll
+                for (int grp = 0; grp < NG; ++grp) {
+                    if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) {
+                        const uint4 x = v[grp & 1][r];
+                        const uint4_t xv = {x.x, x.y, x.z, x.w};
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, xv), acc, 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // 2. decoded block of sub-space gk (Eq. def_center), rotated by E = E_hi E_lo
+                const uint4_t elr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + lo_off + (pl / 2) * (kLo * 16));
+                const uint4_t ehr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + hi_off + (pl / 2) * (NHR * 16));
+                const unsigned hxr = ehr[2 * (pl & 1)], hyr = ehr[2 * (pl & 1) + 1], lxr = elr[2 * (pl & 1)], lyr = elr[2 * (pl & 1) + 1];
+                const float hx = __builtin_bit_cast(float, hxr), hy = __builtin_bit_cast(float, hyr);
+                const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
+                const float ex = hx * lx - hy * ly;
+                const float ey = hx * ly + hy * lx;
+                const float kx = acc[0] - acc[3], ky = acc[1] + acc[2];
+                const float bx = kx * ex - ky * ey;
+                const float by = kx * ey + ky * ex;
+                // 3. partial logits of 4 heads at a time; chained over the planes of the slice
+#pragma unroll
+                for (int x = 0; x < NGRP; ++x) {
+                    t[x] = __builtin_amdgcn_mfma_f32_4x4x1f32(qrow[x][pl][0], bx, t[x], 0, 0, 0);
+                    t[x] = __builtin_amdgcn_mfma_f32_4x4x1f32(qrow[x][pl][1], by, t[x], 0, 0, 0);
+                }
+            }
+            // totals over the 4 lanes of the token: lane (n, gk) keeps head 4 grp + gk
+#pragma unroll
+            for (int x = 0; x < NGRP; ++x) sc[p][x] += swap16_add(swap32_add(t[x][0], t[x][2]), swap32_add(t[x][1], t[x][3]));
+        }
+    }
+
+    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+#pragma unroll
+    for (int x = 0; x < NGRP; ++x) {
+        const int head = 4 * x + gk;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const int tok = tb + p * NW * 16;
+            if (head < G && tok < L) {
+                srow[(size_t)head * L + tok] = sc[p][x];
+                mx = fmaxf(mx, sc[p][x]);
+            }
+        }
+        const float wm = row_max16(mx);
+        float l = 0.f;
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const int tok = tb + p * NW * 16;
+            if (head < G && tok < L) l += __builtin_amdgcn_exp2f((sc[p][x] - wm) * kLog2e);
+        }
+        l = row_sum16(l);
+        if (n == 0 && head < G) wstat[wave][head] = make_float2(wm, l);
+    }
+    __syncthreads();
+    if (tid < G) {
+        float m = -INFINITY;
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
+        float l = 0.f;
+        for (int w = 0; w < NW; ++w) {
+            const float2 st = wstat[w][tid];
+            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+        }
+        sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
+    }
+}
+
 // ------------------------------------------------------------------ k_bins
 struct BinsArgs {
     const uint8_t *val_codes;
@@ -1079,6 +1413,7 @@ commvq_status prep(const commvq_handle *h, const commvq_positions *pos, void *wo
     if (!h) return COMMVQ_ERR_NULL;
     commvq_status st = check_positions(pos);
     if (st != COMMVQ_OK) return st;
+    if (pair_keys(h->cfg) && pos->key_pos) return COMMVQ_ERR_CONFIG;  // paired-code keys: contiguous positions only
     make_plan(h, pos->batch, pos->max_seqlen, use_sliced(h, pos->key_pos != nullptr), plan);
     carve(h, pos->batch, pos->total_tokens, pos->max_seqlen, workspace, w);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < w->bytes)
@@ -1197,6 +1532,54 @@ hipError_t launch_sliced_m(const SliceArgs &a, int G, int tpt, int grid, hipStre
     }
 }
 
+template <int NB, int G, int TPT>
+hipError_t launch_pair_bgt(const SliceArgs &a, int grid, hipStream_t s)
+{
+    constexpr int lds = kPairPlanes * NB * kPairBlock + 8 * kLo * 16 + 8 * (TPT * kSliceThreads / kLo + 1) * 16 + kStatBytes;
+    static bool attr_set = false;  // per instantiation; raising the limit is idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_pair<NB, G, TPT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_score_pair<NB, G, TPT>), dim3(grid), dim3(kSliceThreads), lds, s, a.q, a.key_codes, a.packed,
+                       a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
+    return hipGetLastError();
+}
+template <int NB, int G>
+hipError_t launch_pair_bg(const SliceArgs &a, int tpt, int grid, hipStream_t s)
+{
+    switch (tpt) {
+    case 1: return launch_pair_bgt<NB, G, 1>(a, grid, s);
+    case 2: return launch_pair_bgt<NB, G, 2>(a, grid, s);
+    default: return launch_pair_bgt<NB, G, 4>(a, grid, s);
+    }
+}
+template <int NB>
+hipError_t launch_pair_b(const SliceArgs &a, int G, int tpt, int grid, hipStream_t s)
+{
+    switch (G) {
+    case 1: return launch_pair_bg<NB, 1>(a, tpt, grid, s);
+    case 2: return launch_pair_bg<NB, 2>(a, tpt, grid, s);
+    case 4: return launch_pair_bg<NB, 4>(a, tpt, grid, s);
+    default: return launch_pair_bg<NB, 8>(a, tpt, grid, s);
+    }
+}
+
+// Re-lays a key codebook (index form) or a tied pair table into the LDS-image order of its score kernel.
+hipError_t launch_prep(const commvq_config &c, const void *key_cb, uint4 *packed, hipStream_t s)
+{
+    const size_t n_pieces = packed_key_bytes(c) / 16;
+    if (pair_keys(c))
+        hipLaunchKernelGGL(k_prep_pairs, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, s,
+                           static_cast<const uint4 *>(key_cb), packed, c.n_kv_heads, c.key_levels, pair_blocks(c));
+    else
+        hipLaunchKernelGGL(k_prep, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, s,
+                           static_cast<const uint4 *>(key_cb), packed, c.n_kv_heads, c.m_key);
+    return hipGetLastError();
+}
+
 commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_codes, const void *key_cb,
                          const commvq_positions *pos, const commvq_plan &plan, const Workspace &w, hipStream_t s)
 {
@@ -1206,10 +1589,7 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
         for (const auto &e : h->packed_keys)
             if (e.first == key_cb) packed = e.second;
         if (!packed) {  // not packed ahead of time: re-lay it into the workspace on every call
-            const size_t n_pieces = (size_t)c.n_kv_heads * c.m_key * kK * 16;
-            hipLaunchKernelGGL(k_prep, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, s,
-                               static_cast<const uint4 *>(key_cb), w.packed, c.n_kv_heads, c.m_key);
-            if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+            if (launch_prep(c, key_cb, w.packed, s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
             packed = w.packed;
         }
         SliceArgs sa;
@@ -1219,7 +1599,18 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
         sa.d.q_bf16 = c.q_dtype == COMMVQ_BF16; sa.d.scale = h->scale;
         const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
         const int tpt = plan.score_split_len / kSliceThreads;
-        hipError_t e = c.m_key == 16 ? launch_sliced_m<16>(sa, h->G, tpt, grid, s) : launch_sliced_m<32>(sa, h->G, tpt, grid, s);
+        hipError_t e;
+        if (pair_keys(c)) {
+            // 12-bit pairs -> one byte per index, then the paired-code score kernel
+            hipLaunchKernelGGL(k_unpack_pairs, dim3((unsigned)((pos->max_seqlen + 255) / 256), (unsigned)(pos->batch * c.n_kv_heads)),
+                               dim3(256), 0, s, key_codes, w.pair_bytes, pos->cu_seqlens, c.n_kv_heads, c.key_levels,
+                               pair_record_bytes(c), pair_blocks(c));
+            if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+            sa.key_codes = w.pair_bytes;
+            e = pair_blocks(c) == 1 ? launch_pair_b<1>(sa, h->G, tpt, grid, s) : launch_pair_b<2>(sa, h->G, tpt, grid, s);
+        } else {
+            e = c.m_key == 16 ? launch_sliced_m<16>(sa, h->G, tpt, grid, s) : launch_sliced_m<32>(sa, h->G, tpt, grid, s);
+        }
         return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
     }
     ScoreArgs a;
@@ -1299,7 +1690,15 @@ commvq_status commvq_validate_config(const commvq_config *c)
     if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return COMMVQ_ERR_CONFIG;
     const int G = c->n_q_heads / c->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return COMMVQ_ERR_CONFIG;
-    if ((c->m_key != 16 && c->m_key != 32) || (c->m_val != 16 && c->m_val != 32)) return COMMVQ_ERR_CONFIG;
+    if (c->m_val != 16 && c->m_val != 32) return COMMVQ_ERR_CONFIG;
+    if (c->key_format == COMMVQ_KEYS_INDEXED) {
+        if (c->m_key != 16 && c->m_key != 32) return COMMVQ_ERR_CONFIG;
+    } else if (c->key_format == COMMVQ_KEYS_PAIRED) {
+        // 12 R bits per record must fit the unpack kernel's staging (R <= 21: 32 bytes); one table for a and b, bf16 only
+        if (c->key_levels < 1 || c->key_levels > 21 || c->codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    } else {
+        return COMMVQ_ERR_CONFIG;
+    }
     if (c->q_dtype != COMMVQ_F32 && c->q_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
     if (c->codebook_dtype != COMMVQ_F32 && c->codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
     if (!(c->rope_base > 1.0) || !(c->softmax_scale >= 0.0)) return COMMVQ_ERR_CONFIG;
@@ -1391,7 +1790,7 @@ commvq_status commvq_packed_key_codebook_bytes(const commvq_handle *h, size_t *b
 {
     if (!h || !bytes) return COMMVQ_ERR_NULL;
     if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
-    *bytes = (size_t)h->cfg.n_kv_heads * h->cfg.m_key * kK * kD * 2;
+    *bytes = packed_key_bytes(h->cfg);
     return COMMVQ_OK;
 }
 
@@ -1400,10 +1799,8 @@ commvq_status commvq_pack_key_codebooks(commvq_handle *h, const void *key_cb, vo
     if (!h || !key_cb || !packed) return COMMVQ_ERR_NULL;
     if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
     if ((reinterpret_cast<uintptr_t>(key_cb) | reinterpret_cast<uintptr_t>(packed)) & 15u) return COMMVQ_ERR_SHAPE;
-    const size_t n_pieces = (size_t)h->cfg.n_kv_heads * h->cfg.m_key * kK * 16;
-    hipLaunchKernelGGL(k_prep, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4 *>(key_cb), static_cast<uint4 *>(packed), h->cfg.n_kv_heads, h->cfg.m_key);
-    if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    if (launch_prep(h->cfg, key_cb, static_cast<uint4 *>(packed), static_cast<hipStream_t>(stream)) != hipSuccess)
+        return COMMVQ_ERR_LAUNCH;
     for (auto &e : h->packed_keys)
         if (e.first == key_cb) {
             e.second = static_cast<const uint4 *>(packed);

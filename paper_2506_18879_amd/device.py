@@ -50,8 +50,10 @@ class DecodeAttention:
         dt = B.COMMVQ_BF16 if w.dtype == "bf16" else B.COMMVQ_F32
         if max_position is None:
             max_position = max(int(w.q_pos.max()), w.max_seqlen, 0 if w.key_pos is None else int(w.key_pos.max()))
-        self.cfg = B.Config(w.Hq, w.Hkv, w.d, w.Mk, w.Mv, w.K, dt, dt, float(w.rope_base), float(softmax_scale),
-                            int(max_position))
+        paired = getattr(w, "key_format", "indexed") == "paired"
+        self.cfg = B.Config(w.Hq, w.Hkv, w.d, 16 if paired else w.Mk, w.Mv, w.K, dt, dt, float(w.rope_base),
+                            float(softmax_scale), int(max_position),
+                            B.COMMVQ_KEYS_PAIRED if paired else B.COMMVQ_KEYS_INDEXED, w.key_levels if paired else 0)
         self.handle = B.commvq_create(self.cfg)
         self.plan = B.commvq_plan_query(self.handle, w.B, w.total_tokens, w.max_seqlen)
         self.workspace_bytes = B.commvq_workspace_bytes(self.handle, w.B, w.total_tokens, w.max_seqlen)

@@ -14,6 +14,10 @@ Storage conventions
   * codebooks: ``[Hkv][M][K][d]``; a key codeword row is the sequence of first
     rows ``(x, y)`` of its d/2 RoPE-commuting blocks ``[[x, y], [-y, x]]``
     (Property 1, Eq. C_struct), so the free parameters are exactly the row.
+  * paired key format (App. A.1): per token and KV head ``R`` pairs ``(a_r, b_r)``
+    of 6-bit indices, packed little endian into ``ceil(12 R / 8)`` bytes with
+    pair ``r`` at bits ``12 r .. 12 r + 11`` (``a`` low, ``b`` high); one tied
+    table ``[Hkv][R][64][d]`` serves both indices of a level.
 """
 from __future__ import annotations
 
@@ -61,6 +65,8 @@ class Workload:
     seed: int = 0
     code_dist: str = "uniform"
     extras: dict = field(default_factory=dict)
+    key_format: str = "indexed"  # "indexed": Mk uint8 indices per token; "paired": key_levels packed 12-bit pairs
+    key_levels: int = 0          # R of the paired format (then key_codebooks is the tied table [Hkv][R][64][d])
 
     @property
     def total_tokens(self) -> int:
@@ -143,6 +149,50 @@ def make_workload(name: str, *, B: int, Hq: int, Hkv: int, seqlens, Mk: int, Mv:
                     cu_seqlens=cu, q_pos=q_pos, key_pos=None, seed=seed, code_dist=code_dist)
 
 
+def pack_key_pairs(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """[..., R] 6-bit indices a, b -> [..., ceil(12 R / 8)] bytes (pair r at bits 12 r .. 12 r + 11, a low)."""
+    a = np.asarray(a, dtype=np.uint64)
+    b = np.asarray(b, dtype=np.uint64)
+    assert a.shape == b.shape and a.max(initial=0) < 64 and b.max(initial=0) < 64
+    R = a.shape[-1]
+    pb = (12 * R + 7) // 8
+    out = np.zeros(a.shape[:-1] + (pb,), dtype=np.uint8)
+    for r in range(R):
+        pair = a[..., r] | (b[..., r] << np.uint64(6))   # 12 bits
+        bit = 12 * r
+        for k in range(3):                                # a pair touches at most 2 bytes, 3 covers any shift
+            byte = bit // 8 + k
+            if byte >= pb:
+                break
+            shift = 8 * k - bit % 8
+            chunk = (pair >> np.uint64(shift)) if shift >= 0 else (pair << np.uint64(-shift))
+            out[..., byte] |= (chunk & np.uint64(0xFF)).astype(np.uint8)
+    return out
+
+
+def make_pair_workload(name: str, *, B: int, Hq: int, Hkv: int, seqlens, R: int, Mv: int, seed: int,
+                       d: int = 128, code_dist: str = "uniform", zipf_s: float = 1.1,
+                       rope_base: float = ROPE_BASE) -> Workload:
+    """A workload whose keys are in the paper's paired format: N_c' = 64 centres per level, R levels
+    (R = 11: 1.03 bit per scalar, R = 21: 1.97), bf16 storage; values as in make_workload."""
+    base = make_workload(name, B=B, Hq=Hq, Hkv=Hkv, seqlens=seqlens, Mk=16, Mv=Mv, dtype="bf16", seed=seed, d=d,
+                         code_dist=code_dist, zipf_s=zipf_s, rope_base=rope_base)
+    rng = np.random.Generator(np.random.PCG64(seed ^ 0xA11CE))
+    # block parameters ~ N(0, (2R)^-1/2): a decoded coordinate is a sum of 2R of them
+    table = rng.standard_normal((Hkv, R, 64, d), dtype=np.float32) * np.float32((2 * R) ** -0.5)
+    parts = []
+    for L in np.diff(base.cu_seqlens):
+        if code_dist == "zipf":
+            ab = _zipf_codes(rng, Hkv, int(L), 2 * R, 64, zipf_s)
+        else:
+            ab = rng.integers(0, 64, size=(Hkv, int(L), 2 * R)).astype(np.uint8)
+        parts.append(pack_key_pairs(ab[..., 0::2], ab[..., 1::2]).reshape(-1))
+    base.key_codes = np.concatenate(parts)
+    base.key_codebooks = f32_to_bf16_bits(table)
+    base.key_format, base.key_levels, base.Mk = "paired", R, 2 * R
+    return base
+
+
 def config(idx: int, *, seed: Optional[int] = None, max_len: Optional[int] = None) -> Workload:
     """The five benchmark configurations (1-based ``idx``).
 
@@ -173,4 +223,8 @@ def config(idx: int, *, seed: Optional[int] = None, max_len: Optional[int] = Non
     if idx == 5:  # 70B-shaped layer, batch 4, 128K, 2-bit keys / 1-bit values
         return make_workload("c5_70b_B4_L131072_k2v1", B=4, Hq=64, Hkv=8, seqlens=[cap(131072)] * 4, Mk=32, Mv=16,
                              dtype="bf16", seed=s)
-    raise ValueError(f"config index {idx} not in 1..5")
+    if idx in (6, 7):  # 8B-shaped layer, 128K, keys in the paper's own paired format: 1-bit (R = 11) / 2-bit (R = 21)
+        R = 11 if idx == 6 else 21
+        return make_pair_workload(f"c{idx}_8b_L131072_paired_R{R}", B=1, Hq=32, Hkv=8, seqlens=[cap(131072)], R=R,
+                                  Mv=16 if idx == 6 else 32, seed=s)
+    raise ValueError(f"config index {idx} not in 1..7")

@@ -46,6 +46,15 @@ def test_validate_config_rejects(kw):
     assert cv.commvq_validate_config(good_cfg(**kw)) == 2  # COMMVQ_ERR_CONFIG
 
 
+def test_validate_config_paired_key_format():
+    ok = dict(key_format=cv.COMMVQ_KEYS_PAIRED, key_levels=11, m_key=0)   # m_key is ignored with paired keys
+    assert cv.commvq_validate_config(good_cfg(**ok)) == 0
+    assert cv.commvq_validate_config(good_cfg(**dict(ok, key_levels=21))) == 0
+    for bad in (dict(ok, key_levels=0), dict(ok, key_levels=22), dict(ok, codebook_dtype=0, q_dtype=0),
+                dict(key_format=2, key_levels=11)):
+        assert cv.commvq_validate_config(good_cfg(**bad)) == 2
+
+
 def test_status_strings_are_distinct():
     s = {cv.commvq_status_string(i) for i in range(7)}
     assert len(s) == 7 and "ok" in s

@@ -206,6 +206,76 @@ def test_run_to_run_spread(gpu):
     assert np.array_equal(a, b) and np.array_equal(a, c)
 
 
+# ---------------------------------------------------------------- keys in the paper's own paired format
+def oracle_out_paired(oracle, w, **kw):
+    """The oracle sees the same packed records and the same tied table, as index form with 2R tied codebooks."""
+    kc = oracle.paired_as_indexed(w.key_codes, w.key_levels, w.cu_seqlens, w.Hkv)
+    kcb = oracle.tied_table_as_codebooks(w.as_f64("key_codebooks"), K=w.K)
+    return oracle.decode_attn(w.as_f64("q"), kc, w.val_codes, kcb, w.as_f64("val_codebooks"), w.cu_seqlens, w.q_pos,
+                              rope_base=w.rope_base, n_threads=16, **kw)
+
+
+@pytest.mark.parametrize("R", [11, 21, 3, 16, 17])
+@pytest.mark.parametrize("G,Hkv", [(4, 2), (1, 2), (8, 1), (2, 1)])
+def test_paired_keys_match_oracle(gpu, oracle, R, G, Hkv):
+    if R in (3, 16, 17) and G != 4:
+        pytest.skip("odd level counts are covered at G = 4")
+    w = synth.make_pair_workload(f"pair_R{R}_g{G}", B=2, Hq=G * Hkv, Hkv=Hkv, seqlens=[1500, 333], R=R, Mv=16,
+                                 seed=1000 + 10 * R + G)
+    print(f"case {w.name}", flush=True)
+    got = run_gpu(gpu, w)
+    ref = oracle_out_paired(oracle, w)
+    err = row_err(got, ref)
+    print(f"  max row error {err.max():.3e}", flush=True)
+    assert np.isfinite(got).all() and err.max() <= TOL_OUT
+
+
+@pytest.mark.parametrize("R,L", [(11, 1), (11, 255), (11, 257), (21, 1025), (11, 5000), (21, 4097)])
+def test_paired_keys_lengths_and_logits(gpu, oracle, R, L):
+    import torch
+    w = synth.make_pair_workload(f"pair_R{R}_L{L}", B=1, Hq=8, Hkv=2, seqlens=[L], R=R, Mv=32, seed=77 + L)
+    print(f"case {w.name}", flush=True)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    s = op.scores(dw)
+    out = op(dw)
+    torch.cuda.synchronize()
+    ref, ref_scores, _ = oracle_out_paired(oracle, w, return_intermediates=True)
+    assert np.abs(s.cpu().numpy().astype(np.float64) - ref_scores).max() <= TOL_SCORE
+    assert row_err(out.cpu().numpy(), ref).max() <= TOL_OUT
+    # packing the tied table ahead of time changes nothing
+    op.pack_key_codebooks(dw)
+    out2 = op(dw).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    op.close()
+
+
+def test_paired_keys_query_inside_context_and_rejections(gpu, oracle):
+    import paper_2506_18879_amd as cv
+    w = synth.make_pair_workload("pair_qpos", B=2, Hq=8, Hkv=2, seqlens=[2100, 900], R=11, Mv=16, seed=5)
+    w.q_pos = np.array([700, 60000], np.int32)
+    got = run_gpu(gpu, w, max_position=70000)
+    assert row_err(got, oracle_out_paired(oracle, w)).max() <= TOL_OUT
+    # explicit key positions are not supported with paired keys; neither are fp32 tables or R > 21
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w, max_position=70000)
+    import torch
+    kp = torch.zeros(w.total_tokens, dtype=torch.int32, device="cuda")
+    bad = cv.binding.make_positions(2, dw.cu_seqlens, dw.q_pos, kp, w.total_tokens, w.max_seqlen)
+    with pytest.raises(cv.CommVQError) as e:
+        cv.commvq_decode_attn(op.handle, dw.q, dw.key_codes, dw.val_codes, dw.key_codebooks, dw.val_codebooks, bad,
+                              op.out, op.workspace, op.workspace_bytes)
+    assert e.value.status == 2
+    op.close()
+    cfg = cv.Config(8, 2, 128, 16, 16, 256, cv.COMMVQ_BF16, cv.COMMVQ_BF16, 500000.0, 0.0, 4096, cv.COMMVQ_KEYS_PAIRED, 22)
+    assert cv.commvq_validate_config(cfg) == 2
+    cfg = cv.Config(8, 2, 128, 16, 16, 256, cv.COMMVQ_F32, cv.COMMVQ_F32, 500000.0, 0.0, 4096, cv.COMMVQ_KEYS_PAIRED, 11)
+    assert cv.commvq_validate_config(cfg) == 2
+    cfg = cv.Config(8, 2, 128, 16, 16, 256, cv.COMMVQ_BF16, cv.COMMVQ_BF16, 500000.0, 0.0, 4096, cv.COMMVQ_KEYS_PAIRED, 21)
+    assert cv.commvq_validate_config(cfg) == 0
+
+
 # ---------------------------------------------------------------- argument checking through the C ABI
 def test_error_statuses(gpu):
     import torch

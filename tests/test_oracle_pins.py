@@ -373,3 +373,48 @@ def test_softmax_is_max_subtracted(oracle):
     assert np.isfinite(out).all()
     np.testing.assert_allclose(out[0, 0], [1.0, 2.0], atol=1e-300)
     np.testing.assert_allclose(wt, [0.0, 1.0, 0.0], atol=1e-300)
+
+
+# ---------------------------------------------------------------- paired key format (App. A.1)
+def test_pair_records_hand_packed_bytes(oracle):
+    # two pairs (a, b) = (1, 2), (63, 0): 12-bit fields 0x081 and 0x03F, little endian -> bytes 81 F0 03
+    a, b = oracle.unpack_key_pairs(np.array([0x81, 0xF0, 0x03], np.uint8), 2)
+    assert a.tolist() == [1, 63] and b.tolist() == [2, 0]
+    from paper_2506_18879_amd import synth
+    assert synth.pack_key_pairs(np.array([1, 63]), np.array([2, 0])).tolist() == [0x81, 0xF0, 0x03]
+
+
+@pytest.mark.parametrize("R", [1, 2, 11, 21])
+def test_pair_records_round_trip(oracle, R):
+    from paper_2506_18879_amd import synth
+    rng = np.random.default_rng(R)
+    a = rng.integers(0, 64, (5, 7, R)).astype(np.uint8)
+    b = rng.integers(0, 64, (5, 7, R)).astype(np.uint8)
+    rec = synth.pack_key_pairs(a, b)
+    assert rec.shape == (5, 7, (12 * R + 7) // 8)
+    a2, b2 = oracle.unpack_key_pairs(rec, R)
+    assert np.array_equal(a, a2) and np.array_equal(b, b2)
+
+
+def test_tied_table_decodes_to_appendix_centres(oracle):
+    # Eq. def_center in complex form: a block (x, y) is z = x + iy, its second row (-y, x) is i z, so a
+    # level decodes to z_a + i z_b in every sub-space; R levels add up (residual quantization, Sec. 4.2)
+    rng = np.random.default_rng(4)
+    R, N, d = 3, 64, 16
+    table = rng.standard_normal((1, R, N, d))
+    a = rng.integers(0, N, R)
+    b = rng.integers(0, N, R)
+    cb = oracle.tied_table_as_codebooks(table, K=256)
+    assert cb.shape == (1, 2 * R, 256, d) and not cb[:, :, N:].any()
+    codes = np.empty(2 * R, np.uint8)
+    codes[0::2], codes[1::2] = a, b
+    got = oracle.decode(codes, cb[0])
+    z = table[0, :, :, 0::2] + 1j * table[0, :, :, 1::2]            # [R][N][d/2]
+    want = sum(z[r, a[r]] + 1j * z[r, b[r]] for r in range(R))
+    assert np.abs(got[0::2] - want.real).max() < 1e-14 and np.abs(got[1::2] - want.imag).max() < 1e-14
+    # and every block of the expanded codebooks still commutes with a rotation (Property 1)
+    th = 0.7
+    Rm = np.array([[np.cos(th), -np.sin(th)], [np.sin(th), np.cos(th)]])
+    x, y = cb[0, 1, 5, 0], cb[0, 1, 5, 1]
+    blk = np.array([[x, y], [-y, x]])
+    assert np.abs(blk @ Rm - Rm @ blk).max() < 1e-15
