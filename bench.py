@@ -28,7 +28,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=12)
-    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = 8B-shaped layer, 128K context, 1-bit)")
+    ap.add_argument("--config", type=int, default=3,
+                    help="workload 1..7 (3 = 8B-shaped layer, 128K context, 1-bit; 6, 7 = the same layer with keys in "
+                         "the paper's paired format, R = 11 / 21)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-resident numbers)")
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
@@ -54,8 +56,8 @@ def main():
     w = synth.config(args.config)
     T, G = w.total_tokens, w.Hq // w.Hkv
     esz = 2 if w.dtype == "bf16" else 4
-    code_bytes = T * w.Hkv * (w.Mk + w.Mv)
-    cb_bytes = w.Hkv * w.K * w.d * (w.Mk + w.Mv) * esz
+    code_bytes = w.key_codes.nbytes + w.val_codes.nbytes
+    cb_bytes = w.key_codebooks.nbytes + w.val_codebooks.nbytes
     per_copy = code_bytes + cb_bytes
     n_copies = 1 if args.warm else max(2, -(-COLD_FOOTPRINT // per_copy))
 
@@ -101,7 +103,8 @@ def main():
     units = T * w.Hkv
     score_flops = units * w.d * (w.Mk + 3 + 2 * G)
     achieved_tflops = score_flops / score_s / 1e12 if score_s > 0 else 0.0
-    kname = "k_score_mfma" if w.dtype == "bf16" else "k_score"
+    paired = w.key_format == "paired"
+    kname = "k_score_pair" if paired else ("k_score_mfma" if w.dtype == "bf16" else "k_score")
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -109,7 +112,7 @@ def main():
             traffic = json.load(open(tpath)).get(w.name, {}).get(kname)
         except Exception:
             traffic = None
-    key_stream_gbs = T * w.Hkv * w.Mk / score_s / 1e9 if score_s > 0 else 0.0
+    key_stream_gbs = w.key_codes.nbytes / score_s / 1e9 if score_s > 0 else 0.0
     # the pipes the kernel actually loads: codeword pieces gathered from LDS, and the matrix instructions that
     # sum them (one 16x16x32 bf16 MFMA = 16384 flop per 64 pieces of 16 bytes, half of it multiplications by zero)
     gather_bytes = units * w.Mk * w.d * esz
@@ -118,7 +121,8 @@ def main():
     roofline = {"kernel": kname, "bound": "alu", "achieved": round(achieved_tflops, 3), "peak": FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved_tflops / FP32_PEAK_TFLOPS, 4), "traffic": traffic,
                 "kernel_ms": round(stage_ms[0], 5), "launches_averaged": n_prof,
-                "timed_region_includes": "k_score_mfma only" if prepacked else "codebook re-layout (k_prep) + score kernel",
+                "timed_region_includes": ("index unpacking (k_unpack_pairs) + k_score_pair" if paired else
+                                          "k_score_mfma only" if prepacked else "codebook re-layout (k_prep) + score kernel"),
                 "lds_gather_view": {"codeword_bytes_TBs": round(gather_tbs, 2), "peak_TBs": LDS_PEAK_TBS,
                                     "frac": round(gather_tbs / LDS_PEAK_TBS, 4)},
                 "mfma_view": {"issued_bf16_TFLOPs": round(mfma_tflops, 1), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
@@ -133,6 +137,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "context_tokens": T, "m_key": w.Mk, "m_val": w.Mv, "codewords": w.K, "storage": w.dtype,
+                   "key_format": w.key_format, "key_levels": w.key_levels,
                    "codes": w.code_dist, "buffer_copies_rotated": n_copies,
                    "key_codebooks_packed_before_timed_region": prepacked,
                    "cache_state": "warm" if args.warm else "cold (rotating copies > 256 MB LLC)"},

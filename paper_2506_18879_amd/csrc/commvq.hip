@@ -1109,7 +1109,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
             for (int pl = 0; pl < PL; ++pl) {
                 // 1. gather-sum of the plane: 8 NB pieces per lane, in groups of 4 reads
                 floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-                constexpr int NS = 8 * NB, RG = 4, NG = NS / RG;
+                constexpr int NS = 8 * NB, RG = (NB == 2 || G == 8) ? 2 : 4, NG = NS / RG;  // fewer reads in flight where registers are short
                 uint4 v[2][RG];
                 auto issue = [&](int grp, uint4(&dst)[RG]) {
 #pragma unroll
