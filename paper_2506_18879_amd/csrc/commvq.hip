@@ -889,7 +889,7 @@ constexpr int kPairBlock = kPairK * 256;  // bytes of one (plane, block of 16 le
 __global__ __launch_bounds__(256) void k_unpack_pairs(const uint8_t *__restrict__ pairs, uint8_t *__restrict__ bytes,
                                                       const int32_t *__restrict__ cu, int Hkv, int R, int PB, int NB)
 {
-    __shared__ unsigned stage[256 * 32 / 4 + 2];
+    __shared__ unsigned stage[256 * 32 / 4 + 12];  // a few dwords of slack: threads read 9 whole dwords each
     const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
     const int cu0 = cu[b], L = cu[b + 1] - cu0;
     const int i0 = blockIdx.x * 256;
@@ -909,15 +909,26 @@ __global__ __launch_bounds__(256) void k_unpack_pairs(const uint8_t *__restrict_
     }
     __syncthreads();
     if ((int)threadIdx.x >= cnt) return;
-    const uint8_t *rec = reinterpret_cast<const uint8_t *>(stage) + skew + threadIdx.x * PB;
+    // the thread's record as aligned dwords: whole dwords out of LDS, then one byte-granular funnel shift each
+    const unsigned at = skew + threadIdx.x * PB;
+    const unsigned sh = at & 3u;
+    unsigned raw[9], rec[8];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) raw[k] = 4 * k < PB + 3 ? stage[(at >> 2) + k] : 0u;  // PB <= 32: 9 dwords cover any skew
+#pragma unroll
+    for (int k = 0; k < 8; ++k) rec[k] = __builtin_amdgcn_alignbyte(raw[k + 1], raw[k], sh);
     uint4 *dst = reinterpret_cast<uint4 *>(bytes + ((size_t)cu0 * Hkv + (size_t)g * L + i0 + threadIdx.x) * (32 * NB));
-    for (int blk = 0; blk < NB; ++blk) {
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+        if (blk >= NB) break;
         unsigned wa[4] = {0, 0, 0, 0}, wb[4] = {0, 0, 0, 0};
+#pragma unroll
         for (int col = 0; col < 16; ++col) {
             const int r = 16 * blk + col;
-            if (r < R) {
-                const int at = (3 * r) >> 1;
-                const unsigned pr = (((unsigned)rec[at] | (unsigned)rec[at + 1] << 8) >> (4 * (r & 1))) & 0xfffu;
+            if (r < R && r < 21) {
+                const int bit = 12 * r;  // a pair never needs more than two dwords
+                const unsigned lo = rec[bit >> 5], hi = (bit >> 5) + 1 < 8 ? rec[(bit >> 5) + 1] : 0u;
+                const unsigned pr = __builtin_amdgcn_alignbit(hi, lo, (unsigned)(bit & 31)) & 0xfffu;
                 wa[col >> 2] |= (pr & 63u) << (8 * (col & 3));
                 wb[col >> 2] |= (pr >> 6) << (8 * (col & 3));
             }
