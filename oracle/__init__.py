@@ -43,6 +43,8 @@ def _load():
             [ctypes.c_int] * 7 + [ctypes.c_void_p] * 8 + [ctypes.c_double] * 2 + [ctypes.c_void_p] * 4 + [ctypes.c_int]
         )
         lib.commvq_oracle_decode_attn.restype = ctypes.c_int
+        lib.commvq_oracle_encode_keys.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 6
+        lib.commvq_oracle_encode_keys.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -162,3 +164,32 @@ def paired_as_indexed(records, R, cu_seqlens, Hkv):
     out = np.empty((rec.shape[0], 2 * R), dtype=np.uint8)
     out[:, 0::2], out[:, 1::2] = a, b
     return out.reshape(-1)
+
+
+def encode_keys(keys, codebooks, paired=False, given=None):
+    """Residual nearest-centre encoding of key vectors of ONE KV head (Sec. 4.2 E step, level by level).
+
+    keys [n][d]; codebooks [levels][K][d] (index form) or the tied table [R][K][d] (paired, centres
+    C[r][a] + second rows of C[r][b], Eq. def_center).  Returns (codes, best, taken): codes uint8
+    [n][levels] (or [n][levels][2] = (a, b) when paired) = the nearest centre at every level; best[n][levels]
+    its squared distance to the residual searched; taken[n][levels] the squared residual norm after the
+    level.  With `given` (same shape as codes) the residual is updated with those codes instead, so that
+    another encoder's choices can be judged level by level.
+    """
+    keys = _f64(keys)
+    cb = _f64(codebooks)
+    n, d = keys.shape
+    levels, K, d2 = cb.shape
+    assert d2 == d
+    per = 2 if paired else 1
+    codes = np.zeros((n, levels, per), dtype=np.uint8)
+    best = np.zeros((n, levels), dtype=np.float64)
+    taken = np.zeros((n, levels), dtype=np.float64)
+    g = None
+    if given is not None:
+        g = np.ascontiguousarray(given, dtype=np.uint8).reshape(n, levels, per)
+    rc = _load().commvq_oracle_encode_keys(n, d, levels, K, 1 if paired else 0, _ptr(keys), _ptr(cb), _ptr(g),
+                                           _ptr(codes), _ptr(best), _ptr(taken))
+    if rc != 0:
+        raise ValueError(f"commvq_oracle_encode_keys failed with code {rc}")
+    return (codes if paired else codes[:, :, 0]), best, taken

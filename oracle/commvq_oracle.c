@@ -190,3 +190,84 @@ int commvq_oracle_decode_attn(int B, int Hq, int Hkv, int d, int Mk, int Mv, int
     free(th); free(ws);
     return rc;
 }
+
+/*
+ * Key encoding for cache append (Sec. 4.2: the E step of the clustering -- every vector goes to its
+ * nearest clustering centre -- applied level by level to the quantization error of the previous
+ * level, "conceptually similar to residual vector quantization"; App. A.1 for what a centre is).
+ *
+ *   paired == 0  index form: level m has the K centres C[m][c]; the token stores c_m.
+ *   paired != 0  paper's format: level r has the K*K centres C[r][a] + (second rows of the blocks of
+ *                C[r][b]), i.e. per sub-space (x_a - y_b, y_a + x_b) (Eq. def_center); the token stores
+ *                (a_r, b_r).
+ *
+ *   keys   [n][d]            vectors of ONE KV head (pre-RoPE)
+ *   cb     [levels][K][d]    that head's codebooks / tied table
+ *   given  [n][levels*(paired?2:1)] or NULL.  If not NULL, level l takes the given codes instead of its
+ *          own nearest centre when updating the residual (the search result is still reported), so a
+ *          caller can ask "how good was somebody else's choice at each level, given their earlier ones".
+ *   codes  [n][levels*(paired?2:1)]  nearest centre at each level (a, b interleaved when paired)
+ *   best   [n][levels]       squared distance of that nearest centre to the residual it was searched for
+ *   taken  [n][levels] or NULL  squared distance of the centre actually used (== best when given is NULL)
+ * Every candidate's distance is computed from scratch as sum_e (res_e - centre_e)^2; ties go to the
+ * lowest candidate index (a * K + b when paired).
+ */
+int commvq_oracle_encode_keys(int n, int d, int levels, int K, int paired, const double *keys, const double *cb,
+                              const uint8_t *given, uint8_t *codes, double *best, double *taken)
+{
+    if (n < 0 || d < 2 || (d & 1) || levels < 1 || K < 1 || K > 256) return 1;
+    const int per = paired ? 2 : 1;
+    double *res = (double *)malloc(sizeof(double) * (size_t)d);
+    double *cen = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!res || !cen) { free(res); free(cen); return 2; }
+    for (int t = 0; t < n; ++t) {
+        memcpy(res, keys + (size_t)t * d, sizeof(double) * (size_t)d);
+        for (int l = 0; l < levels; ++l) {
+            const double *C = cb + (size_t)l * K * d;
+            double bd = INFINITY;
+            int ba = 0, bb = 0;
+            const int nb = paired ? K : 1;
+            for (int a = 0; a < K; ++a)
+                for (int b = 0; b < nb; ++b) {
+                    double dist = 0.0;
+                    for (int j = 0; j < d / 2; ++j) {
+                        double cx = C[(size_t)a * d + 2 * j], cy = C[(size_t)a * d + 2 * j + 1];
+                        if (paired) {  /* + second row (-y, x) of block j of centre b */
+                            cx += -C[(size_t)b * d + 2 * j + 1];
+                            cy += C[(size_t)b * d + 2 * j];
+                        }
+                        const double ex = res[2 * j] - cx, ey = res[2 * j + 1] - cy;
+                        dist += ex * ex + ey * ey;
+                    }
+                    if (dist < bd) { bd = dist; ba = a; bb = b; }
+                }
+            codes[((size_t)t * levels + l) * per] = (uint8_t)ba;
+            if (paired) codes[((size_t)t * levels + l) * per + 1] = (uint8_t)bb;
+            best[(size_t)t * levels + l] = bd;
+            int ua = ba, ub = bb;
+            if (given) {
+                ua = given[((size_t)t * levels + l) * per];
+                ub = paired ? given[((size_t)t * levels + l) * per + 1] : 0;
+                if (ua >= K || ub >= K) { free(res); free(cen); return 3; }
+            }
+            for (int j = 0; j < d / 2; ++j) {
+                double cx = C[(size_t)ua * d + 2 * j], cy = C[(size_t)ua * d + 2 * j + 1];
+                if (paired) {
+                    cx += -C[(size_t)ub * d + 2 * j + 1];
+                    cy += C[(size_t)ub * d + 2 * j];
+                }
+                cen[2 * j] = cx;
+                cen[2 * j + 1] = cy;
+            }
+            double td = 0.0;
+            for (int e = 0; e < d; ++e) {
+                res[e] -= cen[e];
+                td += res[e] * res[e];
+            }
+            if (taken) taken[(size_t)t * levels + l] = td;
+        }
+    }
+    free(res);
+    free(cen);
+    return 0;
+}

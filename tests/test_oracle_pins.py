@@ -418,3 +418,57 @@ def test_tied_table_decodes_to_appendix_centres(oracle):
     x, y = cb[0, 1, 5, 0], cb[0, 1, 5, 1]
     blk = np.array([[x, y], [-y, x]])
     assert np.abs(blk @ Rm - Rm @ blk).max() < 1e-15
+
+
+# ---------------------------------------------------------------- key encoding (cache append)
+def test_encode_single_level_is_the_library_nearest_centre(oracle):
+    # one level = plain vector quantization: scipy's vq returns the nearest code and its distance
+    from scipy.cluster.vq import vq
+    rng = np.random.default_rng(8)
+    cb = rng.standard_normal((1, 37, 12))
+    keys = rng.standard_normal((50, 12))
+    codes, best, taken = oracle.encode_keys(keys, cb)
+    want, dist = vq(keys, cb[0])
+    assert np.array_equal(codes[:, 0], want)
+    assert np.abs(np.sqrt(best[:, 0]) - dist).max() < 1e-12 and np.abs(best - taken).max() < 1e-12
+
+
+def test_encode_paired_level_searches_all_centres_of_def_center(oracle):
+    # build the K*K centres z_a + i z_b explicitly (complex form of Eq. def_center) and let scipy search them
+    from scipy.cluster.vq import vq
+    rng = np.random.default_rng(9)
+    K, d = 6, 8
+    table = rng.standard_normal((1, K, d))
+    z = table[0, :, 0::2] + 1j * table[0, :, 1::2]
+    cen = (z[:, None, :] + 1j * z[None, :, :]).reshape(K * K, d // 2)
+    flat = np.empty((K * K, d))
+    flat[:, 0::2], flat[:, 1::2] = cen.real, cen.imag
+    keys = rng.standard_normal((40, d))
+    codes, best, _ = oracle.encode_keys(keys, table, paired=True)
+    want, dist = vq(keys, flat)
+    assert np.array_equal(codes[:, 0, 0].astype(int) * K + codes[:, 0, 1], want)
+    assert np.abs(np.sqrt(best[:, 0]) - dist).max() < 1e-12
+
+
+def test_encode_is_residual_and_decodable(oracle):
+    # level l searches the error left by levels < l (Sec. 4.2), and key - decode(codes) is the last residual
+    rng = np.random.default_rng(10)
+    cb = rng.standard_normal((3, 16, 8))
+    keys = rng.standard_normal((20, 8))
+    codes, best, taken = oracle.encode_keys(keys, cb)
+    for t in range(20):
+        res = keys[t].copy()
+        for l in range(3):
+            d2 = ((res[None, :] - cb[l]) ** 2).sum(axis=1)
+            assert codes[t, l] == int(np.argmin(d2)) and abs(best[t, l] - d2.min()) < 1e-12
+            res -= cb[l, codes[t, l]]
+        assert abs(taken[t, 2] - (res ** 2).sum()) < 1e-12
+        assert np.abs(keys[t] - oracle.decode(codes[t], cb) - res).max() < 1e-13
+    # a key that is exactly a first-level centre is found with distance 0
+    c2, b2, _ = oracle.encode_keys(cb[0, 5][None, :], cb)
+    assert c2[0, 0] == 5 and b2[0, 0] == 0.0
+    # `given` codes steer the residual but not the reported search
+    forced = codes.copy()
+    forced[:, 0] = (forced[:, 0] + 1) % 16
+    c3, b3, t3 = oracle.encode_keys(keys, cb, given=forced)
+    assert np.array_equal(c3[:, 0], codes[:, 0]) and np.all(t3[:, 0] >= b3[:, 0] - 1e-12)
