@@ -161,6 +161,28 @@ commvq_status commvq_pack_key_codebooks(commvq_handle *handle, const void *key_c
 commvq_status commvq_forget_packed_key_codebooks(commvq_handle *handle, const void *key_codebooks);
 
 /*
+ * Key encoding for cache append: the step before the attention call in every decode iteration.
+ * Each new (pre-RoPE) key vector is assigned to its nearest clustering centre (the E step of Sec. 4.2),
+ * level by level on the error left by the previous levels (residual refinement, Sec. 4.2); a centre of
+ * the paired format is C[r][a] + i C[r][b] (Eq. def_center, App. A.1), searched over all 64 x 64 pairs.
+ * Distances are compared in fp32 as ||c||^2 - 2 res.c; ties go to the lowest index (a * 64 + b).
+ *   commvq_encoder_table_bytes / commvq_encoder_prepare
+ *       one-time tables for a set of key codebooks (squared norms of all rows; paired: plus the
+ *       cross terms 2 C[a].(i C[b])): `tables` is a device buffer of that many bytes, 4-byte aligned
+ *   commvq_encode_keys
+ *       keys        [n_tokens][Hkv][d], q_dtype
+ *       codes_out   the record of token t, KV head g is written at codes_out + t * token_stride +
+ *                   g * head_stride (bytes): M_k index bytes, or the ceil(12 R / 8)-byte packed
+ *                   pair record, so that the caller can point straight into its cache layout
+ *       COMMVQ_ERR_SHAPE if strides are smaller than a record, COMMVQ_ERR_CONFIG for fp32 paired tables
+ */
+commvq_status commvq_encoder_table_bytes(const commvq_handle *handle, size_t *bytes);
+commvq_status commvq_encoder_prepare(commvq_handle *handle, const void *key_codebooks, void *tables, void *stream);
+commvq_status commvq_encode_keys(commvq_handle *handle, const void *keys, int32_t n_tokens, const void *key_codebooks,
+                                 const void *tables, uint8_t *codes_out, int64_t token_stride, int64_t head_stride,
+                                 void *stream);
+
+/*
  * The three stages of commvq_decode_attn, callable on their own (tests and profiling).
  * They read/write the same workspace; run them in this order on one stream.
  *   commvq_stage_scores  Eq. new_attention: scaled logits for every (b, h, token) and the

@@ -18,6 +18,9 @@ from .binding import (  # noqa: F401
     commvq_create,
     commvq_decode_attn,
     commvq_destroy,
+    commvq_encode_keys,
+    commvq_encoder_prepare,
+    commvq_encoder_table_bytes,
     commvq_forget_packed_key_codebooks,
     commvq_pack_key_codebooks,
     commvq_packed_key_codebook_bytes,

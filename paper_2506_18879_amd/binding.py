@@ -40,6 +40,7 @@ Handle = c_void_p
 EXPORTS = ("commvq_create", "commvq_destroy", "commvq_validate_config", "commvq_plan_query", "commvq_workspace_bytes",
            "commvq_decode_attn", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
            "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
+           "commvq_encoder_table_bytes", "commvq_encoder_prepare", "commvq_encode_keys",
            "commvq_profile_enable", "commvq_profile_read", "commvq_status_string")
 
 
@@ -71,6 +72,9 @@ def load_library():
     lib.commvq_packed_key_codebook_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.commvq_pack_key_codebooks.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     lib.commvq_forget_packed_key_codebooks.argtypes = [c_void_p, c_void_p]
+    lib.commvq_encoder_table_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
+    lib.commvq_encoder_prepare.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.commvq_encode_keys.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p]
     lib.commvq_profile_enable.argtypes = [c_void_p, c_int32]
     lib.commvq_profile_read.argtypes = [c_void_p, POINTER(c_float), POINTER(c_int32)]
     for name in EXPORTS:
@@ -150,6 +154,24 @@ def commvq_pack_key_codebooks(handle, key_codebooks, packed, stream: int = 0) ->
 def commvq_forget_packed_key_codebooks(handle, key_codebooks=None) -> None:
     _check(load_library().commvq_forget_packed_key_codebooks(handle, _ptr(key_codebooks)),
            "commvq_forget_packed_key_codebooks")
+
+
+def commvq_encoder_table_bytes(handle) -> int:
+    n = c_size_t()
+    _check(load_library().commvq_encoder_table_bytes(handle, byref(n)), "commvq_encoder_table_bytes")
+    return int(n.value)
+
+
+def commvq_encoder_prepare(handle, key_codebooks, tables, stream: int = 0) -> None:
+    _check(load_library().commvq_encoder_prepare(handle, _ptr(key_codebooks), _ptr(tables), stream or None),
+           "commvq_encoder_prepare")
+
+
+def commvq_encode_keys(handle, keys, n_tokens: int, key_codebooks, tables, codes_out, token_stride: int,
+                       head_stride: int, stream: int = 0) -> None:
+    _check(load_library().commvq_encode_keys(handle, _ptr(keys), int(n_tokens), _ptr(key_codebooks), _ptr(tables),
+                                             _ptr(codes_out), int(token_stride), int(head_stride), stream or None),
+           "commvq_encode_keys")
 
 
 def commvq_stage_scores(handle, q, key_codes, key_codebooks, positions: Positions, workspace, workspace_bytes: int,

@@ -1205,6 +1205,146 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
     }
 }
 
+// ------------------------------------------------------------------ key encoding (cache append)
+// Residual nearest-centre search (Sec. 4.2: the E step's assignment, level by level on the error of the
+// previous levels; App. A.1 for the paired centres).  ||res - c||^2 = ||res||^2 - 2 res.c + ||c||^2, so a
+// level needs the dot products of the residual with that level's rows and a table of squared norms:
+//   norms[g][level][K]            ||C[g][level][c]||^2
+//   cross[g][level][K][K]         paired only: 2 C[a] . (i C[b])   (K = 64), so that a paired centre costs
+//                                 norms[a] + norms[b] + cross[a][b] - 2 (res.C[a] + res.(i C[b]))
+template <bool BF16>
+__device__ __forceinline__ float cb_elem(const void *cb, size_t i)
+{
+    if (BF16) return __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(cb)[i] << 16);
+    return static_cast<const float *>(cb)[i];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_encode_tables(const void *__restrict__ cb, float *__restrict__ norms,
+                                                       float *__restrict__ cross, int rows_total, int K, int paired)
+{
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t < (size_t)rows_total) {
+        float acc = 0.f;
+        for (int e = 0; e < kD; ++e) {
+            const float v = cb_elem<BF16>(cb, t * kD + e);
+            acc = __builtin_fmaf(v, v, acc);
+        }
+        norms[t] = acc;
+    }
+    if (paired && t < (size_t)rows_total * K) {
+        const size_t level = t / ((size_t)K * K);   // g * R + r
+        const int a = (int)(t / K % K), b = (int)(t % K);
+        const size_t ra = (level * K + a) * kD, rb = (level * K + b) * kD;
+        float acc = 0.f;
+        for (int j = 0; j < kJ; ++j) {  // (x_a, y_a) . (-y_b, x_b)
+            const float xa = cb_elem<BF16>(cb, ra + 2 * j), ya = cb_elem<BF16>(cb, ra + 2 * j + 1);
+            const float xb = cb_elem<BF16>(cb, rb + 2 * j), yb = cb_elem<BF16>(cb, rb + 2 * j + 1);
+            acc = __builtin_fmaf(ya, xb, __builtin_fmaf(-xa, yb, acc));
+        }
+        cross[t] = 2.f * acc;
+    }
+}
+
+struct EncodeDims {
+    int Hkv, levels, K, key_bf16, record_bytes;
+    long long token_stride, head_stride;
+};
+
+// One workgroup per (token, KV head).  Ties go to the lowest candidate index (a * K + b when paired).
+template <bool PAIRED, bool BF16>
+__global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, const void *__restrict__ cb,
+                                                const float *__restrict__ norms, const float *__restrict__ cross,
+                                                uint8_t *__restrict__ out, const EncodeDims a)
+{
+    __shared__ float res[kD];
+    __shared__ float dots[256];
+    __shared__ float wbest[4];
+    __shared__ int wcand[4];
+    __shared__ int chosen[64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x % a.Hkv;
+    const size_t tok = blockIdx.x / a.Hkv;
+    const int K = a.K;
+    if (tid < kD) {
+        const size_t i = (tok * a.Hkv + g) * kD + tid;
+        res[tid] = a.key_bf16 ? __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(keys)[i] << 16)
+                              : static_cast<const float *>(keys)[i];
+    }
+    __syncthreads();
+    for (int l = 0; l < a.levels; ++l) {
+        const size_t level = (size_t)g * a.levels + l;
+        const size_t base = level * K * kD;
+        float best = INFINITY;
+        int cand = 0x7fffffff;
+        if (!PAIRED) {
+            if (tid < K) {
+                float acc = 0.f;
+                for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
+                best = norms[level * K + tid] - 2.f * acc;
+                cand = tid;
+            }
+        } else {
+            if (tid < 2 * K) {  // res . C[a] for tid < K, res . (i C[b]) = sum_j (-res_x y_b + res_y x_b) after
+                const int c = tid % K;
+                float acc = 0.f;
+                for (int j = 0; j < kJ; ++j) {
+                    const float x = cb_elem<BF16>(cb, base + (size_t)c * kD + 2 * j), y = cb_elem<BF16>(cb, base + (size_t)c * kD + 2 * j + 1);
+                    acc = tid < K ? __builtin_fmaf(res[2 * j + 1], y, __builtin_fmaf(res[2 * j], x, acc))
+                                  : __builtin_fmaf(res[2 * j + 1], x, __builtin_fmaf(-res[2 * j], y, acc));
+                }
+                dots[tid] = acc;
+            }
+            __syncthreads();
+            for (int c = tid; c < K * K; c += 256) {
+                const int ca = c / K, cb2 = c % K;
+                const float sc = norms[level * K + ca] + norms[level * K + cb2] + cross[level * K * K + c] - 2.f * (dots[ca] + dots[K + cb2]);
+                if (sc < best) { best = sc; cand = c; }
+            }
+        }
+        // argmin over the workgroup, lowest candidate on ties
+        const float wm = -wave_max(-best);
+        int wc = best == wm ? cand : 0x7fffffff;
+        for (int off = 32; off > 0; off >>= 1) wc = min(wc, __shfl_xor(wc, off));
+        if (lane == 0) { wbest[wave] = wm; wcand[wave] = wc; }
+        __syncthreads();
+        if (tid == 0) {
+            float m = wbest[0];
+            int c = wcand[0];
+            for (int w = 1; w < 4; ++w)
+                if (wbest[w] < m || (wbest[w] == m && wcand[w] < c)) { m = wbest[w]; c = wcand[w]; }
+            chosen[l] = c;
+        }
+        __syncthreads();
+        const int c = chosen[l];
+        if (tid < kD) {
+            if (!PAIRED) {
+                res[tid] -= cb_elem<BF16>(cb, base + (size_t)c * kD + tid);
+            } else {
+                const int ca = c / K, cb2 = c % K;
+                // element e of i C[b]: (-y_b, x_b) of its sub-space
+                const float second = (tid & 1) ? cb_elem<BF16>(cb, base + (size_t)cb2 * kD + tid - 1)
+                                               : -cb_elem<BF16>(cb, base + (size_t)cb2 * kD + tid + 1);
+                res[tid] -= cb_elem<BF16>(cb, base + (size_t)ca * kD + tid) + second;
+            }
+        }
+        __syncthreads();
+    }
+    uint8_t *dst = out + tok * a.token_stride + (long long)g * a.head_stride;
+    if (!PAIRED) {
+        if (tid < a.levels) dst[tid] = (uint8_t)chosen[tid];
+    } else if (tid < a.record_bytes) {
+        // byte tid of the record: the 12-bit pairs (a | b << 6) that overlap bits 8 tid .. 8 tid + 7
+        unsigned v = 0;
+        for (int r = (8 * tid) / 12; r < a.levels && 12 * r < 8 * tid + 8; ++r) {
+            const unsigned pr = (unsigned)(chosen[r] / K) | (unsigned)(chosen[r] % K) << 6;
+            const int sh = 12 * r - 8 * tid;
+            v |= sh >= 0 ? pr << sh : pr >> -sh;
+        }
+        dst[tid] = (uint8_t)(v & 0xffu);
+    }
+}
+
 // ------------------------------------------------------------------ k_bins
 struct BinsArgs {
     const uint8_t *val_codes;
@@ -1834,6 +1974,62 @@ commvq_status commvq_forget_packed_key_codebooks(commvq_handle *h, const void *k
             --i;
         }
     return COMMVQ_OK;
+}
+
+commvq_status commvq_encoder_table_bytes(const commvq_handle *h, size_t *bytes)
+{
+    if (!h || !bytes) return COMMVQ_ERR_NULL;
+    const commvq_config &c = h->cfg;
+    const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
+    const size_t levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
+    *bytes = (size_t)c.n_kv_heads * levels * K * sizeof(float) * (paired ? 1 + K : 1);
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void *tables, void *stream)
+{
+    if (!h || !key_cb || !tables) return COMMVQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(tables) & 3u) return COMMVQ_ERR_SHAPE;
+    const commvq_config &c = h->cfg;
+    const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
+    const int levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
+    const int rows = c.n_kv_heads * levels * K;
+    float *norms = static_cast<float *>(tables), *cross = norms + rows;
+    const size_t n = paired ? (size_t)rows * K : (size_t)rows;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (c.codebook_dtype == COMMVQ_BF16)
+        hipLaunchKernelGGL(k_encode_tables<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, key_cb, norms, cross, rows, K, paired ? 1 : 0);
+    else
+        hipLaunchKernelGGL(k_encode_tables<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, key_cb, norms, cross, rows, K, paired ? 1 : 0);
+    return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+}
+
+commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_tokens, const void *key_cb, const void *tables,
+                                 uint8_t *codes_out, int64_t token_stride, int64_t head_stride, void *stream)
+{
+    if (!h || !keys || !key_cb || !tables || !codes_out) return COMMVQ_ERR_NULL;
+    const commvq_config &c = h->cfg;
+    const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
+    const int levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
+    const int rec = paired ? (12 * levels + 7) / 8 : levels;
+    if (n_tokens < 1 || (int64_t)n_tokens * c.n_kv_heads > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
+    if (head_stride < rec || token_stride < rec) return COMMVQ_ERR_SHAPE;  // records must not overlap
+    EncodeDims d;
+    d.Hkv = c.n_kv_heads; d.levels = levels; d.K = K; d.key_bf16 = c.q_dtype == COMMVQ_BF16; d.record_bytes = rec;
+    d.token_stride = token_stride; d.head_stride = head_stride;
+    const int rows = c.n_kv_heads * levels * K;
+    const float *norms = static_cast<const float *>(tables), *cross = norms + rows;
+    const dim3 grid((unsigned)(n_tokens * c.n_kv_heads));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
+    if (paired) {
+        if (bf16) hipLaunchKernelGGL((k_encode<true, true>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
+        else return COMMVQ_ERR_CONFIG;
+    } else {
+        if (bf16) hipLaunchKernelGGL((k_encode<false, true>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
+        else hipLaunchKernelGGL((k_encode<false, false>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
+    }
+    return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
 
 commvq_status commvq_stage_scores(commvq_handle *h, const void *q, const uint8_t *key_codes, const void *key_cb,

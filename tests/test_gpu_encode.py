@@ -1,0 +1,134 @@
+"""GPU parity of the key encoder (cache append) against the fp64 oracle.
+
+The encoder decides integers (nearest centre per level) from fp32 distances; the oracle decides them in
+fp64.  A different choice is correct when the two centres are equidistant up to rounding, and from then
+on the residuals differ, so the comparison is: (i) almost all records are identical, and (ii) for EVERY
+record, at every level, the centre the GPU took is as near to the residual left by its own earlier
+choices as the nearest centre the oracle finds for that residual, within fp32 rounding.
+"""
+import numpy as np
+import pytest
+
+from paper_2506_18879_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2506_18879_amd as cv
+    cv.load_library()
+    from paper_2506_18879_amd import device
+    return device
+
+
+def encode_on_gpu(gpu, w, keys_bits, L_cap):
+    """Encode keys [n][Hkv][d] (bf16 bits) straight into a cache-shaped buffer [Hkv][L_cap][record]."""
+    import torch
+    import paper_2506_18879_amd as cv
+    n = keys_bits.shape[0]
+    paired = w.key_format == "paired"
+    rec = (12 * w.key_levels + 7) // 8 if paired else w.Mk
+    op = gpu.DecodeAttention(w)
+    kcb = gpu.to_device(w.key_codebooks, True)
+    keys = gpu.to_device(keys_bits, True)
+    tables = torch.empty(cv.commvq_encoder_table_bytes(op.handle), dtype=torch.uint8, device="cuda")
+    cache = torch.full((w.Hkv, L_cap, rec), 0xEE, dtype=torch.uint8, device="cuda")
+    cv.commvq_encoder_prepare(op.handle, kcb, tables)
+    cv.commvq_encode_keys(op.handle, keys, n, kcb, tables, cache, rec, L_cap * rec)
+    torch.cuda.synchronize()
+    out = cache.cpu().numpy()
+    assert (out[:, n:] == 0xEE).all()          # nothing written past the n appended tokens
+    op.close()
+    return out[:, :n]                           # [Hkv][n][rec]
+
+
+def judge(oracle, keys_f64, cb_f64, gpu_codes, paired):
+    """keys [n][d], cb [levels][K][d], gpu_codes [n][levels(,2)] of one head."""
+    want, _, _ = oracle.encode_keys(keys_f64, cb_f64, paired=paired)
+    _, best, taken = oracle.encode_keys(keys_f64, cb_f64, paired=paired, given=gpu_codes)
+    same = np.all((want == gpu_codes).reshape(len(keys_f64), -1), axis=1)
+    # validity: the centre taken is (up to fp32 rounding of distances of order ||key||^2) the nearest one
+    scale = (keys_f64 ** 2).sum(axis=1, keepdims=True)
+    assert np.all(taken <= best + 2e-5 * scale + 1e-6), float((taken - best - 2e-5 * scale).max())
+    return same
+
+
+@pytest.mark.parametrize("Mk", [16, 32])
+def test_encode_index_form(gpu, oracle, Mk):
+    w = synth.make_workload(f"enc_m{Mk}", B=1, Hq=4, Hkv=2, seqlens=[8], Mk=Mk, Mv=16, dtype="bf16", seed=200 + Mk)
+    rng = np.random.default_rng(Mk)
+    n = 96
+    keys = synth.f32_to_bf16_bits(rng.standard_normal((n, w.Hkv, w.d)).astype(np.float32))
+    got = encode_on_gpu(gpu, w, keys, L_cap=n + 5)
+    kf = synth.bf16_bits_to_f32(keys).astype(np.float64)
+    cb = w.as_f64("key_codebooks")
+    same = np.concatenate([judge(oracle, kf[:, g], cb[g], got[g], False) for g in range(w.Hkv)])
+    print(f"  identical records: {same.mean():.4f}", flush=True)
+    assert same.mean() >= 0.97
+
+
+@pytest.mark.parametrize("R", [11, 21, 2])
+def test_encode_paired_format(gpu, oracle, R):
+    w = synth.make_pair_workload(f"enc_R{R}", B=1, Hq=4, Hkv=2, seqlens=[8], R=R, Mv=16, seed=300 + R)
+    rng = np.random.default_rng(R)
+    n = 40
+    keys = synth.f32_to_bf16_bits(rng.standard_normal((n, w.Hkv, w.d)).astype(np.float32))
+    got = encode_on_gpu(gpu, w, keys, L_cap=n)
+    kf = synth.bf16_bits_to_f32(keys).astype(np.float64)
+    tab = w.as_f64("key_codebooks")
+    sames = []
+    for g in range(w.Hkv):
+        a, b = oracle.unpack_key_pairs(got[g], R)                       # the same bytes the attention call reads
+        codes = np.stack([a, b], axis=-1)
+        sames.append(judge(oracle, kf[:, g], tab[g], codes, True))
+    same = np.concatenate(sames)
+    print(f"  identical records: {same.mean():.4f}", flush=True)
+    assert same.mean() >= 0.9
+
+
+def test_encode_recovers_exact_centres_and_feeds_attention(gpu, oracle):
+    """Keys that ARE first-level centres come back as that centre; and records written by the encoder are
+    consumed by commvq_decode_attn (append, then attend) with the oracle agreeing on the result."""
+    import torch
+    R = 11
+    L = 300
+    w = synth.make_pair_workload("enc_attn", B=1, Hq=8, Hkv=2, seqlens=[L], R=R, Mv=16, seed=42)
+    tab_bits = w.key_codebooks                                           # [Hkv][R][64][d] bf16 bits
+    keys = np.stack([tab_bits[g, 0, np.arange(L) % 64] for g in range(w.Hkv)], axis=1)   # [L][Hkv][d]
+    got = encode_on_gpu(gpu, w, keys, L_cap=L)
+    tab = w.as_f64("key_codebooks")
+    for g in range(w.Hkv):
+        a, b = oracle.unpack_key_pairs(got[g], R)
+        # the first level must reproduce the key up to the best partner b: distance <= that of (a = own index, any b)
+        codes = np.stack([a, b], axis=-1)
+        judge(oracle, synth.bf16_bits_to_f32(keys[:, g]).astype(np.float64), tab[g], codes, True)
+    # append -> attend
+    w.key_codes = np.ascontiguousarray(got).reshape(-1)                  # [Hkv][L][PB] of the single sequence
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    out = op(dw)
+    torch.cuda.synchronize()
+    kc = oracle.paired_as_indexed(w.key_codes, R, w.cu_seqlens, w.Hkv)
+    ref = oracle.decode_attn(w.as_f64("q"), kc, w.val_codes, oracle.tied_table_as_codebooks(tab, K=w.K),
+                             w.as_f64("val_codebooks"), w.cu_seqlens, w.q_pos, rope_base=w.rope_base, n_threads=8)
+    err = np.abs(out.cpu().numpy() - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+    assert err.max() <= 2e-3
+    op.close()
+
+
+def test_encode_rejects_overlapping_records(gpu):
+    import torch
+    import paper_2506_18879_amd as cv
+    w = synth.make_workload("enc_err", B=1, Hq=4, Hkv=2, seqlens=[8], Mk=16, Mv=16, dtype="bf16", seed=1)
+    op = gpu.DecodeAttention(w)
+    buf = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(cv.CommVQError) as e:
+        cv.commvq_encode_keys(op.handle, buf, 1, buf, buf, buf, 8, 16)
+    assert e.value.status == 3
+    with pytest.raises(cv.CommVQError) as e:
+        cv.commvq_encode_keys(op.handle, buf, 0, buf, buf, buf, 16, 16)
+    assert e.value.status == 3
+    op.close()
