@@ -36,7 +36,74 @@ def parse():
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
     ap.add_argument("--no-prepack", action="store_true",
                     help="re-lay the key codebook inside every call instead of once before the timed region")
+    ap.add_argument("--what", choices=["decode_attn", "encode"], default="decode_attn",
+                    help="encode: time the key encoder (cache append) on --encode-tokens new tokens instead")
+    ap.add_argument("--encode-tokens", type=int, default=4096)
     return ap.parse_args()
+
+
+def bench_encode(args):
+    """One step = commvq_encode_keys over a chunk of new tokens (all KV heads) of the chosen workload's layer."""
+    import numpy as np
+    import torch
+
+    from paper_2506_18879_amd import binding as B
+    from paper_2506_18879_amd import synth
+    from paper_2506_18879_amd.device import DecodeAttention, to_device
+
+    torch.cuda.set_device(0)
+    w = synth.config(args.config, max_len=64)
+    assert w.dtype == "bf16", "the encoder benchmark uses the bf16 workloads"
+    paired = w.key_format == "paired"
+    levels = w.key_levels if paired else w.Mk
+    K = 64 if paired else w.K
+    rec = (12 * levels + 7) // 8 if paired else levels
+    n = args.encode_tokens
+    rng = np.random.default_rng(synth.BASE_SEED)
+    keys = to_device(synth.f32_to_bf16_bits(rng.standard_normal((n, w.Hkv, w.d)).astype(np.float32)), True)
+    kcb = to_device(w.key_codebooks, True)
+    op = DecodeAttention(w)
+    tables = torch.empty(B.commvq_encoder_table_bytes(op.handle), dtype=torch.uint8, device="cuda")
+    cache = torch.zeros((w.Hkv, n, rec), dtype=torch.uint8, device="cuda")
+    B.commvq_encoder_prepare(op.handle, kcb, tables)
+    sp = op.stream_ptr()
+    for _ in range(args.warmup):
+        B.commvq_encode_keys(op.handle, keys, n, kcb, tables, cache, rec, n * rec, sp)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        B.commvq_encode_keys(op.handle, keys, n, kcb, tables, cache, rec, n * rec, sp)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    # algorithmic work per (token, head, level): the dot products with the level's rows, the candidate scan
+    flop = n * w.Hkv * levels * (2 * w.d * (2 * K if paired else K) + (5 * K * K if paired else 2 * K) + 2 * w.d)
+    tf = flop / (kernel_ms * 1e-3) / 1e12
+    result = {"metric": "key-encode new tokens/sec per layer (cache append)", "value": round(n / (ms * 1e-3), 1),
+              "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+              "dtype": "f32", "data": "synthetic",
+              "config": {"workload": f"encode_{n}_tokens_of_{w.name}", "kv_heads": w.Hkv, "head_dim": w.d,
+                         "key_format": w.key_format, "levels": levels, "centres_per_level": K * K if paired else K},
+              "roofline": {"kernel": "k_encode", "bound": "alu", "achieved": round(tf, 3), "peak": FP32_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": round(tf / FP32_PEAK_TFLOPS, 4), "traffic": None,
+                           "kernel_ms": round(kernel_ms, 5)}}
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        m = min(n, 16 if paired else 256)
+        kf = synth.bf16_bits_to_f32(keys[:m, 0].view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        c0 = time.perf_counter()
+        oracle.encode_keys(kf, w.as_f64("key_codebooks")[0], paired=paired)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": round(m / w.Hkv / (c1 - c0), 1), "unit": "tokens/s per layer", "cores": 1,
+                                  "kind": "oracle", "sample": f"{m} vectors of one KV head, {c1 - c0:.1f} s wall"}
+    print(json.dumps(result))
+    op.close()
 
 
 def main():
@@ -45,6 +112,8 @@ def main():
         print("bench.py: this build runs on ONE GPU; the path shards by KV head or sequence without any exchange "
               "(see DESIGN.md), but no multi-GPU launch is provided. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.what == "encode":
+        return bench_encode(args)
     import numpy as np
     import torch
 
