@@ -1280,7 +1280,24 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
         if (!PAIRED) {
             if (tid < K) {
                 float acc = 0.f;
-                for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
+                if (BF16) {  // a row is 16 pieces of 8 bf16; all loads of the row are issued before the first use
+                    const uint4 *row = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(cb) + base + (size_t)tid * kD);
+                    uint4 pc[16];
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) pc[x] = row[x];
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) {
+                        const unsigned v[4] = {pc[x].x, pc[x].y, pc[x].z, pc[x].w};
+#pragma unroll
+                        for (int y = 0; y < 4; ++y) {
+                            acc = __builtin_fmaf(res[8 * x + 2 * y], bf16_lo(v[y]), acc);
+                            acc = __builtin_fmaf(res[8 * x + 2 * y + 1], bf16_hi(v[y]), acc);
+                        }
+                    }
+                } else {
+#pragma unroll 16
+                    for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
+                }
                 best = norms[level * K + tid] - 2.f * acc;
                 cand = tid;
             }
@@ -1335,6 +1352,140 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
         if (tid < a.levels) dst[tid] = (uint8_t)chosen[tid];
     } else if (tid < a.record_bytes) {
         // byte tid of the record: the 12-bit pairs (a | b << 6) that overlap bits 8 tid .. 8 tid + 7
+        unsigned v = 0;
+        for (int r = (8 * tid) / 12; r < a.levels && 12 * r < 8 * tid + 8; ++r) {
+            const unsigned pr = (unsigned)(chosen[r] / K) | (unsigned)(chosen[r] % K) << 6;
+            const int sh = 12 * r - 8 * tid;
+            v |= sh >= 0 ? pr << sh : pr >> -sh;
+        }
+        dst[tid] = (uint8_t)(v & 0xffu);
+    }
+}
+
+// Same search for bf16 rows, shaped for latency (a decode step appends one token per sequence, and the R
+// levels are a dependent chain): the rows, norms and cross terms of level l + 1 do not depend on the
+// residual, so they are fetched into registers while level l is searched and parked in the other half
+// of a double-buffered LDS image; every level then runs out of LDS.  Rows are padded to 65 dwords so
+// that 64 lanes reading 64 different rows hit 64 different banks.
+constexpr int kEncRowDw = kD / 2 + 1;  // dwords per padded bf16 row
+template <bool PAIRED>
+__global__ __launch_bounds__(256) void k_encode_lds(const void *__restrict__ keys, const unsigned *__restrict__ cb,
+                                                    const float *__restrict__ norms, const float *__restrict__ cross,
+                                                    uint8_t *__restrict__ out, const EncodeDims a)
+{
+    constexpr int K = PAIRED ? 64 : 256;
+    constexpr int ROWS_DW = K * kEncRowDw;             // one level's rows
+    constexpr int CROSS = PAIRED ? K * K : 0;
+    constexpr int RPT = K * (kD / 2) / 256;            // row dwords per thread: 16 (paired) or 64
+    constexpr int XPT = CROSS / 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned enc_lds[];
+    unsigned *rows = enc_lds;                                          // [2][K][65]
+    float *xs = reinterpret_cast<float *>(enc_lds + 2 * ROWS_DW);      // [2][K * K]  (paired)
+    float *ns = xs + 2 * CROSS;                                        // [2][K]
+    float *res = ns + 2 * K;                                           // [d]
+    float *dots = res + kD;                                            // [256]
+    float *wbest = dots + 256;                                         // [4]
+    int *wcand = reinterpret_cast<int *>(wbest + 4);                   // [4]
+    int *chosen = wcand + 4;                                           // [32]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x % a.Hkv;
+    const size_t tok = blockIdx.x / a.Hkv;
+
+    unsigned prow[RPT];
+    float pcross[XPT > 0 ? XPT : 1], pnorm = 0.f;
+    auto fetch_level = [&](int l) {
+        const size_t level = (size_t)g * a.levels + l;
+#pragma unroll
+        for (int x = 0; x < RPT; ++x) prow[x] = cb[level * K * (kD / 2) + x * 256 + tid];
+#pragma unroll
+        for (int x = 0; x < XPT; ++x) pcross[x] = cross[level * CROSS + x * 256 + tid];
+        if (tid < K) pnorm = norms[level * K + tid];
+    };
+    auto park_level = [&](int buf) {
+#pragma unroll
+        for (int x = 0; x < RPT; ++x) {
+            const int i = x * 256 + tid;  // dword i of the level: row i / 64, column i % 64
+            rows[buf * ROWS_DW + (i >> 6) * kEncRowDw + (i & 63)] = prow[x];
+        }
+#pragma unroll
+        for (int x = 0; x < XPT; ++x) xs[buf * CROSS + x * 256 + tid] = pcross[x];
+        if (tid < K) ns[buf * K + tid] = pnorm;
+    };
+    fetch_level(0);
+    if (tid < kD) {
+        const size_t i = (tok * a.Hkv + g) * kD + tid;
+        res[tid] = a.key_bf16 ? __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(keys)[i] << 16)
+                              : static_cast<const float *>(keys)[i];
+    }
+    park_level(0);
+    __syncthreads();
+    for (int l = 0; l < a.levels; ++l) {
+        const int buf = l & 1;
+        if (l + 1 < a.levels) fetch_level(l + 1);
+        const unsigned *R = rows + buf * ROWS_DW;
+        float best = INFINITY;
+        int cand = 0x7fffffff;
+        if (!PAIRED) {
+            float acc = 0.f;
+#pragma unroll 16
+            for (int j = 0; j < kJ; ++j) {
+                const unsigned v = R[tid * kEncRowDw + j];
+                acc = __builtin_fmaf(res[2 * j], bf16_lo(v), acc);
+                acc = __builtin_fmaf(res[2 * j + 1], bf16_hi(v), acc);
+            }
+            best = ns[buf * K + tid] - 2.f * acc;
+            cand = tid;
+        } else {
+            // thread = (row c, a-dot or b-dot, which half of the sub-spaces); the two halves are added in a fixed order
+            const int c = tid & 63, second = (tid >> 6) & 1, hj = tid >> 7;
+            float acc = 0.f;
+#pragma unroll 16
+            for (int j = 32 * hj; j < 32 * hj + 32; ++j) {
+                const unsigned v = R[c * kEncRowDw + j];
+                const float x = bf16_lo(v), y = bf16_hi(v);
+                acc = second ? __builtin_fmaf(res[2 * j + 1], x, __builtin_fmaf(-res[2 * j], y, acc))
+                             : __builtin_fmaf(res[2 * j + 1], y, __builtin_fmaf(res[2 * j], x, acc));
+            }
+            dots[tid] = acc;
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < K * K / 256; ++k) {
+                const int cc = k * 256 + tid, ca = cc / K, cb2 = cc % K;
+                const float da = dots[ca] + dots[128 + ca], db = dots[64 + cb2] + dots[192 + cb2];
+                const float sc = ns[buf * K + ca] + ns[buf * K + cb2] + xs[buf * CROSS + cc] - 2.f * (da + db);
+                if (sc < best) { best = sc; cand = cc; }
+            }
+        }
+        const float wm = -wave_max(-best);
+        int wc = best == wm ? cand : 0x7fffffff;
+        for (int off = 32; off > 0; off >>= 1) wc = min(wc, __shfl_xor(wc, off));
+        if (lane == 0) { wbest[wave] = wm; wcand[wave] = wc; }
+        __syncthreads();
+        {
+            float m = wbest[0];
+            int c = wcand[0];
+            for (int w = 1; w < 4; ++w)
+                if (wbest[w] < m || (wbest[w] == m && wcand[w] < c)) { m = wbest[w]; c = wcand[w]; }
+            if (tid == 0) chosen[l] = c;
+            if (tid < kD) {
+                const int e2 = tid >> 1;
+                if (!PAIRED) {
+                    const unsigned v = R[c * kEncRowDw + e2];
+                    res[tid] -= (tid & 1) ? bf16_hi(v) : bf16_lo(v);
+                } else {
+                    const unsigned va = R[(c / K) * kEncRowDw + e2], vb = R[(c % K) * kEncRowDw + e2];
+                    // element of i C[b]: (-y_b, x_b) of its sub-space
+                    res[tid] -= (tid & 1) ? bf16_hi(va) + bf16_lo(vb) : bf16_lo(va) - bf16_hi(vb);
+                }
+            }
+        }
+        if (l + 1 < a.levels) park_level(buf ^ 1);
+        __syncthreads();
+    }
+    uint8_t *dst = out + tok * a.token_stride + (long long)g * a.head_stride;
+    if (!PAIRED) {
+        if (tid < a.levels) dst[tid] = (uint8_t)chosen[tid];
+    } else if (tid < a.record_bytes) {
         unsigned v = 0;
         for (int r = (8 * tid) / 12; r < a.levels && 12 * r < 8 * tid + 8; ++r) {
             const unsigned pr = (unsigned)(chosen[r] / K) | (unsigned)(chosen[r] % K) << 6;
@@ -2022,12 +2173,21 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
     const dim3 grid((unsigned)(n_tokens * c.n_kv_heads));
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
-    if (paired) {
-        if (bf16) hipLaunchKernelGGL((k_encode<true, true>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
-        else return COMMVQ_ERR_CONFIG;
+    if (paired && !bf16) return COMMVQ_ERR_CONFIG;
+    if (paired) {  // rows, norms and cross terms staged in LDS, next level prefetched
+        const int lds = (2 * K * kEncRowDw + 2 * K * K + 2 * K + kD + 256 + 8 + 32) * 4;
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_lds<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+                return COMMVQ_ERR_LAUNCH;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(k_encode_lds<true>, grid, dim3(256), lds, s, keys, static_cast<const unsigned *>(key_cb), norms, cross, codes_out, d);
+    } else if (bf16) {
+        hipLaunchKernelGGL((k_encode<false, true>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
     } else {
-        if (bf16) hipLaunchKernelGGL((k_encode<false, true>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
-        else hipLaunchKernelGGL((k_encode<false, false>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
+        hipLaunchKernelGGL((k_encode<false, false>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
     }
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
