@@ -72,6 +72,10 @@ typedef struct {
     int32_t max_position;    /* largest |q_pos - key position| that will occur; sizes the phase tables */
     int32_t key_format;      /* commvq_key_format; 0 (indexed) keeps every field above as described */
     int32_t key_levels;      /* R, 1..21; COMMVQ_KEYS_PAIRED only (m_key is then ignored; bf16 tables, implicit key positions) */
+    int32_t position_free;   /* 1: no rotation at all -- the case Sec. 4.2 sets aside ("R_i independent of i", e.g. keys
+                                quantized after RoPE): scores are (q . k_hat_i) * scale, computed with a scalar look-up
+                                table T[m][c] = scale * q . C[m][c] and M_k look-ups per token; q_pos / key_pos are
+                                ignored.  Indexed keys only.  0: RoPE as described above. */
 } commvq_config;
 
 /* Host struct of device pointers: where the tokens sit (ragged batch). */

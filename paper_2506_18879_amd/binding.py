@@ -22,7 +22,7 @@ class Config(Structure):
     _fields_ = [("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32), ("m_key", c_int32),
                 ("m_val", c_int32), ("k", c_int32), ("q_dtype", c_int32), ("codebook_dtype", c_int32),
                 ("rope_base", c_double), ("softmax_scale", c_double), ("max_position", c_int32),
-                ("key_format", c_int32), ("key_levels", c_int32)]
+                ("key_format", c_int32), ("key_levels", c_int32), ("position_free", c_int32)]
 
 
 class Positions(Structure):

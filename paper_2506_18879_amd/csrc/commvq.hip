@@ -89,6 +89,7 @@ struct Workspace {
     float *partial;   // [B * Hq * out_chunks][d]
     uint4 *packed;    // key codebook re-laid slice-major for k_score_mfma / k_score_pair
     uint8_t *pair_bytes;  // paired-code keys: one byte per index, [T * Hkv][32 * blocks]
+    float *lut;           // position-free keys: scale * q . C, [B * Hkv][M_k * K][G]
     size_t bytes;
 };
 
@@ -96,6 +97,7 @@ struct Workspace {
 // (fp32 codebooks, explicit key positions) goes through the gather kernel.
 bool use_sliced(const commvq_handle *h, bool explicit_positions)
 {
+    if (h->cfg.position_free) return true;  // scalar look-up table kernel: same tiling, positions play no role
     return h->cfg.codebook_dtype == COMMVQ_BF16 && !explicit_positions;
 }
 
@@ -166,6 +168,7 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     w->partial = take((size_t)B * c.n_q_heads * pa.out_chunks * kD);
     w->packed = reinterpret_cast<uint4 *>(take(packed_key_bytes(c) / 4));
     w->pair_bytes = pair_keys(c) ? reinterpret_cast<uint8_t *>(take((size_t)T * c.n_kv_heads * 8 * pair_blocks(c))) : nullptr;
+    w->lut = c.position_free ? take((size_t)B * c.n_q_heads * c.m_key * kK) : nullptr;
     w->bytes = off;
 }
 
@@ -203,6 +206,14 @@ __device__ __forceinline__ float wave_max(float v)
     u = __builtin_bit_cast(unsigned, v);
     auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return fmaxf(__builtin_bit_cast(float, (unsigned)r32[0]), __builtin_bit_cast(float, (unsigned)r32[1]));
+}
+
+// element i of a bf16 or fp32 array, widened exactly
+template <bool BF16>
+__device__ __forceinline__ float cb_elem(const void *cb, size_t i)
+{
+    if (BF16) return __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(cb)[i] << 16);
+    return static_cast<const float *>(cb)[i];
 }
 
 __device__ __forceinline__ float bf16_lo(unsigned v) { return __builtin_bit_cast(float, v << 16); }
@@ -872,6 +883,133 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     }
 }
 
+// ------------------------------------------------------------------ position-free keys: scalar look-up table
+// The case the paper sets aside in Sec. 4.2: if the rotation did not depend on the token (keys quantized
+// after RoPE, or no positional rotation at all), (q C^T) could be computed once and every token's
+// score would be M scalar look-ups:  s_i = sum_m T[m][code_i,m],  T[m][c] = scale * q . C[m][c].
+//
+// k_lut_build: T[b][g][m][c][G] fp32, one thread per (b, g, m, c) row; the G queries sit in LDS.
+template <int G, bool BF16>
+__global__ __launch_bounds__(256) void k_lut_build(const void *__restrict__ q, const void *__restrict__ cb,
+                                                   float *__restrict__ lut, int Hkv, int M, int q_bf16, float scale)
+{
+    __shared__ float qs[G][kD];
+    const int rows_per_head = M * kK;                       // rows of one KV head
+    const int blocks_per_head = rows_per_head / 256;
+    const int bg = blockIdx.x / blocks_per_head;            // b * Hkv + g
+    const int g = bg % Hkv, b = bg / Hkv;
+    const int row = (blockIdx.x % blocks_per_head) * 256 + threadIdx.x;  // m * K + c
+    for (int x = threadIdx.x; x < G * kD; x += 256) {
+        const size_t i = ((size_t)b * Hkv * G + (size_t)g * G) * kD + x;
+        const float v = q_bf16 ? __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(q)[i] << 16)
+                               : static_cast<const float *>(q)[i];
+        qs[x / kD][x % kD] = v * scale;
+    }
+    __syncthreads();
+    float acc[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) acc[h] = 0.f;
+    const size_t base = ((size_t)g * rows_per_head + row) * kD;
+#pragma unroll 8
+    for (int e = 0; e < kD; ++e) {
+        const float v = cb_elem<BF16>(cb, base + e);
+#pragma unroll
+        for (int h = 0; h < G; ++h) acc[h] = __builtin_fmaf(qs[h][e], v, acc[h]);
+    }
+    float *dst = lut + ((size_t)bg * rows_per_head + row) * G;
+#pragma unroll
+    for (int h = 0; h < G; ++h) dst[h] = acc[h];
+}
+
+// k_score_lut: one workgroup per (sequence, KV head, tile of TPT * 1024 tokens); the head group's table
+// (M * 256 * HG floats, HG = min(G, 4) heads at a time) sits in LDS, a lane owns TPT tokens: M code bytes
+// in, M look-ups of HG floats, HG logits out.  Bound by the code stream and the logit writes (HBM).
+template <int M, int G, int TPT>
+__global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__restrict__ lut, const uint8_t *__restrict__ key_codes,
+                                                             const int32_t *__restrict__ cu, float *__restrict__ scores,
+                                                             float2 *__restrict__ sstat, const SliceDims a)
+{
+    constexpr int HG = G < 4 ? G : 4;
+    constexpr int NGRP = G / HG;
+    constexpr int TILE = TPT * kSliceThreads;
+    constexpr int NW = kSliceThreads / 64;
+    extern __shared__ __attribute__((aligned(16))) float tabf[];  // [M * 256][HG]
+    __shared__ float2 wstat[NW][HG];
+    int id = blockIdx.x;
+    const int g = id % a.Hkv;
+    id /= a.Hkv;
+    const int tile = id % a.nsplit;
+    const int b = id / a.nsplit;
+    const int cu0 = cu[b];
+    const int L = cu[b + 1] - cu0;
+    const int t0 = tile * TILE;
+    if (t0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
+    const float *src = lut + ((size_t)b * a.Hkv + g) * (M * kK) * G;
+    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    for (int grp = 0; grp < NGRP; ++grp) {
+        __syncthreads();
+        for (int x = tid; x < M * kK; x += kSliceThreads)
+#pragma unroll
+            for (int h = 0; h < HG; ++h) tabf[x * HG + h] = src[(size_t)x * G + grp * HG + h];
+        __syncthreads();
+        float mx[HG], sc[TPT][HG];
+#pragma unroll
+        for (int h = 0; h < HG; ++h) mx[h] = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < TPT; ++k) {
+            const int tok = t0 + k * kSliceThreads + tid;
+            const int tc = min(tok, L - 1);
+            unsigned cw[M / 4];
+#pragma unroll
+            for (int v = 0; v < M / 16; ++v) {
+                const uint4 c4 = reinterpret_cast<const uint4 *>(codes + (size_t)tc * M)[v];
+                cw[4 * v] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
+            }
+            float acc[HG];
+#pragma unroll
+            for (int h = 0; h < HG; ++h) acc[h] = 0.f;
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
+                const float *e = tabf + ((size_t)m * kK + c) * HG;
+#pragma unroll
+                for (int h = 0; h < HG; ++h) acc[h] += e[h];
+            }
+#pragma unroll
+            for (int h = 0; h < HG; ++h) {
+                sc[k][h] = acc[h];
+                if (tok < L) {
+                    srow[(size_t)(grp * HG + h) * L + tok] = acc[h];
+                    mx[h] = fmaxf(mx[h], acc[h]);
+                }
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < HG; ++h) {
+            const float wm = wave_max(mx[h]);
+            float l = 0.f;
+#pragma unroll
+            for (int k = 0; k < TPT; ++k)
+                if (t0 + k * kSliceThreads + tid < L) l += __builtin_amdgcn_exp2f((sc[k][h] - wm) * kLog2e);
+            l = wave_sum(l);
+            if (lane == 0) wstat[wave][h] = make_float2(wm, l);
+        }
+        __syncthreads();
+        if (tid < HG) {
+            float m = -INFINITY;
+            for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
+            float l = 0.f;
+            for (int w = 0; w < NW; ++w) {
+                const float2 st = wstat[w][tid];
+                if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+            }
+            sstat[((size_t)b * a.Hq + (size_t)g * G + grp * HG + tid) * a.nsplit + tile] = make_float2(m, l);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ paired-code keys (App. A.1)
 // The paper's own key format: per token and KV head R residual levels, each a pair (a, b) of 6-bit
 // indices into ONE table of N_c' = 64 centres per level; level r contributes C[r][a] + i C[r][b]
@@ -1212,13 +1350,6 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
 //   norms[g][level][K]            ||C[g][level][c]||^2
 //   cross[g][level][K][K]         paired only: 2 C[a] . (i C[b])   (K = 64), so that a paired centre costs
 //                                 norms[a] + norms[b] + cross[a][b] - 2 (res.C[a] + res.(i C[b]))
-template <bool BF16>
-__device__ __forceinline__ float cb_elem(const void *cb, size_t i)
-{
-    if (BF16) return __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(cb)[i] << 16);
-    return static_cast<const float *>(cb)[i];
-}
-
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_encode_tables(const void *__restrict__ cb, float *__restrict__ norms,
                                                        float *__restrict__ cross, int rows_total, int K, int paired)
@@ -1882,10 +2013,62 @@ hipError_t launch_prep(const commvq_config &c, const void *key_cb, uint4 *packed
     return hipGetLastError();
 }
 
+template <int M, int G, int TPT>
+hipError_t launch_lut_mgt(const float *lut, const uint8_t *key_codes, const int32_t *cu, float *scores, float2 *sstat,
+                          const SliceDims &d, int grid, hipStream_t s)
+{
+    constexpr int lds = M * kK * (G < 4 ? G : 4) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_lut<M, G, TPT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_score_lut<M, G, TPT>), dim3(grid), dim3(kSliceThreads), lds, s, lut, key_codes, cu, scores, sstat, d);
+    return hipGetLastError();
+}
+template <int M, int G>
+hipError_t launch_lut_mg(const void *q, const void *key_cb, bool bf16, float *lut, const uint8_t *key_codes, const int32_t *cu,
+                         float *scores, float2 *sstat, const SliceDims &d, int B, int tpt, int grid, hipStream_t s)
+{
+    const int blocks = B * d.Hkv * (M * kK / 256);
+    if (bf16) hipLaunchKernelGGL((k_lut_build<G, true>), dim3(blocks), dim3(256), 0, s, q, key_cb, lut, d.Hkv, M, d.q_bf16, d.scale);
+    else hipLaunchKernelGGL((k_lut_build<G, false>), dim3(blocks), dim3(256), 0, s, q, key_cb, lut, d.Hkv, M, d.q_bf16, d.scale);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    switch (tpt) {
+    case 1: return launch_lut_mgt<M, G, 1>(lut, key_codes, cu, scores, sstat, d, grid, s);
+    case 2: return launch_lut_mgt<M, G, 2>(lut, key_codes, cu, scores, sstat, d, grid, s);
+    default: return launch_lut_mgt<M, G, 4>(lut, key_codes, cu, scores, sstat, d, grid, s);
+    }
+}
+template <int M>
+hipError_t launch_lut_m(int G, const void *q, const void *key_cb, bool bf16, float *lut, const uint8_t *key_codes,
+                        const int32_t *cu, float *scores, float2 *sstat, const SliceDims &d, int B, int tpt, int grid, hipStream_t s)
+{
+    switch (G) {
+    case 1: return launch_lut_mg<M, 1>(q, key_cb, bf16, lut, key_codes, cu, scores, sstat, d, B, tpt, grid, s);
+    case 2: return launch_lut_mg<M, 2>(q, key_cb, bf16, lut, key_codes, cu, scores, sstat, d, B, tpt, grid, s);
+    case 4: return launch_lut_mg<M, 4>(q, key_cb, bf16, lut, key_codes, cu, scores, sstat, d, B, tpt, grid, s);
+    default: return launch_lut_mg<M, 8>(q, key_cb, bf16, lut, key_codes, cu, scores, sstat, d, B, tpt, grid, s);
+    }
+}
+
 commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_codes, const void *key_cb,
                          const commvq_positions *pos, const commvq_plan &plan, const Workspace &w, hipStream_t s)
 {
     const commvq_config &c = h->cfg;
+    if (c.position_free) {  // scalar look-up table: build T = scale q C^T, then M look-ups per token
+        SliceDims d;
+        d.Hq = c.n_q_heads; d.Hkv = c.n_kv_heads; d.nsplit = plan.score_splits; d.n_hi = h->n_hi;
+        d.q_bf16 = c.q_dtype == COMMVQ_BF16; d.scale = h->scale;
+        const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
+        const int tpt = plan.score_split_len / kSliceThreads;
+        const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
+        hipError_t e = c.m_key == 16 ? launch_lut_m<16>(h->G, q, key_cb, bf16, w.lut, key_codes, pos->cu_seqlens, w.scores, w.sstat, d, pos->batch, tpt, grid, s)
+                                     : launch_lut_m<32>(h->G, q, key_cb, bf16, w.lut, key_codes, pos->cu_seqlens, w.scores, w.sstat, d, pos->batch, tpt, grid, s);
+        return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+    }
     if (plan.reserved) {  // slice-streaming kernel: needs the codebook in LDS-image order
         const uint4 *packed = nullptr;
         for (const auto &e : h->packed_keys)
@@ -2001,6 +2184,7 @@ commvq_status commvq_validate_config(const commvq_config *c)
     } else {
         return COMMVQ_ERR_CONFIG;
     }
+    if (c->position_free != 0 && (c->position_free != 1 || c->key_format != COMMVQ_KEYS_INDEXED)) return COMMVQ_ERR_CONFIG;
     if (c->q_dtype != COMMVQ_F32 && c->q_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
     if (c->codebook_dtype != COMMVQ_F32 && c->codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
     if (!(c->rope_base > 1.0) || !(c->softmax_scale >= 0.0)) return COMMVQ_ERR_CONFIG;

@@ -45,7 +45,7 @@ class DeviceWorkload:
 class DecodeAttention:
     """Owns a libcommvq handle, a workspace and an output buffer for one batch shape."""
 
-    def __init__(self, w, max_position: Optional[int] = None, softmax_scale: float = 0.0):
+    def __init__(self, w, max_position: Optional[int] = None, softmax_scale: float = 0.0, position_free: bool = False):
         torch = _torch()
         dt = B.COMMVQ_BF16 if w.dtype == "bf16" else B.COMMVQ_F32
         if max_position is None:
@@ -53,7 +53,8 @@ class DecodeAttention:
         paired = getattr(w, "key_format", "indexed") == "paired"
         self.cfg = B.Config(w.Hq, w.Hkv, w.d, 16 if paired else w.Mk, w.Mv, w.K, dt, dt, float(w.rope_base),
                             float(softmax_scale), int(max_position),
-                            B.COMMVQ_KEYS_PAIRED if paired else B.COMMVQ_KEYS_INDEXED, w.key_levels if paired else 0)
+                            B.COMMVQ_KEYS_PAIRED if paired else B.COMMVQ_KEYS_INDEXED, w.key_levels if paired else 0,
+                            1 if position_free else 0)
         self.handle = B.commvq_create(self.cfg)
         self.plan = B.commvq_plan_query(self.handle, w.B, w.total_tokens, w.max_seqlen)
         self.workspace_bytes = B.commvq_workspace_bytes(self.handle, w.B, w.total_tokens, w.max_seqlen)

@@ -55,6 +55,12 @@ def test_validate_config_paired_key_format():
         assert cv.commvq_validate_config(good_cfg(**bad)) == 2
 
 
+def test_validate_config_position_free():
+    assert cv.commvq_validate_config(good_cfg(position_free=1)) == 0
+    assert cv.commvq_validate_config(good_cfg(position_free=2)) == 2
+    assert cv.commvq_validate_config(good_cfg(position_free=1, key_format=cv.COMMVQ_KEYS_PAIRED, key_levels=11)) == 2
+
+
 def test_status_strings_are_distinct():
     s = {cv.commvq_status_string(i) for i in range(7)}
     assert len(s) == 7 and "ok" in s

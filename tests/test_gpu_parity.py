@@ -276,6 +276,40 @@ def test_paired_keys_query_inside_context_and_rejections(gpu, oracle):
     assert cv.commvq_validate_config(cfg) == 0
 
 
+# ---------------------------------------------------------------- position-free keys (scalar look-up table)
+def oracle_out_position_free(oracle, w, **kw):
+    """No rotation at all == every key at the query's position (the rotations cancel in the dot product)."""
+    kp = np.concatenate([np.full(int(n), int(p), np.int32) for n, p in zip(np.diff(w.cu_seqlens), w.q_pos)])
+    return oracle.decode_attn(w.as_f64("q"), w.key_codes, w.val_codes, w.as_f64("key_codebooks"),
+                              w.as_f64("val_codebooks"), w.cu_seqlens, w.q_pos, key_pos=kp, rope_base=w.rope_base,
+                              n_threads=16, **kw)
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 1), (4, 2), (8, 1)])
+@pytest.mark.parametrize("Mk,dtype", [(16, "bf16"), (32, "bf16"), (32, "f32")])
+def test_position_free_scalar_lut(gpu, oracle, G, Hkv, Mk, dtype):
+    import torch
+    w = synth.make_workload(f"lut_g{G}_m{Mk}_{dtype}", B=2, Hq=G * Hkv, Hkv=Hkv, seqlens=[2300, 517], Mk=Mk, Mv=16,
+                            dtype=dtype, seed=50 + 3 * G + Mk)
+    print(f"case {w.name}", flush=True)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w, position_free=True)
+    s = op.scores(dw)
+    out = op(dw)
+    torch.cuda.synchronize()
+    ref, ref_scores, _ = oracle_out_position_free(oracle, w, return_intermediates=True)
+    assert np.abs(s.cpu().numpy().astype(np.float64) - ref_scores).max() <= TOL_SCORE
+    assert row_err(out.cpu().numpy(), ref).max() <= TOL_OUT
+    op.close()
+
+
+@pytest.mark.parametrize("L", [1, 1023, 1025, 4097, 9000])
+def test_position_free_lengths(gpu, oracle, L):
+    w = synth.make_workload(f"lut_L{L}", B=1, Hq=8, Hkv=2, seqlens=[L], Mk=16, Mv=32, dtype="bf16", seed=600 + L)
+    got = run_gpu(gpu, w, position_free=True)
+    assert row_err(got, oracle_out_position_free(oracle, w)).max() <= TOL_OUT
+
+
 # ---------------------------------------------------------------- argument checking through the C ABI
 def test_error_statuses(gpu):
     import torch
