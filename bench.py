@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
     ap.add_argument("--no-prepack", action="store_true",
                     help="re-lay the key codebook inside every call instead of once before the timed region")
+    ap.add_argument("--position-free", action="store_true",
+                    help="no RoPE between query and keys: scores through the scalar look-up table kernel (HBM-bound)")
     ap.add_argument("--what", choices=["decode_attn", "encode"], default="decode_attn",
                     help="encode: time the key encoder (cache append) on --encode-tokens new tokens instead")
     ap.add_argument("--encode-tokens", type=int, default=4096)
@@ -138,11 +140,11 @@ def main():
         c.key_codes, c.val_codes = base.key_codes.clone(), base.val_codes.clone()
         c.key_codebooks, c.val_codebooks = base.key_codebooks.clone(), base.val_codebooks.clone()
         copies.append(c)
-    op = DecodeAttention(w)
+    op = DecodeAttention(w, position_free=args.position_free)
     stream = torch.cuda.current_stream()
     # the key codebooks are per-layer constants: their re-layout for the score kernel is done once, outside
     # the timed region (commvq_pack_key_codebooks); --no-prepack keeps it inside every call instead
-    prepacked = w.dtype == "bf16" and not args.no_prepack
+    prepacked = w.dtype == "bf16" and not args.no_prepack and not args.position_free
     if prepacked:
         for c in copies:
             op.pack_key_codebooks(c)
@@ -174,6 +176,8 @@ def main():
     achieved_tflops = score_flops / score_s / 1e12 if score_s > 0 else 0.0
     paired = w.key_format == "paired"
     kname = "k_score_pair" if paired else ("k_score_mfma" if w.dtype == "bf16" else "k_score")
+    if args.position_free:
+        kname = "k_score_lut"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -199,6 +203,13 @@ def main():
                 "hbm_view": {"key_code_stream_GBs": round(key_stream_gbs, 1),
                              "frac_of_hbm_peak": round(key_stream_gbs / HBM_PEAK_GBS, 4)}}
 
+    if args.position_free:
+        # scalar-LUT scores: the stage streams the key codes in and the logits out; judged against HBM
+        lut_bytes = w.key_codes.nbytes + T * w.Hq * 4
+        gbs = lut_bytes / score_s / 1e9 if score_s > 0 else 0.0
+        roofline = {"kernel": kname, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel_ms": round(stage_ms[0], 5),
+                    "launches_averaged": n_prof, "timed_region_includes": "k_lut_build + k_score_lut"}
     result = {
         "metric": "decode-attention context tokens/sec per layer at 128K; % of HBM roofline",
         "value": round(tokens_per_s, 1), "unit": "context tokens/s per layer", "n_gpus": 1, "steps": args.steps,
@@ -206,7 +217,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "context_tokens": T, "m_key": w.Mk, "m_val": w.Mv, "codewords": w.K, "storage": w.dtype,
-                   "key_format": w.key_format, "key_levels": w.key_levels,
+                   "key_format": w.key_format, "key_levels": w.key_levels, "position_free": bool(args.position_free),
                    "codes": w.code_dist, "buffer_copies_rotated": n_copies,
                    "key_codebooks_packed_before_timed_region": prepacked,
                    "cache_state": "warm" if args.warm else "cold (rotating copies > 256 MB LLC)"},

@@ -948,6 +948,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const float *src = lut + ((size_t)b * a.Hkv + g) * (M * kK) * G;
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+#pragma unroll 1
     for (int grp = 0; grp < NGRP; ++grp) {
         __syncthreads();
         for (int x = tid; x < M * kK; x += kSliceThreads)
@@ -957,25 +958,41 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
         float mx[HG], sc[TPT][HG];
 #pragma unroll
         for (int h = 0; h < HG; ++h) mx[h] = -INFINITY;
+        int tfirst = t0 + tid;
+        asm volatile("" : "+v"(tfirst));  // per head group: keeps the code loads and table addresses inside this loop
 #pragma unroll
         for (int k = 0; k < TPT; ++k) {
-            const int tok = t0 + k * kSliceThreads + tid;
+            const int tok = tfirst + k * kSliceThreads;
             const int tc = min(tok, L - 1);
-            unsigned cw[M / 4];
-#pragma unroll
-            for (int v = 0; v < M / 16; ++v) {
-                const uint4 c4 = reinterpret_cast<const uint4 *>(codes + (size_t)tc * M)[v];
-                cw[4 * v] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
-            }
             float acc[HG];
+            floatx4_t accv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int h = 0; h < HG; ++h) acc[h] = 0.f;
 #pragma unroll
-            for (int m = 0; m < M; ++m) {
-                const unsigned c = (cw[m / 4] >> (8 * (m % 4))) & 0xffu;
-                const float *e = tabf + ((size_t)m * kK + c) * HG;
+            for (int v = 0; v < M / 16; ++v) {  // 16 codes at a time, 8 look-ups in flight: keeps registers flat
+                const uint4 c4 = reinterpret_cast<const uint4 *>(codes + (size_t)tc * M)[v];
+                const unsigned cw[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-                for (int h = 0; h < HG; ++h) acc[h] += e[h];
+                for (int half = 0; half < 2; ++half) {
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) {
+                        const int m = 16 * v + 8 * half + x;
+                        const unsigned c = (cw[(m % 16) / 4] >> (8 * (m % 4))) & 0xffu;
+                        const float *e = tabf + ((size_t)m * kK + c) * HG;
+                        if (HG == 4) {  // one 16-byte read, added as a vector right away
+                            accv += *reinterpret_cast<const floatx4_t *>(e);
+                        } else {
+#pragma unroll
+                            for (int h = 0; h < HG; ++h) acc[h] += e[h];
+                        }
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (HG == 4) {
+#pragma unroll
+                for (int h = 0; h < HG; ++h) acc[h] = accv[h];
             }
 #pragma unroll
             for (int h = 0; h < HG; ++h) {
@@ -992,7 +1009,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
             float l = 0.f;
 #pragma unroll
             for (int k = 0; k < TPT; ++k)
-                if (t0 + k * kSliceThreads + tid < L) l += __builtin_amdgcn_exp2f((sc[k][h] - wm) * kLog2e);
+                if (tfirst + k * kSliceThreads < L) l += __builtin_amdgcn_exp2f((sc[k][h] - wm) * kLog2e);
             l = wave_sum(l);
             if (lane == 0) wstat[wave][h] = make_float2(wm, l);
         }
