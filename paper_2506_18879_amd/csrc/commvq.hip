@@ -1666,7 +1666,7 @@ struct BinsArgs {
 template <int M, int G>
 __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 {
-    extern __shared__ unsigned bins[];  // [G][M][K]
+    extern __shared__ __attribute__((aligned(8))) unsigned bins[];  // [G][M][K]; for G >= 2 used as 64-bit pairs
     __shared__ float eoff_s[G];
     int id = blockIdx.x;
     const int g = id % a.Hkv;
@@ -1681,6 +1681,9 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NB = G * M * kK;
 
+    // For G >= 2 the bins of heads 2p and 2p + 1 share one 64-bit word (low / high half): one 64-bit LDS
+    // atomic then serves two heads.  Each half stays below 2^31 (see above), so no carry crosses.
+    unsigned long long *bins2 = reinterpret_cast<unsigned long long *>(bins);  // [G / 2][M][K]
     for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0u;
     if (wave < G) {
         const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
@@ -1740,13 +1743,27 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         for (int k = 0; k < M; ++k) {
             const unsigned c = (rv[k / 4] >> (8 * (k % 4))) & 0xffu;
             const unsigned idx = ((((unsigned)k << 8) + (rot << 8)) & ((unsigned)(M - 1) << 8)) | c;  // m * K + c
+            if (G == 1) {
+                atomicAdd(&bins[idx], p[0]);
+            } else {
 #pragma unroll
-            for (int hh = 0; hh < G; ++hh) atomicAdd(&bins[hh * M * kK + idx], p[hh]);
+                for (int hp = 0; hp < G / 2; ++hp)
+                    atomicAdd(&bins2[hp * M * kK + idx], (unsigned long long)p[2 * hp] | (unsigned long long)p[2 * hp + 1] << 32);
+            }
         }
     }
     __syncthreads();
-    unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB;
-    for (int x = tid; x < NB; x += kBinsThreads) dst[x] = bins[x];
+    unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB;  // [G][M][K] whatever the LDS packing
+    if (G == 1) {
+        for (int x = tid; x < NB; x += kBinsThreads) dst[x] = bins[x];
+    } else {
+        for (int x = tid; x < NB / 2; x += kBinsThreads) {
+            const unsigned long long v = bins2[x];
+            const int hp = x / (M * kK), i = x % (M * kK);
+            dst[(2 * hp) * M * kK + i] = (unsigned)v;
+            dst[(2 * hp + 1) * M * kK + i] = (unsigned)(v >> 32);
+        }
+    }
 }
 
 // ------------------------------------------------------------------ k_out
