@@ -112,7 +112,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by KV head or sequence without any exchange "
-              "(see DESIGN.md), but no multi-GPU launch is provided. Use --gpus 1.", file=sys.stderr)
+              "(each KV head or sequence is an independent unit), but no multi-GPU launch is provided. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     if args.what == "encode":
         return bench_encode(args)

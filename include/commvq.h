@@ -187,6 +187,23 @@ commvq_status commvq_encode_keys(commvq_handle *handle, const void *keys, int32_
                                  void *stream);
 
 /*
+ * Offline: one iteration of the EM-like learner of the RoPE-commutative key codebook (Sec. 4.2,
+ * Algorithm 1; App. A.2), for n_subspaces independent 2-D sub-spaces at once.  Needs no handle.
+ *   data         device [n_subspaces][n_points][2] fp32: the calibration points of every sub-space
+ *   phi          device [n_subspaces][n_centres][2] fp32, in/out: (x_l, y_l) of the blocks [[x, y], [-y, x]];
+ *                the n_centres^2 clustering centres are (x_a - y_b, y_a + x_b) (Eq. def_center)
+ *   temperature  T > 0 of the soft assignment W = softmax(-D / T), D = Euclidean distance (Eq. W); the caller
+ *                anneals it over the iterations
+ *   n_centres    1..64
+ * E step and M step as in App. A.2; the M step solves the 2 n_centres x 2 n_centres normal equations of
+ * the closed form phi* = (T^T S T)^-1 T^T S m by Cholesky factorisation.  COMMVQ_ERR_SHAPE for sizes out
+ * of range, COMMVQ_ERR_CONFIG for T <= 0, COMMVQ_ERR_WORKSPACE as for commvq_decode_attn.
+ */
+commvq_status commvq_em_workspace_bytes(int32_t n_subspaces, int32_t n_points, int32_t n_centres, size_t *bytes);
+commvq_status commvq_em_step(const float *data, int32_t n_subspaces, int32_t n_points, int32_t n_centres,
+                             float temperature, float *phi, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The three stages of commvq_decode_attn, callable on their own (tests and profiling).
  * They read/write the same workspace; run them in this order on one stream.
  *   commvq_stage_scores  Eq. new_attention: scaled logits for every (b, h, token) and the

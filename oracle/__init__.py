@@ -193,3 +193,58 @@ def encode_keys(keys, codebooks, paired=False, given=None):
     if rc != 0:
         raise ValueError(f"commvq_oracle_encode_keys failed with code {rc}")
     return (codes if paired else codes[:, :, 0]), best, taken
+
+
+def em_centres(phi):
+    """All N_c'^2 clustering centres of one 2-D sub-space (Eq. def_center): phi [Nc][2] = (x_l, y_l);
+    centre (a, b) = (x_a - y_b, y_a + x_b), returned as [Nc*Nc][2] with index a * Nc + b."""
+    phi = _f64(phi)
+    x, y = phi[:, 0], phi[:, 1]
+    cx = x[:, None] - y[None, :]
+    cy = y[:, None] + x[None, :]
+    return np.stack([cx.reshape(-1), cy.reshape(-1)], axis=1)
+
+
+def em_step(data, phi, temperature=None):
+    """One iteration of the EM-like codebook learner for ONE 2-D sub-space (Sec. 4.2 Alg. 1, App. A.2).
+
+    data [N][2]: calibration points; phi [Nc][2]: current (x_l, y_l).  E step: soft assignment
+    W_ij = softmax_j(-D_ij / T) over the Nc^2 centres, D the Euclidean distance (Eq. W); temperature None
+    means hard assignment to the nearest centre.  M step: the closed form
+    phi* = (T^T S T)^-1 T^T S m with the constant matrix T of App. A.2 written out entry by entry,
+    S = diag of the assigned weight of every centre (twice: one entry per coordinate) and m the weighted
+    mean of the points assigned to it.  Returns (phi_new [Nc][2], weighted squared error before the update).
+    """
+    data = _f64(data)
+    phi = _f64(phi)
+    Nc = phi.shape[0]
+    cen = em_centres(phi)
+    D = np.sqrt(((data[:, None, :] - cen[None, :, :]) ** 2).sum(axis=2))        # [N][Nc^2]
+    if temperature is None:
+        W = np.zeros_like(D)
+        W[np.arange(len(data)), np.argmin(D, axis=1)] = 1.0
+    else:
+        Z = -D / float(temperature)
+        Z -= Z.max(axis=1, keepdims=True)
+        W = np.exp(Z)
+        W /= W.sum(axis=1, keepdims=True)
+    Nij = W.sum(axis=0)                                                          # weight of every centre
+    sums = W.T @ data                                                            # [Nc^2][2]
+    mean = np.where(Nij[:, None] > 0, sums / np.maximum(Nij[:, None], 1e-300), 0.0)
+    # T: (2 Nc^2) x (2 Nc); row 2(a Nc + b) is the x coordinate of centre (a, b) = x_a - y_b,
+    # row 2(a Nc + b) + 1 its y coordinate = y_a + x_b; phi is ordered x_0, y_0, x_1, y_1, ...
+    Tm = np.zeros((2 * Nc * Nc, 2 * Nc))
+    for a in range(Nc):
+        for b in range(Nc):
+            r = 2 * (a * Nc + b)
+            Tm[r, 2 * a] += 1.0
+            Tm[r, 2 * b + 1] += -1.0
+            Tm[r + 1, 2 * b] += 1.0
+            Tm[r + 1, 2 * a + 1] += 1.0
+    S = np.repeat(Nij, 2)
+    m = mean.reshape(-1)
+    A = Tm.T @ (S[:, None] * Tm)
+    rhs = Tm.T @ (S * m)
+    sol = np.linalg.solve(A, rhs)
+    err = float((W * D ** 2).sum())
+    return sol.reshape(Nc, 2), err

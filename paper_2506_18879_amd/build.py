@@ -7,18 +7,20 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 SRC = os.path.join(PKG, "csrc", "commvq.hip")
+SOURCES = [SRC, os.path.join(PKG, "csrc", "commvq_em.hip")]
 LIB = os.path.join(PKG, "libcommvq.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-# packed fp32 VALU forms are kept off for every device compile (build flags)
+# packed fp32 VALU forms (v_pk_*_f32) are kept off for every device compile: some of their forms have
+# given wrong results on this hardware, and the kernels do not need them
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
 def build(verbose: bool = False) -> str:
-    """Compile csrc/commvq.hip for gfx950 into paper_2506_18879_amd/libcommvq.so."""
+    """Compile csrc/*.hip for gfx950 into paper_2506_18879_amd/libcommvq.so."""
     extra = os.environ.get("COMMVQ_EXTRA_FLAGS", "").split()  # tuning experiments, e.g. -DCOMMVQ_SCORE_CHUNK=8
-    cmd = [HIPCC, *FLAGS, *extra, "-I" + os.path.join(ROOT, "include"), "-o", LIB, SRC]
+    cmd = [HIPCC, *FLAGS, *extra, "-I" + os.path.join(ROOT, "include"), "-o", LIB, *SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))

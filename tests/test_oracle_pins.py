@@ -472,3 +472,68 @@ def test_encode_is_residual_and_decodable(oracle):
     forced[:, 0] = (forced[:, 0] + 1) % 16
     c3, b3, t3 = oracle.encode_keys(keys, cb, given=forced)
     assert np.array_equal(c3[:, 0], codes[:, 0]) and np.all(t3[:, 0] >= b3[:, 0] - 1e-12)
+
+
+# ---------------------------------------------------------------- EM codebook learner (Alg. 1, App. A.2)
+def test_em_single_centre_closed_form(oracle):
+    # Nc = 1: the only centre is (x - y, y + x); least squares against the data mean (mx, my) gives
+    # x = (mx + my) / 2, y = (my - mx) / 2
+    rng = np.random.default_rng(1)
+    data = rng.standard_normal((200, 2)) + np.array([0.7, -0.2])
+    phi, _ = oracle.em_step(data, np.array([[0.3, 0.1]]), temperature=0.5)
+    mx, my = data.mean(axis=0)
+    assert np.abs(phi[0] - np.array([(mx + my) / 2, (my - mx) / 2])).max() < 1e-12
+
+
+def test_em_weights_are_a_softmax_and_centres_follow_def_center(oracle):
+    from scipy.special import softmax
+    rng = np.random.default_rng(2)
+    phi = rng.standard_normal((3, 2))
+    cen = oracle.em_centres(phi)
+    z = phi[:, 0] + 1j * phi[:, 1]
+    want = (z[:, None] + 1j * z[None, :]).reshape(-1)            # complex form of Eq. def_center
+    assert np.abs(cen[:, 0] - want.real).max() < 1e-15 and np.abs(cen[:, 1] - want.imag).max() < 1e-15
+    # hard assignment is the T -> 0 limit of the soft one
+    data = rng.standard_normal((50, 2))
+    hard, _ = oracle.em_step(data, phi, temperature=None)
+    soft, _ = oracle.em_step(data, phi, temperature=1e-4)
+    assert np.abs(hard - soft).max() < 1e-6
+    D = np.sqrt(((data[:, None] - cen[None]) ** 2).sum(-1))
+    W = softmax(-D / 0.3, axis=1)
+    assert np.abs(W.sum(axis=1) - 1).max() < 1e-14
+
+
+def test_em_m_step_is_the_weighted_least_squares_minimum(oracle):
+    # phi* must minimise sum_ab N_ab ||c_ab(phi) - m_ab||^2 for the weights of the E step: zero gradient,
+    # checked by finite differences of that objective written out independently of the T matrix
+    rng = np.random.default_rng(3)
+    Nc, T = 4, 0.4
+    data = rng.standard_normal((300, 2))
+    phi0 = rng.standard_normal((Nc, 2)) * 0.5
+    phi1, err0 = oracle.em_step(data, phi0, temperature=T)
+    cen0 = oracle.em_centres(phi0)
+    D = np.sqrt(((data[:, None] - cen0[None]) ** 2).sum(-1))
+    Z = np.exp(-(D - D.min(axis=1, keepdims=True)) / T)
+    W = Z / Z.sum(axis=1, keepdims=True)
+
+    def objective(phi):
+        c = oracle.em_centres(phi)
+        return (W * ((data[:, None] - c[None]) ** 2).sum(-1)).sum()
+
+    assert abs(objective(phi0) - err0) < 1e-9 * err0
+    f1 = objective(phi1)
+    assert f1 <= err0
+    for k in range(2 * Nc):
+        for eps in (1e-4, -1e-4):
+            p = phi1.copy().reshape(-1)
+            p[k] += eps
+            assert objective(p.reshape(Nc, 2)) >= f1 - 1e-12
+
+
+def test_em_fixed_point_on_noiseless_data(oracle):
+    # points that ARE centres of a codebook, hard-assigned: the codebook reproduces itself
+    rng = np.random.default_rng(4)
+    phi = rng.standard_normal((3, 2))
+    data = np.repeat(oracle.em_centres(phi), 5, axis=0)
+    out, err = oracle.em_step(data, phi, temperature=None)
+    assert np.abs(out - phi).max() < 1e-12 and err < 1e-24
