@@ -38,10 +38,70 @@ def parse():
                     help="re-lay the key codebook inside every call instead of once before the timed region")
     ap.add_argument("--position-free", action="store_true",
                     help="no RoPE between query and keys: scores through the scalar look-up table kernel (HBM-bound)")
-    ap.add_argument("--what", choices=["decode_attn", "encode"], default="decode_attn",
-                    help="encode: time the key encoder (cache append) on --encode-tokens new tokens instead")
+    ap.add_argument("--what", choices=["decode_attn", "encode", "em"], default="decode_attn",
+                    help="encode: time the key encoder (cache append) on --encode-tokens new tokens instead; "
+                         "em: time one iteration of the EM codebook learner (64 sub-spaces, --em-points points each)")
+    ap.add_argument("--em-points", type=int, default=8192)
     ap.add_argument("--encode-tokens", type=int, default=4096)
     return ap.parse_args()
+
+
+def bench_em(args):
+    """One step = one EM iteration (E step + M step) for the 64 sub-spaces of a head, N_c' = 64."""
+    import numpy as np
+    import torch
+
+    from paper_2506_18879_amd import binding as B
+    from paper_2506_18879_amd import synth
+
+    torch.cuda.set_device(0)
+    J, N, Nc, T = 64, args.em_points, 64, 0.2
+    rng = np.random.default_rng(synth.BASE_SEED)
+    data = rng.standard_normal((J, N, 2)).astype(np.float32)
+    phi0 = (rng.standard_normal((J, Nc, 2)) * 0.5).astype(np.float32)
+    d = torch.from_numpy(data).cuda()
+    nb = B.commvq_em_workspace_bytes(J, N, Nc)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    sp = int(torch.cuda.current_stream().cuda_stream)
+    p = torch.from_numpy(phi0).cuda()
+    for _ in range(args.warmup):
+        p.copy_(torch.from_numpy(phi0))
+        B.commvq_em_step(d, J, N, Nc, T, p, ws, nb, sp)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p.copy_(torch.from_numpy(phi0))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        B.commvq_em_step(d, J, N, Nc, T, p, ws, nb, sp)   # successive iterations of the same run
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    # per (point, centre) pair: distance (5 flop + sqrt) and exp in both passes, 5 more to accumulate
+    flop = J * N * Nc * Nc * (2 * 8 + 5)
+    tf = flop / (kernel_ms * 1e-3) / 1e12
+    result = {"metric": "EM codebook learner: calibration points/sec per head (one iteration, 64 sub-spaces)",
+              "value": round(N / (ms * 1e-3), 1), "unit": "points/s per head", "n_gpus": 1, "steps": args.steps,
+              "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "config": {"workload": f"em_64_subspaces_{N}_points_64_levels", "centres_per_subspace": Nc * Nc,
+                         "temperature": T},
+              "roofline": {"kernel": "k_em_norm + k_em_accum", "bound": "alu", "achieved": round(tf, 3),
+                           "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / FP32_PEAK_TFLOPS, 4),
+                           "traffic": None, "kernel_ms": round(kernel_ms, 5)}}
+    if not args.no_cpu_baseline:
+        import oracle
+        m = min(N, 1024)
+        c0 = time.perf_counter()
+        oracle.em_step(data[0, :m], phi0[0], temperature=T)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": round(m / 64 / (c1 - c0), 1), "unit": "points/s per head", "cores": 1,
+                                  "kind": "oracle", "sample": f"one sub-space, {m} points, {c1 - c0:.1f} s wall "
+                                                              "(a head has 64 sub-spaces)"}
+    print(json.dumps(result))
 
 
 def bench_encode(args):
@@ -116,6 +176,8 @@ def main():
         sys.exit(2)
     if args.what == "encode":
         return bench_encode(args)
+    if args.what == "em":
+        return bench_em(args)
     import numpy as np
     import torch
 

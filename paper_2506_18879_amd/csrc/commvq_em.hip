@@ -41,17 +41,17 @@ __global__ __launch_bounds__(256) void k_em_norm(const float2 *__restrict__ data
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     const float2 k = data[(size_t)j * N + i];
-    float dm = INFINITY;
+    // one pass with a running minimum: when a nearer centre turns up the partial sum is rescaled
+    float dm = INFINITY, z = 0.f;
     for (int a = 0; a < Nc; ++a)
         for (int b = 0; b < Nc; ++b) {
             const float ex = k.x - (ph[a].x - ph[b].y), ey = k.y - (ph[a].y + ph[b].x);
-            dm = fminf(dm, __builtin_sqrtf(ex * ex + ey * ey));
-        }
-    float z = 0.f;
-    for (int a = 0; a < Nc; ++a)
-        for (int b = 0; b < Nc; ++b) {
-            const float ex = k.x - (ph[a].x - ph[b].y), ey = k.y - (ph[a].y + ph[b].x);
-            z += __builtin_amdgcn_exp2f(-(__builtin_sqrtf(ex * ex + ey * ey) - dm) * inv_t * kLog2eEm);
+            const float d = __builtin_sqrtf(ex * ex + ey * ey);
+            if (d < dm) {
+                z *= __builtin_amdgcn_exp2f(-(dm - d) * inv_t * kLog2eEm);  // dm = inf the first time: z stays 0
+                dm = d;
+            }
+            z += __builtin_amdgcn_exp2f(-(d - dm) * inv_t * kLog2eEm);
         }
     dmin[(size_t)j * N + i] = dm;
     zsum[(size_t)j * N + i] = z;
