@@ -276,6 +276,27 @@ def test_paired_keys_query_inside_context_and_rejections(gpu, oracle):
     assert cv.commvq_validate_config(cfg) == 0
 
 
+@pytest.mark.parametrize("idx,units", [(6, 2), (7, 1)])
+def test_paired_keys_full_size_sampled_units(gpu, oracle, idx, units):
+    """The 128K paired-format workloads at full size (the launch shapes bench.py --config 6 / 7 times); the
+    oracle computes `units` sampled (sequence, KV head) units."""
+    w = synth.config(idx)
+    print(f"full-size case {w.name} T={w.total_tokens}", flush=True)
+    got = run_gpu(gpu, w)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(idx)
+    mask = np.zeros(w.B * w.Hkv, bool)
+    mask[rng.choice(w.B * w.Hkv, size=units, replace=False)] = True
+    ref = oracle_out_paired(oracle, w, unit_mask=mask.reshape(w.B, w.Hkv))
+    G = w.Hq // w.Hkv
+    worst = 0.0
+    for u in np.flatnonzero(mask):
+        b, g = divmod(int(u), w.Hkv)
+        worst = max(worst, row_err(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G]).max())
+    print(f"  worst row error over {units} units: {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT
+
+
 # ---------------------------------------------------------------- position-free keys (scalar look-up table)
 def oracle_out_position_free(oracle, w, **kw):
     """No rotation at all == every key at the query's position (the rotations cancel in the dot product)."""
