@@ -331,6 +331,42 @@ def test_position_free_lengths(gpu, oracle, L):
     assert row_err(got, oracle_out_position_free(oracle, w)).max() <= TOL_OUT
 
 
+# ---------------------------------------------------------------- HIP graph capture of the whole call
+@pytest.mark.parametrize("idx", [3, 6])
+def test_decode_attn_replays_from_a_hip_graph(gpu, idx):
+    """commvq_decode_attn allocates nothing and clears memory with kernels only, so a caller may capture it.
+    Every replay (with eager work and synchronisations in between, and with new queries) must give the
+    eager result bit for bit."""
+    import torch
+    w = synth.config(idx, max_len=6000)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    eager0 = op(dw).clone()                       # also the warm-up that sets kernel attributes
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        op(dw)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            op(dw)
+    torch.cuda.synchronize()
+    q0 = dw.q.clone()
+    for rep in range(3):
+        if rep:                                   # new query contents in the captured buffer
+            dw.q.copy_((q0.float() * (1.0 + 0.25 * rep)).to(q0.dtype))
+        op.out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = op.out.clone()
+        eager = op(dw).clone()                    # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, eager), rep
+        if rep == 0:
+            assert torch.equal(replayed, eager0)
+    op.close()
+
+
 # ---------------------------------------------------------------- argument checking through the C ABI
 def test_error_statuses(gpu):
     import torch
