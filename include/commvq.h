@@ -95,7 +95,8 @@ typedef struct {
     int32_t value_split_len;  /* context tokens per value workgroup */
     int32_t value_splits;     /* value workgroups per (sequence, KV head) for max_seqlen */
     int32_t out_chunks;       /* codebook-row chunks per (sequence, KV head) in the bins x codebook product */
-    int32_t reserved;
+    int32_t score_kernel;     /* 0: rows gathered through L1 (fp32 codebooks or explicit key positions);
+                                 1: codebook slices streamed through LDS (or the look-up table of position_free) */
 } commvq_plan;
 
 typedef struct commvq_handle commvq_handle;

@@ -141,7 +141,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
     p->out_chunks = h->cfg.m_val * kK / kOutRows;
-    p->reserved = sliced ? 1 : 0;
+    p->score_kernel = sliced ? 1 : 0;
 }
 
 // Carves the workspace.  Array sizes are the larger of what the two score kernels need, so one
@@ -1399,21 +1399,20 @@ struct EncodeDims {
     long long token_stride, head_stride;
 };
 
-// One workgroup per (token, KV head).  Ties go to the lowest candidate index (a * K + b when paired).
-template <bool PAIRED, bool BF16>
+// Index-form keys: one workgroup per (token, KV head), one thread per centre of the level; a row is read once,
+// straight from L2.  Ties go to the lowest index.
+template <bool BF16>
 __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, const void *__restrict__ cb,
-                                                const float *__restrict__ norms, const float *__restrict__ cross,
-                                                uint8_t *__restrict__ out, const EncodeDims a)
+                                                const float *__restrict__ norms, uint8_t *__restrict__ out, const EncodeDims a)
 {
     __shared__ float res[kD];
-    __shared__ float dots[256];
     __shared__ float wbest[4];
     __shared__ int wcand[4];
-    __shared__ int chosen[64];
+    __shared__ int chosen[32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x % a.Hkv;
     const size_t tok = blockIdx.x / a.Hkv;
-    const int K = a.K;
+    const int K = a.K;  // 256 = the workgroup size
     if (tid < kD) {
         const size_t i = (tok * a.Hkv + g) * kD + tid;
         res[tid] = a.key_bf16 ? __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(keys)[i] << 16)
@@ -1423,94 +1422,45 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
     for (int l = 0; l < a.levels; ++l) {
         const size_t level = (size_t)g * a.levels + l;
         const size_t base = level * K * kD;
-        float best = INFINITY;
-        int cand = 0x7fffffff;
-        if (!PAIRED) {
-            if (tid < K) {
-                float acc = 0.f;
-                if (BF16) {  // a row is 16 pieces of 8 bf16; all loads of the row are issued before the first use
-                    const uint4 *row = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(cb) + base + (size_t)tid * kD);
-                    uint4 pc[16];
+        float acc = 0.f;
+        if (BF16) {  // a row is 16 pieces of 8 bf16; all loads of the row are issued before the first use
+            const uint4 *row = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(cb) + base + (size_t)tid * kD);
+            uint4 pc[16];
 #pragma unroll
-                    for (int x = 0; x < 16; ++x) pc[x] = row[x];
+            for (int x = 0; x < 16; ++x) pc[x] = row[x];
 #pragma unroll
-                    for (int x = 0; x < 16; ++x) {
-                        const unsigned v[4] = {pc[x].x, pc[x].y, pc[x].z, pc[x].w};
+            for (int x = 0; x < 16; ++x) {
+                const unsigned v[4] = {pc[x].x, pc[x].y, pc[x].z, pc[x].w};
 #pragma unroll
-                        for (int y = 0; y < 4; ++y) {
-                            acc = __builtin_fmaf(res[8 * x + 2 * y], bf16_lo(v[y]), acc);
-                            acc = __builtin_fmaf(res[8 * x + 2 * y + 1], bf16_hi(v[y]), acc);
-                        }
-                    }
-                } else {
-#pragma unroll 16
-                    for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
+                for (int y = 0; y < 4; ++y) {
+                    acc = __builtin_fmaf(res[8 * x + 2 * y], bf16_lo(v[y]), acc);
+                    acc = __builtin_fmaf(res[8 * x + 2 * y + 1], bf16_hi(v[y]), acc);
                 }
-                best = norms[level * K + tid] - 2.f * acc;
-                cand = tid;
             }
         } else {
-            if (tid < 2 * K) {  // res . C[a] for tid < K, res . (i C[b]) = sum_j (-res_x y_b + res_y x_b) after
-                const int c = tid % K;
-                float acc = 0.f;
-                for (int j = 0; j < kJ; ++j) {
-                    const float x = cb_elem<BF16>(cb, base + (size_t)c * kD + 2 * j), y = cb_elem<BF16>(cb, base + (size_t)c * kD + 2 * j + 1);
-                    acc = tid < K ? __builtin_fmaf(res[2 * j + 1], y, __builtin_fmaf(res[2 * j], x, acc))
-                                  : __builtin_fmaf(res[2 * j + 1], x, __builtin_fmaf(-res[2 * j], y, acc));
-                }
-                dots[tid] = acc;
-            }
-            __syncthreads();
-            for (int c = tid; c < K * K; c += 256) {
-                const int ca = c / K, cb2 = c % K;
-                const float sc = norms[level * K + ca] + norms[level * K + cb2] + cross[level * K * K + c] - 2.f * (dots[ca] + dots[K + cb2]);
-                if (sc < best) { best = sc; cand = c; }
-            }
+#pragma unroll 16
+            for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
         }
-        // argmin over the workgroup, lowest candidate on ties
+        const float best = norms[level * K + tid] - 2.f * acc;
+        // argmin over the workgroup, lowest index on ties
         const float wm = -wave_max(-best);
-        int wc = best == wm ? cand : 0x7fffffff;
+        int wc = best == wm ? tid : 0x7fffffff;
         for (int off = 32; off > 0; off >>= 1) wc = min(wc, __shfl_xor(wc, off));
         if (lane == 0) { wbest[wave] = wm; wcand[wave] = wc; }
         __syncthreads();
-        if (tid == 0) {
-            float m = wbest[0];
-            int c = wcand[0];
-            for (int w = 1; w < 4; ++w)
-                if (wbest[w] < m || (wbest[w] == m && wcand[w] < c)) { m = wbest[w]; c = wcand[w]; }
-            chosen[l] = c;
-        }
-        __syncthreads();
-        const int c = chosen[l];
-        if (tid < kD) {
-            if (!PAIRED) {
-                res[tid] -= cb_elem<BF16>(cb, base + (size_t)c * kD + tid);
-            } else {
-                const int ca = c / K, cb2 = c % K;
-                // element e of i C[b]: (-y_b, x_b) of its sub-space
-                const float second = (tid & 1) ? cb_elem<BF16>(cb, base + (size_t)cb2 * kD + tid - 1)
-                                               : -cb_elem<BF16>(cb, base + (size_t)cb2 * kD + tid + 1);
-                res[tid] -= cb_elem<BF16>(cb, base + (size_t)ca * kD + tid) + second;
-            }
-        }
+        float m = wbest[0];
+        int c = wcand[0];
+        for (int w = 1; w < 4; ++w)
+            if (wbest[w] < m || (wbest[w] == m && wcand[w] < c)) { m = wbest[w]; c = wcand[w]; }
+        if (tid == 0) chosen[l] = c;
+        if (tid < kD) res[tid] -= cb_elem<BF16>(cb, base + (size_t)c * kD + tid);
         __syncthreads();
     }
-    uint8_t *dst = out + tok * a.token_stride + (long long)g * a.head_stride;
-    if (!PAIRED) {
-        if (tid < a.levels) dst[tid] = (uint8_t)chosen[tid];
-    } else if (tid < a.record_bytes) {
-        // byte tid of the record: the 12-bit pairs (a | b << 6) that overlap bits 8 tid .. 8 tid + 7
-        unsigned v = 0;
-        for (int r = (8 * tid) / 12; r < a.levels && 12 * r < 8 * tid + 8; ++r) {
-            const unsigned pr = (unsigned)(chosen[r] / K) | (unsigned)(chosen[r] % K) << 6;
-            const int sh = 12 * r - 8 * tid;
-            v |= sh >= 0 ? pr << sh : pr >> -sh;
-        }
-        dst[tid] = (uint8_t)(v & 0xffu);
-    }
+    if (tid < a.levels) out[tok * a.token_stride + (long long)g * a.head_stride + tid] = (uint8_t)chosen[tid];
 }
 
-// Same search for bf16 rows, shaped for latency (a decode step appends one token per sequence, and the R
+// Paired-format keys (and the template's index-form variant, not dispatched: staging 64 KiB of rows that are
+// used once does not pay), shaped for latency (a decode step appends one token per sequence, and the R
 // levels are a dependent chain): the rows, norms and cross terms of level l + 1 do not depend on the
 // residual, so they are fetched into registers while level l is searched and parked in the other half
 // of a double-buffered LDS image; every level then runs out of LDS.  Rows are padded to 65 dwords so
@@ -2103,7 +2053,7 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
                                      : launch_lut_m<32>(h->G, q, key_cb, bf16, w.lut, key_codes, pos->cu_seqlens, w.scores, w.sstat, d, pos->batch, tpt, grid, s);
         return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
     }
-    if (plan.reserved) {  // slice-streaming kernel: needs the codebook in LDS-image order
+    if (plan.score_kernel) {  // slice-streaming kernel: needs the codebook in LDS-image order
         const uint4 *packed = nullptr;
         for (const auto &e : h->packed_keys)
             if (e.first == key_cb) packed = e.second;
@@ -2403,9 +2353,9 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
         }
         hipLaunchKernelGGL(k_encode_lds<true>, grid, dim3(256), lds, s, keys, static_cast<const unsigned *>(key_cb), norms, cross, codes_out, d);
     } else if (bf16) {
-        hipLaunchKernelGGL((k_encode<false, true>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
+        hipLaunchKernelGGL(k_encode<true>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);
     } else {
-        hipLaunchKernelGGL((k_encode<false, false>), grid, dim3(256), 0, s, keys, key_cb, norms, cross, codes_out, d);
+        hipLaunchKernelGGL(k_encode<false>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);
     }
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
