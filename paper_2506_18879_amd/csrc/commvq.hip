@@ -1459,6 +1459,114 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
     if (tid < a.levels) out[tok * a.token_stride + (long long)g * a.head_stride + tid] = (uint8_t)chosen[tid];
 }
 
+// Index-form keys, many tokens at once (prefill-sized chunks): the dot products of a level are a
+// (256 rows x 128) x (128 x tokens) matrix product, so they run on the matrix cores.  A workgroup takes 64
+// tokens of one KV head (16 per wavefront) and stages the level's 256 bf16 rows in LDS once for all of them.
+// The fp32 residual of a token is split EXACTLY into three bf16 parts (its 24 mantissa bits are 8 + 8 + 8:
+// truncate, subtract, truncate, subtract), each multiplied with the exact bf16 rows and accumulated in fp32:
+// the same dot product as the fp32 FMA chain of k_encode up to summation order.
+//   first operand : 16 rows x 32 elements from LDS (row stride 288 bytes: the 16 lanes of a k-group and the two
+//                   k-groups that are checked together hit different banks)
+//   second operand: lane (n, g) supplies elements 32 kc + 8 g .. + 7 of token n, the part of the residual it keeps
+//   result        : lane (n, g) receives rows 4 g .. 4 g + 3 of the row tile for token n
+constexpr int kEbTokens = 64;
+constexpr int kEbRowBytes = 288;
+constexpr int kEbLds = 256 * kEbRowBytes + 256 * 4 + (kEbTokens * 32);
+__global__ __launch_bounds__(256) void k_encode_batch(const void *__restrict__ keys, const uint4 *__restrict__ cb,
+                                                      const float *__restrict__ norms, uint8_t *__restrict__ out,
+                                                      const EncodeDims a, int n_tokens)
+{
+    extern __shared__ __attribute__((aligned(16))) uint4 eb_lds[];
+    char *rows = reinterpret_cast<char *>(eb_lds);
+    float *nrm = reinterpret_cast<float *>(rows + 256 * kEbRowBytes);
+    uint8_t *chosen = reinterpret_cast<uint8_t *>(nrm + 256);  // [64 tokens][32 levels]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gk = lane >> 4;
+    const int g = blockIdx.x % a.Hkv;
+    const int tl = wave * 16 + n;                                // token within the workgroup
+    const long long tok = (long long)(blockIdx.x / a.Hkv) * kEbTokens + tl;
+    const size_t tokc = (size_t)(tok < n_tokens ? tok : n_tokens - 1);
+    float res[4][8];
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) {
+        const size_t i = (tokc * a.Hkv + g) * kD + kc * 32 + 8 * gk;
+        if (a.key_bf16) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(keys) + i);
+            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { res[kc][2 * e] = bf16_lo(w[e]); res[kc][2 * e + 1] = bf16_hi(w[e]); }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) res[kc][e] = static_cast<const float *>(keys)[i + e];
+        }
+    }
+    for (int l = 0; l < a.levels; ++l) {
+        const size_t level = (size_t)g * a.levels + l;
+        __syncthreads();  // the previous level's rows are no longer read
+        for (int x = tid; x < 256 * 16; x += 256)
+            *reinterpret_cast<uint4 *>(rows + (x >> 4) * kEbRowBytes + (x & 15) * 16) = cb[level * 256 * 16 + x];
+        nrm[tid] = norms[level * 256 + tid];
+        __syncthreads();
+        // exact three-way bf16 split of the lane's part of the residual, packed as MFMA operands
+        uint4_t part[3][4];
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float v0 = res[kc][2 * e], v1 = res[kc][2 * e + 1];
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) {
+                    const unsigned t0 = __builtin_bit_cast(unsigned, v0) & 0xffff0000u, t1 = __builtin_bit_cast(unsigned, v1) & 0xffff0000u;
+                    part[s3][kc][e] = (t0 >> 16) | t1;
+                    v0 -= __builtin_bit_cast(float, t0);
+                    v1 -= __builtin_bit_cast(float, t1);
+                }
+            }
+        float best = INFINITY;
+        int brow = 0;
+#pragma unroll 2
+        for (int rt = 0; rt < 16; ++rt) {
+            floatx4_t D = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kc = 0; kc < 4; ++kc) {
+                const uint4 pc = *reinterpret_cast<const uint4 *>(rows + (rt * 16 + n) * kEbRowBytes + kc * 64 + gk * 16);
+                const uint4_t pv = {pc.x, pc.y, pc.z, pc.w};
+                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, pv);
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, part[s3][kc]), D, 0, 0, 0);
+            }
+            const float4 nr = *reinterpret_cast<const float4 *>(nrm + rt * 16 + 4 * gk);
+            const float nv[4] = {nr.x, nr.y, nr.z, nr.w};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float sc = nv[r] - 2.f * D[r];
+                if (sc < best) { best = sc; brow = rt * 16 + 4 * gk + r; }  // rows come in increasing order: ties keep the lowest
+            }
+        }
+        // the four lanes of a token hold the minima of disjoint row sets
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            const float ov = __shfl_xor(best, off);
+            const int orow = __shfl_xor(brow, off);
+            if (ov < best || (ov == best && orow < brow)) { best = ov; brow = orow; }
+        }
+        if (gk == 0) chosen[tl * 32 + l] = (uint8_t)brow;
+        // residual -= chosen row (the lane's 32 elements of it)
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc) {
+            const uint4 pc = *reinterpret_cast<const uint4 *>(rows + brow * kEbRowBytes + kc * 64 + gk * 16);
+            const unsigned w[4] = {pc.x, pc.y, pc.z, pc.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { res[kc][2 * e] -= bf16_lo(w[e]); res[kc][2 * e + 1] -= bf16_hi(w[e]); }
+        }
+    }
+    __syncthreads();
+    if (tok < n_tokens) {
+        uint8_t *dst = out + tok * a.token_stride + (long long)g * a.head_stride;
+        for (int l = gk; l < a.levels; l += 4) dst[l] = chosen[tl * 32 + l];
+    }
+}
+
 // Paired-format keys (and the template's index-form variant, not dispatched: staging 64 KiB of rows that are
 // used once does not pay), shaped for latency (a decode step appends one token per sequence, and the R
 // levels are a dependent chain): the rows, norms and cross terms of level l + 1 do not depend on the
@@ -2352,6 +2460,17 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
             attr_set = true;
         }
         hipLaunchKernelGGL(k_encode_lds<true>, grid, dim3(256), lds, s, keys, static_cast<const unsigned *>(key_cb), norms, cross, codes_out, d);
+    } else if (bf16 && n_tokens >= kEbTokens) {  // many tokens: rows staged once per 64 tokens, dot products on the matrix cores
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_batch), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kEbLds) != hipSuccess)
+                return COMMVQ_ERR_LAUNCH;
+            attr_set = true;
+        }
+        const dim3 bgrid((unsigned)((n_tokens + kEbTokens - 1) / kEbTokens * c.n_kv_heads));
+        hipLaunchKernelGGL(k_encode_batch, bgrid, dim3(256), kEbLds, s, keys, static_cast<const uint4 *>(key_cb), norms, codes_out, d,
+                           n_tokens);
     } else if (bf16) {
         hipLaunchKernelGGL(k_encode<true>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);
     } else {

@@ -56,11 +56,12 @@ def judge(oracle, keys_f64, cb_f64, gpu_codes, paired):
     return same
 
 
+@pytest.mark.parametrize("n", [5, 96, 200])
 @pytest.mark.parametrize("Mk", [16, 32])
-def test_encode_index_form(gpu, oracle, Mk):
+def test_encode_index_form(gpu, oracle, Mk, n):
+    # n < 64: one workgroup per token (decode-step append); n >= 64: 64 tokens per workgroup on the matrix cores
     w = synth.make_workload(f"enc_m{Mk}", B=1, Hq=4, Hkv=2, seqlens=[8], Mk=Mk, Mv=16, dtype="bf16", seed=200 + Mk)
-    rng = np.random.default_rng(Mk)
-    n = 96
+    rng = np.random.default_rng(Mk + n)
     keys = synth.f32_to_bf16_bits(rng.standard_normal((n, w.Hkv, w.d)).astype(np.float32))
     got = encode_on_gpu(gpu, w, keys, L_cap=n + 5)
     kf = synth.bf16_bits_to_f32(keys).astype(np.float64)
