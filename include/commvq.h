@@ -173,9 +173,9 @@ commvq_status commvq_forget_packed_key_codebooks(commvq_handle *handle, const vo
  * Distances are compared in fp32 as ||c||^2 - 2 res.c; ties go to the lowest index (a * 64 + b).
  *   commvq_encoder_table_bytes / commvq_encoder_prepare
  *       one-time tables for a set of key codebooks (squared norms of all rows; paired: plus the
- *       cross terms 2 C[a].(i C[b])): `tables` is a device buffer of that many bytes, 4-byte aligned
+ *       cross terms 2 C[a].(i C[b])): `tables` is a device buffer of that many bytes, 16-byte aligned
  *   commvq_encode_keys
- *       keys        [n_tokens][Hkv][d], q_dtype
+ *       keys        [n_tokens][Hkv][d], q_dtype, 16-byte aligned (as are key_codebooks and tables)
  *       codes_out   the record of token t, KV head g is written at codes_out + t * token_stride +
  *                   g * head_stride (bytes): M_k index bytes, or the ceil(12 R / 8)-byte packed
  *                   pair record, so that the caller can point straight into its cache layout

@@ -1567,6 +1567,144 @@ __global__ __launch_bounds__(256) void k_encode_batch(const void *__restrict__ k
     }
 }
 
+// Paired-format keys, many tokens at once.  Same scheme as k_encode_batch for the two sets of 64 dot products of a
+// level -- P[a] = res . C[a] and Q[b] = res . (i C[b]) = res' . C[b] with res' = (res_y, -res_x) per sub-space, whose
+// bf16 parts are the parts of res with halves swapped and one sign flipped -- then every lane scans 16 x 64 of the
+// token's 4096 centres:  ||c_ab||^2 - 2 res . c_ab = (N[a] - 2 P[a]) + (N[b] - 2 Q[b]) + X[a][b].
+constexpr int kEpRowBytes = 288;
+constexpr int kEpVecBytes = 272;  // padded stride of a token's 64 floats: 16 tokens hit 64 different banks
+constexpr int kEpLds = 64 * kEpRowBytes + 64 * 64 * 4 + 64 * 4 + 2 * kEbTokens * kEpVecBytes + kEbTokens * 64;
+__global__ __launch_bounds__(256) void k_encode_pair_batch(const void *__restrict__ keys, const uint4 *__restrict__ cb,
+                                                           const float *__restrict__ norms, const float *__restrict__ cross,
+                                                           uint8_t *__restrict__ out, const EncodeDims a, int n_tokens)
+{
+    extern __shared__ __attribute__((aligned(16))) uint4 ep_lds[];
+    char *rows = reinterpret_cast<char *>(ep_lds);                        // [64][288 B]
+    float *xs = reinterpret_cast<float *>(rows + 64 * kEpRowBytes);       // [64][64]
+    float *nrm = xs + 64 * 64;                                            // [64]
+    char *uvec = reinterpret_cast<char *>(nrm + 64);                      // [64 tokens][272 B]: N[a] - 2 P[a]
+    char *vvec = uvec + kEbTokens * kEpVecBytes;                          // [64 tokens][272 B]: N[b] - 2 Q[b]
+    uint8_t *chosen = reinterpret_cast<uint8_t *>(vvec + kEbTokens * kEpVecBytes);  // [64 tokens][32 levels][2]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gk = lane >> 4;
+    const int g = blockIdx.x % a.Hkv;
+    const int tl = wave * 16 + n;
+    const long long tok = (long long)(blockIdx.x / a.Hkv) * kEbTokens + tl;
+    const size_t tokc = (size_t)(tok < n_tokens ? tok : n_tokens - 1);
+    float res[4][8];
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) {
+        const size_t i = (tokc * a.Hkv + g) * kD + kc * 32 + 8 * gk;
+        if (a.key_bf16) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(keys) + i);
+            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { res[kc][2 * e] = bf16_lo(w[e]); res[kc][2 * e + 1] = bf16_hi(w[e]); }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) res[kc][e] = static_cast<const float *>(keys)[i + e];
+        }
+    }
+    for (int l = 0; l < a.levels; ++l) {
+        const size_t level = (size_t)g * a.levels + l;
+        __syncthreads();  // the previous level's tables are no longer read
+        for (int x = tid; x < 64 * 16; x += 256)
+            *reinterpret_cast<uint4 *>(rows + (x >> 4) * kEpRowBytes + (x & 15) * 16) = cb[level * 64 * 16 + x];
+        for (int x = tid; x < 64 * 64 / 4; x += 256)
+            reinterpret_cast<float4 *>(xs)[x] = reinterpret_cast<const float4 *>(cross + level * 64 * 64)[x];
+        if (tid < 64) nrm[tid] = norms[level * 64 + tid];
+        __syncthreads();
+        uint4_t part[3][4];
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float v0 = res[kc][2 * e], v1 = res[kc][2 * e + 1];
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) {
+                    const unsigned t0 = __builtin_bit_cast(unsigned, v0) & 0xffff0000u, t1 = __builtin_bit_cast(unsigned, v1) & 0xffff0000u;
+                    part[s3][kc][e] = (t0 >> 16) | t1;
+                    v0 -= __builtin_bit_cast(float, t0);
+                    v1 -= __builtin_bit_cast(float, t1);
+                }
+            }
+        // P and Q for the 64 rows, 16 at a time; lane (n, gk) receives rows 16 rt + 4 gk .. + 3 of token n
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            floatx4_t DP = {0.f, 0.f, 0.f, 0.f}, DQ = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kc = 0; kc < 4; ++kc) {
+                const uint4 pc = *reinterpret_cast<const uint4 *>(rows + (rt * 16 + n) * kEpRowBytes + kc * 64 + gk * 16);
+                const uint4_t pv = {pc.x, pc.y, pc.z, pc.w};
+                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, pv);
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) {
+                    DP = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, part[s3][kc]), DP, 0, 0, 0);
+                    uint4_t rot;  // (x, y) -> (y, -x): swap the halves, flip the sign of the new upper half
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rot[e] = __builtin_amdgcn_alignbit(part[s3][kc][e], part[s3][kc][e], 16) ^ 0x80000000u;
+                    DQ = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, rot), DQ, 0, 0, 0);
+                }
+            }
+            const float4 nr = *reinterpret_cast<const float4 *>(nrm + rt * 16 + 4 * gk);
+            *reinterpret_cast<float4 *>(uvec + tl * kEpVecBytes + (rt * 16 + 4 * gk) * 4) =
+                make_float4(nr.x - 2.f * DP[0], nr.y - 2.f * DP[1], nr.z - 2.f * DP[2], nr.w - 2.f * DP[3]);
+            *reinterpret_cast<float4 *>(vvec + tl * kEpVecBytes + (rt * 16 + 4 * gk) * 4) =
+                make_float4(nr.x - 2.f * DQ[0], nr.y - 2.f * DQ[1], nr.z - 2.f * DQ[2], nr.w - 2.f * DQ[3]);
+        }
+        __syncthreads();
+        // scan: lane (n, gk) takes a = 16 gk .. 16 gk + 15 and all b of token n, in increasing a * 64 + b
+        float best = INFINITY;
+        int bc = 0;
+        for (int ai = 0; ai < 16; ++ai) {
+            const int ca = 16 * gk + ai;
+            const float ua = *reinterpret_cast<const float *>(uvec + tl * kEpVecBytes + ca * 4);
+#pragma unroll 4
+            for (int b4 = 0; b4 < 16; ++b4) {
+                const float4 vb = *reinterpret_cast<const float4 *>(vvec + tl * kEpVecBytes + b4 * 16);
+                const float4 xb = *reinterpret_cast<const float4 *>(xs + ca * 64 + b4 * 4);
+                const float sc[4] = {ua + (vb.x + xb.x), ua + (vb.y + xb.y), ua + (vb.z + xb.z), ua + (vb.w + xb.w)};
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (sc[r] < best) { best = sc[r]; bc = ca * 64 + b4 * 4 + r; }
+            }
+        }
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            const float ov = __shfl_xor(best, off);
+            const int oc = __shfl_xor(bc, off);
+            if (ov < best || (ov == best && oc < bc)) { best = ov; bc = oc; }
+        }
+        const int ca = bc >> 6, cb2 = bc & 63;
+        if (gk == 0) { chosen[(tl * 32 + l) * 2] = (uint8_t)ca; chosen[(tl * 32 + l) * 2 + 1] = (uint8_t)cb2; }
+        // residual -= C[a] + i C[b]: per sub-space (x_a - y_b, y_a + x_b)
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc) {
+            const uint4 pa = *reinterpret_cast<const uint4 *>(rows + ca * kEpRowBytes + kc * 64 + gk * 16);
+            const uint4 pb = *reinterpret_cast<const uint4 *>(rows + cb2 * kEpRowBytes + kc * 64 + gk * 16);
+            const unsigned wa[4] = {pa.x, pa.y, pa.z, pa.w}, wb[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                res[kc][2 * e] -= bf16_lo(wa[e]) - bf16_hi(wb[e]);
+                res[kc][2 * e + 1] -= bf16_hi(wa[e]) + bf16_lo(wb[e]);
+            }
+        }
+    }
+    __syncthreads();
+    if (tok < n_tokens) {
+        uint8_t *dst = out + tok * a.token_stride + (long long)g * a.head_stride;
+        for (int byte = gk; byte < a.record_bytes; byte += 4) {
+            unsigned v = 0;
+            for (int r = (8 * byte) / 12; r < a.levels && 12 * r < 8 * byte + 8; ++r) {
+                const unsigned pr = (unsigned)chosen[(tl * 32 + r) * 2] | (unsigned)chosen[(tl * 32 + r) * 2 + 1] << 6;
+                const int sh = 12 * r - 8 * byte;
+                v |= sh >= 0 ? pr << sh : pr >> -sh;
+            }
+            dst[byte] = (uint8_t)(v & 0xffu);
+        }
+    }
+}
+
 // Paired-format keys (and the template's index-form variant, not dispatched: staging 64 KiB of rows that are
 // used once does not pay), shaped for latency (a decode step appends one token per sequence, and the R
 // levels are a dependent chain): the rows, norms and cross terms of level l + 1 do not depend on the
@@ -2416,7 +2554,7 @@ commvq_status commvq_encoder_table_bytes(const commvq_handle *h, size_t *bytes)
 commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void *tables, void *stream)
 {
     if (!h || !key_cb || !tables) return COMMVQ_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(tables) & 3u) return COMMVQ_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(tables) & 15u) return COMMVQ_ERR_SHAPE;
     const commvq_config &c = h->cfg;
     const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
     const int levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
@@ -2441,6 +2579,8 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
     const int rec = paired ? (12 * levels + 7) / 8 : levels;
     if (n_tokens < 1 || (int64_t)n_tokens * c.n_kv_heads > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
     if (head_stride < rec || token_stride < rec) return COMMVQ_ERR_SHAPE;  // records must not overlap
+    if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(keys) | reinterpret_cast<uintptr_t>(key_cb)) & 15u)
+        return COMMVQ_ERR_SHAPE;
     EncodeDims d;
     d.Hkv = c.n_kv_heads; d.levels = levels; d.K = K; d.key_bf16 = c.q_dtype == COMMVQ_BF16; d.record_bytes = rec;
     d.token_stride = token_stride; d.head_stride = head_stride;
@@ -2450,7 +2590,18 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
     if (paired && !bf16) return COMMVQ_ERR_CONFIG;
-    if (paired) {  // rows, norms and cross terms staged in LDS, next level prefetched
+    if (paired && n_tokens >= kEbTokens) {  // many tokens: 64 per workgroup, dot products on the matrix cores
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_pair_batch), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kEpLds) != hipSuccess)
+                return COMMVQ_ERR_LAUNCH;
+            attr_set = true;
+        }
+        const dim3 bgrid((unsigned)((n_tokens + kEbTokens - 1) / kEbTokens * c.n_kv_heads));
+        hipLaunchKernelGGL(k_encode_pair_batch, bgrid, dim3(256), kEpLds, s, keys, static_cast<const uint4 *>(key_cb), norms, cross,
+                           codes_out, d, n_tokens);
+    } else if (paired) {  // rows, norms and cross terms staged in LDS, next level prefetched
         const int lds = (2 * K * kEncRowDw + 2 * K * K + 2 * K + kD + 256 + 8 + 32) * 4;
         static bool attr_set = false;
         if (!attr_set) {

@@ -71,11 +71,12 @@ def test_encode_index_form(gpu, oracle, Mk, n):
     assert same.mean() >= 0.97
 
 
+@pytest.mark.parametrize("n", [40, 130])
 @pytest.mark.parametrize("R", [11, 21, 2])
-def test_encode_paired_format(gpu, oracle, R):
+def test_encode_paired_format(gpu, oracle, R, n):
+    # n < 64: one workgroup per token; n >= 64: 64 tokens per workgroup, dot products on the matrix cores
     w = synth.make_pair_workload(f"enc_R{R}", B=1, Hq=4, Hkv=2, seqlens=[8], R=R, Mv=16, seed=300 + R)
-    rng = np.random.default_rng(R)
-    n = 40
+    rng = np.random.default_rng(R + n)
     keys = synth.f32_to_bf16_bits(rng.standard_normal((n, w.Hkv, w.d)).astype(np.float32))
     got = encode_on_gpu(gpu, w, keys, L_cap=n)
     kf = synth.bf16_bits_to_f32(keys).astype(np.float64)
@@ -131,5 +132,8 @@ def test_encode_rejects_overlapping_records(gpu):
     assert e.value.status == 3
     with pytest.raises(cv.CommVQError) as e:
         cv.commvq_encode_keys(op.handle, buf, 0, buf, buf, buf, 16, 16)
+    assert e.value.status == 3
+    with pytest.raises(cv.CommVQError) as e:        # misaligned tables
+        cv.commvq_encode_keys(op.handle, buf, 1, buf, buf.data_ptr() + 4, buf, 16, 16)
     assert e.value.status == 3
     op.close()
