@@ -157,6 +157,16 @@ def bench_encode(args):
         roof = {"kernel": "k_encode_batch", "bound": "mfma", "achieved": round(mf, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(mf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                 "kernel_ms": round(kernel_ms, 5)}
+    if paired and n >= 64:
+        # 64 tokens per workgroup: the 2 x 64 dot products of a level run as bf16 MFMA (three exact parts), the scan
+        # of the 64 x 64 centres is one add and one minimum per centre on the vector ALU (peak counts fused,
+        # packed operations: plain ones reach a quarter of it) and reads each cross term from LDS once per token
+        ops = n * w.Hkv * levels * 2 * K * K / (kernel_ms * 1e-3) / 1e12
+        lds = n * w.Hkv * levels * 4 * K * K / (kernel_ms * 1e-3) / 1e12
+        roof = {"kernel": "k_encode_pair_batch", "bound": "alu", "achieved": round(ops, 2), "peak": FP32_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(ops / FP32_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel_ms": round(kernel_ms, 5),
+                "lds_view": {"cross_term_TBs": round(lds, 1), "peak_TBs": LDS_PEAK_TBS, "frac": round(lds / LDS_PEAK_TBS, 3)}}
     result = {"metric": "key-encode new tokens/sec per layer (cache append)", "value": round(n / (ms * 1e-3), 1),
               "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
               "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

@@ -1605,14 +1605,33 @@ __global__ __launch_bounds__(256) void k_encode_pair_batch(const void *__restric
             for (int e = 0; e < 8; ++e) res[kc][e] = static_cast<const float *>(keys)[i + e];
         }
     }
+    // a level's tables do not depend on the residual: they are fetched into registers one level ahead
+    uint4 prow0, prow1, prow2, prow3;
+    float4 pcr0, pcr1, pcr2, pcr3;
+    float pnorm = 0.f;
+#define COMMVQ_EP_FETCH(l_)                                                                        \
+    {                                                                                              \
+        const size_t level_ = (size_t)g * a.levels + (l_);                                         \
+        const uint4 *r_ = cb + level_ * 64 * 16 + tid;                                             \
+        const float4 *c_ = reinterpret_cast<const float4 *>(cross + level_ * 64 * 64) + tid;       \
+        prow0 = r_[0]; prow1 = r_[256]; prow2 = r_[512]; prow3 = r_[768];                          \
+        pcr0 = c_[0]; pcr1 = c_[256]; pcr2 = c_[512]; pcr3 = c_[768];                              \
+        if (tid < 64) pnorm = norms[level_ * 64 + tid];                                            \
+    }
+    COMMVQ_EP_FETCH(0)
     for (int l = 0; l < a.levels; ++l) {
-        const size_t level = (size_t)g * a.levels + l;
         __syncthreads();  // the previous level's tables are no longer read
-        for (int x = tid; x < 64 * 16; x += 256)
-            *reinterpret_cast<uint4 *>(rows + (x >> 4) * kEpRowBytes + (x & 15) * 16) = cb[level * 64 * 16 + x];
-        for (int x = tid; x < 64 * 64 / 4; x += 256)
-            reinterpret_cast<float4 *>(xs)[x] = reinterpret_cast<const float4 *>(cross + level * 64 * 64)[x];
-        if (tid < 64) nrm[tid] = norms[level * 64 + tid];
+        {
+            char *rp = rows + (tid >> 4) * kEpRowBytes + (tid & 15) * 16;  // element tid + 256 x: 16 rows further on
+            *reinterpret_cast<uint4 *>(rp) = prow0;
+            *reinterpret_cast<uint4 *>(rp + 16 * kEpRowBytes) = prow1;
+            *reinterpret_cast<uint4 *>(rp + 32 * kEpRowBytes) = prow2;
+            *reinterpret_cast<uint4 *>(rp + 48 * kEpRowBytes) = prow3;
+            float4 *xp = reinterpret_cast<float4 *>(xs) + tid;
+            xp[0] = pcr0; xp[256] = pcr1; xp[512] = pcr2; xp[768] = pcr3;
+        }
+        if (tid < 64) nrm[tid] = pnorm;
+        if (l + 1 < a.levels) COMMVQ_EP_FETCH(l + 1)
         __syncthreads();
         uint4_t part[3][4];
 #pragma unroll
@@ -1653,29 +1672,68 @@ __global__ __launch_bounds__(256) void k_encode_pair_batch(const void *__restric
                 make_float4(nr.x - 2.f * DQ[0], nr.y - 2.f * DQ[1], nr.z - 2.f * DQ[2], nr.w - 2.f * DQ[3]);
         }
         __syncthreads();
-        // scan: lane (n, gk) takes a = 16 gk .. 16 gk + 15 and all b of token n, in increasing a * 64 + b
-        float best = INFINITY;
-        int bc = 0;
-        for (int ai = 0; ai < 16; ++ai) {
-            const int ca = 16 * gk + ai;
-            const float ua = *reinterpret_cast<const float *>(uvec + tl * kEpVecBytes + ca * 4);
-#pragma unroll 4
-            for (int b4 = 0; b4 < 16; ++b4) {
-                const float4 vb = *reinterpret_cast<const float4 *>(vvec + tl * kEpVecBytes + b4 * 16);
-                const float4 xb = *reinterpret_cast<const float4 *>(xs + ca * 64 + b4 * 4);
-                const float sc[4] = {ua + (vb.x + xb.x), ua + (vb.y + xb.y), ua + (vb.z + xb.z), ua + (vb.w + xb.w)};
+        // scan in two stages, with the result of a sequential scan in increasing a * 64 + b under a strict "<":
+        // rounding is monotone, so min over b of fl(u + t[b]) is fl(u + min t[b]), and stage one needs only an add
+        // and half a three-way minimum per centre.  Lane (n, gk) takes a = 16 gk .. 16 gk + 15 and all b of token n.
+        float vb[64];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (sc[r] < best) { best = sc[r]; bc = ca * 64 + b4 * 4 + r; }
+        for (int b4 = 0; b4 < 16; ++b4) {
+            const float4 v4 = *reinterpret_cast<const float4 *>(vvec + tl * kEpVecBytes + b4 * 16);
+            vb[4 * b4] = v4.x; vb[4 * b4 + 1] = v4.y; vb[4 * b4 + 2] = v4.z; vb[4 * b4 + 3] = v4.w;
+        }
+        float best = INFINITY;
+        int ca = 0;
+        {
+            // the cross terms are read a quarter row (four float4) ahead of their use; the read ahead of the last
+            // quarter of row 63 lands on the norms that follow the cross table in LDS and is not used
+            const float4 *xrow = reinterpret_cast<const float4 *>(xs) + 16 * gk * 16;
+            float4 cur[4], nxt[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) cur[q] = xrow[q];
+            for (int ai = 0; ai < 16; ++ai) {
+                float m = INFINITY;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) nxt[q] = xrow[ai * 16 + (c + 1) * 4 + q];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int b = 16 * c + 4 * q;
+                        m = fminf(fminf(m, vb[b] + cur[q].x), vb[b + 1] + cur[q].y);
+                        m = fminf(fminf(m, vb[b + 2] + cur[q].z), vb[b + 3] + cur[q].w);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+                }
+                const int a2 = 16 * gk + ai;
+                const float sc = *reinterpret_cast<const float *>(uvec + tl * kEpVecBytes + a2 * 4) + m;
+                if (sc < best) { best = sc; ca = a2; }
             }
         }
 #pragma unroll
         for (int off = 16; off <= 32; off <<= 1) {
             const float ov = __shfl_xor(best, off);
-            const int oc = __shfl_xor(bc, off);
-            if (ov < best || (ov == best && oc < bc)) { best = ov; bc = oc; }
+            const int oc = __shfl_xor(ca, off);
+            if (ov < best || (ov == best && oc < ca)) { best = ov; ca = oc; }
         }
-        const int ca = bc >> 6, cb2 = bc & 63;
+        // stage two: the lowest b of row ca whose sum rounds to the minimum; the four lanes of a token take 16 b each
+        int cb2 = 64;
+        {
+            const float ua = *reinterpret_cast<const float *>(uvec + tl * kEpVecBytes + ca * 4);
+#pragma unroll
+            for (int b4 = 3; b4 >= 0; --b4) {
+                const float4 v4 = *reinterpret_cast<const float4 *>(vvec + tl * kEpVecBytes + (4 * gk + b4) * 16);
+                const float4 xb = *reinterpret_cast<const float4 *>(xs + ca * 64 + (4 * gk + b4) * 4);
+                const int b0 = 16 * gk + 4 * b4;
+                if (ua + (v4.w + xb.w) == best) cb2 = b0 + 3;
+                if (ua + (v4.z + xb.z) == best) cb2 = b0 + 2;
+                if (ua + (v4.y + xb.y) == best) cb2 = b0 + 1;
+                if (ua + (v4.x + xb.x) == best) cb2 = b0;
+            }
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) cb2 = min(cb2, __shfl_xor(cb2, off));
+            cb2 &= 63;  // always below 64 for finite input; keeps the row read in range otherwise
+        }
         if (gk == 0) { chosen[(tl * 32 + l) * 2] = (uint8_t)ca; chosen[(tl * 32 + l) * 2 + 1] = (uint8_t)cb2; }
         // residual -= C[a] + i C[b]: per sub-space (x_a - y_b, y_a + x_b)
 #pragma unroll
@@ -1704,6 +1762,8 @@ __global__ __launch_bounds__(256) void k_encode_pair_batch(const void *__restric
         }
     }
 }
+
+#undef COMMVQ_EP_FETCH
 
 // Paired-format keys (and the template's index-form variant, not dispatched: staging 64 KiB of rows that are
 // used once does not pay), shaped for latency (a decode step appends one token per sequence, and the R
