@@ -551,6 +551,12 @@ struct SliceDims {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
+// 16-byte LDS read at an absolute LDS byte address.  The score kernels keep their dynamic LDS at address 0
+// (no static LDS), but the compiler only learns that after instruction selection: a read through the array's
+// base costs one "add 0" per read.
+typedef __attribute__((address_space(3))) const uint4_t *lds_u4_ptr;
+__device__ __forceinline__ uint4_t lds_read_b128(unsigned byte_addr) { return *reinterpret_cast<lds_u4_ptr>(byte_addr); }
+
 // Max / sum over the lanes of a wavefront that hold logits of the same query head in k_score_mfma:
 // one 16-lane row (M = 16), or the two rows r and r + 2 (M = 32).
 template <int M>
@@ -772,9 +778,8 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             // phase factors of the lane's token and part, from LDS (16 consecutive tokens read 16 consecutive
             // fine rows and at most two coarse rows: no bank conflicts)
             const int d16 = dist16 - p * (NW * 16 * SETS * 16);
-            const uint4_t elr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + elo_base + (unsigned)(d16 & ((kLo - 1) * 16)));
-            const uint4_t ehr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + ehi_base +
-                                                                   (unsigned)(((d16 >> (kLoBits + 4)) - hmin) * 16));
+            const uint4_t elr = lds_read_b128(elo_base + (unsigned)(d16 & ((kLo - 1) * 16)));
+            const uint4_t ehr = lds_read_b128(ehi_base + (unsigned)(((d16 >> (kLoBits + 4)) - hmin) * 16));
             __builtin_amdgcn_sched_barrier(0);
             fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
@@ -788,15 +793,15 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             // 1. gather-sum on the matrix cores; LDS reads in groups of RG, two groups in flight
             floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
             constexpr int RG = (G == 8 && TPT == 4) ? 2 : 4, NG = NS / RG;  // fewer reads in flight where registers are short
-            uint4 v[2][RG];
-            auto issue = [&](int grp, uint4(&dst)[RG]) {
+            uint4_t v[2][RG];
+            auto issue = [&](int grp, uint4_t(&dst)[RG]) {
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
                     const int st = grp * RG + r;  // step st reads codebook 16 (st / 8) + 8 par + (n + st) mod 8
                     // address bytes: [0] column, [1] code byte st % 4 of its dword, [2] block (M = 32: st / 8), [3] zero
                     const unsigned sel = 0x0c000000u | (unsigned)(M == 16 ? 2 : 2 + st / 8) << 16 | (unsigned)(4 + st % 4) << 8;
                     const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], sel);
-                    dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + addr);
+                    dst[r] = lds_read_b128(addr);
                 }
             };
             issue(0, v[0]);
@@ -806,9 +811,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
-                    const uint4 x = v[grp & 1][r];
-                    const uint4_t xv = {x.x, x.y, x.z, x.w};
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, xv), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, v[grp & 1][r]), acc, 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -1276,15 +1279,15 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
                 // 1. gather-sum of the plane: 8 NB pieces per lane, in groups of 4 reads
                 floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
                 constexpr int NS = 8 * NB, RG = (NB == 2 || G == 8) ? 2 : 4, NG = NS / RG;  // fewer reads in flight where registers are short
-                uint4 v[2][RG];
-                auto issue = [&](int grp, uint4(&dst)[RG]) {
+                uint4_t v[2][RG];
+                auto issue = [&](int grp, uint4_t(&dst)[RG]) {
 #pragma unroll
                     for (int r = 0; r < RG; ++r) {
                         const int st = grp * RG + r;       // level 16 (st / 8) + 8 half + (n + st) mod 8
                         const int idx = pl * NB + st / 8;  // (plane, block) image of 16 KiB
                         const unsigned selb = 0x0c000000u | (unsigned)(2 + idx / 4) << 16 | (unsigned)(4 + st % 4) << 8;
                         const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], selb);
-                        dst[r] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(tab) + (idx % 4) * kPairBlock + addr);
+                        dst[r] = lds_read_b128((unsigned)((idx % 4) * kPairBlock) + addr);
                     }
                 };
                 issue(0, v[0]);
@@ -1294,15 +1297,13 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int r = 0; r < RG; ++r) {
-                        const uint4 x = v[grp & 1][r];
-                        const uint4_t xv = {x.x, x.y, x.z, x.w};
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, xv), acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, v[grp & 1][r]), acc, 0, 0, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 // 2. decoded block of sub-space gk (Eq. def_center), rotated by E = E_hi E_lo
-                const uint4_t elr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + lo_off + (pl / 2) * (kLo * 16));
-                const uint4_t ehr = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(tab) + hi_off + (pl / 2) * (NHR * 16));
+                const uint4_t elr = lds_read_b128(lo_off + (unsigned)((pl / 2) * (kLo * 16)));
+                const uint4_t ehr = lds_read_b128(hi_off + (unsigned)((pl / 2) * (NHR * 16)));
                 const unsigned hxr = ehr[2 * (pl & 1)], hyr = ehr[2 * (pl & 1) + 1], lxr = elr[2 * (pl & 1)], lyr = elr[2 * (pl & 1) + 1];
                 const float hx = __builtin_bit_cast(float, hxr), hy = __builtin_bit_cast(float, hyr);
                 const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
