@@ -205,29 +205,24 @@ def em_centres(phi):
     return np.stack([cx.reshape(-1), cy.reshape(-1)], axis=1)
 
 
-def em_step(data, phi, temperature=None):
-    """One iteration of the EM-like codebook learner for ONE 2-D sub-space (Sec. 4.2 Alg. 1, App. A.2).
-
-    data [N][2]: calibration points; phi [Nc][2]: current (x_l, y_l).  E step: soft assignment
-    W_ij = softmax_j(-D_ij / T) over the Nc^2 centres, D the Euclidean distance (Eq. W); temperature None
-    means hard assignment to the nearest centre.  M step: the closed form
-    phi* = (T^T S T)^-1 T^T S m with the constant matrix T of App. A.2 written out entry by entry,
-    S = diag of the assigned weight of every centre (twice: one entry per coordinate) and m the weighted
-    mean of the points assigned to it.  Returns (phi_new [Nc][2], weighted squared error before the update).
-    """
-    data = _f64(data)
-    phi = _f64(phi)
-    Nc = phi.shape[0]
-    cen = em_centres(phi)
-    D = np.sqrt(((data[:, None, :] - cen[None, :, :]) ** 2).sum(axis=2))        # [N][Nc^2]
+def _em_assign(D, temperature):
+    """Assignment weights of Eq. W from a distance matrix D [N][centres]: softmax(-D / T) per point, or the
+    indicator of the nearest centre when temperature is None (Algorithm 1's E step as printed)."""
     if temperature is None:
         W = np.zeros_like(D)
-        W[np.arange(len(data)), np.argmin(D, axis=1)] = 1.0
-    else:
-        Z = -D / float(temperature)
-        Z -= Z.max(axis=1, keepdims=True)
-        W = np.exp(Z)
-        W /= W.sum(axis=1, keepdims=True)
+        W[np.arange(D.shape[0]), np.argmin(D, axis=1)] = 1.0
+        return W
+    Z = -D / float(temperature)
+    Z -= Z.max(axis=1, keepdims=True)
+    W = np.exp(Z)
+    W /= W.sum(axis=1, keepdims=True)
+    return W
+
+
+def _em_mstep(W, data, Nc):
+    """M step of App. A.2 for one 2-D sub-space: phi* = (T^T S T)^-1 T^T S m with the constant matrix T written
+    out entry by entry, S = diag of every centre's assigned weight (one entry per coordinate), m the weighted
+    mean of the points assigned to it.  W [N][Nc^2], data [N][2]; returns phi [Nc][2]."""
     Nij = W.sum(axis=0)                                                          # weight of every centre
     sums = W.T @ data                                                            # [Nc^2][2]
     mean = np.where(Nij[:, None] > 0, sums / np.maximum(Nij[:, None], 1e-300), 0.0)
@@ -245,6 +240,44 @@ def em_step(data, phi, temperature=None):
     m = mean.reshape(-1)
     A = Tm.T @ (S[:, None] * Tm)
     rhs = Tm.T @ (S * m)
-    sol = np.linalg.solve(A, rhs)
-    err = float((W * D ** 2).sum())
-    return sol.reshape(Nc, 2), err
+    return np.linalg.solve(A, rhs).reshape(Nc, 2)
+
+
+def em_step_shared(data, phi, temperature=None):
+    """One EM iteration when a group of g sub-spaces shares its quantized value (Sec. 4.2: s^0 = ... = s^{g-1};
+    g = 64 = the whole head in the paper's configurations).
+
+    data [N][g][2]: the calibration vectors, cut into their g sub-vectors; phi [g][Nc][2]: every sub-space's
+    (x_l, y_l).  A clustering centre is the pair (a, b) applied in all g sub-spaces at once, so the E step
+    measures the distance of the whole vector to the whole centre, D_i,ab = sqrt(sum_j ||k_i^j - c_ab^j||^2),
+    and gives one weight matrix W (Eq. W) for the group; the M step is App. A.2's closed form in every
+    sub-space with that common W.  Returns (phi_new [g][Nc][2], weighted squared error before the update).
+    """
+    data = _f64(data)
+    phi = _f64(phi)
+    g, Nc = phi.shape[0], phi.shape[1]
+    D2 = np.zeros((data.shape[0], Nc * Nc))
+    for j in range(g):
+        cen = em_centres(phi[j])
+        D2 += ((data[:, j, None, :] - cen[None, :, :]) ** 2).sum(axis=2)
+    D = np.sqrt(D2)
+    W = _em_assign(D, temperature)
+    new = np.stack([_em_mstep(W, data[:, j, :], Nc) for j in range(g)])
+    return new, float((W * D2).sum())
+
+
+def em_step(data, phi, temperature=None):
+    """One iteration of the EM-like codebook learner for ONE 2-D sub-space (Sec. 4.2 Alg. 1, App. A.2).
+
+    data [N][2]: calibration points; phi [Nc][2]: current (x_l, y_l).  E step: soft assignment
+    W_ij = softmax_j(-D_ij / T) over the Nc^2 centres, D the Euclidean distance (Eq. W); temperature None
+    means hard assignment to the nearest centre.  M step: the closed form phi* = (T^T S T)^-1 T^T S m
+    (_em_mstep).  Returns (phi_new [Nc][2], weighted squared error before the update).
+    """
+    data = _f64(data)
+    phi = _f64(phi)
+    Nc = phi.shape[0]
+    cen = em_centres(phi)
+    D = np.sqrt(((data[:, None, :] - cen[None, :, :]) ** 2).sum(axis=2))        # [N][Nc^2]
+    W = _em_assign(D, temperature)
+    return _em_mstep(W, data, Nc), float((W * D ** 2).sum())

@@ -537,3 +537,67 @@ def test_em_fixed_point_on_noiseless_data(oracle):
     data = np.repeat(oracle.em_centres(phi), 5, axis=0)
     out, err = oracle.em_step(data, phi, temperature=None)
     assert np.abs(out - phi).max() < 1e-12 and err < 1e-24
+
+
+# ---------------------------------------------------------------- EM with one code shared by a group of sub-spaces
+def test_em_shared_group_of_one_is_algorithm_1(oracle):
+    rng = np.random.default_rng(5)
+    data = rng.standard_normal((120, 2))
+    phi = rng.standard_normal((4, 2)) * 0.6
+    for T in (None, 0.3):
+        a, ea = oracle.em_step(data, phi, temperature=T)
+        b, eb = oracle.em_step_shared(data[:, None, :], phi[None], temperature=T)
+        assert np.abs(a - b[0]).max() < 1e-13 and abs(ea - eb) < 1e-10
+
+
+def test_em_shared_identical_sub_spaces_rescale_the_temperature(oracle):
+    # g copies of one sub-space: the whole-vector distance is sqrt(g) times the 2-D one, so the shared step is
+    # Algorithm 1 in that sub-space at temperature T / sqrt(g)
+    rng = np.random.default_rng(6)
+    g, T = 5, 0.7
+    data = rng.standard_normal((150, 2))
+    phi = rng.standard_normal((3, 2)) * 0.5
+    one, err1 = oracle.em_step(data, phi, temperature=T / np.sqrt(g))
+    grp, errg = oracle.em_step_shared(np.repeat(data[:, None, :], g, axis=1), np.repeat(phi[None], g, axis=0), temperature=T)
+    assert np.abs(grp - one[None]).max() < 1e-12 and abs(errg - g * err1) < 1e-9 * errg
+
+
+def test_em_shared_m_step_minimises_the_whole_vector_objective(oracle):
+    # with W fixed, phi* of every sub-space must minimise sum_i,ab W_i,ab ||k_i - c_ab||^2 over the whole
+    # vector (the sum of the per-sub-space objectives): finite differences, objective written out independently
+    rng = np.random.default_rng(7)
+    g, Nc, T = 3, 3, 0.9
+    data = rng.standard_normal((200, g, 2))
+    phi0 = rng.standard_normal((g, Nc, 2)) * 0.5
+    phi1, err0 = oracle.em_step_shared(data, phi0, temperature=T)
+    cen0 = np.stack([oracle.em_centres(phi0[j]) for j in range(g)], axis=1)         # [Nc^2][g][2]
+    D = np.sqrt(((data[:, None] - cen0[None]) ** 2).sum(axis=(2, 3)))
+    Z = np.exp(-(D - D.min(axis=1, keepdims=True)) / T)
+    W = Z / Z.sum(axis=1, keepdims=True)
+
+    def objective(phi):
+        c = np.stack([oracle.em_centres(phi[j]) for j in range(g)], axis=1)
+        return (W * ((data[:, None] - c[None]) ** 2).sum(axis=(2, 3))).sum()
+
+    assert abs(objective(phi0) - err0) < 1e-9 * err0
+    f1 = objective(phi1)
+    assert f1 <= err0
+    for k in range(phi1.size):
+        for eps in (1e-4, -1e-4):
+            p = phi1.copy().reshape(-1)
+            p[k] += eps
+            assert objective(p.reshape(phi1.shape)) >= f1 - 1e-12
+
+
+def test_em_shared_hard_assignment_is_the_paired_encoder_choice(oracle):
+    # the E step with a shared code picks, for every vector, the pair (a, b) that the key encoder picks for one
+    # level of the tied table C[a] + i C[b]: noiseless vectors reproduce the codebook
+    rng = np.random.default_rng(8)
+    g, Nc = 4, 3
+    phi = rng.standard_normal((g, Nc, 2))
+    cen = np.stack([oracle.em_centres(phi[j]) for j in range(g)], axis=1)           # [Nc^2][g][2]
+    out, err = oracle.em_step_shared(np.repeat(cen, 3, axis=0), phi, temperature=None)
+    assert np.abs(out - phi).max() < 1e-12 and err < 1e-24
+    table = phi.transpose(1, 0, 2).reshape(1, Nc, 2 * g)                            # one level [Nc][d] of rows C[a]
+    codes, _, _ = oracle.encode_keys(cen.reshape(Nc * Nc, 2 * g), table, paired=True)
+    assert np.array_equal(codes[:, 0, 0] * Nc + codes[:, 0, 1], np.arange(Nc * Nc))
