@@ -45,6 +45,8 @@ def parse():
                     help="encode: time the key encoder (cache append) on --encode-tokens new tokens instead; "
                          "em: time one iteration of the EM codebook learner (64 sub-spaces, --em-points points each)")
     ap.add_argument("--em-points", type=int, default=8192)
+    ap.add_argument("--em-shared", action="store_true",
+                    help="with --what em: the 64 sub-spaces share one code per vector (the learner of the paired key table)")
     ap.add_argument("--encode-tokens", type=int, default=4096)
     return ap.parse_args()
 
@@ -104,6 +106,61 @@ def bench_em(args):
         result["cpu_baseline"] = {"value": round(m / 64 / (c1 - c0), 1), "unit": "points/s per head", "cores": 1,
                                   "kind": "oracle", "sample": f"one sub-space, {m} points, {c1 - c0:.1f} s wall "
                                                               "(a head has 64 sub-spaces)"}
+    print(json.dumps(result))
+
+
+def bench_em_shared(args):
+    """One step = one EM iteration for a head whose 64 sub-spaces share one code per vector, N_c' = 64."""
+    import numpy as np
+    import torch
+
+    from paper_2506_18879_amd import binding as B
+    from paper_2506_18879_amd import synth
+
+    torch.cuda.set_device(0)
+    J, N, Nc, T = 64, args.em_points, 64, 2.0
+    rng = np.random.default_rng(synth.BASE_SEED)
+    data = rng.standard_normal((N, J, 2)).astype(np.float32)
+    phi0 = (rng.standard_normal((J, Nc, 2)) * 0.5).astype(np.float32)
+    d = torch.from_numpy(data).cuda()
+    nb = B.commvq_em_shared_workspace_bytes(J, N, Nc)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    sp = int(torch.cuda.current_stream().cuda_stream)
+    p = torch.from_numpy(phi0).cuda()
+    for _ in range(args.warmup):
+        p.copy_(torch.from_numpy(phi0))
+        B.commvq_em_step_shared(d, J, N, Nc, T, p, ws, nb, sp)
+    p.copy_(torch.from_numpy(phi0))
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        B.commvq_em_step_shared(d, J, N, Nc, T, p, ws, nb, sp)   # successive iterations of the same run
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    # per point: 2 x Nc dot products of length 2J, then four sweeps over the Nc^2 centres (4 adds + sqrt, and exp in three)
+    flop = N * (2 * Nc * 2 * 2 * J + Nc * Nc * (4 * 6 + 3 * 3))
+    tf = flop / (kernel_ms * 1e-3) / 1e12
+    result = {"metric": "EM codebook learner, one code per vector: calibration vectors/sec per head (one iteration)",
+              "value": round(N / (ms * 1e-3), 1), "unit": "vectors/s per head", "n_gpus": 1, "steps": args.steps,
+              "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "config": {"workload": f"em_shared_group64_{N}_vectors_64_levels", "centres": Nc * Nc, "temperature": T},
+              "roofline": {"kernel": "k_ems_assign", "bound": "alu", "achieved": round(tf, 3), "peak": FP32_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": round(tf / FP32_PEAK_TFLOPS, 4), "traffic": None,
+                           "kernel_ms": round(kernel_ms, 5)}}
+    if not args.no_cpu_baseline:
+        import oracle
+        m = min(N, 512)
+        c0 = time.perf_counter()
+        oracle.em_step_shared(data[:m], phi0, temperature=T)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": round(m / (c1 - c0), 1), "unit": "vectors/s per head", "cores": 1,
+                                  "kind": "oracle", "sample": f"{m} vectors, {c1 - c0:.1f} s wall"}
     print(json.dumps(result))
 
 
@@ -197,7 +254,7 @@ def main():
     if args.what == "encode":
         return bench_encode(args)
     if args.what == "em":
-        return bench_em(args)
+        return bench_em_shared(args) if args.em_shared else bench_em(args)
     import numpy as np
     import torch
 

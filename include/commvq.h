@@ -205,6 +205,24 @@ commvq_status commvq_em_step(const float *data, int32_t n_subspaces, int32_t n_p
                              float temperature, float *phi, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same iteration when a group of sub-spaces shares its quantized value (Sec. 4.2: s^0 = ... = s^{g-1};
+ * g = 64, the whole head, in the paper's configurations), i.e. the learner of the tied table that the paired
+ * key format stores.  A clustering centre is the pair (a, b) applied in all `group` sub-spaces at once: the E step
+ * weighs whole vectors, W_i,ab = softmax_ab(-D_i,ab / T) with D_i,ab = sqrt(sum_j ||k_i^j - c_ab^j||^2), and the
+ * M step is App. A.2's closed form in every sub-space with that common W (one matrix T^T S T, `group`
+ * right-hand sides).  Residual levels are learned one after the other by the caller, on the residuals.
+ *   data         device [n_points][group][2] fp32: the calibration vectors (d = 2 * group values each)
+ *   phi          device [group][n_centres][2] fp32, in/out
+ *   group        1..64;  n_centres 1..64;  n_points 1..2^24
+ * Results do not depend on the launch shape (all sums run in a fixed order).  A first or second index whose
+ * total weight underflows to zero makes the system singular (as in the paper's closed form): keep T large
+ * enough for every index to keep weight.  Status codes as commvq_em_step.
+ */
+commvq_status commvq_em_shared_workspace_bytes(int32_t group, int32_t n_points, int32_t n_centres, size_t *bytes);
+commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_points, int32_t n_centres,
+                                    float temperature, float *phi, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The three stages of commvq_decode_attn, callable on their own (tests and profiling).
  * They read/write the same workspace; run them in this order on one stream.
  *   commvq_stage_scores  Eq. new_attention: scaled logits for every (b, h, token) and the

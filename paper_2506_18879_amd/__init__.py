@@ -18,7 +18,9 @@ from .binding import (  # noqa: F401
     commvq_create,
     commvq_decode_attn,
     commvq_destroy,
+    commvq_em_shared_workspace_bytes,
     commvq_em_step,
+    commvq_em_step_shared,
     commvq_em_workspace_bytes,
     commvq_encode_keys,
     commvq_encoder_prepare,

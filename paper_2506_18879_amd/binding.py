@@ -41,7 +41,7 @@ EXPORTS = ("commvq_create", "commvq_destroy", "commvq_validate_config", "commvq_
            "commvq_decode_attn", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
            "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
            "commvq_encoder_table_bytes", "commvq_encoder_prepare", "commvq_encode_keys",
-           "commvq_em_workspace_bytes", "commvq_em_step",
+           "commvq_em_workspace_bytes", "commvq_em_step", "commvq_em_shared_workspace_bytes", "commvq_em_step_shared",
            "commvq_profile_enable", "commvq_profile_read", "commvq_status_string")
 
 
@@ -78,6 +78,8 @@ def load_library():
     lib.commvq_encode_keys.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p]
     lib.commvq_em_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, POINTER(c_size_t)]
     lib.commvq_em_step.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.commvq_em_shared_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, POINTER(c_size_t)]
+    lib.commvq_em_step_shared.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.commvq_profile_enable.argtypes = [c_void_p, c_int32]
     lib.commvq_profile_read.argtypes = [c_void_p, POINTER(c_float), POINTER(c_int32)]
     for name in EXPORTS:
@@ -189,6 +191,20 @@ def commvq_em_step(data, n_subspaces: int, n_points: int, n_centres: int, temper
     _check(load_library().commvq_em_step(_ptr(data), int(n_subspaces), int(n_points), int(n_centres), float(temperature),
                                          _ptr(phi), _ptr(workspace), int(workspace_bytes), stream or None),
            "commvq_em_step")
+
+
+def commvq_em_shared_workspace_bytes(group: int, n_points: int, n_centres: int) -> int:
+    n = c_size_t()
+    _check(load_library().commvq_em_shared_workspace_bytes(int(group), int(n_points), int(n_centres), byref(n)),
+           "commvq_em_shared_workspace_bytes")
+    return int(n.value)
+
+
+def commvq_em_step_shared(data, group: int, n_points: int, n_centres: int, temperature: float, phi, workspace,
+                          workspace_bytes: int, stream: int = 0) -> None:
+    _check(load_library().commvq_em_step_shared(_ptr(data), int(group), int(n_points), int(n_centres), float(temperature),
+                                                _ptr(phi), _ptr(workspace), int(workspace_bytes), stream or None),
+           "commvq_em_step_shared")
 
 
 def commvq_stage_scores(handle, q, key_codes, key_codebooks, positions: Positions, workspace, workspace_bytes: int,

@@ -168,6 +168,276 @@ __global__ __launch_bounds__(256) void k_em_solve(const float *__restrict__ nab,
     if (tid < Nc) phi[(size_t)j * Nc + tid] = make_float2(rhs[2 * tid], rhs[2 * tid + 1]);
 }
 
+// ------------------------------------------------------------------ one code shared by a group of sub-spaces
+// Sec. 4.2 groups g consecutive sub-spaces under one quantized value, so a clustering centre is the pair (a, b)
+// applied in all g sub-spaces and the E step weighs whole vectors:  D_i,ab^2 = sum_j ||k_i^j - c_ab^j||^2
+//   = ||k_i||^2 + (N_a - 2 P_i[a]) + (N_b - 2 Q_i[b]) + X_ab,   P_i[a] = k_i . C[a],  Q_i[b] = k_i . (i C[b]),
+//   N_a = ||C[a]||^2,  X_ab = 2 C[a] . (i C[b])     (C[a] = the row (x_a^j, y_a^j)_j; i C = (-y, x) per sub-space)
+// -- the tables of the key encoder.  The M step is App. A.2's closed form in every sub-space with the common W:
+// one matrix T^T S T (it only holds N_ab = sum_i W_i,ab) and one right-hand side per sub-space, which needs
+// only the marginals of W:  rhs_j[x_a] = sum_i k_i^jx Wa_i[a] + k_i^jy Wb_i[a],  rhs_j[y_a] = sum_i k_i^jy Wa_i[a] -
+// k_i^jx Wb_i[a],  Wa_i[a] = sum_b W_i,ab,  Wb_i[a] = sum_b W_i,ba.
+constexpr int kEmsPts = 64;     // points per workgroup of k_ems_assign
+constexpr int kEmsSplits = 16;  // point ranges whose right-hand-side partials are summed in a fixed order
+
+// X_ab and N_a of the current codebook (one thread per (a, b)).
+__global__ __launch_bounds__(256) void k_ems_tables(const float2 *__restrict__ phi, float *__restrict__ xab, float *__restrict__ nn,
+                                                    int J, int Nc)
+{
+    const int ab = blockIdx.x * 256 + threadIdx.x;
+    if (ab >= Nc * Nc) return;
+    const int a = ab / Nc, b = ab % Nc;
+    float x = 0.f, n = 0.f;
+    for (int j = 0; j < J; ++j) {
+        const float2 pa = phi[(size_t)j * Nc + a], pb = phi[(size_t)j * Nc + b];
+        x += pa.y * pb.x - pa.x * pb.y;
+        n += pa.x * pa.x + pa.y * pa.y;
+    }
+    xab[ab] = 2.f * x;
+    if (b == 0) nn[a] = n;
+}
+
+// Workgroup = 64 points.  LDS: the codebook, the points, u = N_a - 2 P[a] and v = N_b - 2 Q[b] per point, X.
+// 1. P, Q by plain FMAs (thread = point x quarter of the rows);  2. per point, four lanes sweep the Nc^2 centres
+// twice: nearest distance, then the softmax denominator;  3. per centre pair, four lanes sweep the 64 points:
+// N_ab partial of the workgroup and the marginal Wa (first index fixed), then again transposed for Wb.
+__global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ data, const float2 *__restrict__ phi,
+                                                    const float *__restrict__ xab_g, const float *__restrict__ nn_g,
+                                                    float *__restrict__ nab_part, float *__restrict__ wa_g, float *__restrict__ wb_g,
+                                                    int N, int J, int Nc, float c)
+{
+    extern __shared__ __attribute__((aligned(16))) float ems_lds[];
+    const int JS = J + 1, NS = Nc + 1;                      // padded strides
+    float2 *ph = reinterpret_cast<float2 *>(ems_lds);       // [J][Nc]
+    float2 *pts = ph + J * Nc;                              // [64][J + 1]
+    float *u = reinterpret_cast<float *>(pts + kEmsPts * JS);  // [64][Nc + 1]
+    float *v = u + kEmsPts * NS;                            // [64][Nc + 1]
+    float *xs = v + kEmsPts * NS;                           // [Nc][Nc]
+    float *kk = xs + Nc * Nc;                               // [64] ||k||^2
+    float *dmin = kk + kEmsPts;                             // [64]
+    float *rz = dmin + kEmsPts;                             // [64] 1 / softmax denominator
+    const int tid = threadIdx.x;
+    const int i0 = blockIdx.x * kEmsPts;
+    const int cnt = min(kEmsPts, N - i0);
+    for (int x = tid; x < J * Nc; x += 256) ph[x] = phi[x];
+    for (int x = tid; x < Nc * Nc; x += 256) xs[x] = xab_g[x];
+    for (int x = tid; x < kEmsPts * J; x += 256) {
+        const int i = x / J, j = x % J;
+        pts[i * JS + j] = i < cnt ? data[(size_t)(i0 + i) * J + j] : make_float2(0.f, 0.f);
+    }
+    __syncthreads();
+    {   // 1. thread = (point i, rows a = ag, ag + 4, ...)
+        const int i = tid & 63, ag = tid >> 6;
+        for (int a = ag; a < Nc; a += 4) {
+            float P = 0.f, Q = 0.f;
+            for (int j = 0; j < J; ++j) {
+                const float2 k = pts[i * JS + j], r = ph[j * Nc + a];
+                P += k.x * r.x + k.y * r.y;
+                Q += k.y * r.x - k.x * r.y;
+            }
+            const float na = nn_g[a];
+            u[i * NS + a] = na - 2.f * P;
+            v[i * NS + a] = na - 2.f * Q;
+        }
+        if (ag == 0) {
+            float s = 0.f;
+            for (int j = 0; j < J; ++j) { const float2 k = pts[i * JS + j]; s += k.x * k.x + k.y * k.y; }
+            kk[i] = s;
+        }
+    }
+    __syncthreads();
+    {   // 2. lane (n, q) of wavefront w: point 16 w + n, first indices a = q, q + 4, ...
+        const int n = tid & 15, q = (tid >> 4) & 3, i = (tid >> 6) * 16 + n;
+        const float ki = kk[i];
+        float d2m = INFINITY;
+        for (int a = q; a < Nc; a += 4) {
+            const float ua = ki + u[i * NS + a];
+            for (int b = 0; b < Nc; ++b) d2m = fminf(d2m, ua + (v[i * NS + b] + xs[a * Nc + b]));
+        }
+        d2m = fminf(d2m, __shfl_xor(d2m, 16));
+        d2m = fminf(d2m, __shfl_xor(d2m, 32));
+        const float dm = __builtin_sqrtf(fmaxf(d2m, 0.f));
+        float z = 0.f;
+        for (int a = q; a < Nc; a += 4) {
+            const float ua = ki + u[i * NS + a];
+            for (int b = 0; b < Nc; ++b) {
+                const float d = __builtin_sqrtf(fmaxf(ua + (v[i * NS + b] + xs[a * Nc + b]), 0.f));
+                z += __builtin_amdgcn_exp2f(-(d - dm) * c);
+            }
+        }
+        z += __shfl_xor(z, 16);
+        z += __shfl_xor(z, 32);
+        if (q == 0) { dmin[i] = dm; rz[i] = 1.f / z; }
+    }
+    __syncthreads();
+    // 3. thread = (first index f = tid / 4, second indices s = tid % 4, + 4, ...); tr = 1: the same with the
+    // roles of the two indices exchanged (marginal over the first index)
+    const int f = tid >> 2, sq = tid & 3;
+    for (int tr = 0; tr < 2; ++tr) {
+        float nacc[kEmMaxNc / 4];
+#pragma unroll
+        for (int e = 0; e < kEmMaxNc / 4; ++e) nacc[e] = 0.f;
+        float *marg = tr == 0 ? wa_g : wb_g;
+        for (int i = 0; i < cnt; ++i) {
+            float w = 0.f;
+            if (f < Nc) {
+                const float base = kk[i] + (tr == 0 ? u[i * NS + f] : v[i * NS + f]);
+                const float dm = dmin[i], r = rz[i];
+#pragma unroll
+                for (int e = 0; e < kEmMaxNc / 4; ++e) {
+                    const int s2 = sq + 4 * e;
+                    if (s2 < Nc) {
+                        const float other = tr == 0 ? v[i * NS + s2] : u[i * NS + s2];
+                        const float x = tr == 0 ? xs[f * Nc + s2] : xs[s2 * Nc + f];
+                        const float d = __builtin_sqrtf(fmaxf(base + (other + x), 0.f));
+                        const float wi = __builtin_amdgcn_exp2f(-(d - dm) * c) * r;
+                        nacc[e] += wi;
+                        w += wi;
+                    }
+                }
+            }
+            w += __shfl_xor(w, 1);
+            w += __shfl_xor(w, 2);
+            if (f < Nc && sq == 0) marg[(size_t)(i0 + i) * Nc + f] = w;
+        }
+        if (tr == 0 && f < Nc) {
+#pragma unroll
+            for (int e = 0; e < kEmMaxNc / 4; ++e) {
+                const int s2 = sq + 4 * e;
+                if (s2 < Nc) nab_part[(size_t)blockIdx.x * Nc * Nc + f * Nc + s2] = nacc[e];
+            }
+        }
+    }
+}
+
+// N_ab = sum of the workgroups' partials, in workgroup order.
+__global__ __launch_bounds__(256) void k_ems_reduce(const float *__restrict__ nab_part, float *__restrict__ nab, int n_wg, int Nc)
+{
+    const int ab = blockIdx.x * 256 + threadIdx.x;
+    if (ab >= Nc * Nc) return;
+    float s = 0.f;
+    for (int w = 0; w < n_wg; ++w) s += nab_part[(size_t)w * Nc * Nc + ab];
+    nab[ab] = s;
+}
+
+// Right-hand sides: workgroup = (sub-space j, range of points), thread = a.
+__global__ __launch_bounds__(kEmMaxNc) void k_ems_rhs(const float2 *__restrict__ data, const float *__restrict__ wa_g,
+                                                     const float *__restrict__ wb_g, float2 *__restrict__ rhs_part, int N, int J, int Nc)
+{
+    const int j = blockIdx.x, sp = blockIdx.y, a = threadIdx.x;
+    const int per = (N + kEmsSplits - 1) / kEmsSplits;
+    const int i0 = sp * per, i1 = min(N, i0 + per);
+    float rx = 0.f, ry = 0.f;
+    if (a < Nc) {
+#pragma unroll 4
+        for (int i = i0; i < i1; ++i) {
+            const float2 k = data[(size_t)i * J + j];
+            const float wa = wa_g[(size_t)i * Nc + a], wb = wb_g[(size_t)i * Nc + a];
+            rx += k.x * wa + k.y * wb;
+            ry += k.y * wa - k.x * wb;
+        }
+        rhs_part[((size_t)sp * J + j) * Nc + a] = make_float2(rx, ry);
+    }
+}
+
+// One workgroup: the common 2Nc x 2Nc matrix, its Cholesky factor, and the J right-hand sides side by side.
+__global__ __launch_bounds__(256) void k_ems_solve(const float *__restrict__ nab, const float2 *__restrict__ rhs_part,
+                                                   float2 *__restrict__ phi, int J, int Nc)
+{
+    extern __shared__ float em_lds[];
+    const int n2 = 2 * Nc, ld = n2 + 1;
+    float *A = em_lds;                 // [n2][n2 + 1]
+    float *R = A + n2 * ld;            // [n2][J]
+    const int tid = threadIdx.x;
+    for (int x = tid; x < n2 * ld; x += 256) A[x] = 0.f;
+    __syncthreads();
+    for (int x = tid; x < Nc * Nc; x += 256) {
+        const int a = x / Nc, b = x % Nc;
+        const float v = nab[b * Nc + a] - nab[a * Nc + b];
+        A[(2 * a) * ld + 2 * b + 1] = v;
+        A[(2 * b + 1) * ld + 2 * a] = v;
+    }
+    for (int x = tid; x < Nc * J; x += 256) {
+        const int a = x / J, j = x % J;
+        float rx = 0.f, ry = 0.f;
+        for (int sp = 0; sp < kEmsSplits; ++sp) {
+            const float2 p = rhs_part[((size_t)sp * J + j) * Nc + a];
+            rx += p.x;
+            ry += p.y;
+        }
+        R[(2 * a) * J + j] = rx;
+        R[(2 * a + 1) * J + j] = ry;
+    }
+    __syncthreads();
+    if (tid < Nc) {
+        float d = 0.f;
+        for (int b = 0; b < Nc; ++b) d += nab[tid * Nc + b] + nab[b * Nc + tid];
+        A[(2 * tid) * ld + 2 * tid] = d;
+        A[(2 * tid + 1) * ld + 2 * tid + 1] = d;
+    }
+    __syncthreads();
+    for (int k = 0; k < n2; ++k) {
+        if (tid == 0) A[k * ld + k] = __builtin_sqrtf(A[k * ld + k]);
+        __syncthreads();
+        const float dk = A[k * ld + k];
+        for (int r = k + 1 + tid; r < n2; r += 256) A[r * ld + k] /= dk;
+        __syncthreads();
+        const int m = n2 - k - 1;
+        for (int x = tid; x < m * m; x += 256) {
+            const int r = k + 1 + x / m, cc = k + 1 + x % m;
+            if (cc <= r) A[r * ld + cc] -= A[r * ld + k] * A[cc * ld + k];
+        }
+        __syncthreads();
+    }
+    // L Z = R, then L^T Phi = Z, all J columns at once
+    for (int k = 0; k < n2; ++k) {
+        const float dk = A[k * ld + k];
+        for (int j = tid; j < J; j += 256) R[k * J + j] /= dk;
+        __syncthreads();
+        const int m = n2 - k - 1;
+        for (int x = tid; x < m * J; x += 256) {
+            const int r = k + 1 + x / J, j = x % J;
+            R[r * J + j] -= A[r * ld + k] * R[k * J + j];
+        }
+        __syncthreads();
+    }
+    for (int k = n2 - 1; k >= 0; --k) {
+        const float dk = A[k * ld + k];
+        for (int j = tid; j < J; j += 256) R[k * J + j] /= dk;
+        __syncthreads();
+        for (int x = tid; x < k * J; x += 256) {
+            const int r = x / J, j = x % J;
+            R[r * J + j] -= A[k * ld + r] * R[k * J + j];
+        }
+        __syncthreads();
+    }
+    for (int x = tid; x < J * Nc; x += 256) {
+        const int j = x / Nc, a = x % Nc;
+        phi[x] = make_float2(R[(2 * a) * J + j], R[(2 * a + 1) * J + j]);
+    }
+}
+
+struct EmsLayout {
+    size_t xab, nn, wa, wb, nab_part, nab, rhs_part, bytes;
+    int n_wg;
+};
+inline EmsLayout ems_layout(int J, int N, int Nc)
+{
+    EmsLayout l;
+    l.n_wg = (N + kEmsPts - 1) / kEmsPts;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += em_align(bytes); return at; };
+    l.xab = take((size_t)Nc * Nc * 4);
+    l.nn = take((size_t)Nc * 4);
+    l.wa = take((size_t)N * Nc * 4);
+    l.wb = take((size_t)N * Nc * 4);
+    l.nab_part = take((size_t)l.n_wg * Nc * Nc * 4);
+    l.nab = take((size_t)Nc * Nc * 4);
+    l.rhs_part = take((size_t)kEmsSplits * J * Nc * 8);
+    l.bytes = off;
+    return l;
+}
+
 }  // namespace
 
 extern "C" {
@@ -216,6 +486,58 @@ commvq_status commvq_em_step(const float *data, int32_t n_subspaces, int32_t n_p
         attr_set = true;
     }
     hipLaunchKernelGGL(k_em_solve, dim3((unsigned)n_subspaces), dim3(256), lds, s, nab, sab, p2, n_centres);
+    return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+}
+
+commvq_status commvq_em_shared_workspace_bytes(int32_t group, int32_t n_points, int32_t n_centres, size_t *bytes)
+{
+    if (!bytes) return COMMVQ_ERR_NULL;
+    if (group < 1 || group > 64 || n_points < 1 || n_points > (1 << 24) || n_centres < 1 || n_centres > kEmMaxNc) return COMMVQ_ERR_SHAPE;
+    *bytes = ems_layout(group, n_points, n_centres).bytes;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_points, int32_t n_centres, float temperature,
+                                    float *phi, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!data || !phi || !workspace) return COMMVQ_ERR_NULL;
+    size_t need = 0;
+    commvq_status st = commvq_em_shared_workspace_bytes(group, n_points, n_centres, &need);
+    if (st != COMMVQ_OK) return st;
+    if (!(temperature > 0.f)) return COMMVQ_ERR_CONFIG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return COMMVQ_ERR_WORKSPACE;
+    const int J = group, N = n_points, Nc = n_centres;
+    const EmsLayout l = ems_layout(J, N, Nc);
+    char *w = static_cast<char *>(workspace);
+    float *xab = reinterpret_cast<float *>(w + l.xab), *nn = reinterpret_cast<float *>(w + l.nn);
+    float *wa = reinterpret_cast<float *>(w + l.wa), *wb = reinterpret_cast<float *>(w + l.wb);
+    float *nab_part = reinterpret_cast<float *>(w + l.nab_part), *nab = reinterpret_cast<float *>(w + l.nab);
+    float2 *rhs_part = reinterpret_cast<float2 *>(w + l.rhs_part);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const float2 *d2 = reinterpret_cast<const float2 *>(data);
+    float2 *p2 = reinterpret_cast<float2 *>(phi);
+    const unsigned cgrid = (unsigned)((Nc * Nc + 255) / 256);
+    hipLaunchKernelGGL(k_ems_tables, dim3(cgrid), dim3(256), 0, s, p2, xab, nn, J, Nc);
+    if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    const int lds_a = (J * Nc * 2 + kEmsPts * (J + 1) * 2 + 2 * kEmsPts * (Nc + 1) + Nc * Nc + 3 * kEmsPts) * 4;
+    const int lds_s = (2 * Nc * (2 * Nc + 1) + 2 * Nc * J) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int max_a = (64 * 64 * 2 + kEmsPts * 65 * 2 + 2 * kEmsPts * 65 + 64 * 64 + 3 * kEmsPts) * 4;
+        const int max_s = (128 * 129 + 128 * 64) * 4;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_assign), hipFuncAttributeMaxDynamicSharedMemorySize, max_a) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_solve), hipFuncAttributeMaxDynamicSharedMemorySize, max_s) != hipSuccess)
+            return COMMVQ_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_ems_assign, dim3((unsigned)l.n_wg), dim3(256), lds_a, s, d2, p2, xab, nn, nab_part, wa, wb, N, J, Nc,
+                       kLog2eEm / temperature);
+    if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_ems_reduce, dim3(cgrid), dim3(256), 0, s, nab_part, nab, l.n_wg, Nc);
+    if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_ems_rhs, dim3((unsigned)J, (unsigned)kEmsSplits), dim3(kEmMaxNc), 0, s, d2, wa, wb, rhs_part, N, J, Nc);
+    if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_ems_solve, dim3(1), dim3(256), lds_s, s, nab, rhs_part, p2, J, Nc);
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
 
