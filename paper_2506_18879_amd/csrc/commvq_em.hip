@@ -100,6 +100,156 @@ __global__ __launch_bounds__(256) void k_em_accum(const float2 *__restrict__ dat
     }
 }
 
+// Blocked Cholesky A = L L^T in place (lower triangle of A [n][ld] in LDS), 256 threads, 16 columns per step:
+// the 16 x 16 diagonal block is factored by the first 16 lanes of wavefront 0, a row per lane, exchanging
+// columns by lane shuffles; then one thread per row below solves its 16 entries; then all threads subtract the
+// panel's outer product from the rest.  Three barriers per 16 columns instead of three per column.
+constexpr int kEmNb = 16;
+template <int NT>
+__device__ __forceinline__ void em_cholesky(float *A, int ld, int n, int tid)
+{
+    for (int k0 = 0; k0 < n; k0 += kEmNb) {
+        const int nb = min(kEmNb, n - k0);
+        if (tid < 64) {
+            float row[kEmNb];
+#pragma unroll
+            for (int c = 0; c < kEmNb; ++c)
+                row[c] = (tid < nb && c <= tid) ? A[(k0 + tid) * ld + k0 + c] : (c == tid ? 1.f : 0.f);  // identity beyond the matrix
+#pragma unroll
+            for (int c = 0; c < kEmNb; ++c) {
+                const float d = __builtin_sqrtf(__shfl(row[c], c));
+                if (tid == c) row[c] = d;
+                else if (tid > c) row[c] /= d;
+#pragma unroll
+                for (int cc = c + 1; cc < kEmNb; ++cc) {
+                    const float l = __shfl(row[c], cc);  // L[cc][c]
+                    if (tid >= cc) row[cc] -= row[c] * l;
+                }
+            }
+            if (tid < nb) {
+#pragma unroll
+                for (int c = 0; c < kEmNb; ++c)
+                    if (c <= tid) A[(k0 + tid) * ld + k0 + c] = row[c];
+            }
+        }
+        __syncthreads();
+        for (int r = k0 + nb + tid; r < n; r += NT) {  // x L_d^T = a for the rows below the block
+            float x[kEmNb];
+#pragma unroll
+            for (int c = 0; c < kEmNb; ++c) {
+                if (c < nb) {
+                    float v = A[r * ld + k0 + c];
+#pragma unroll
+                    for (int e = 0; e < kEmNb; ++e)
+                        if (e < c) v -= x[e] * A[(k0 + c) * ld + k0 + e];
+                    x[c] = v / A[(k0 + c) * ld + k0 + c];
+                    A[r * ld + k0 + c] = x[c];
+                }
+            }
+        }
+        __syncthreads();
+        // rest -= panel panel^T (lower triangle): 32 lanes walk a row's columns, the row's panel entries in registers
+        for (int r = k0 + nb + tid / 32; r < n; r += NT / 32) {
+            float pr[kEmNb];
+#pragma unroll
+            for (int e = 0; e < kEmNb; ++e) pr[e] = e < nb ? A[r * ld + k0 + e] : 0.f;
+            for (int cc = k0 + nb + tid % 32; cc <= r; cc += 32) {
+                float sum = 0.f;
+#pragma unroll
+                for (int e = 0; e < kEmNb; ++e)
+                    if (e < nb) sum += pr[e] * A[cc * ld + k0 + e];
+                A[r * ld + cc] -= sum;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// L Z = R, then L^T X = Z, for the nr columns of R [n][nr] in LDS, blocked like em_cholesky: one thread per
+// column substitutes through a 16 x 16 diagonal block, then all threads update the rows that remain.
+template <int NT>
+__device__ __forceinline__ void em_substitute(const float *A, int ld, int n, float *R, int nr, int tid)
+{
+    for (int k0 = 0; k0 < n; k0 += kEmNb) {
+        const int nb = min(kEmNb, n - k0);
+        for (int j = tid; j < nr; j += NT) {
+            float z[kEmNb];
+#pragma unroll
+            for (int c = 0; c < kEmNb; ++c) {
+                if (c < nb) {
+                    float v = R[(k0 + c) * nr + j];
+#pragma unroll
+                    for (int e = 0; e < kEmNb; ++e)
+                        if (e < c) v -= A[(k0 + c) * ld + k0 + e] * z[e];
+                    z[c] = v / A[(k0 + c) * ld + k0 + c];
+                    R[(k0 + c) * nr + j] = z[c];
+                }
+            }
+        }
+        __syncthreads();
+        // rows below: 64 lanes take the columns (their 16 solved entries in registers), NT / 64 rows at a time;
+        // a single column: one thread per row
+        if (nr == 1) {
+            for (int r = k0 + nb + tid; r < n; r += NT) {
+                float sum = 0.f;
+                for (int e = 0; e < nb; ++e) sum += A[r * ld + k0 + e] * R[k0 + e];
+                R[r] -= sum;
+            }
+        } else
+        for (int j = tid % 64; j < nr; j += 64) {
+            float zz[kEmNb];
+#pragma unroll
+            for (int e = 0; e < kEmNb; ++e) zz[e] = e < nb ? R[(k0 + e) * nr + j] : 0.f;
+            for (int r = k0 + nb + tid / 64; r < n; r += NT / 64) {
+                float sum = 0.f;
+#pragma unroll
+                for (int e = 0; e < kEmNb; ++e)
+                    if (e < nb) sum += A[r * ld + k0 + e] * zz[e];
+                R[r * nr + j] -= sum;
+            }
+        }
+        __syncthreads();
+    }
+    for (int k0 = (n - 1) / kEmNb * kEmNb; k0 >= 0; k0 -= kEmNb) {
+        const int nb = min(kEmNb, n - k0);
+        for (int j = tid; j < nr; j += NT) {
+            float z[kEmNb];
+#pragma unroll
+            for (int c = kEmNb - 1; c >= 0; --c) {
+                if (c < nb) {
+                    float v = R[(k0 + c) * nr + j];
+#pragma unroll
+                    for (int e = kEmNb - 1; e >= 0; --e)
+                        if (e > c && e < nb) v -= A[(k0 + e) * ld + k0 + c] * z[e];
+                    z[c] = v / A[(k0 + c) * ld + k0 + c];
+                    R[(k0 + c) * nr + j] = z[c];
+                }
+            }
+        }
+        __syncthreads();
+        if (nr == 1) {
+            for (int r = tid; r < k0; r += NT) {
+                float sum = 0.f;
+                for (int e = 0; e < nb; ++e) sum += A[(k0 + e) * ld + r] * R[k0 + e];
+                R[r] -= sum;
+            }
+        } else
+        for (int j = tid % 64; j < nr; j += 64) {
+            float zz[kEmNb];
+#pragma unroll
+            for (int e = 0; e < kEmNb; ++e) zz[e] = e < nb ? R[(k0 + e) * nr + j] : 0.f;
+            for (int r = tid / 64; r < k0; r += NT / 64) {
+                float sum = 0.f;
+#pragma unroll
+                for (int e = 0; e < kEmNb; ++e)
+                    if (e < nb) sum += A[(k0 + e) * ld + r] * zz[e];
+                R[r * nr + j] -= sum;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // One workgroup per sub-space: build the 2Nc x 2Nc normal equations, Cholesky, two triangular solves.
 __global__ __launch_bounds__(256) void k_em_solve(const float *__restrict__ nab, const float2 *__restrict__ sab,
                                                   float2 *__restrict__ phi, int Nc)
@@ -136,35 +286,8 @@ __global__ __launch_bounds__(256) void k_em_solve(const float *__restrict__ nab,
         rhs[2 * a + 1] = ry;
     }
     __syncthreads();
-    // right-looking Cholesky A = L L^T in place (lower triangle)
-    for (int k = 0; k < n2; ++k) {
-        if (tid == 0) A[k * ld + k] = __builtin_sqrtf(A[k * ld + k]);
-        __syncthreads();
-        const float dk = A[k * ld + k];
-        for (int r = k + 1 + tid; r < n2; r += 256) A[r * ld + k] /= dk;
-        __syncthreads();
-        const int m = n2 - k - 1;
-        for (int x = tid; x < m * m; x += 256) {
-            const int r = k + 1 + x / m, c = k + 1 + x % m;
-            if (c <= r) A[r * ld + c] -= A[r * ld + k] * A[c * ld + k];
-        }
-        __syncthreads();
-    }
-    // L z = rhs, then L^T phi = z (column-oriented substitutions)
-    for (int k = 0; k < n2; ++k) {
-        const float zk = rhs[k] / A[k * ld + k];
-        __syncthreads();
-        if (tid == 0) rhs[k] = zk;
-        for (int r = k + 1 + tid; r < n2; r += 256) rhs[r] -= A[r * ld + k] * zk;
-        __syncthreads();
-    }
-    for (int k = n2 - 1; k >= 0; --k) {
-        const float pk = rhs[k] / A[k * ld + k];
-        __syncthreads();
-        if (tid == 0) rhs[k] = pk;
-        for (int r = tid; r < k; r += 256) rhs[r] -= A[k * ld + r] * pk;
-        __syncthreads();
-    }
+    em_cholesky<256>(A, ld, n2, tid);
+    em_substitute<256>(A, ld, n2, rhs, 1, tid);
     if (tid < Nc) phi[(size_t)j * Nc + tid] = make_float2(rhs[2 * tid], rhs[2 * tid + 1]);
 }
 
@@ -177,7 +300,7 @@ __global__ __launch_bounds__(256) void k_em_solve(const float *__restrict__ nab,
 // one matrix T^T S T (it only holds N_ab = sum_i W_i,ab) and one right-hand side per sub-space, which needs
 // only the marginals of W:  rhs_j[x_a] = sum_i k_i^jx Wa_i[a] + k_i^jy Wb_i[a],  rhs_j[y_a] = sum_i k_i^jy Wa_i[a] -
 // k_i^jx Wb_i[a],  Wa_i[a] = sum_b W_i,ab,  Wb_i[a] = sum_b W_i,ba.
-constexpr int kEmsPts = 64;     // points per workgroup of k_ems_assign
+constexpr int kEmsPts = 32;     // points per workgroup of k_ems_assign
 constexpr int kEmsSplits = 16;  // point ranges whose right-hand-side partials are summed in a fixed order
 
 // X_ab and N_a of the current codebook (one thread per (a, b)).
@@ -197,9 +320,10 @@ __global__ __launch_bounds__(256) void k_ems_tables(const float2 *__restrict__ p
     if (b == 0) nn[a] = n;
 }
 
-// Workgroup = 64 points.  LDS: the codebook, the points, u = N_a - 2 P[a] and v = N_b - 2 Q[b] per point, X.
-// 1. P, Q by plain FMAs (thread = point x quarter of the rows);  2. per point, four lanes sweep the Nc^2 centres
-// twice: nearest distance, then the softmax denominator;  3. per centre pair, four lanes sweep the 64 points:
+// Workgroup = 32 points.  LDS: the codebook (later overwritten by X), the points, u = N_a - 2 P[a] and
+// v = N_b - 2 Q[b] per point.
+// 1. P, Q by plain FMAs (thread = point x eighth of the rows);  2. per point, eight lanes sweep the Nc^2 centres
+// twice: nearest distance, then the softmax denominator;  3. per centre pair, four lanes sweep the 32 points:
 // N_ab partial of the workgroup and the marginal Wa (first index fixed), then again transposed for Wb.
 __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ data, const float2 *__restrict__ phi,
                                                     const float *__restrict__ xab_g, const float *__restrict__ nn_g,
@@ -208,27 +332,27 @@ __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ d
 {
     extern __shared__ __attribute__((aligned(16))) float ems_lds[];
     const int JS = J + 1, NS = Nc + 1;                      // padded strides
-    float2 *ph = reinterpret_cast<float2 *>(ems_lds);       // [J][Nc]
-    float2 *pts = ph + J * Nc;                              // [64][J + 1]
-    float *u = reinterpret_cast<float *>(pts + kEmsPts * JS);  // [64][Nc + 1]
-    float *v = u + kEmsPts * NS;                            // [64][Nc + 1]
-    float *xs = v + kEmsPts * NS;                           // [Nc][Nc]
-    float *kk = xs + Nc * Nc;                               // [64] ||k||^2
-    float *dmin = kk + kEmsPts;                             // [64]
-    float *rz = dmin + kEmsPts;                             // [64] 1 / softmax denominator
+    const int r0 = (max(J * Nc * 2, Nc * Nc) + 1) & ~1;     // floats (even) of the region that holds phi, then X
+    float2 *ph = reinterpret_cast<float2 *>(ems_lds);       // [J][Nc]      (step 1)
+    float *xs = ems_lds;                                    // [Nc][Nc]     (steps 2 and 3)
+    float2 *pts = reinterpret_cast<float2 *>(ems_lds + r0); // [32][J + 1]
+    float *u = reinterpret_cast<float *>(pts + kEmsPts * JS);  // [32][Nc + 1]
+    float *v = u + kEmsPts * NS;                            // [32][Nc + 1]
+    float *kk = v + kEmsPts * NS;                           // [32] ||k||^2
+    float *dmin = kk + kEmsPts;                             // [32]
+    float *rz = dmin + kEmsPts;                             // [32] 1 / softmax denominator
     const int tid = threadIdx.x;
     const int i0 = blockIdx.x * kEmsPts;
     const int cnt = min(kEmsPts, N - i0);
     for (int x = tid; x < J * Nc; x += 256) ph[x] = phi[x];
-    for (int x = tid; x < Nc * Nc; x += 256) xs[x] = xab_g[x];
     for (int x = tid; x < kEmsPts * J; x += 256) {
         const int i = x / J, j = x % J;
         pts[i * JS + j] = i < cnt ? data[(size_t)(i0 + i) * J + j] : make_float2(0.f, 0.f);
     }
     __syncthreads();
-    {   // 1. thread = (point i, rows a = ag, ag + 4, ...)
-        const int i = tid & 63, ag = tid >> 6;
-        for (int a = ag; a < Nc; a += 4) {
+    {   // 1. thread = (point i, rows a = ag, ag + 8, ...)
+        const int i = tid & (kEmsPts - 1), ag = tid / kEmsPts;
+        for (int a = ag; a < Nc; a += 256 / kEmsPts) {
             float P = 0.f, Q = 0.f;
             for (int j = 0; j < J; ++j) {
                 const float2 k = pts[i * JS + j], r = ph[j * Nc + a];
@@ -245,26 +369,31 @@ __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ d
             kk[i] = s;
         }
     }
+    __syncthreads();  // phi is no longer read: X takes its place
+    for (int x = tid; x < Nc * Nc; x += 256) xs[x] = xab_g[x];
     __syncthreads();
-    {   // 2. lane (n, q) of wavefront w: point 16 w + n, first indices a = q, q + 4, ...
-        const int n = tid & 15, q = (tid >> 4) & 3, i = (tid >> 6) * 16 + n;
+    {   // 2. lane (n, q) of wavefront w: point 8 w + n, first indices a = q, q + 8, ...
+        const int n = tid & 7, q = (tid >> 3) & 7, i = (tid >> 6) * 8 + n;
         const float ki = kk[i];
         float d2m = INFINITY;
-        for (int a = q; a < Nc; a += 4) {
+        for (int a = q; a < Nc; a += 8) {
             const float ua = ki + u[i * NS + a];
             for (int b = 0; b < Nc; ++b) d2m = fminf(d2m, ua + (v[i * NS + b] + xs[a * Nc + b]));
         }
+        d2m = fminf(d2m, __shfl_xor(d2m, 8));
         d2m = fminf(d2m, __shfl_xor(d2m, 16));
         d2m = fminf(d2m, __shfl_xor(d2m, 32));
         const float dm = __builtin_sqrtf(fmaxf(d2m, 0.f));
         float z = 0.f;
-        for (int a = q; a < Nc; a += 4) {
+        for (int a = q; a < Nc; a += 8) {
             const float ua = ki + u[i * NS + a];
+#pragma unroll 4
             for (int b = 0; b < Nc; ++b) {
                 const float d = __builtin_sqrtf(fmaxf(ua + (v[i * NS + b] + xs[a * Nc + b]), 0.f));
                 z += __builtin_amdgcn_exp2f(-(d - dm) * c);
             }
         }
+        z += __shfl_xor(z, 8);
         z += __shfl_xor(z, 16);
         z += __shfl_xor(z, 32);
         if (q == 0) { dmin[i] = dm; rz[i] = 1.f / z; }
@@ -274,22 +403,25 @@ __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ d
     // roles of the two indices exchanged (marginal over the first index)
     const int f = tid >> 2, sq = tid & 3;
     for (int tr = 0; tr < 2; ++tr) {
-        float nacc[kEmMaxNc / 4];
+        float nacc[kEmMaxNc / 4], xr[kEmMaxNc / 4];
 #pragma unroll
-        for (int e = 0; e < kEmMaxNc / 4; ++e) nacc[e] = 0.f;
+        for (int e = 0; e < kEmMaxNc / 4; ++e) {
+            nacc[e] = 0.f;
+            const int s2 = sq + 4 * e;
+            xr[e] = (f < Nc && s2 < Nc) ? (tr == 0 ? xs[f * Nc + s2] : xs[s2 * Nc + f]) : 0.f;
+        }
+        const float *mine = tr == 0 ? u : v, *other = tr == 0 ? v : u;
         float *marg = tr == 0 ? wa_g : wb_g;
         for (int i = 0; i < cnt; ++i) {
             float w = 0.f;
             if (f < Nc) {
-                const float base = kk[i] + (tr == 0 ? u[i * NS + f] : v[i * NS + f]);
+                const float base = kk[i] + mine[i * NS + f];
                 const float dm = dmin[i], r = rz[i];
 #pragma unroll
                 for (int e = 0; e < kEmMaxNc / 4; ++e) {
                     const int s2 = sq + 4 * e;
                     if (s2 < Nc) {
-                        const float other = tr == 0 ? v[i * NS + s2] : u[i * NS + s2];
-                        const float x = tr == 0 ? xs[f * Nc + s2] : xs[s2 * Nc + f];
-                        const float d = __builtin_sqrtf(fmaxf(base + (other + x), 0.f));
+                        const float d = __builtin_sqrtf(fmaxf(base + (other[i * NS + s2] + xr[e]), 0.f));
                         const float wi = __builtin_amdgcn_exp2f(-(d - dm) * c) * r;
                         nacc[e] += wi;
                         w += wi;
@@ -310,14 +442,19 @@ __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ d
     }
 }
 
-// N_ab = sum of the workgroups' partials, in workgroup order.
+// N_ab = sum of the workgroups' partials in a fixed order: 16 lanes per centre pair take every 16th workgroup,
+// then a butterfly over the 16 lanes.
 __global__ __launch_bounds__(256) void k_ems_reduce(const float *__restrict__ nab_part, float *__restrict__ nab, int n_wg, int Nc)
 {
-    const int ab = blockIdx.x * 256 + threadIdx.x;
-    if (ab >= Nc * Nc) return;
+    const int ab = blockIdx.x * 16 + (threadIdx.x >> 4), l = threadIdx.x & 15;
     float s = 0.f;
-    for (int w = 0; w < n_wg; ++w) s += nab_part[(size_t)w * Nc * Nc + ab];
-    nab[ab] = s;
+    if (ab < Nc * Nc)
+        for (int w = l; w < n_wg; w += 16) s += nab_part[(size_t)w * Nc * Nc + ab];
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 4);
+    s += __shfl_xor(s, 8);
+    if (ab < Nc * Nc && l == 0) nab[ab] = s;
 }
 
 // Right-hand sides: workgroup = (sub-space j, range of points), thread = a.
@@ -341,7 +478,8 @@ __global__ __launch_bounds__(kEmMaxNc) void k_ems_rhs(const float2 *__restrict__
 }
 
 // One workgroup: the common 2Nc x 2Nc matrix, its Cholesky factor, and the J right-hand sides side by side.
-__global__ __launch_bounds__(256) void k_ems_solve(const float *__restrict__ nab, const float2 *__restrict__ rhs_part,
+constexpr int kEmsSolveThreads = 1024;
+__global__ __launch_bounds__(kEmsSolveThreads) void k_ems_solve(const float *__restrict__ nab, const float2 *__restrict__ rhs_part,
                                                    float2 *__restrict__ phi, int J, int Nc)
 {
     extern __shared__ float em_lds[];
@@ -349,15 +487,15 @@ __global__ __launch_bounds__(256) void k_ems_solve(const float *__restrict__ nab
     float *A = em_lds;                 // [n2][n2 + 1]
     float *R = A + n2 * ld;            // [n2][J]
     const int tid = threadIdx.x;
-    for (int x = tid; x < n2 * ld; x += 256) A[x] = 0.f;
+    for (int x = tid; x < n2 * ld; x += kEmsSolveThreads) A[x] = 0.f;
     __syncthreads();
-    for (int x = tid; x < Nc * Nc; x += 256) {
+    for (int x = tid; x < Nc * Nc; x += kEmsSolveThreads) {
         const int a = x / Nc, b = x % Nc;
         const float v = nab[b * Nc + a] - nab[a * Nc + b];
         A[(2 * a) * ld + 2 * b + 1] = v;
         A[(2 * b + 1) * ld + 2 * a] = v;
     }
-    for (int x = tid; x < Nc * J; x += 256) {
+    for (int x = tid; x < Nc * J; x += kEmsSolveThreads) {
         const int a = x / J, j = x % J;
         float rx = 0.f, ry = 0.f;
         for (int sp = 0; sp < kEmsSplits; ++sp) {
@@ -376,42 +514,9 @@ __global__ __launch_bounds__(256) void k_ems_solve(const float *__restrict__ nab
         A[(2 * tid + 1) * ld + 2 * tid + 1] = d;
     }
     __syncthreads();
-    for (int k = 0; k < n2; ++k) {
-        if (tid == 0) A[k * ld + k] = __builtin_sqrtf(A[k * ld + k]);
-        __syncthreads();
-        const float dk = A[k * ld + k];
-        for (int r = k + 1 + tid; r < n2; r += 256) A[r * ld + k] /= dk;
-        __syncthreads();
-        const int m = n2 - k - 1;
-        for (int x = tid; x < m * m; x += 256) {
-            const int r = k + 1 + x / m, cc = k + 1 + x % m;
-            if (cc <= r) A[r * ld + cc] -= A[r * ld + k] * A[cc * ld + k];
-        }
-        __syncthreads();
-    }
-    // L Z = R, then L^T Phi = Z, all J columns at once
-    for (int k = 0; k < n2; ++k) {
-        const float dk = A[k * ld + k];
-        for (int j = tid; j < J; j += 256) R[k * J + j] /= dk;
-        __syncthreads();
-        const int m = n2 - k - 1;
-        for (int x = tid; x < m * J; x += 256) {
-            const int r = k + 1 + x / J, j = x % J;
-            R[r * J + j] -= A[r * ld + k] * R[k * J + j];
-        }
-        __syncthreads();
-    }
-    for (int k = n2 - 1; k >= 0; --k) {
-        const float dk = A[k * ld + k];
-        for (int j = tid; j < J; j += 256) R[k * J + j] /= dk;
-        __syncthreads();
-        for (int x = tid; x < k * J; x += 256) {
-            const int r = x / J, j = x % J;
-            R[r * J + j] -= A[k * ld + r] * R[k * J + j];
-        }
-        __syncthreads();
-    }
-    for (int x = tid; x < J * Nc; x += 256) {
+    em_cholesky<kEmsSolveThreads>(A, ld, n2, tid);
+    em_substitute<kEmsSolveThreads>(A, ld, n2, R, J, tid);
+    for (int x = tid; x < J * Nc; x += kEmsSolveThreads) {
         const int j = x / Nc, a = x % Nc;
         phi[x] = make_float2(R[(2 * a) * J + j], R[(2 * a + 1) * J + j]);
     }
@@ -519,11 +624,11 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
     const unsigned cgrid = (unsigned)((Nc * Nc + 255) / 256);
     hipLaunchKernelGGL(k_ems_tables, dim3(cgrid), dim3(256), 0, s, p2, xab, nn, J, Nc);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
-    const int lds_a = (J * Nc * 2 + kEmsPts * (J + 1) * 2 + 2 * kEmsPts * (Nc + 1) + Nc * Nc + 3 * kEmsPts) * 4;
+    const int lds_a = ((((J * Nc * 2 > Nc * Nc ? J * Nc * 2 : Nc * Nc) + 1) & ~1) + kEmsPts * (J + 1) * 2 + 2 * kEmsPts * (Nc + 1) + 3 * kEmsPts) * 4;
     const int lds_s = (2 * Nc * (2 * Nc + 1) + 2 * Nc * J) * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        const int max_a = (64 * 64 * 2 + kEmsPts * 65 * 2 + 2 * kEmsPts * 65 + 64 * 64 + 3 * kEmsPts) * 4;
+        const int max_a = (64 * 64 * 2 + kEmsPts * 65 * 2 + 2 * kEmsPts * 65 + 3 * kEmsPts) * 4;
         const int max_s = (128 * 129 + 128 * 64) * 4;
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_assign), hipFuncAttributeMaxDynamicSharedMemorySize, max_a) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_solve), hipFuncAttributeMaxDynamicSharedMemorySize, max_s) != hipSuccess)
@@ -533,11 +638,11 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
     hipLaunchKernelGGL(k_ems_assign, dim3((unsigned)l.n_wg), dim3(256), lds_a, s, d2, p2, xab, nn, nab_part, wa, wb, N, J, Nc,
                        kLog2eEm / temperature);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(k_ems_reduce, dim3(cgrid), dim3(256), 0, s, nab_part, nab, l.n_wg, Nc);
+    hipLaunchKernelGGL(k_ems_reduce, dim3((unsigned)((Nc * Nc + 15) / 16)), dim3(256), 0, s, nab_part, nab, l.n_wg, Nc);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
     hipLaunchKernelGGL(k_ems_rhs, dim3((unsigned)J, (unsigned)kEmsSplits), dim3(kEmMaxNc), 0, s, d2, wa, wb, rhs_part, N, J, Nc);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(k_ems_solve, dim3(1), dim3(256), lds_s, s, nab, rhs_part, p2, J, Nc);
+    hipLaunchKernelGGL(k_ems_solve, dim3(1), dim3(kEmsSolveThreads), lds_s, s, nab, rhs_part, p2, J, Nc);
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
 
