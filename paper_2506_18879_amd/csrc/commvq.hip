@@ -1400,8 +1400,8 @@ struct EncodeDims {
     long long token_stride, head_stride;
 };
 
-// Index-form keys: one workgroup per (token, KV head), one thread per centre of the level; a row is read once,
-// straight from L2.  Ties go to the lowest index.
+// Index-form keys, fp32 codebooks: one workgroup per (token, KV head), one thread per centre of the level, rows
+// straight from L2.  Ties go to the lowest index.  (bf16 codebooks: k_encode_dma and k_encode_batch below.)
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, const void *__restrict__ cb,
                                                 const float *__restrict__ norms, uint8_t *__restrict__ out, const EncodeDims a)
@@ -1424,24 +1424,8 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
         const size_t level = (size_t)g * a.levels + l;
         const size_t base = level * K * kD;
         float acc = 0.f;
-        if (BF16) {  // a row is 16 pieces of 8 bf16; all loads of the row are issued before the first use
-            const uint4 *row = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(cb) + base + (size_t)tid * kD);
-            uint4 pc[16];
-#pragma unroll
-            for (int x = 0; x < 16; ++x) pc[x] = row[x];
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                const unsigned v[4] = {pc[x].x, pc[x].y, pc[x].z, pc[x].w};
-#pragma unroll
-                for (int y = 0; y < 4; ++y) {
-                    acc = __builtin_fmaf(res[8 * x + 2 * y], bf16_lo(v[y]), acc);
-                    acc = __builtin_fmaf(res[8 * x + 2 * y + 1], bf16_hi(v[y]), acc);
-                }
-            }
-        } else {
 #pragma unroll 16
-            for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
-        }
+        for (int e = 0; e < kD; ++e) acc = __builtin_fmaf(res[e], cb_elem<BF16>(cb, base + (size_t)tid * kD + e), acc);
         const float best = norms[level * K + tid] - 2.f * acc;
         // argmin over the workgroup, lowest index on ties
         const float wm = -wave_max(-best);
@@ -1457,6 +1441,98 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
         if (tid < kD) res[tid] -= cb_elem<BF16>(cb, base + (size_t)c * kD + tid);
         __syncthreads();
     }
+    if (tid < a.levels) out[tok * a.token_stride + (long long)g * a.head_stride + tid] = (uint8_t)chosen[tid];
+}
+
+// Index-form keys, few tokens (a decode step appends one token per sequence): the levels are a dependent chain,
+// so what counts is the latency of one level.  The rows of level l + 1 do not depend on the residual: they travel
+// from memory straight into LDS (global_load_lds_dwordx4: 16 bytes per lane, no register destination) while
+// level l is searched, into the other half of a double buffer; a level then reads its rows -- and the winning
+// row for the residual update -- from LDS instead of waiting for memory twice.  Image of a level: row-major,
+// [256 rows][16 slots] x 16 bytes, with piece x of row t in slot (x + t) mod 16 of its row: a thread then reads its
+// own row without bank conflicts, and one load instruction (64 lanes -> 64 consecutive slots from the slot in
+// M0) still covers four whole rows = 1 KiB of contiguous memory, only permuted within each row: lane (r, col) of
+// the instruction fetches piece (col - t) mod 16 of row t = first row + r.  (One row per lane, the obvious
+// mapping, touches 64 different cache lines per instruction: 2 us per level instead of 0.5.)
+// The loads are issued from inline asm: the compiler
+// then knows nothing of them and makes no LDS access wait for them; the kernel waits itself (s_waitcnt vmcnt(0))
+// at the top of the next level.  No static LDS: the images sit at LDS address 0.
+constexpr int kEdImg = 16 * 256;  // 16-byte pieces of one level's rows
+constexpr int kEdLds = 2 * kEdImg * 16 + kD * 4 + 8 * 4 + 8 * 4 + 32 * 4;
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_byte_addr_uniform)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte_addr_uniform), "v"(gptr) : "memory");
+}
+__global__ __launch_bounds__(256) void k_encode_dma(const void *__restrict__ keys, const uint4 *__restrict__ cb,
+                                                    const float *__restrict__ norms, uint8_t *__restrict__ out, const EncodeDims a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint4 ed_lds[];
+    uint4 *img = ed_lds;                                              // [2][16][256]
+    float *res = reinterpret_cast<float *>(ed_lds + 2 * kEdImg);      // [d]
+    float *wbest = res + kD;                                          // [2][4]
+    int *wcand = reinterpret_cast<int *>(wbest + 8);                  // [2][4]
+    int *chosen = wcand + 8;                                          // [32]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x % a.Hkv;
+    const size_t tok = blockIdx.x / a.Hkv;
+    const uint4 *rows = cb + (size_t)g * a.levels * kK * 16;  // level 0 of this head; a level is kK * 16 pieces on
+    auto dma_level = [&](int l, int buf) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {  // instruction i of the wavefront: rows 64 wave + 4 i .. + 3
+            const int t = wave * 64 + 4 * i + (lane >> 4);
+            const unsigned slot = __builtin_amdgcn_readfirstlane((unsigned)(buf * kEdImg + (wave * 64 + 4 * i) * 16));
+            lds_dma16(rows + ((size_t)l * kK + t) * 16 + ((lane - t) & 15), slot * 16u);
+        }
+    };
+    dma_level(0, 0);
+    if (tid < kD) {
+        const size_t i = (tok * a.Hkv + g) * kD + tid;
+        res[tid] = a.key_bf16 ? __builtin_bit_cast(float, (unsigned)static_cast<const uint16_t *>(keys)[i] << 16)
+                              : static_cast<const float *>(keys)[i];
+    }
+    float nrm = norms[(size_t)g * a.levels * kK + tid];
+    for (int l = 0; l < a.levels; ++l) {
+        const int buf = l & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's rows of level l have landed
+        __syncthreads();                                   // ... and everybody's; the residual is up to date
+        uint4 pc[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) pc[x] = img[buf * kEdImg + tid * 16 + ((x + tid) & 15)];
+        float nrm_next = 0.f;
+        if (l + 1 < a.levels) {
+            // the other image was last read during level l - 1, before the barrier above
+            dma_level(l + 1, buf ^ 1);
+            nrm_next = norms[((size_t)g * a.levels + l + 1) * kK + tid];
+        }
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            const unsigned v[4] = {pc[x].x, pc[x].y, pc[x].z, pc[x].w};
+            const float4 r0 = *reinterpret_cast<const float4 *>(res + 8 * x), r1 = *reinterpret_cast<const float4 *>(res + 8 * x + 4);
+            a0 = __builtin_fmaf(r0.x, bf16_lo(v[0]), a0); a1 = __builtin_fmaf(r0.y, bf16_hi(v[0]), a1);
+            a2 = __builtin_fmaf(r0.z, bf16_lo(v[1]), a2); a3 = __builtin_fmaf(r0.w, bf16_hi(v[1]), a3);
+            a0 = __builtin_fmaf(r1.x, bf16_lo(v[2]), a0); a1 = __builtin_fmaf(r1.y, bf16_hi(v[2]), a1);
+            a2 = __builtin_fmaf(r1.z, bf16_lo(v[3]), a2); a3 = __builtin_fmaf(r1.w, bf16_hi(v[3]), a3);
+        }
+        const float best = nrm - 2.f * ((a0 + a1) + (a2 + a3));
+        // argmin over the workgroup, lowest index on ties
+        const float wm = -wave_max(-best);
+        const unsigned long long hit = __ballot(best == wm);
+        if (lane == 0) { wbest[buf * 4 + wave] = wm; wcand[buf * 4 + wave] = wave * 64 + (int)__builtin_ctzll(hit); }
+        __syncthreads();
+        float m = wbest[buf * 4];
+        int c = wcand[buf * 4];
+        for (int w = 1; w < 4; ++w)
+            if (wbest[buf * 4 + w] < m || (wbest[buf * 4 + w] == m && wcand[buf * 4 + w] < c)) { m = wbest[buf * 4 + w]; c = wcand[buf * 4 + w]; }
+        if (tid == 0) chosen[l] = c;
+        if (tid < kD / 2) {  // dword tid of row c: piece tid / 4
+            const unsigned v = reinterpret_cast<const unsigned *>(img)[(buf * kEdImg + c * 16 + (((tid >> 2) + c) & 15)) * 4 + (tid & 3)];
+            res[2 * tid] -= bf16_lo(v);
+            res[2 * tid + 1] -= bf16_hi(v);
+        }
+        nrm = nrm_next;
+    }
+    __syncthreads();
     if (tid < a.levels) out[tok * a.token_stride + (long long)g * a.head_stride + tid] = (uint8_t)chosen[tid];
 }
 
@@ -1843,21 +1919,25 @@ __global__ __launch_bounds__(256) void k_encode_lds(const void *__restrict__ key
         } else {
             // thread = (row c, a-dot or b-dot, which half of the sub-spaces); the two halves are added in a fixed order
             const int c = tid & 63, second = (tid >> 6) & 1, hj = tid >> 7;
-            float acc = 0.f;
+            float acc0 = 0.f, acc1 = 0.f;  // two chains (even / odd sub-spaces), added in a fixed order
 #pragma unroll 16
-            for (int j = 32 * hj; j < 32 * hj + 32; ++j) {
-                const unsigned v = R[c * kEncRowDw + j];
-                const float x = bf16_lo(v), y = bf16_hi(v);
-                acc = second ? __builtin_fmaf(res[2 * j + 1], x, __builtin_fmaf(-res[2 * j], y, acc))
-                             : __builtin_fmaf(res[2 * j + 1], y, __builtin_fmaf(res[2 * j], x, acc));
+            for (int j = 32 * hj; j < 32 * hj + 32; j += 2) {
+                const unsigned v = R[c * kEncRowDw + j], w = R[c * kEncRowDw + j + 1];
+                const float4 r = *reinterpret_cast<const float4 *>(res + 2 * j);
+                const float x = bf16_lo(v), y = bf16_hi(v), x1 = bf16_lo(w), y1 = bf16_hi(w);
+                acc0 = second ? __builtin_fmaf(r.y, x, __builtin_fmaf(-r.x, y, acc0)) : __builtin_fmaf(r.y, y, __builtin_fmaf(r.x, x, acc0));
+                acc1 = second ? __builtin_fmaf(r.w, x1, __builtin_fmaf(-r.z, y1, acc1)) : __builtin_fmaf(r.w, y1, __builtin_fmaf(r.z, x1, acc1));
             }
-            dots[tid] = acc;
+            dots[tid] = acc0 + acc1;
             __syncthreads();
+            // candidate k * 256 + tid is the pair (a = 4 k + tid / 64, b = tid % 64): b is the thread's own
+            const int cb2 = tid & (K - 1);
+            const float vb = ns[buf * K + cb2] - 2.f * (dots[64 + cb2] + dots[192 + cb2]);
 #pragma unroll
             for (int k = 0; k < K * K / 256; ++k) {
-                const int cc = k * 256 + tid, ca = cc / K, cb2 = cc % K;
-                const float da = dots[ca] + dots[128 + ca], db = dots[64 + cb2] + dots[192 + cb2];
-                const float sc = ns[buf * K + ca] + ns[buf * K + cb2] + xs[buf * CROSS + cc] - 2.f * (da + db);
+                const int cc = k * 256 + tid, ca = cc / K;
+                const float ua = ns[buf * K + ca] - 2.f * (dots[ca] + dots[128 + ca]);
+                const float sc = ua + (vb + xs[buf * CROSS + cc]);
                 if (sc < best) { best = sc; cand = cc; }
             }
         }
@@ -2683,8 +2763,15 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
         const dim3 bgrid((unsigned)((n_tokens + kEbTokens - 1) / kEbTokens * c.n_kv_heads));
         hipLaunchKernelGGL(k_encode_batch, bgrid, dim3(256), kEbLds, s, keys, static_cast<const uint4 *>(key_cb), norms, codes_out, d,
                            n_tokens);
-    } else if (bf16) {
-        hipLaunchKernelGGL(k_encode<true>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);
+    } else if (bf16) {  // few tokens: next level's rows on their way into LDS while this level is searched
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_dma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kEdLds) != hipSuccess)
+                return COMMVQ_ERR_LAUNCH;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(k_encode_dma, grid, dim3(256), kEdLds, s, keys, static_cast<const uint4 *>(key_cb), norms, codes_out, d);
     } else {
         hipLaunchKernelGGL(k_encode<false>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);
     }
