@@ -550,6 +550,8 @@ struct SliceDims {
 // ------------------------------------------------------------------ k_score_mfma
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x16_t __attribute__((ext_vector_type(16)));
+typedef unsigned uint8v_t __attribute__((ext_vector_type(8)));
 
 // 16-byte LDS read at an absolute LDS byte address.  The score kernels keep their dynamic LDS at address 0
 // (no static LDS), but the compiler only learns that after instruction selection: a read through the array's
@@ -630,7 +632,6 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     constexpr int NHR = TILE / kLo + 1;                       // coarse phase rows a tile can touch
     constexpr int NGRP = (G + 3) / 4;                         // groups of 4 heads (padded with zero queries)
     constexpr int NOUT = M == 16 ? 1 : 2;                     // heads per group whose totals a lane keeps
-    constexpr int NS = M / 2;                                 // gather MFMAs per pass and slice
     constexpr int CW = M / 8;                                 // code dwords a lane needs per token
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
     extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces, then the phase factors
@@ -652,7 +653,6 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const int n = lane & 15, gk = lane >> 4;
     const int par = gk & 1;                                   // odd / even codebook of a gather step
     const int set = gk >> 1;                                  // M = 32: which 16-token set the lane gathers for
-    const int plane = M == 16 ? (gk >> 1) : 0;
     const int el = M == 16 ? 4 * gk : 4 * par;                // first of the lane's 4 slice elements
     const int qpos = q_pos[b];
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
@@ -664,12 +664,25 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     constexpr int PIECES = P * M * kK;
     constexpr int PPT = PIECES / kSliceThreads;
 
-    // selection matrix operand: lane (i = n, k-group gk) holds row i, columns 8 gk .. 8 gk + 7:
-    // one-hot at e = i - 8 (gk >> 1) when that lies in 0..7
+    // Selection operand of v_smfmac_f32_16x16x64_bf16 (first operand structured-sparse: two of every four
+    // consecutive k kept, 2-bit positions in an index register).  Its second operand takes two 16-byte pieces per
+    // lane, A (elements 0..7) and B (8..15); measured layout (micro-benchmark smfmac_layouts): logical k =
+    // 32 * (A | B) + 8 * (lane / 16) + element, and first-operand lane (row i, block q) covers k = 16 q .. 16 q + 15
+    // with stored slots 2 t, 2 t + 1 for its t-th group of four.  Rows 0..7 must add element i of the four lanes'
+    // A pieces, rows 8..15 element i - 8 of their B pieces: lane (i, q) is active when (i < 8) == (q < 2) and then
+    // keeps 1.0 at position e % 4 of groups e / 4 and 2 + e / 4 (e = i % 8); every other stored value is 0.0.
     uint4_t sel = {0u, 0u, 0u, 0u};
+    unsigned sidx = 0x44444444u;  // default positions (0, 1) of every stored pair
     {
-        const int e = n - 8 * (gk >> 1);
-        if (e >= 0 && e < 8) sel[e >> 1] = (e & 1) ? 0x3f800000u : 0x00003f80u;
+        const int e = n & 7;
+        if ((n < 8) == (gk < 2)) {
+            const int t = e >> 2, pos = e & 3, other = pos == 0 ? 1 : 0;
+            sel[t] = 0x00003f80u;        // slot 2 t      = 1.0, slot 2 t + 1 = 0.0
+            sel[2 + t] = 0x00003f80u;    // slot 4 + 2 t  = 1.0
+            const unsigned pair = (unsigned)pos | (unsigned)other << 2;
+            sidx = (sidx & ~(0xfu << (4 * t)) & ~(0xfu << (4 * (2 + t)))) | pair << (4 * t) | pair << (4 * (2 + t));
+            sidx = (sidx & 0xffffu) | sidx << 16;
+        }
     }
     const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
     // as first operand of the query contraction the lane supplies head 4 grp + n % 4; rows past the last
@@ -684,35 +697,47 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 #pragma unroll
             for (int o = 0; o < NOUT; ++o) sc[p][x][o] = 0.f;
 
-    // The lane gathers the 8 codebooks 8 par .. 8 par + 7 (M = 32: and 16 more) of its token, in the
-    // rotated order (n + st) mod 8: in every group of lanes that the LDS checks against each other
-    // for bank conflicts the 16 pieces then come from 16 different bank columns, whatever the codes.
-    // xreg[st]: byte 0 = 16 * column read at step st, byte 2 = 64 KiB block of the lane (M = 16: its
-    // plane), byte 3 = 1; a byte permute splices the code in as byte 1, which yields the LDS byte
-    // address 65536 blk + 256 c + 16 col in one instruction.
-    unsigned xreg[8];
+    // What a lane gathers (gk = (hi, par)):
+    //   M = 16: for its own token the 4 codebooks 8 par + (n + 4 hi + st) mod 8, st = 0..3, piece A from plane 0 and
+    //           piece B from plane 1 of each: the four lanes of a token cover its 16 codebooks in 4 instructions;
+    //   M = 32: for tokens n (piece A) and n + 16 (piece B) of the pass the 8 codebooks 16 hi + 8 par + (n + st) mod 8.
+    // In every group of lanes that the LDS checks against each other for bank conflicts the 16 pieces of one read
+    // then come from 16 different bank columns, whatever the codes.  xreg[st]: byte 0 = 16 * column read at step
+    // st, byte 2 = 64 KiB block (M = 16: 0, and byte 3 = 1 for plane 1; M = 32: hi); a byte permute splices the code
+    // in as byte 1, which yields the LDS byte address 65536 blk + 256 c + 16 col in one instruction.
+    const int hi = gk >> 1;
+    constexpr int NST = M == 16 ? 4 : 8;  // gather steps = sparse matrix instructions per pass
+    unsigned xreg[NST];
 #pragma unroll
-    for (int st = 0; st < 8; ++st) xreg[st] = (unsigned)(8 * par + ((n + st) & 7)) * 16u | (unsigned)plane << 16 | 1u << 24;
-    // byte selectors that rotate the lane's 8 code bytes by n mod 8, so that step st finds its code at byte st
+    for (int st = 0; st < NST; ++st)
+        xreg[st] = (unsigned)(8 * par + ((n + st + (M == 16 ? 4 * hi : 0)) & 7)) * 16u | (M == 16 ? 1u << 24 : (unsigned)hi << 16);
+    // byte selectors that rotate 8 code bytes so that step st finds its code at byte st
     unsigned rsel_lo = 0u, rsel_hi = 0u;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-        rsel_lo |= (unsigned)((x + n) & 7) << (8 * x);
+        rsel_lo |= (unsigned)((x + n + (M == 16 ? 4 * hi : 0)) & 7) << (8 * x);
         rsel_hi |= (unsigned)((x + 4 + n) & 7) << (8 * x);
     }
 
     // Codes are fetched one pass ahead (the fetch for pass 0 of the next slice rides on the last
     // pass of this one), so that their latency hides behind a whole pass of gather work.  tb is the
-    // lane's first token; it is re-read through an opaque copy in every slice so that nothing that
-    // depends on a token index (code loads, table offsets) is hoisted out of the slice loop.
+    // lane's first token (the one whose logits it ends up with); it is re-read through an opaque copy in every
+    // slice so that nothing that depends on a token index (code loads, table offsets) is hoisted out of the slice
+    // loop.  M = 32: the lane gathers for tokens tb - 16 set and tb - 16 set + 16.
     int tb = t0 + wave * (16 * SETS) + n + 16 * (M == 16 ? 0 : set);
     unsigned cw[2][CW];
     auto fetch_codes = [&](int p, unsigned(&dst)[CW]) {
-        const int tok = min(tb + p * NW * 16 * SETS, L - 1);
+        if (M == 16) {  // bytes 8 par .. + 7 of the token's codes
+            const int tok = min(tb + p * NW * 16, L - 1);
+            const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * M + 8u * par, 0, 0);
+            dst[0] = c2[0]; dst[1] = c2[1];
+        } else {        // bytes 16 hi + 8 par .. + 7 of both tokens
 #pragma unroll
-        for (int v = 0; v < M / 16; ++v) {  // bytes 16 v + 8 par .. + 7 of the token's codes
-            const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * M + 8u * par + 16u * v, 0, 0);
-            dst[2 * v + 0] = c2[0]; dst[2 * v + 1] = c2[1];
+            for (int v = 0; v < 2; ++v) {
+                const int tok = min(tb - 16 * set + 16 * v + p * NW * 32, L - 1);
+                const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * M + 16u * hi + 8u * par, 0, 0);
+                dst[2 * v + 0] = c2[0]; dst[2 * v + 1] = c2[1];
+            }
         }
     };
     fetch_codes(0, cw[0]);
@@ -783,25 +808,35 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             __builtin_amdgcn_sched_barrier(0);
             fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
-            unsigned cc[CW];
+            // cc[v][h]: rotated code bytes 4 h .. 4 h + 3 of token v (M = 16: one token, steps 0..3 only)
+            unsigned cc[M == 16 ? 1 : 2][M == 16 ? 1 : 2];
+            if (M == 16) {
+                cc[0][0] = __builtin_amdgcn_perm(cw[p & 1][1], cw[p & 1][0], rsel_lo);
+            } else {
 #pragma unroll
-            for (int v = 0; v < M / 16; ++v) {
-                cc[2 * v + 0] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_lo);
-                cc[2 * v + 1] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_hi);
+                for (int v = 0; v < 2; ++v) {
+                    cc[v][0] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_lo);
+                    cc[v][M == 16 ? 0 : 1] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_hi);
+                }
             }
 
-            // 1. gather-sum on the matrix cores; LDS reads in groups of RG, two groups in flight
+            // 1. gather-sum on the matrix cores: per step two LDS reads (pieces A and B) and one sparse MFMA;
+            //    reads in groups of RG steps, two groups in flight
             floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-            constexpr int RG = (G == 8 && TPT == 4) ? 2 : 4, NG = NS / RG;  // fewer reads in flight where registers are short
-            uint4_t v[2][RG];
-            auto issue = [&](int grp, uint4_t(&dst)[RG]) {
+            constexpr int RG = (G == 8 && TPT == 4) ? 1 : 2, NG = NST / RG;  // fewer reads in flight where registers are short
+            uint4_t v[2][RG][2];
+            auto issue = [&](int grp, uint4_t(&dst)[RG][2]) {
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
-                    const int st = grp * RG + r;  // step st reads codebook 16 (st / 8) + 8 par + (n + st) mod 8
-                    // address bytes: [0] column, [1] code byte st % 4 of its dword, [2] block (M = 32: st / 8), [3] zero
-                    const unsigned sel = 0x0c000000u | (unsigned)(M == 16 ? 2 : 2 + st / 8) << 16 | (unsigned)(4 + st % 4) << 8;
-                    const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], sel);
-                    dst[r] = lds_read_b128(addr);
+                    const int st = grp * RG + r;
+#pragma unroll
+                    for (int ab = 0; ab < 2; ++ab) {
+                        // address bytes: [0] column, [1] code byte st % 4 of its dword, [2] block, [3] zero.  M = 16: block =
+                        // plane = ab (xreg bytes 2, 3 hold 0, 1); M = 32: block = hi (xreg byte 2), the code is token ab's
+                        const unsigned sel = 0x0c000000u | (unsigned)(M == 16 ? 2 + ab : 2) << 16 | (unsigned)(4 + st % 4) << 8;
+                        const unsigned addr = __builtin_amdgcn_perm(cc[M == 16 ? 0 : ab][M == 16 ? 0 : st / 4], xreg[st], sel);
+                        dst[r][ab] = lds_read_b128(addr);
+                    }
                 }
             };
             issue(0, v[0]);
@@ -811,7 +846,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, v[grp & 1][r]), acc, 0, 0, 0);
+                    const uint4_t pa = v[grp & 1][r][0], pb = v[grp & 1][r][1];
+                    const uint8v_t both = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
+                    acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(selv, __builtin_bit_cast(bf16x16_t, both), acc, (int)sidx, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
