@@ -350,10 +350,12 @@ def main():
             traffic = None
     key_stream_gbs = w.key_codes.nbytes / score_s / 1e9 if score_s > 0 else 0.0
     # the pipes the kernel actually loads: codeword pieces gathered from LDS, and the matrix instructions that
-    # sum them (one 16x16x32 bf16 MFMA = 16384 flop per 64 pieces of 16 bytes, half of it multiplications by zero)
+    # sum them: 256 issued flop per 16-byte piece (mostly multiplications by zero), as one dense 16x16x32 bf16 MFMA
+    # per 64 pieces (paired keys) or one structured-sparse 16x16x64 per 128 (index form; twice the dense rate)
     gather_bytes = units * w.Mk * w.d * esz
     gather_tbs = gather_bytes / score_s / 1e12 if score_s > 0 else 0.0
     mfma_tflops = (gather_bytes / 16 / 64 * 16384) / score_s / 1e12 if (score_s > 0 and w.dtype == "bf16") else 0.0
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if paired else 2.0 * MFMA_BF16_PEAK_TFLOPS
     roofline = {"kernel": kname, "bound": "alu", "achieved": round(achieved_tflops, 3), "peak": FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved_tflops / FP32_PEAK_TFLOPS, 4), "traffic": traffic,
                 "kernel_ms": round(stage_ms[0], 5), "launches_averaged": n_prof,
@@ -361,8 +363,9 @@ def main():
                                           "k_score_mfma only" if prepacked else "codebook re-layout (k_prep) + score kernel"),
                 "lds_gather_view": {"codeword_bytes_TBs": round(gather_tbs, 2), "peak_TBs": LDS_PEAK_TBS,
                                     "frac": round(gather_tbs / LDS_PEAK_TBS, 4)},
-                "mfma_view": {"issued_bf16_TFLOPs": round(mfma_tflops, 1), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
-                              "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+                "mfma_view": {"issued_bf16_TFLOPs": round(mfma_tflops, 1), "peak_TFLOPs": mfma_peak,
+                              "instruction": "v_mfma_f32_16x16x32_bf16" if paired else "v_smfmac_f32_16x16x64_bf16 (sparse first operand)",
+                              "frac": round(mfma_tflops / mfma_peak, 4)},
                 "hbm_view": {"key_code_stream_GBs": round(key_stream_gbs, 1),
                              "frac_of_hbm_peak": round(key_stream_gbs / HBM_PEAK_GBS, 4)}}
 
