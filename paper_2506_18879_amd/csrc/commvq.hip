@@ -797,14 +797,17 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 }
             }
         }
+        // the passes of a lane are a whole number of coarse rows (64 tokens) apart: one fine phase factor serves
+        // them all, and the coarse row steps down by a constant
+        static_assert((NW * 16 * SETS) % kLo == 0, "pass stride in whole coarse rows");
+        const uint4_t elr = lds_read_b128(elo_base + (unsigned)(dist16 & ((kLo - 1) * 16)));
+        const unsigned ehi_last = ehi_base + (unsigned)(((dist16 >> (kLoBits + 4)) - hmin - (NPASS - 1) * (NW * 16 * SETS / kLo)) * 16);
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure flat
-            // phase factors of the lane's token and part, from LDS (16 consecutive tokens read 16 consecutive
-            // fine rows and at most two coarse rows: no bank conflicts)
-            const int d16 = dist16 - p * (NW * 16 * SETS * 16);
-            const uint4_t elr = lds_read_b128(elo_base + (unsigned)(d16 & ((kLo - 1) * 16)));
-            const uint4_t ehr = lds_read_b128(ehi_base + (unsigned)(((d16 >> (kLoBits + 4)) - hmin) * 16));
+            // coarse phase factor of the lane's token and part, from LDS: a pass is a whole number of coarse rows
+            // further on (16 consecutive tokens read at most two rows: no bank conflicts)
+            const uint4_t ehr = lds_read_b128(ehi_last + (unsigned)((NPASS - 1 - p) * (NW * 16 * SETS / kLo) * 16));
             __builtin_amdgcn_sched_barrier(0);
             fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
