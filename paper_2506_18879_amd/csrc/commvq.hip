@@ -597,15 +597,15 @@ __device__ __forceinline__ float swap32_add(float x, float y)
 // Works on the key codebook repacked by k_prep: slice sl (DS = 256 / M consecutive elements of
 // every codeword) sits in LDS as tab[P][M][K] 16-byte pieces while all tokens of the tile pass by.
 //
-//  1. Gather-sum: v_mfma_f32_16x16x32_bf16 with a constant 0/1 selection matrix as first operand
-//     and 64 gathered pieces as second (lane n + 16 g supplies the 8 elements of its piece as rows
-//     8g .. 8g+7 of column n).  Products with 1.0 are exact, so this is the plain fp32 sum of the
-//     M codeword slices.  Row i of the result is element (i mod 8) of k-groups {0,1} (i < 8) or
-//     {2,3} (i >= 8):
-//       M = 16 (two planes): a pass covers 16 tokens; k-groups = plane x (even | odd codebook);
+//  1. Gather-sum: v_smfmac_f32_16x16x64_bf16 (structured-sparse first operand) with a constant 0/1
+//     selection matrix as first operand and 128 gathered pieces as second: lane n + 16 g supplies two
+//     pieces, A and B, for column n.  Products with 1.0 are exact, so this is the plain fp32 sum of the
+//     M codeword slices.  Rows 0..7 of the result are the elements of the four lanes' A pieces added up,
+//     rows 8..15 those of their B pieces:
+//       M = 16 (two planes): a pass covers 16 tokens; A / B = plane 0 / plane 1 of one codebook;
 //               lane (n, g) receives elements 4g .. 4g+3 of the slice for token n;
-//       M = 32 (one plane):  a pass covers 32 tokens in two sets; k-groups = set x (even | odd
-//               codebook); lane (n, g) receives elements 4 (g & 1) .. +3 for token n + 16 (g >> 1).
+//       M = 32 (one plane):  a pass covers 32 tokens in two sets; A / B = the same codebook for tokens
+//               n and n + 16; lane (n, g) receives elements 4 (g & 1) .. +3 for token n + 16 (g >> 1).
 //  2. Each lane rotates its two (x, y) sub-spaces by the token's relative position (two-level
 //     phase tables) -- the only per-token vector arithmetic left on the vector ALUs.
 //  3. Contraction with the queries: four v_mfma_f32_4x4x1_16b_f32 per group of 4 heads.  In each
@@ -1213,11 +1213,21 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
         make_rsrc(static_cast<const char *>(q) + ((size_t)b * a.Hq + (size_t)g * G) * kD * qesz, (unsigned)G * kD * qesz);
     constexpr int PPT = SLICE / 16 / kSliceThreads;
 
-    // selection matrix operand: row i = n takes, from the k-groups of its type (i >> 1) & 1, element 2 (i >> 2) + (i & 1)
+    // Selection operand of the structured-sparse v_smfmac_f32_16x16x64_bf16 (layout: see k_score_mfma).  Second
+    // operand: two pieces per lane, both from levels of the lane's own type.  Row i = n adds element
+    // e = 2 (i >> 2) + (i & 1) of both pieces of the two lanes of its type (i >> 1) & 1: first-operand lane (i, q)
+    // covers the pieces of second-operand lanes 2 (q & 1), 2 (q & 1) + 1, i.e. of type q & 1 (its first piece for
+    // q < 2, its second for q >= 2), and keeps 1.0 at position e % 4 of groups e / 4 and 2 + e / 4.
     uint4_t sel = {0u, 0u, 0u, 0u};
-    if (type == ((n >> 1) & 1)) {
+    unsigned sidx = 0x44444444u;  // default positions (0, 1) of every stored pair
+    if ((gk & 1) == ((n >> 1) & 1)) {
         const int e = 2 * (n >> 2) + (n & 1);
-        sel[e >> 1] = (e & 1) ? 0x3f800000u : 0x00003f80u;
+        const int t = e >> 2, pos = e & 3, other = pos == 0 ? 1 : 0;
+        sel[t] = 0x00003f80u;
+        sel[2 + t] = 0x00003f80u;
+        const unsigned pair = (unsigned)pos | (unsigned)other << 2;
+        sidx = (sidx & ~(0xfu << (4 * t)) & ~(0xfu << (4 * (2 + t)))) | pair << (4 * t) | pair << (4 * (2 + t));
+        sidx = (sidx & 0xffffu) | sidx << 16;
     }
     const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
 
@@ -1336,8 +1346,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
                     if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int r = 0; r < RG; ++r) {
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(selv, __builtin_bit_cast(bf16x8_t, v[grp & 1][r]), acc, 0, 0, 0);
+                    for (int r = 0; r < RG; r += 2) {
+                        const uint4_t pa = v[grp & 1][r], pb = v[grp & 1][r + 1];
+                        const uint8v_t both = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
+                        acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(selv, __builtin_bit_cast(bf16x16_t, both), acc, (int)sidx, 0, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
