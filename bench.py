@@ -205,7 +205,7 @@ def bench_encode(args):
     # algorithmic work per (token, head, level): the dot products with the level's rows, the candidate scan
     flop = n * w.Hkv * levels * (2 * w.d * (2 * K if paired else K) + (5 * K * K if paired else 2 * K) + 2 * w.d)
     tf = flop / (kernel_ms * 1e-3) / 1e12
-    roof = {"kernel": "k_encode_lds" if paired else "k_encode", "bound": "alu", "achieved": round(tf, 3),
+    roof = {"kernel": "k_encode_lds" if paired else "k_encode_dma", "bound": "alu", "achieved": round(tf, 3),
             "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / FP32_PEAK_TFLOPS, 4), "traffic": None,
             "kernel_ms": round(kernel_ms, 5)}
     if not paired and n >= 64:
