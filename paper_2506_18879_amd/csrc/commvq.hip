@@ -52,6 +52,7 @@ constexpr int kLo = 1 << kLoBits;
 constexpr int kScoreThreads = COMMVQ_SCORE_THREADS;
 constexpr int kBinsThreads = 512;
 constexpr int kOutThreads = 256;
+constexpr int kMaxValueSplits = 256;  // value_splits never exceeds 256 / (batch * KV heads), at least 1
 constexpr int kOutRows = 64;    // codebook rows per k_out workgroup
 constexpr int kProfRing = 64;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -85,7 +86,7 @@ struct Workspace {
     float2 *sstat;    // [B * Hq * score_splits] (max, sum of exp(logit - max)) of each score split
     float *vscale;    // [B * Hq * value_splits] 2^-S: value of one fixed-point unit of that split's bins
     float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over that value split
-    unsigned *bins;   // [B * Hkv * value_splits][G * Mv * K] fixed-point bins
+    unsigned *bins;   // [B * Hkv * value_splits][K][Mv][G] fixed-point bins (codeword-major: see k_bins)
     float *partial;   // [B * Hq * out_chunks][d]
     uint4 *packed;    // key codebook re-laid slice-major for k_score_mfma / k_score_pair
     uint8_t *pair_bytes;  // paired-code keys: one byte per index, [T * Hkv][32 * blocks]
@@ -2072,7 +2073,12 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 
     // For G >= 2 the bins of heads 2p and 2p + 1 share one 64-bit word (low / high half): one 64-bit LDS
     // atomic then serves two heads.  Each half stays below 2^31 (see above), so no carry crosses.
-    unsigned long long *bins2 = reinterpret_cast<unsigned long long *>(bins);  // [G / 2][M][K]
+    // Layout [K codewords][M codebooks][G heads]: the LDS bank of a bin is then fixed by (codebook, head pair)
+    // alone -- (m * G/2 + pair) mod 32 in 8-byte units -- whatever the code, and a wavefront whose lanes
+    // spread over the codebooks and start at different head pairs puts exactly two lanes on every bank pair (the
+    // floor for 64 x 8 bytes on 64 banks), where random codes in a [codebook][codeword] layout pile up ~5 deep.
+    constexpr int NP = G >= 2 ? G / 2 : 1;
+    unsigned long long *bins2 = reinterpret_cast<unsigned long long *>(bins);  // [K][M][G / 2]
     for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0u;
     if (wave < G) {
         const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
@@ -2100,7 +2106,16 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
     constexpr int CW = M / 4;
-    const unsigned rot = lane & (M - 1);
+    // A 64-bit LDS operation is served 32 lanes at a time, so it is within each half of the wavefront that the
+    // (codebook, pair) starting points must fall on 32 different bank pairs: (m * NP + pair) mod 32 distinct.
+    const unsigned rot = NP == 4 ? ((unsigned)(lane & 7) | ((unsigned)(lane >> 5) & 1u) << 3) : (unsigned)lane & (unsigned)(M - 1);
+    const unsigned qsh = NP == 4 ? (unsigned)(lane >> 3) & 3u : (unsigned)(lane >> 4) & (unsigned)(NP - 1);
+    // LDS byte offsets within a (codeword, codebook) row of NP 64-bit bins: the pair the lane updates at step hp
+    typedef __attribute__((address_space(3))) unsigned long long *lds_u64_ptr;
+    const unsigned bins_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned *)bins;
+    unsigned qoff[NP];
+#pragma unroll
+    for (int hp = 0; hp < NP; ++hp) qoff[hp] = bins_base + ((((unsigned)hp + qsh) & (unsigned)(NP - 1)) << 3);
     for (int i = v0 + tid; i < v1; i += kBinsThreads) {
         unsigned cw[M / 4];
         const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)i * M);
@@ -2114,9 +2129,10 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         for (int hh = 0; hh < G; ++hh)
             p[hh] = (unsigned)(__builtin_amdgcn_exp2f(srow[(size_t)hh * L + i] * kLog2e + eoff[hh]) + 0.5f);
         // Lane l walks the codebooks in the order (l + k) % M, so that at every step the 64
-        // lanes spread over all M codebooks: skewed code usage (one codeword taking ~20 % of the
-        // tokens) would otherwise put a dozen lanes on the same LDS address in one instruction.
-        // The code vector is rotated by `rot` bytes once per token (dword selects + alignbyte).
+        // lanes spread over all M codebooks (bank columns, see above; skewed code usage would otherwise also
+        // put a dozen lanes on the same LDS address in one instruction), and the head pairs in the order
+        // (l / 16 + hp) % (G / 2).  The code vector is rotated by `rot` bytes once per token (dword selects +
+        // alignbyte).
 #pragma unroll
         for (int st = 1; st < CW; st <<= 1) {
             unsigned t[CW];
@@ -2128,31 +2144,39 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         unsigned rv[CW];
 #pragma unroll
         for (int j = 0; j < CW; ++j) rv[j] = __builtin_amdgcn_alignbyte(cw[(j + 1) % CW], cw[j], rot & 3u);
+        // the lane's head pairs, rotated so that entry hp is pair (hp + lane / 16) % NP
+        unsigned long long pp[NP];
+        if (G >= 2) {
+#pragma unroll
+            for (int hp = 0; hp < NP; ++hp) pp[hp] = (unsigned long long)p[(2 * hp) % G] | (unsigned long long)p[(2 * hp + 1) % G] << 32;
+#pragma unroll
+            for (int st = 1; st < NP; st <<= 1) {
+                unsigned long long t[NP];
+#pragma unroll
+                for (int hp = 0; hp < NP; ++hp) t[hp] = (qsh & st) ? pp[(hp + st) % NP] : pp[hp];
+#pragma unroll
+                for (int hp = 0; hp < NP; ++hp) pp[hp] = t[hp];
+            }
+        }
 #pragma unroll
         for (int k = 0; k < M; ++k) {
             const unsigned c = (rv[k / 4] >> (8 * (k % 4))) & 0xffu;
-            const unsigned idx = ((((unsigned)k << 8) + (rot << 8)) & ((unsigned)(M - 1) << 8)) | c;  // m * K + c
+            const unsigned m = ((unsigned)k + rot) & (unsigned)(M - 1);
+            const unsigned cm = c * M + m;
             if (G == 1) {
-                atomicAdd(&bins[idx], p[0]);
+                atomicAdd(&bins[cm], p[0]);
             } else {
+                const unsigned row = cm * (unsigned)(NP * 8);
 #pragma unroll
-                for (int hp = 0; hp < G / 2; ++hp)
-                    atomicAdd(&bins2[hp * M * kK + idx], (unsigned long long)p[2 * hp] | (unsigned long long)p[2 * hp + 1] << 32);
+                for (int hp = 0; hp < NP; ++hp)
+                    __hip_atomic_fetch_add(reinterpret_cast<lds_u64_ptr>(row + qoff[hp]), pp[hp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
     __syncthreads();
-    unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB;  // [G][M][K] whatever the LDS packing
-    if (G == 1) {
-        for (int x = tid; x < NB; x += kBinsThreads) dst[x] = bins[x];
-    } else {
-        for (int x = tid; x < NB / 2; x += kBinsThreads) {
-            const unsigned long long v = bins2[x];
-            const int hp = x / (M * kK), i = x % (M * kK);
-            dst[(2 * hp) * M * kK + i] = (unsigned)v;
-            dst[(2 * hp + 1) * M * kK + i] = (unsigned)(v >> 32);
-        }
-    }
+    // the LDS image is the memory layout: [K][M][G] 32-bit bins (a pair's two halves are heads 2p, 2p + 1)
+    uint4 *dst = reinterpret_cast<uint4 *>(a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB);
+    for (int x = tid; x < NB / 4; x += kBinsThreads) dst[x] = reinterpret_cast<const uint4 *>(bins)[x];
 }
 
 // ------------------------------------------------------------------ k_out
@@ -2173,6 +2197,8 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
 {
     __shared__ float wsum[G][kOutRows];
     __shared__ float red[kOutThreads / 64][G][kD];
+    __shared__ float scl[G][kMaxValueSplits];                       // value of one fixed-point unit, per head and split
+    __shared__ float part[kOutThreads / kOutRows][kOutRows][G];     // sums over every fourth split
     int id = blockIdx.x;
     const int chunk = id % a.nchunk;
     id /= a.nchunk;
@@ -2183,27 +2209,65 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
     const int MK = a.Mv * kK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+    // bins: [split][K][Mv][G]; the chunk's 64 rows are kOutRows / Mv consecutive codewords of every codebook, one
+    // contiguous run of 64 * G bins per split; local row r = (codeword - first) * Mv + codebook.  A thread reads
+    // the G bins of its row with one vector load and takes every fourth split.
+    for (int x = tid; x < G * nvs; x += kOutThreads)
+        scl[x / nvs][x % nvs] = a.vscale[((size_t)b * a.Hq + (size_t)g * G + x / nvs) * a.nvsplit + x % nvs];
+    __syncthreads();
+    {
+        constexpr int NSG = kOutThreads / kOutRows;
+        const int r = tid % kOutRows, sg = tid / kOutRows;
+        const unsigned *src = a.bins + (size_t)(b * a.Hkv + g) * a.nvsplit * G * MK + (size_t)(chunk * kOutRows + r) * G;
+        float s[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) s[hh] = 0.f;
+#pragma unroll 4
+        for (int v = sg; v < nvs; v += NSG) {
+            unsigned bv[G];
+            const unsigned *pv = src + (size_t)v * G * MK;
+            if (G >= 4) {
+#pragma unroll
+                for (int q4 = 0; q4 < G / 4; ++q4) {
+                    const uint4 t4 = reinterpret_cast<const uint4 *>(pv)[q4];
+                    bv[4 * q4 + 0] = t4.x; bv[4 * q4 + 1 < G ? 4 * q4 + 1 : 0] = t4.y; bv[4 * q4 + 2 < G ? 4 * q4 + 2 : 0] = t4.z; bv[4 * q4 + 3 < G ? 4 * q4 + 3 : 0] = t4.w;
+                }
+            } else if (G == 2) {
+                const uint2 t2 = *reinterpret_cast<const uint2 *>(pv);
+                bv[0] = t2.x; bv[G - 1] = t2.y;
+            } else {
+                bv[0] = pv[0];
+            }
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) s[hh] += (float)bv[hh] * scl[hh][v];
+        }
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) part[sg][r][hh] = s[hh];
+    }
+    __syncthreads();
     for (int x = tid; x < G * kOutRows; x += kOutThreads) {
-        const int hh = x / kOutRows, r = x % kOutRows;
-        const unsigned *src = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit * G + hh) * MK + chunk * kOutRows + r;
-        const float *sc = a.vscale + ((size_t)b * a.Hq + (size_t)g * G + hh) * a.nvsplit;
+        const int hh = x % G, r = x / G;
         float s = 0.f;
-#pragma unroll 8
-        for (int v = 0; v < nvs; ++v) s += (float)src[(size_t)v * G * MK] * sc[v];
+#pragma unroll
+        for (int sg = 0; sg < kOutThreads / kOutRows; ++sg) s += part[sg][r][hh];
         wsum[hh][r] = s;
     }
     __syncthreads();
     float2 acc[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) acc[hh] = make_float2(0.f, 0.f);
-    const size_t row0 = (size_t)g * MK + (size_t)chunk * kOutRows;
-    for (int r = wave; r < kOutRows; r += kOutThreads / 64) {
+    // a wavefront takes a quarter of the codebooks and the chunk's codewords of each: runs of consecutive rows
+    const int cpc = kOutRows / a.Mv, mpw = a.Mv / (kOutThreads / 64);  // codewords per chunk, codebooks per wavefront
+    for (int i = 0; i < kOutRows / (kOutThreads / 64); ++i) {
+        const int m = wave * mpw + i / cpc, cl = i % cpc;
+        const int r = cl * a.Mv + m;
+        const size_t row = (size_t)g * MK + (size_t)m * kK + (size_t)chunk * cpc + cl;
         float2 c;
         if (BF16) {
-            const unsigned v = static_cast<const unsigned *>(a.val_cb)[(row0 + r) * kJ + lane];
+            const unsigned v = static_cast<const unsigned *>(a.val_cb)[row * kJ + lane];
             c = make_float2(bf16_lo(v), bf16_hi(v));
         } else {
-            c = static_cast<const float2 *>(a.val_cb)[(row0 + r) * kJ + lane];
+            c = static_cast<const float2 *>(a.val_cb)[row * kJ + lane];
         }
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
