@@ -2080,6 +2080,19 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     constexpr int NP = G >= 2 ? G / 2 : 1;
     unsigned long long *bins2 = reinterpret_cast<unsigned long long *>(bins);  // [K][M][G / 2]
     for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0u;
+    // The token's codes and logits are fetched one iteration ahead (the first before the statistics below), so
+    // that their latency runs under the previous token's atomics.
+    const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
+    const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    uint4 cnext[M / 16];
+    float snext[G];
+#define COMMVQ_BINS_FETCH(i_)                                                                            \
+    do {                                                                                                 \
+        const uint4 *cp_ = reinterpret_cast<const uint4 *>(codes + (size_t)(i_) * M);                    \
+        _Pragma("unroll") for (int v = 0; v < M / 16; ++v) cnext[v] = cp_[v];                            \
+        _Pragma("unroll") for (int hh = 0; hh < G; ++hh) snext[hh] = srow[(size_t)hh * L + (i_)];        \
+    } while (0)
+    if (v0 + tid < v1) COMMVQ_BINS_FETCH(v0 + tid);
     if (wave < G) {
         const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
         const float2 *st = a.sstat + ((size_t)b * a.Hq + (size_t)g * G + wave) * a.nsplit;
@@ -2103,8 +2116,6 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) eoff[hh] = eoff_s[hh];
 
-    const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
-    const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
     constexpr int CW = M / 4;
     // A 64-bit LDS operation is served 32 lanes at a time, so it is within each half of the wavefront that the
     // (codebook, pair) starting points must fall on 32 different bank pairs: (m * NP + pair) mod 32 distinct.
@@ -2118,16 +2129,17 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     for (int hp = 0; hp < NP; ++hp) qoff[hp] = bins_base + ((((unsigned)hp + qsh) & (unsigned)(NP - 1)) << 3);
     for (int i = v0 + tid; i < v1; i += kBinsThreads) {
         unsigned cw[M / 4];
-        const uint4 *cp = reinterpret_cast<const uint4 *>(codes + (size_t)i * M);
 #pragma unroll
         for (int v = 0; v < M / 16; ++v) {
-            const uint4 c4 = cp[v];
+            const uint4 c4 = cnext[v];
             cw[4 * v + 0] = c4.x; cw[4 * v + 1] = c4.y; cw[4 * v + 2] = c4.z; cw[4 * v + 3] = c4.w;
         }
         unsigned p[G];
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
-            p[hh] = (unsigned)(__builtin_amdgcn_exp2f(srow[(size_t)hh * L + i] * kLog2e + eoff[hh]) + 0.5f);
+            p[hh] = (unsigned)(__builtin_amdgcn_exp2f(snext[hh] * kLog2e + eoff[hh]) + 0.5f);
+        if (i + kBinsThreads < v1) COMMVQ_BINS_FETCH(i + kBinsThreads);
+        asm volatile("" ::: "memory");  // keeps the compiler from sinking the fetch below the atomics
         // Lane l walks the codebooks in the order (l + k) % M, so that at every step the 64
         // lanes spread over all M codebooks (bank columns, see above; skewed code usage would otherwise also
         // put a dozen lanes on the same LDS address in one instruction), and the head pairs in the order
@@ -2173,6 +2185,7 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
             }
         }
     }
+#undef COMMVQ_BINS_FETCH
     __syncthreads();
     // the LDS image is the memory layout: [K][M][G] 32-bit bins (a pair's two halves are heads 2p, 2p + 1)
     uint4 *dst = reinterpret_cast<uint4 *>(a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB);

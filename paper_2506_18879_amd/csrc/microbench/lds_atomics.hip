@@ -23,6 +23,14 @@ __global__ __launch_bounds__(512) void k(const unsigned* __restrict__ idx, float
       else if (MODE == 4) p += bins[ad];                                        // plain load
       else if (MODE == 5) { ad = (ad & ~63u) | (threadIdx.x & 63); atomicAdd(&bins[ad], p); } // conflict-free f32
       else if (MODE == 6) { ad = (u * 64 + it) & (NB - 1); atomicAdd(&bins[ad], p); } // all lanes same address
+      else if (MODE >= 7) {  // ds_add_u64, random 256-byte row, the lane's bank pair (8-byte column) by pattern
+        const unsigned l = threadIdx.x & 63;
+        const unsigned bp = MODE == 7 ? l & 31                              // halves of the wavefront conflict-free
+                          : MODE == 8 ? (4 * (l & 15) + (l >> 4)) & 31      // lanes l, l + 8 of a half collide
+                          : MODE == 9 ? (l & 15) | (l >> 5) << 4            // lanes l, l + 16 of a half collide
+                                      : (l >> 1) & 31;                      // lanes 2i, 2i + 1 collide
+        atomicAdd(reinterpret_cast<unsigned long long*>(bins) + (((ad >> 1) & ~31u) | bp), 3ull);
+      }
     }
   }
   __syncthreads();
@@ -56,5 +64,9 @@ int main() {
   run<4>("ds_read_b32 random", d_idx, d_out, grid, iters);
   run<5>("ds_add_f32 conflict-free", d_idx, d_out, grid, iters);
   run<6>("ds_add_f32 same address", d_idx, d_out, grid, iters);
+  run<7>("ds_add_u64 banks l%32", d_idx, d_out, grid, iters);
+  run<8>("ds_add_u64 l,l+8 collide", d_idx, d_out, grid, iters);
+  run<9>("ds_add_u64 l,l+16 collide", d_idx, d_out, grid, iters);
+  run<10>("ds_add_u64 2i,2i+1 collide", d_idx, d_out, grid, iters);
   return 0;
 }
