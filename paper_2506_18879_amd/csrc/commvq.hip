@@ -50,7 +50,7 @@ constexpr int kLo = 1 << kLoBits;
 #define COMMVQ_SCORE_THREADS 256
 #endif
 constexpr int kScoreThreads = COMMVQ_SCORE_THREADS;
-constexpr int kBinsThreads = 512;
+constexpr int kBinsThreads = 1024;
 constexpr int kOutThreads = 256;
 constexpr int kMaxValueSplits = 256;  // value_splits never exceeds 256 / (batch * KV heads), at least 1
 constexpr int kOutRows = 64;    // codebook rows per k_out workgroup
@@ -2044,6 +2044,7 @@ struct BinsArgs {
     float *vscale, *lsum;
     int Hq, Hkv, nsplit, split_len;  // score-stage split geometry (for the statistics)
     int nvsplit, vsplit_len;
+    int Gtot;  // query heads per KV head; a workgroup handles G of them (all, unless their bins exceed the LDS)
 };
 
 // One thread per token: w = exp(logit - max) for the G heads of the group, then M_v * G
@@ -2056,11 +2057,14 @@ struct BinsArgs {
 template <int M, int G>
 __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 {
-    extern __shared__ __attribute__((aligned(8))) unsigned bins[];  // [G][M][K]; for G >= 2 used as 64-bit pairs
+    extern __shared__ __attribute__((aligned(8))) unsigned bins[];  // G * M * K; for G >= 2 used as 64-bit pairs
     __shared__ float eoff_s[G];
     int id = blockIdx.x;
     const int g = id % a.Hkv;
     id /= a.Hkv;
+    const int ngrp = a.Gtot / G;
+    const int h0 = g * a.Gtot + (id % ngrp) * G;  // first of the G query heads of this workgroup
+    id /= ngrp;
     const int vs = id % a.nvsplit;
     const int b = id / a.nvsplit;
     const int cu0 = a.cu[b];
@@ -2073,17 +2077,16 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 
     // For G >= 2 the bins of heads 2p and 2p + 1 share one 64-bit word (low / high half): one 64-bit LDS
     // atomic then serves two heads.  Each half stays below 2^31 (see above), so no carry crosses.
-    // Layout [K codewords][M codebooks][G heads]: the LDS bank of a bin is then fixed by (codebook, head pair)
-    // alone -- (m * G/2 + pair) mod 32 in 8-byte units -- whatever the code, and a wavefront whose lanes
-    // spread over the codebooks and start at different head pairs puts exactly two lanes on every bank pair (the
-    // floor for 64 x 8 bytes on 64 banks), where random codes in a [codebook][codeword] layout pile up ~5 deep.
+    // LDS layout [K codewords][G/2 pairs][M codebooks]: a 64-bit LDS operation is served 16 lanes at a time, and
+    // 16 lanes that update the same pair of 16 consecutive codebooks (cyclically) touch 16 consecutive 8-byte
+    // words -- 16 different bank pairs whatever their codes, where a [codebook][codeword] layout lets random
+    // codes collide.  The pair is an immediate offset, so an atomic costs no address arithmetic of its own.
     constexpr int NP = G >= 2 ? G / 2 : 1;
-    unsigned long long *bins2 = reinterpret_cast<unsigned long long *>(bins);  // [K][M][G / 2]
     for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0u;
     // The token's codes and logits are fetched one iteration ahead (the first before the statistics below), so
     // that their latency runs under the previous token's atomics.
     const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
-    const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    const float *srow = a.scores + (size_t)cu0 * a.Hq + (size_t)h0 * L;
     uint4 cnext[M / 16];
     float snext[G];
 #define COMMVQ_BINS_FETCH(i_)                                                                            \
@@ -2095,8 +2098,8 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     if (v0 + tid < v1) COMMVQ_BINS_FETCH(v0 + tid);
     if (wave < G) {
         const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
-        const float2 *st = a.sstat + ((size_t)b * a.Hq + (size_t)g * G + wave) * a.nsplit;
-        float mx = -INFINITY;  // maximum logit of head (g*G + wave) over the whole sequence
+        const float2 *st = a.sstat + ((size_t)b * a.Hq + h0 + wave) * a.nsplit;
+        float mx = -INFINITY;  // maximum logit of head h0 + wave over the whole sequence
         for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, st[s].x);
         mx = wave_max(mx);
         const int sa = v0 / a.split_len, sb = min((v1 + a.split_len - 1) / a.split_len, ns);
@@ -2107,8 +2110,8 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         if (l >= 1e-30f) S = min(30 - ilogbf(l), 120);
         if (lane == 0) {
             eoff_s[wave] = (float)S - mx * kLog2e;
-            a.vscale[((size_t)b * a.Hq + (size_t)g * G + wave) * a.nvsplit + vs] = ldexpf(1.f, -S);
-            a.lsum[((size_t)b * a.Hq + (size_t)g * G + wave) * a.nvsplit + vs] = l;
+            a.vscale[((size_t)b * a.Hq + h0 + wave) * a.nvsplit + vs] = ldexpf(1.f, -S);
+            a.lsum[((size_t)b * a.Hq + h0 + wave) * a.nvsplit + vs] = l;
         }
     }
     __syncthreads();
@@ -2117,16 +2120,9 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     for (int hh = 0; hh < G; ++hh) eoff[hh] = eoff_s[hh];
 
     constexpr int CW = M / 4;
-    // A 64-bit LDS operation is served 32 lanes at a time, so it is within each half of the wavefront that the
-    // (codebook, pair) starting points must fall on 32 different bank pairs: (m * NP + pair) mod 32 distinct.
-    const unsigned rot = NP == 4 ? ((unsigned)(lane & 7) | ((unsigned)(lane >> 5) & 1u) << 3) : (unsigned)lane & (unsigned)(M - 1);
-    const unsigned qsh = NP == 4 ? (unsigned)(lane >> 3) & 3u : (unsigned)(lane >> 4) & (unsigned)(NP - 1);
-    // LDS byte offsets within a (codeword, codebook) row of NP 64-bit bins: the pair the lane updates at step hp
+    const unsigned rot = (unsigned)lane & (unsigned)(M - 1);
     typedef __attribute__((address_space(3))) unsigned long long *lds_u64_ptr;
     const unsigned bins_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned *)bins;
-    unsigned qoff[NP];
-#pragma unroll
-    for (int hp = 0; hp < NP; ++hp) qoff[hp] = bins_base + ((((unsigned)hp + qsh) & (unsigned)(NP - 1)) << 3);
     for (int i = v0 + tid; i < v1; i += kBinsThreads) {
         unsigned cw[M / 4];
 #pragma unroll
@@ -2140,11 +2136,10 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
             p[hh] = (unsigned)(__builtin_amdgcn_exp2f(snext[hh] * kLog2e + eoff[hh]) + 0.5f);
         if (i + kBinsThreads < v1) COMMVQ_BINS_FETCH(i + kBinsThreads);
         asm volatile("" ::: "memory");  // keeps the compiler from sinking the fetch below the atomics
-        // Lane l walks the codebooks in the order (l + k) % M, so that at every step the 64
-        // lanes spread over all M codebooks (bank columns, see above; skewed code usage would otherwise also
-        // put a dozen lanes on the same LDS address in one instruction), and the head pairs in the order
-        // (l / 16 + hp) % (G / 2).  The code vector is rotated by `rot` bytes once per token (dword selects +
-        // alignbyte).
+        // Lane l walks the codebooks in the order (l + k) % M, so that at every step the 64 lanes spread over
+        // all M codebooks (bank columns, see above; skewed code usage would otherwise also put a dozen lanes on
+        // the same LDS address in one instruction).  The code vector is rotated by `rot` bytes once per token
+        // (dword selects + alignbyte).
 #pragma unroll
         for (int st = 1; st < CW; st <<= 1) {
             unsigned t[CW];
@@ -2156,40 +2151,54 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         unsigned rv[CW];
 #pragma unroll
         for (int j = 0; j < CW; ++j) rv[j] = __builtin_amdgcn_alignbyte(cw[(j + 1) % CW], cw[j], rot & 3u);
-        // the lane's head pairs, rotated so that entry hp is pair (hp + lane / 16) % NP
         unsigned long long pp[NP];
         if (G >= 2) {
 #pragma unroll
             for (int hp = 0; hp < NP; ++hp) pp[hp] = (unsigned long long)p[(2 * hp) % G] | (unsigned long long)p[(2 * hp + 1) % G] << 32;
-#pragma unroll
-            for (int st = 1; st < NP; st <<= 1) {
-                unsigned long long t[NP];
-#pragma unroll
-                for (int hp = 0; hp < NP; ++hp) t[hp] = (qsh & st) ? pp[(hp + st) % NP] : pp[hp];
-#pragma unroll
-                for (int hp = 0; hp < NP; ++hp) pp[hp] = t[hp];
-            }
         }
 #pragma unroll
         for (int k = 0; k < M; ++k) {
             const unsigned c = (rv[k / 4] >> (8 * (k % 4))) & 0xffu;
             const unsigned m = ((unsigned)k + rot) & (unsigned)(M - 1);
-            const unsigned cm = c * M + m;
             if (G == 1) {
-                atomicAdd(&bins[cm], p[0]);
+                atomicAdd(&bins[c * M + m], p[0]);
             } else {
-                const unsigned row = cm * (unsigned)(NP * 8);
+                const unsigned ad = bins_base + c * (unsigned)(NP * M * 8) + m * 8u;
 #pragma unroll
                 for (int hp = 0; hp < NP; ++hp)
-                    __hip_atomic_fetch_add(reinterpret_cast<lds_u64_ptr>(row + qoff[hp]), pp[hp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __hip_atomic_fetch_add(reinterpret_cast<lds_u64_ptr>(ad + (unsigned)(hp * M * 8)), pp[hp], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
 #undef COMMVQ_BINS_FETCH
     __syncthreads();
-    // the LDS image is the memory layout: [K][M][G] 32-bit bins (a pair's two halves are heads 2p, 2p + 1)
-    uint4 *dst = reinterpret_cast<uint4 *>(a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * NB);
-    for (int x = tid; x < NB / 4; x += kBinsThreads) dst[x] = reinterpret_cast<const uint4 *>(bins)[x];
+    // memory layout [K][M][Gtot] 32-bit bins (heads innermost: a pair's two halves are heads 2p, 2p + 1)
+    unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * (size_t)(a.Gtot * M * kK) + (h0 - g * a.Gtot);
+    if (G == 1) {
+        if (a.Gtot == 1) {
+            for (int x = tid; x < NB / 4; x += kBinsThreads)
+                reinterpret_cast<uint4 *>(dst)[x] = reinterpret_cast<const uint4 *>(bins)[x];
+        } else {
+            for (int x = tid; x < NB; x += kBinsThreads) dst[(size_t)x * a.Gtot] = bins[x];
+        }
+    } else {
+        const uint2 *src = reinterpret_cast<const uint2 *>(bins);  // [K][NP][M] pairs
+        for (int x = tid; x < kK * M; x += kBinsThreads) {
+            const int c = x / M, m = x % M;
+            uint2 v[NP];
+#pragma unroll
+            for (int hp = 0; hp < NP; ++hp) v[hp] = src[(c * NP + hp) * M + m];
+            unsigned *row = dst + (size_t)x * a.Gtot;  // 8-byte aligned for G = 2, 16-byte aligned for G >= 4
+            if (NP == 1) {
+                *reinterpret_cast<uint2 *>(row) = v[0];
+            } else {
+#pragma unroll
+                for (int hp = 0; hp < NP; hp += 2)
+                    *reinterpret_cast<uint4 *>(row + 2 * hp) = make_uint4(v[hp].x, v[hp].y, v[(hp + 1) % NP].x, v[(hp + 1) % NP].y);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------ k_out
@@ -2388,8 +2397,10 @@ hipError_t launch_score_m(const ScoreArgs &a, int G, bool bf16, int grid, hipStr
 }
 
 template <int M, int G>
-hipError_t launch_bins_mg(const BinsArgs &a, int grid, hipStream_t s)
+hipError_t launch_bins_mg(BinsArgs a, int Gtot, int grid, hipStream_t s)
 {
+    a.Gtot = Gtot;
+    grid *= Gtot / G;
     const size_t lds = (size_t)G * M * kK * sizeof(unsigned);
     static bool attr_set = false;  // per instantiation; raising the limit is idempotent
     if (!attr_set) {
@@ -2405,10 +2416,13 @@ template <int M>
 hipError_t launch_bins_m(const BinsArgs &a, int G, int grid, hipStream_t s)
 {
     switch (G) {
-    case 1: return launch_bins_mg<M, 1>(a, grid, s);
-    case 2: return launch_bins_mg<M, 2>(a, grid, s);
-    case 4: return launch_bins_mg<M, 4>(a, grid, s);
-    default: return launch_bins_mg<M, 8>(a, grid, s);
+    case 1: return launch_bins_mg<M, 1>(a, 1, grid, s);
+    case 2: return launch_bins_mg<M, 2>(a, 2, grid, s);
+    case 4: return launch_bins_mg<M, 4>(a, 4, grid, s);
+    default:
+        // 8 heads x 32 codebooks of bins are 256 KiB, more than a compute unit's LDS: two workgroups of 4 heads
+        if (M == 32) return launch_bins_mg<M, 4>(a, 8, grid, s);
+        return launch_bins_mg<M, 8>(a, 8, grid, s);
     }
 }
 

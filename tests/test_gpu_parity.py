@@ -126,6 +126,15 @@ def test_group_sizes_and_dtypes(gpu, oracle, G, Hkv, dtype):
     check(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 1), (4, 2), (8, 2)])
+def test_two_bit_values_with_every_group_size(gpu, oracle, G, Hkv):
+    # M_v = 32: with 8 heads the bins of a KV head exceed a compute unit's LDS and are split over two workgroups
+    w = synth.make_workload(f"v32_g{G}", B=2, Hq=G * Hkv, Hkv=Hkv, seqlens=[1300, 2300], Mk=16, Mv=32, dtype="bf16",
+                            seed=57 * G + Hkv)
+    print(f"case {w.name}", flush=True)
+    check(gpu, oracle, w)
+
+
 @pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (8, 1)])
 @pytest.mark.parametrize("L", [900, 2600, 5000])
 def test_one_bit_keys_group_sizes_and_tile_lengths(gpu, oracle, G, Hkv, L):
