@@ -2099,12 +2099,16 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     if (wave < G) {
         const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
         const float2 *st = a.sstat + ((size_t)b * a.Hq + h0 + wave) * a.nsplit;
-        float mx = -INFINITY;  // maximum logit of head h0 + wave over the whole sequence
-        for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, st[s].x);
+        // the first 64 splits' statistics stay in registers: one round of loads serves both passes
+        const float2 first = lane < ns ? st[lane] : make_float2(-INFINITY, 0.f);
+        float mx = first.x;  // maximum logit of head h0 + wave over the whole sequence
+        for (int s = lane + 64; s < ns; s += 64) mx = fmaxf(mx, st[s].x);
         mx = wave_max(mx);
         const int sa = v0 / a.split_len, sb = min((v1 + a.split_len - 1) / a.split_len, ns);
         float l = 0.f;  // sum of exp(logit - mx) over this value split
-        for (int s = sa + lane; s < sb; s += 64) l += st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
+        if (lane >= sa && lane < sb) l = first.y * __builtin_amdgcn_exp2f((first.x - mx) * kLog2e);
+        for (int s = lane + 64; s < sb; s += 64)
+            if (s >= sa) l += st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
         l = wave_sum(l);
         int S = 0;
         if (l >= 1e-30f) S = min(30 - ilogbf(l), 120);

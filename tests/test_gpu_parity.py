@@ -135,6 +135,23 @@ def test_two_bit_values_with_every_group_size(gpu, oracle, G, Hkv):
     check(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_every_combination_of_group_size_and_code_widths(gpu, oracle, dtype):
+    # every instantiation the library dispatches to: G x M_k x M_v (x codebook type), at a length with a ragged tail
+    worst = 0.0
+    for G in (1, 2, 4, 8):
+        for Mk in (16, 32):
+            for Mv in (16, 32):
+                w = synth.make_workload(f"all_g{G}_k{Mk}_v{Mv}_{dtype}", B=2, Hq=G, Hkv=1, seqlens=[333, 1090], Mk=Mk, Mv=Mv,
+                                        dtype=dtype, seed=1000 * G + 10 * Mk + Mv)
+                print(f"case {w.name}", flush=True)
+                got = run_gpu(gpu, w)
+                err = row_err(got, oracle_out(oracle, w)).max()
+                assert np.isfinite(got).all() and err <= TOL_OUT, (w.name, err)
+                worst = max(worst, err)
+    print(f"  worst row error {worst:.3e}", flush=True)
+
+
 @pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (8, 1)])
 @pytest.mark.parametrize("L", [900, 2600, 5000])
 def test_one_bit_keys_group_sizes_and_tile_lengths(gpu, oracle, G, Hkv, L):
