@@ -9,7 +9,8 @@
 //               through LDS, gather-sum and query contraction on the matrix cores);
 //               fp32 codebooks or explicit key positions: k_score (rows gathered through L1).
 //   k_bins      Softmax(A) S_V of Eq. optimized_v (unnormalised): exp(logit - max) is
-//               scatter-added into LDS bins [G][M_v][K], one bin set per context split.  The
+//               scatter-added into LDS bins (one per head, value codebook and codeword; written out
+//               as [K][M_v][G]), one bin set per context split.  The
 //               bins are 32-bit fixed point (integer LDS atomics run ~20x faster than fp32 ones
 //               on gfx950); the scale of each split is chosen from its known exp-sum so that
 //               no bin can overflow and the worst-case error is (tokens per split) * 2^-32.
