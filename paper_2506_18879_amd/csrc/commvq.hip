@@ -761,6 +761,19 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
 
     for (int sl = 0; sl < S; ++sl) {
         if (!PREFETCH) fetch_slice(sl);
+        // queries of this slice (head 4 grp + n % 4, the lane's 4 elements): requested before the barriers, so
+        // that they have arrived when the first pass needs them
+        uint4_t qraw[NGRP];
+#pragma unroll
+        for (int x = 0; x < NGRP; ++x) {
+            const unsigned off = q_off + (unsigned)x * (4u * kD);
+            if (a.q_bf16) {
+                const uint2_t q2 = __builtin_amdgcn_raw_buffer_load_b64(q_rs, off * 2u, (unsigned)sl * DS * 2u, 0);
+                qraw[x][0] = q2[0]; qraw[x][1] = q2[1]; qraw[x][2] = 0u; qraw[x][3] = 0u;
+            } else {
+                qraw[x] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, off * 4u, (unsigned)sl * DS * 4u, 0);
+            }
+        }
         __syncthreads();  // everyone is done reading the previous slice
 #pragma unroll
         for (int x = 0; x < PPT; ++x) reinterpret_cast<uint4_t *>(tab)[x * kSliceThreads + tid] = stage[x];
@@ -781,20 +794,17 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         asm volatile("" : "+v"(tb));
         // byte offsets (in the LDS phase tables) of the lane's part, and its distance to the query, times 16
         const int dist16 = (qpos - tb) * 16;
-        // scaled queries of this slice: head 4 grp + n % 4, the lane's 4 elements
+        // scaled queries of this slice
         float qrow[NGRP][4];
 #pragma unroll
         for (int x = 0; x < NGRP; ++x) {
-            const unsigned off = q_off + (unsigned)x * (4u * kD);
             if (a.q_bf16) {
-                const uint2_t qraw = __builtin_amdgcn_raw_buffer_load_b64(q_rs, off * 2u, (unsigned)sl * DS * 2u, 0);
-                qrow[x][0] = bf16_lo(qraw[0]) * a.scale; qrow[x][1] = bf16_hi(qraw[0]) * a.scale;
-                qrow[x][2] = bf16_lo(qraw[1]) * a.scale; qrow[x][3] = bf16_hi(qraw[1]) * a.scale;
+                qrow[x][0] = bf16_lo(qraw[x][0]) * a.scale; qrow[x][1] = bf16_hi(qraw[x][0]) * a.scale;
+                qrow[x][2] = bf16_lo(qraw[x][1]) * a.scale; qrow[x][3] = bf16_hi(qraw[x][1]) * a.scale;
             } else {
-                const uint4_t qraw = __builtin_amdgcn_raw_buffer_load_b128(q_rs, off * 4u, (unsigned)sl * DS * 4u, 0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const unsigned u = qraw[r];
+                    const unsigned u = qraw[x][r];
                     qrow[x][r] = __builtin_bit_cast(float, u) * a.scale;
                 }
             }
@@ -1267,6 +1277,21 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
     const unsigned ehi_base = (unsigned)SLICE + (unsigned)(PARTS * kLo) * 16u + (unsigned)(2 * gk) * (NHR * 16u);
 
     for (int sl = 0; sl < S; ++sl) {
+        // queries of this slice (head 4 grp + n % 4, sub-space gk of each of the 4 planes): requested ahead of the
+        // slice itself, so that they have arrived when the first pass needs them
+        uint2_t qraw[NGRP][PL];
+#pragma unroll
+        for (int x = 0; x < NGRP; ++x)
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl) {
+                const unsigned off = (unsigned)(4 * x + (n & 3)) * kD + 2u * (unsigned)(16 * sl + 4 * pl + gk);  // elements
+                if (a.q_bf16) {
+                    qraw[x][pl][0] = __builtin_amdgcn_raw_buffer_load_b32(q_rs, off * 2u, 0, 0);
+                    qraw[x][pl][1] = 0u;
+                } else {
+                    qraw[x][pl] = __builtin_amdgcn_raw_buffer_load_b64(q_rs, off * 4u, 0, 0);
+                }
+            }
         __syncthreads();  // everyone is done reading the previous slice
         {
             uint4 stage[PPT];
@@ -1293,19 +1318,16 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
         __syncthreads();
         asm volatile("" : "+v"(tb));
         const int dist16 = (qpos - tb) * 16;
-        // scaled queries of this slice: head 4 grp + n % 4, sub-space gk of each of the 4 planes
+        // scaled queries of this slice
         float qrow[NGRP][PL][2];
 #pragma unroll
         for (int x = 0; x < NGRP; ++x)
 #pragma unroll
             for (int pl = 0; pl < PL; ++pl) {
-                const unsigned off = (unsigned)(4 * x + (n & 3)) * kD + 2u * (unsigned)(16 * sl + 4 * pl + gk);  // elements
+                const unsigned u0 = qraw[x][pl][0], u1 = qraw[x][pl][1];
                 if (a.q_bf16) {
-                    const unsigned qraw = __builtin_amdgcn_raw_buffer_load_b32(q_rs, off * 2u, 0, 0);
-                    qrow[x][pl][0] = bf16_lo(qraw) * a.scale; qrow[x][pl][1] = bf16_hi(qraw) * a.scale;
+                    qrow[x][pl][0] = bf16_lo(u0) * a.scale; qrow[x][pl][1] = bf16_hi(u0) * a.scale;
                 } else {
-                    const uint2_t qraw = __builtin_amdgcn_raw_buffer_load_b64(q_rs, off * 4u, 0, 0);
-                    const unsigned u0 = qraw[0], u1 = qraw[1];
                     qrow[x][pl][0] = __builtin_bit_cast(float, u0) * a.scale; qrow[x][pl][1] = __builtin_bit_cast(float, u1) * a.scale;
                 }
             }
