@@ -172,6 +172,16 @@ def test_contiguous_keys_with_query_inside_or_far_beyond_the_context(gpu, oracle
     check(gpu, oracle, w, max_position=80000)
 
 
+@pytest.mark.parametrize("Mk,Mv", [(16, 16), (32, 32)])
+def test_million_token_context_at_the_position_limit(gpu, oracle, Mk, Mv):
+    # one sequence of 2^20 + 77 tokens with the query at the largest supported position (2^24 - 1): 257 score
+    # tiles, the maximum of 256 value splits, coarse phase rows up to the end of the table
+    L = (1 << 20) + 77
+    w = synth.make_workload(f"long_m{Mk}", B=1, Hq=4, Hkv=1, seqlens=[L], Mk=Mk, Mv=Mv, dtype="bf16", seed=2020 + Mk)
+    w.q_pos = np.array([(1 << 24) - 1], np.int32)
+    check(gpu, oracle, w, max_position=1 << 24)
+
+
 def test_ragged_batch_with_length_one_sequence(gpu, oracle):
     w = synth.make_workload("ragged", B=5, Hq=8, Hkv=2, seqlens=[1, 2100, 64, 1, 517], Mk=32, Mv=32, dtype="bf16", seed=5)
     got, ref = check(gpu, oracle, w)
