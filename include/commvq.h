@@ -81,7 +81,8 @@ typedef struct {
 /* Host struct of device pointers: where the tokens sit (ragged batch). */
 typedef struct {
     int32_t batch;             /* B >= 1 */
-    const int32_t *cu_seqlens; /* device [B+1]: prefix sums of the context lengths L_b, L_b >= 1 */
+    const int32_t *cu_seqlens; /* device [B+1]: prefix sums of the context lengths L_b >= 0; a sequence with
+                                  L_b = 0 (softmax over nothing) gets all-zero output rows */
     const int32_t *q_pos;      /* device [B]: position t of the query token (q <- q R_t) */
     const int32_t *key_pos;    /* device [T] or NULL; NULL means token i of a sequence sits at position i */
     int64_t total_tokens;      /* T = cu_seqlens[B] (host copy, sizes grids without a sync) */

@@ -2361,7 +2361,7 @@ __global__ __launch_bounds__(kD) void k_out_final(OutArgs a)
         if (threadIdx.x == 0) l_s = l;
     }
     __syncthreads();
-    a.out[(size_t)bh * kD + threadIdx.x] = s / l_s;
+    a.out[(size_t)bh * kD + threadIdx.x] = l_s > 0.f ? s / l_s : 0.f;  // a sequence without context tokens: zeros
 }
 
 // ------------------------------------------------------------------ host side
@@ -2370,7 +2370,7 @@ commvq_status check_positions(const commvq_positions *p)
     if (!p) return COMMVQ_ERR_NULL;
     if (!p->cu_seqlens || !p->q_pos) return COMMVQ_ERR_NULL;
     if (p->batch < 1 || p->max_seqlen < 1) return COMMVQ_ERR_SHAPE;
-    if (p->total_tokens < p->batch || p->total_tokens < p->max_seqlen) return COMMVQ_ERR_SHAPE;
+    if (p->total_tokens < p->max_seqlen) return COMMVQ_ERR_SHAPE;
     if (p->total_tokens > (int64_t)p->batch * p->max_seqlen) return COMMVQ_ERR_SHAPE;
     if (p->total_tokens > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
     return COMMVQ_OK;
@@ -2793,7 +2793,7 @@ commvq_status commvq_plan_query(const commvq_handle *h, int32_t batch, int64_t t
                                 commvq_plan *plan)
 {
     if (!h || !plan) return COMMVQ_ERR_NULL;
-    if (batch < 1 || max_seqlen < 1 || total_tokens < batch || total_tokens < max_seqlen ||
+    if (batch < 1 || max_seqlen < 1 || total_tokens < max_seqlen ||
         total_tokens > (int64_t)batch * max_seqlen)
         return COMMVQ_ERR_SHAPE;
     make_plan(h, batch, max_seqlen, use_sliced(h, false), plan);

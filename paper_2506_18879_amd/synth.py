@@ -113,7 +113,7 @@ def make_workload(name: str, *, B: int, Hq: int, Hkv: int, seqlens, Mk: int, Mv:
     assert dtype in ("f32", "bf16") and Hq % Hkv == 0 and d % 2 == 0
     rng = np.random.Generator(np.random.PCG64(seed))
     seqlens = np.asarray(seqlens, dtype=np.int64)
-    assert seqlens.shape == (B,) and np.all(seqlens >= 1)
+    assert seqlens.shape == (B,) and np.all(seqlens >= 0) and seqlens.max() >= 1  # a sequence may be empty
     cu = np.zeros(B + 1, dtype=np.int32)
     cu[1:] = np.cumsum(seqlens)
 
@@ -143,7 +143,7 @@ def make_workload(name: str, *, B: int, Hq: int, Hkv: int, seqlens, Mk: int, Mv:
 
     key_codes = codes(Mk)
     val_codes = codes(Mv)
-    q_pos = (seqlens - 1).astype(np.int32)  # the query's own key is the last cached row
+    q_pos = np.maximum(seqlens - 1, 0).astype(np.int32)  # the query's own key is the last cached row
     return Workload(name=name, B=B, Hq=Hq, Hkv=Hkv, d=d, Mk=Mk, Mv=Mv, K=K, dtype=dtype, rope_base=rope_base,
                     q=q, key_codes=key_codes, val_codes=val_codes, key_codebooks=key_cb, val_codebooks=val_cb,
                     cu_seqlens=cu, q_pos=q_pos, key_pos=None, seed=seed, code_dist=code_dist)

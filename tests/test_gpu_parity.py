@@ -182,6 +182,22 @@ def test_million_token_context_at_the_position_limit(gpu, oracle, Mk, Mv):
     check(gpu, oracle, w, max_position=1 << 24)
 
 
+def test_batch_with_empty_sequences(gpu, oracle):
+    # a sequence without context tokens (softmax over nothing) gets zero rows; its neighbours are unaffected
+    lens = [0, 300, 0, 0, 1077, 0]
+    w = synth.make_workload("empties", B=6, Hq=8, Hkv=2, seqlens=lens, Mk=16, Mv=32, dtype="bf16", seed=99)
+    got = run_gpu(gpu, w)
+    keep = [b for b, L in enumerate(lens) if L > 0]
+    ref = oracle.decode_attn(w.as_f64("q")[keep], w.key_codes, w.val_codes, w.as_f64("key_codebooks"), w.as_f64("val_codebooks"),
+                             np.concatenate([[0], np.cumsum([lens[b] for b in keep])]).astype(np.int32), w.q_pos[keep],
+                             rope_base=w.rope_base, n_threads=4)
+    assert np.isfinite(got).all()
+    assert row_err(got[keep], ref).max() <= TOL_OUT
+    for b, L in enumerate(lens):
+        if L == 0:
+            assert not got[b].any()
+
+
 def test_ragged_batch_with_length_one_sequence(gpu, oracle):
     w = synth.make_workload("ragged", B=5, Hq=8, Hkv=2, seqlens=[1, 2100, 64, 1, 517], Mk=32, Mv=32, dtype="bf16", seed=5)
     got, ref = check(gpu, oracle, w)
