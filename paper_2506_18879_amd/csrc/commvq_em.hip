@@ -100,64 +100,83 @@ __global__ __launch_bounds__(256) void k_em_accum(const float2 *__restrict__ dat
     }
 }
 
-// Blocked Cholesky A = L L^T in place (lower triangle of A [n][ld] in LDS), 256 threads, 16 columns per step:
-// the 16 x 16 diagonal block is factored by the first 16 lanes of wavefront 0, a row per lane, exchanging
-// columns by lane shuffles; then one thread per row below solves its 16 entries; then all threads subtract the
-// panel's outer product from the rest.  Three barriers per 16 columns instead of three per column.
+// Blocked Cholesky A = L L^T in place (lower triangle of A [np][ld] in LDS; np a multiple of 16, the rows and
+// columns past the system's size n hold the identity), 16 columns per step.  The 16 x 16 diagonal block is
+// factored by wavefront 0 with a row per lane, columns exchanged through v_readlane (constant lanes: scalar
+// broadcasts, no LDS round trips); the same lanes then invert the triangular block, so that everything below --
+// the panel's rows here, the right-hand sides in em_substitute -- is a product with inv(L_kk) by independent
+// threads instead of a 16-step chain per thread.  Dinv [np / 16][16][16] receives the inverses.
 constexpr int kEmNb = 16;
-template <int NT>
-__device__ __forceinline__ void em_cholesky(float *A, int ld, int n, int tid)
+__device__ __forceinline__ int em_pad(int n) { return (n + kEmNb - 1) / kEmNb * kEmNb; }
+__device__ __forceinline__ float em_lane(float v, int l)
 {
-    for (int k0 = 0; k0 < n; k0 += kEmNb) {
-        const int nb = min(kEmNb, n - k0);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ __forceinline__ float em_rcp(float d)
+{
+    const float x = __builtin_amdgcn_rcpf(d);
+    return x * (2.f - d * x);
+}
+template <int NT>
+__device__ __forceinline__ void em_cholesky(float *A, int ld, int np, float *Dinv, int tid)
+{
+    for (int k0 = 0; k0 < np; k0 += kEmNb) {
+        float *Di = Dinv + (k0 / kEmNb) * (kEmNb * kEmNb);
         if (tid < 64) {
-            float row[kEmNb];
+            const int t = tid & (kEmNb - 1);  // lanes 16..63 repeat lanes 0..15 and store nothing
+            float row[kEmNb], isd[kEmNb];
 #pragma unroll
-            for (int c = 0; c < kEmNb; ++c)
-                row[c] = (tid < nb && c <= tid) ? A[(k0 + tid) * ld + k0 + c] : (c == tid ? 1.f : 0.f);  // identity beyond the matrix
+            for (int c = 0; c < kEmNb; ++c) row[c] = c <= t ? A[(k0 + t) * ld + k0 + c] : 0.f;
 #pragma unroll
             for (int c = 0; c < kEmNb; ++c) {
-                const float d = __builtin_sqrtf(__shfl(row[c], c));
-                if (tid == c) row[c] = d;
-                else if (tid > c) row[c] /= d;
+                const float d = __builtin_sqrtf(em_lane(row[c], c));
+                isd[c] = em_rcp(d);
+                row[c] = t == c ? d : row[c] * isd[c];  // entries above the diagonal are never read
 #pragma unroll
-                for (int cc = c + 1; cc < kEmNb; ++cc) {
-                    const float l = __shfl(row[c], cc);  // L[cc][c]
-                    if (tid >= cc) row[cc] -= row[c] * l;
-                }
+                for (int cc = c + 1; cc < kEmNb; ++cc) row[cc] -= row[c] * em_lane(row[c], cc);  // L[t][c] L[cc][c]
             }
-            if (tid < nb) {
+            // column t of X = inv(L_kk):  X[i][t] = (delta_it - sum_{k < i} L[i][k] X[k][t]) / L[i][i]
+            float x[kEmNb];
 #pragma unroll
-                for (int c = 0; c < kEmNb; ++c)
-                    if (c <= tid) A[(k0 + tid) * ld + k0 + c] = row[c];
+            for (int i = 0; i < kEmNb; ++i) {
+                float v = i == t ? 1.f : 0.f;
+#pragma unroll
+                for (int k = 0; k < i; ++k) v -= em_lane(row[k], i) * x[k];
+                x[i] = i >= t ? v * isd[i] : 0.f;
+            }
+            if (tid < kEmNb) {
+#pragma unroll
+                for (int c = 0; c < kEmNb; ++c) {
+                    if (c <= t) A[(k0 + t) * ld + k0 + c] = row[c];
+                    Di[c * kEmNb + t] = x[c];
+                }
             }
         }
         __syncthreads();
-        for (int r = k0 + nb + tid; r < n; r += NT) {  // x L_d^T = a for the rows below the block
-            float x[kEmNb];
+        for (int r = k0 + kEmNb + tid; r < np; r += NT) {  // x L_kk^T = a for the rows below: x = a inv(L_kk)^T
+            float av[kEmNb], xv[kEmNb];
+#pragma unroll
+            for (int e = 0; e < kEmNb; ++e) av[e] = A[r * ld + k0 + e];
 #pragma unroll
             for (int c = 0; c < kEmNb; ++c) {
-                if (c < nb) {
-                    float v = A[r * ld + k0 + c];
+                float v = 0.f;
 #pragma unroll
-                    for (int e = 0; e < kEmNb; ++e)
-                        if (e < c) v -= x[e] * A[(k0 + c) * ld + k0 + e];
-                    x[c] = v / A[(k0 + c) * ld + k0 + c];
-                    A[r * ld + k0 + c] = x[c];
-                }
+                for (int e = 0; e <= c; ++e) v += av[e] * Di[c * kEmNb + e];
+                xv[c] = v;
             }
+#pragma unroll
+            for (int c = 0; c < kEmNb; ++c) A[r * ld + k0 + c] = xv[c];
         }
         __syncthreads();
         // rest -= panel panel^T (lower triangle): 32 lanes walk a row's columns, the row's panel entries in registers
-        for (int r = k0 + nb + tid / 32; r < n; r += NT / 32) {
+        for (int r = k0 + kEmNb + tid / 32; r < np; r += NT / 32) {
             float pr[kEmNb];
 #pragma unroll
-            for (int e = 0; e < kEmNb; ++e) pr[e] = e < nb ? A[r * ld + k0 + e] : 0.f;
-            for (int cc = k0 + nb + tid % 32; cc <= r; cc += 32) {
+            for (int e = 0; e < kEmNb; ++e) pr[e] = A[r * ld + k0 + e];
+            for (int cc = k0 + kEmNb + tid % 32; cc <= r; cc += 32) {
                 float sum = 0.f;
 #pragma unroll
-                for (int e = 0; e < kEmNb; ++e)
-                    if (e < nb) sum += pr[e] * A[cc * ld + k0 + e];
+                for (int e = 0; e < kEmNb; ++e) sum += pr[e] * A[cc * ld + k0 + e];
                 A[r * ld + cc] -= sum;
             }
         }
@@ -165,86 +184,51 @@ __device__ __forceinline__ void em_cholesky(float *A, int ld, int n, int tid)
     }
 }
 
-// L Z = R, then L^T X = Z, for the nr columns of R [n][nr] in LDS, blocked like em_cholesky: one thread per
-// column substitutes through a 16 x 16 diagonal block, then all threads update the rows that remain.
+// L Z = R, then L^T X = Z, for the nr columns of R [np][nr] in LDS (16 nr <= NT), blocked like em_cholesky: thread
+// (c, j) forms entry c of a block's solution for column j as a product with the inverted diagonal block, then
+// every thread takes one (row, column) of what remains and subtracts the block's contribution.
 template <int NT>
-__device__ __forceinline__ void em_substitute(const float *A, int ld, int n, float *R, int nr, int tid)
+__device__ __forceinline__ void em_substitute(const float *A, int ld, int np, const float *Dinv, float *R, int nr, int tid)
 {
-    for (int k0 = 0; k0 < n; k0 += kEmNb) {
-        const int nb = min(kEmNb, n - k0);
-        for (int j = tid; j < nr; j += NT) {
-            float z[kEmNb];
+    const bool act = tid < kEmNb * nr;
+    const int c = tid / nr, j = tid % nr;
+    for (int k0 = 0; k0 < np; k0 += kEmNb) {
+        const float *Di = Dinv + (k0 / kEmNb) * (kEmNb * kEmNb);
+        float v = 0.f;
+        if (act) {
 #pragma unroll
-            for (int c = 0; c < kEmNb; ++c) {
-                if (c < nb) {
-                    float v = R[(k0 + c) * nr + j];
-#pragma unroll
-                    for (int e = 0; e < kEmNb; ++e)
-                        if (e < c) v -= A[(k0 + c) * ld + k0 + e] * z[e];
-                    z[c] = v / A[(k0 + c) * ld + k0 + c];
-                    R[(k0 + c) * nr + j] = z[c];
-                }
-            }
+            for (int e = 0; e < kEmNb; ++e)
+                if (e <= c) v += Di[c * kEmNb + e] * R[(k0 + e) * nr + j];
         }
         __syncthreads();
-        // rows below: 64 lanes take the columns (their 16 solved entries in registers), NT / 64 rows at a time;
-        // a single column: one thread per row
-        if (nr == 1) {
-            for (int r = k0 + nb + tid; r < n; r += NT) {
-                float sum = 0.f;
-                for (int e = 0; e < nb; ++e) sum += A[r * ld + k0 + e] * R[k0 + e];
-                R[r] -= sum;
-            }
-        } else
-        for (int j = tid % 64; j < nr; j += 64) {
-            float zz[kEmNb];
+        if (act) R[(k0 + c) * nr + j] = v;
+        __syncthreads();
+        for (int x = tid; x < (np - k0 - kEmNb) * nr; x += NT) {
+            const int r = k0 + kEmNb + x / nr, jj = x % nr;
+            float sum = 0.f;
 #pragma unroll
-            for (int e = 0; e < kEmNb; ++e) zz[e] = e < nb ? R[(k0 + e) * nr + j] : 0.f;
-            for (int r = k0 + nb + tid / 64; r < n; r += NT / 64) {
-                float sum = 0.f;
-#pragma unroll
-                for (int e = 0; e < kEmNb; ++e)
-                    if (e < nb) sum += A[r * ld + k0 + e] * zz[e];
-                R[r * nr + j] -= sum;
-            }
+            for (int e = 0; e < kEmNb; ++e) sum += A[r * ld + k0 + e] * R[(k0 + e) * nr + jj];
+            R[r * nr + jj] -= sum;
         }
         __syncthreads();
     }
-    for (int k0 = (n - 1) / kEmNb * kEmNb; k0 >= 0; k0 -= kEmNb) {
-        const int nb = min(kEmNb, n - k0);
-        for (int j = tid; j < nr; j += NT) {
-            float z[kEmNb];
+    for (int k0 = np - kEmNb; k0 >= 0; k0 -= kEmNb) {
+        const float *Di = Dinv + (k0 / kEmNb) * (kEmNb * kEmNb);
+        float v = 0.f;
+        if (act) {
 #pragma unroll
-            for (int c = kEmNb - 1; c >= 0; --c) {
-                if (c < nb) {
-                    float v = R[(k0 + c) * nr + j];
-#pragma unroll
-                    for (int e = kEmNb - 1; e >= 0; --e)
-                        if (e > c && e < nb) v -= A[(k0 + e) * ld + k0 + c] * z[e];
-                    z[c] = v / A[(k0 + c) * ld + k0 + c];
-                    R[(k0 + c) * nr + j] = z[c];
-                }
-            }
+            for (int e = 0; e < kEmNb; ++e)
+                if (e >= c) v += Di[e * kEmNb + c] * R[(k0 + e) * nr + j];  // inv(L_kk)^T
         }
         __syncthreads();
-        if (nr == 1) {
-            for (int r = tid; r < k0; r += NT) {
-                float sum = 0.f;
-                for (int e = 0; e < nb; ++e) sum += A[(k0 + e) * ld + r] * R[k0 + e];
-                R[r] -= sum;
-            }
-        } else
-        for (int j = tid % 64; j < nr; j += 64) {
-            float zz[kEmNb];
+        if (act) R[(k0 + c) * nr + j] = v;
+        __syncthreads();
+        for (int x = tid; x < k0 * nr; x += NT) {
+            const int r = x / nr, jj = x % nr;
+            float sum = 0.f;
 #pragma unroll
-            for (int e = 0; e < kEmNb; ++e) zz[e] = e < nb ? R[(k0 + e) * nr + j] : 0.f;
-            for (int r = tid / 64; r < k0; r += NT / 64) {
-                float sum = 0.f;
-#pragma unroll
-                for (int e = 0; e < kEmNb; ++e)
-                    if (e < nb) sum += A[(k0 + e) * ld + r] * zz[e];
-                R[r * nr + j] -= sum;
-            }
+            for (int e = 0; e < kEmNb; ++e) sum += A[(k0 + e) * ld + r] * R[(k0 + e) * nr + jj];
+            R[r * nr + jj] -= sum;
         }
         __syncthreads();
     }
@@ -255,15 +239,18 @@ __global__ __launch_bounds__(256) void k_em_solve(const float *__restrict__ nab,
                                                   float2 *__restrict__ phi, int Nc)
 {
     extern __shared__ float em_lds[];
-    const int n2 = 2 * Nc;
-    float *A = em_lds;                 // [n2][n2 + 1]: padded rows
-    float *rhs = A + n2 * (n2 + 1);    // [n2]
-    const int ld = n2 + 1;
+    const int n2 = 2 * Nc, np = em_pad(n2);
+    float *A = em_lds;                 // [np][np + 1]: padded rows; identity past n2
+    float *rhs = A + np * (np + 1);    // [np]
+    float *Dinv = rhs + np;            // [np / 16][16][16]
+    const int ld = np + 1;
     const int j = blockIdx.x, tid = threadIdx.x;
     const float *Nj = nab + (size_t)j * Nc * Nc;
     const float2 *Sj = sab + (size_t)j * Nc * Nc;
-    for (int x = tid; x < n2 * ld; x += 256) A[x] = 0.f;
+    for (int x = tid; x < np * ld; x += 256) A[x] = 0.f;
+    if (tid < np) rhs[tid] = 0.f;
     __syncthreads();
+    if (tid >= n2 && tid < np) A[tid * ld + tid] = 1.f;
     // off-diagonal blocks: A[x_a][y_b] = A[y_b][x_a] = N_ba - N_ab  (unknown order x_0, y_0, x_1, y_1, ...)
     for (int x = tid; x < Nc * Nc; x += 256) {
         const int a = x / Nc, b = x % Nc;
@@ -286,8 +273,8 @@ __global__ __launch_bounds__(256) void k_em_solve(const float *__restrict__ nab,
         rhs[2 * a + 1] = ry;
     }
     __syncthreads();
-    em_cholesky<256>(A, ld, n2, tid);
-    em_substitute<256>(A, ld, n2, rhs, 1, tid);
+    em_cholesky<256>(A, ld, np, Dinv, tid);
+    em_substitute<256>(A, ld, np, Dinv, rhs, 1, tid);
     if (tid < Nc) phi[(size_t)j * Nc + tid] = make_float2(rhs[2 * tid], rhs[2 * tid + 1]);
 }
 
@@ -477,34 +464,42 @@ __global__ __launch_bounds__(kEmMaxNc) void k_ems_rhs(const float2 *__restrict__
     }
 }
 
-// One workgroup: the common 2Nc x 2Nc matrix, its Cholesky factor, and the J right-hand sides side by side.
+// The common 2Nc x 2Nc matrix, its Cholesky factor, and the right-hand sides of the J sub-spaces side by side.
+// The factorisation is a chain of dependent steps that one workgroup runs as fast as sixteen, while the
+// right-hand sides are independent: workgroup w repeats the (cheap) factorisation and substitutes for the
+// kEmsSolveCols sub-spaces w * kEmsSolveCols ... only.
 constexpr int kEmsSolveThreads = 1024;
+constexpr int kEmsSolveCols = 4;
 __global__ __launch_bounds__(kEmsSolveThreads) void k_ems_solve(const float *__restrict__ nab, const float2 *__restrict__ rhs_part,
                                                    float2 *__restrict__ phi, int J, int Nc)
 {
     extern __shared__ float em_lds[];
-    const int n2 = 2 * Nc, ld = n2 + 1;
-    float *A = em_lds;                 // [n2][n2 + 1]
-    float *R = A + n2 * ld;            // [n2][J]
+    const int n2 = 2 * Nc, np = em_pad(n2), ld = np + 1;
     const int tid = threadIdx.x;
-    for (int x = tid; x < n2 * ld; x += kEmsSolveThreads) A[x] = 0.f;
+    const int j0 = blockIdx.x * kEmsSolveCols, jn = min(kEmsSolveCols, J - j0);
+    float *A = em_lds;                 // [np][np + 1]; identity past n2
+    float *R = A + np * ld;            // [np][jn]
+    float *Dinv = R + np * kEmsSolveCols;  // [np / 16][16][16]
+    for (int x = tid; x < np * ld; x += kEmsSolveThreads) A[x] = 0.f;
+    for (int x = tid; x < np * jn; x += kEmsSolveThreads) R[x] = 0.f;
     __syncthreads();
+    if (tid >= n2 && tid < np) A[tid * ld + tid] = 1.f;
     for (int x = tid; x < Nc * Nc; x += kEmsSolveThreads) {
         const int a = x / Nc, b = x % Nc;
         const float v = nab[b * Nc + a] - nab[a * Nc + b];
         A[(2 * a) * ld + 2 * b + 1] = v;
         A[(2 * b + 1) * ld + 2 * a] = v;
     }
-    for (int x = tid; x < Nc * J; x += kEmsSolveThreads) {
-        const int a = x / J, j = x % J;
+    for (int x = tid; x < Nc * jn; x += kEmsSolveThreads) {
+        const int a = x / jn, j = x % jn;
         float rx = 0.f, ry = 0.f;
         for (int sp = 0; sp < kEmsSplits; ++sp) {
-            const float2 p = rhs_part[((size_t)sp * J + j) * Nc + a];
+            const float2 p = rhs_part[((size_t)sp * J + j0 + j) * Nc + a];
             rx += p.x;
             ry += p.y;
         }
-        R[(2 * a) * J + j] = rx;
-        R[(2 * a + 1) * J + j] = ry;
+        R[(2 * a) * jn + j] = rx;
+        R[(2 * a + 1) * jn + j] = ry;
     }
     __syncthreads();
     if (tid < Nc) {
@@ -514,11 +509,11 @@ __global__ __launch_bounds__(kEmsSolveThreads) void k_ems_solve(const float *__r
         A[(2 * tid + 1) * ld + 2 * tid + 1] = d;
     }
     __syncthreads();
-    em_cholesky<kEmsSolveThreads>(A, ld, n2, tid);
-    em_substitute<kEmsSolveThreads>(A, ld, n2, R, J, tid);
-    for (int x = tid; x < J * Nc; x += kEmsSolveThreads) {
+    em_cholesky<kEmsSolveThreads>(A, ld, np, Dinv, tid);
+    em_substitute<kEmsSolveThreads>(A, ld, np, Dinv, R, jn, tid);
+    for (int x = tid; x < jn * Nc; x += kEmsSolveThreads) {
         const int j = x / Nc, a = x % Nc;
-        phi[x] = make_float2(R[(2 * a) * J + j], R[(2 * a + 1) * J + j]);
+        phi[(size_t)j0 * Nc + x] = make_float2(R[(2 * a) * jn + j], R[(2 * a + 1) * jn + j]);
     }
 }
 
@@ -581,12 +576,12 @@ commvq_status commvq_em_step(const float *data, int32_t n_subspaces, int32_t n_p
     hipLaunchKernelGGL(k_em_accum, dim3((unsigned)((n_centres * n_centres + 255) / 256), (unsigned)n_subspaces), dim3(256), 0, s,
                        d2, p2, dmin, zsum, nab, sab, n_points, n_centres, inv_t);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
-    const int n2 = 2 * n_centres;
-    const int lds = (n2 * (n2 + 1) + n2) * 4;
+    const int np = (2 * n_centres + 15) / 16 * 16;  // the system padded to whole 16-column blocks
+    const int lds = (np * (np + 1) + np + np * 16) * 4;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_em_solve), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (2 * kEmMaxNc * (2 * kEmMaxNc + 1) + 2 * kEmMaxNc) * 4) != hipSuccess)
+                                (2 * kEmMaxNc * (2 * kEmMaxNc + 1) + 2 * kEmMaxNc + 2 * kEmMaxNc * 16) * 4) != hipSuccess)
             return COMMVQ_ERR_LAUNCH;
         attr_set = true;
     }
@@ -625,11 +620,12 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
     hipLaunchKernelGGL(k_ems_tables, dim3(cgrid), dim3(256), 0, s, p2, xab, nn, J, Nc);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
     const int lds_a = ((((J * Nc * 2 > Nc * Nc ? J * Nc * 2 : Nc * Nc) + 1) & ~1) + kEmsPts * (J + 1) * 2 + 2 * kEmsPts * (Nc + 1) + 3 * kEmsPts) * 4;
-    const int lds_s = (2 * Nc * (2 * Nc + 1) + 2 * Nc * J) * 4;
+    const int np_s = (2 * Nc + 15) / 16 * 16;
+    const int lds_s = (np_s * (np_s + 1) + np_s * kEmsSolveCols + np_s * 16) * 4;
     static bool attr_set = false;
     if (!attr_set) {
         const int max_a = (64 * 64 * 2 + kEmsPts * 65 * 2 + 2 * kEmsPts * 65 + 3 * kEmsPts) * 4;
-        const int max_s = (128 * 129 + 128 * 64) * 4;
+        const int max_s = (128 * 129 + 128 * kEmsSolveCols + 128 * 16) * 4;
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_assign), hipFuncAttributeMaxDynamicSharedMemorySize, max_a) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_solve), hipFuncAttributeMaxDynamicSharedMemorySize, max_s) != hipSuccess)
             return COMMVQ_ERR_LAUNCH;
@@ -642,7 +638,8 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
     hipLaunchKernelGGL(k_ems_rhs, dim3((unsigned)J, (unsigned)kEmsSplits), dim3(kEmMaxNc), 0, s, d2, wa, wb, rhs_part, N, J, Nc);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(k_ems_solve, dim3(1), dim3(kEmsSolveThreads), lds_s, s, nab, rhs_part, p2, J, Nc);
+    hipLaunchKernelGGL(k_ems_solve, dim3((unsigned)((J + kEmsSolveCols - 1) / kEmsSolveCols)), dim3(kEmsSolveThreads), lds_s, s, nab,
+                       rhs_part, p2, J, Nc);
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
 
