@@ -246,12 +246,15 @@ commvq_status commvq_stage_output(commvq_handle *handle, const void *val_codeboo
                                   size_t workspace_bytes, void *stream);
 
 /*
- * Per-stage timing.  When enabled, commvq_decode_attn brackets each stage with HIP events on
- * the caller's stream (a ring of 64 calls).  commvq_profile_read synchronises on the recorded
- * events and returns the mean duration in milliseconds of [scores, bins, output] over the calls
- * recorded since the last read (host array of 3 floats) and their count.
+ * Per-stage timing.  commvq_profile_enable(handle, every): every > 0 makes every `every`-th commvq_decode_attn
+ * (the first, the every + 1-th, ...) bracket each of its stages with HIP events on the caller's stream (a ring of
+ * 64 recorded calls); 0 switches it off.  An event between two kernels costs a few microseconds of GPU time
+ * (the next kernel's dispatch no longer overlaps the previous one's end), which is why a caller that times whole
+ * calls as well samples with every > 1.  commvq_profile_read synchronises on the recorded events and returns the
+ * mean duration in milliseconds of [scores, bins, output] over the calls recorded since the last read (host
+ * array of 3 floats) and their count.
  */
-commvq_status commvq_profile_enable(commvq_handle *handle, int32_t enable);
+commvq_status commvq_profile_enable(commvq_handle *handle, int32_t every);
 commvq_status commvq_profile_read(commvq_handle *handle, float *mean_ms /* host [3] */, int32_t *n_calls /* host */);
 
 const char *commvq_status_string(commvq_status status);

@@ -226,8 +226,9 @@ def commvq_stage_output(handle, val_codebooks, positions: Positions, out, worksp
            "commvq_stage_output")
 
 
-def commvq_profile_enable(handle, enable: bool) -> None:
-    _check(load_library().commvq_profile_enable(handle, 1 if enable else 0), "commvq_profile_enable")
+def commvq_profile_enable(handle, every) -> None:
+    """Stage events on every `every`-th call (True = every call, 0 / False = off)."""
+    _check(load_library().commvq_profile_enable(handle, int(every)), "commvq_profile_enable")
 
 
 def commvq_profile_read(handle):

@@ -72,7 +72,7 @@ struct commvq_handle {
     int device;
     float2 *tbl_hi;  // [n_hi][64]  exp(i * theta_j * 64 * hi)
     float2 *tbl_lo;  // [64][64]    exp(i * theta_j * lo)
-    int prof_on;
+    int prof_every, prof_calls;  // stage events on every prof_every-th call (0: never)
     int prof_head, prof_count;
     hipEvent_t prof_ev[kProfRing][4];
     bool prof_ev_made;
@@ -2748,7 +2748,7 @@ commvq_status commvq_create(const commvq_config *config, commvq_handle **out)
     h->n_hi = (config->max_position >> kLoBits) + 1;
     h->device = dev;
     h->tbl_hi = h->tbl_lo = nullptr;
-    h->prof_on = 0; h->prof_head = h->prof_count = 0; h->prof_ev_made = false;
+    h->prof_every = 0; h->prof_calls = 0; h->prof_head = h->prof_count = 0; h->prof_ev_made = false;
     // exact phases in fp64, rounded once to fp32
     std::vector<float2> hi((size_t)h->n_hi * kJ), lo((size_t)kLo * kJ);
     for (int j = 0; j < kJ; ++j) {
@@ -3003,7 +3003,7 @@ commvq_status commvq_decode_attn(commvq_handle *h, const void *q, const uint8_t 
     if (st != COMMVQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipEvent_t *ev = nullptr;
-    if (h->prof_on) {
+    if (h->prof_every > 0 && h->prof_calls++ % h->prof_every == 0) {
         if (!h->prof_ev_made) {
             for (int i = 0; i < kProfRing; ++i)
                 for (int k = 0; k < 4; ++k)
@@ -3029,10 +3029,11 @@ commvq_status commvq_decode_attn(commvq_handle *h, const void *q, const uint8_t 
     return COMMVQ_OK;
 }
 
-commvq_status commvq_profile_enable(commvq_handle *h, int32_t enable)
+commvq_status commvq_profile_enable(commvq_handle *h, int32_t every)
 {
     if (!h) return COMMVQ_ERR_NULL;
-    h->prof_on = enable ? 1 : 0;
+    h->prof_every = every > 0 ? every : 0;
+    h->prof_calls = 0;
     h->prof_head = h->prof_count = 0;
     return COMMVQ_OK;
 }
