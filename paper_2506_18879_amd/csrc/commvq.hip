@@ -2340,18 +2340,23 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
 }
 
 // One workgroup per (sequence, head): sum of the chunk partials in a fixed order, division
-// by the softmax denominator (sum of the value splits' exp-sums).  Measured: finishing inside
-// k_out by a last-arriving workgroup costs more than this launch, because the device-scope
-// release/acquire it needs writes back and invalidates L2.
-__global__ __launch_bounds__(kD) void k_out_final(OutArgs a)
+// by the softmax denominator (sum of the value splits' exp-sums).  Four threads per output element take every
+// fourth chunk each, so that a thread's loads are one round of independent requests; their four sums are then
+// added in a fixed order.  Measured: finishing inside k_out by a last-arriving workgroup costs more than this
+// launch, because the device-scope release/acquire it needs writes back and invalidates L2.
+constexpr int kFinalParts = 4;
+__global__ __launch_bounds__(kD * kFinalParts) void k_out_final(OutArgs a)
 {
     __shared__ float l_s;
+    __shared__ float part[kFinalParts][kD];
     const int bh = blockIdx.x;
     const int b = bh / a.Hq;
-    const float *pp = a.partial + (size_t)bh * a.nchunk * kD + threadIdx.x;
+    const int e = threadIdx.x % kD, q = threadIdx.x / kD;
+    const float *pp = a.partial + (size_t)bh * a.nchunk * kD + e;
     float s = 0.f;
-#pragma unroll 8
-    for (int c = 0; c < a.nchunk; ++c) s += pp[(size_t)c * kD];
+#pragma unroll 16
+    for (int c = q; c < a.nchunk; c += kFinalParts) s += pp[(size_t)c * kD];
+    part[q][e] = s;
     if (threadIdx.x < 64) {
         const int L = a.cu[b + 1] - a.cu[b];
         const int nvs = min((L + a.vsplit_len - 1) / a.vsplit_len, a.nvsplit);
@@ -2361,7 +2366,12 @@ __global__ __launch_bounds__(kD) void k_out_final(OutArgs a)
         if (threadIdx.x == 0) l_s = l;
     }
     __syncthreads();
-    a.out[(size_t)bh * kD + threadIdx.x] = l_s > 0.f ? s / l_s : 0.f;  // a sequence without context tokens: zeros
+    if (q == 0) {
+        float t = part[0][e];
+#pragma unroll
+        for (int k = 1; k < kFinalParts; ++k) t += part[k][e];
+        a.out[(size_t)bh * kD + e] = l_s > 0.f ? t / l_s : 0.f;  // a sequence without context tokens: zeros
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -2686,7 +2696,7 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
     default: e = launch_out_g<8>(a, bf16, grid, s); break;
     }
     if (e != hipSuccess) return COMMVQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(k_out_final, dim3(pos->batch * c.n_q_heads), dim3(kD), 0, s, a);
+    hipLaunchKernelGGL(k_out_final, dim3(pos->batch * c.n_q_heads), dim3(kD * kFinalParts), 0, s, a);
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
 
