@@ -1339,7 +1339,7 @@ struct BinsArgs {
 template <int M, int G>
 __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
 {
-    extern __shared__ __attribute__((aligned(8))) unsigned bins[];  // G * M * K; for G >= 2 used as 64-bit pairs
+    extern __shared__ __attribute__((aligned(16))) unsigned bins[];  // G * M * K; for G >= 2 used as 64-bit pairs
     __shared__ float eoff_s[G];
     int id = blockIdx.x;
     const int g = id % a.Hkv;
@@ -1364,7 +1364,6 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
     // words -- 16 different bank pairs whatever their codes, where a [codebook][codeword] layout lets random
     // codes collide.  The pair is an immediate offset, so an atomic costs no address arithmetic of its own.
     constexpr int NP = G >= 2 ? G / 2 : 1;
-    for (int x = tid; x < NB; x += kBinsThreads) bins[x] = 0u;
     // The token's codes and logits are fetched one iteration ahead (the first before the statistics below), so
     // that their latency runs under the previous token's atomics.
     const uint8_t *codes = a.val_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
@@ -1378,6 +1377,7 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         _Pragma("unroll") for (int hh = 0; hh < G; ++hh) snext[hh] = srow[(size_t)hh * L + (i_)];        \
     } while (0)
     if (v0 + tid < v1) COMMVQ_BINS_FETCH(v0 + tid);
+    for (int x = tid; x < NB / 4; x += kBinsThreads) reinterpret_cast<uint4 *>(bins)[x] = make_uint4(0u, 0u, 0u, 0u);
     if (wave < G) {
         const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
         const float2 *st = a.sstat + ((size_t)b * a.Hq + h0 + wave) * a.nsplit;
