@@ -30,6 +30,10 @@ constexpr float kLog2eEm = 1.4426950408889634f;
 
 inline size_t em_align(size_t v) { return (v + 255) / 256 * 256; }
 
+// v_sqrt_f32 as it is (1 ulp): the library square root adds a scaling and a correction step per call, and the
+// E step takes one per (point, centre) pair.
+__device__ __forceinline__ float em_sqrt(float v) { return __builtin_amdgcn_sqrtf(v); }
+
 // dmin[j][i] = min_ab D_i,ab ;  zsum[j][i] = sum_ab exp(-(D_i,ab - dmin) / T)
 __global__ __launch_bounds__(256) void k_em_norm(const float2 *__restrict__ data, const float2 *__restrict__ phi,
                                                  float *__restrict__ dmin, float *__restrict__ zsum, int N, int Nc, float inv_t)
@@ -41,17 +45,21 @@ __global__ __launch_bounds__(256) void k_em_norm(const float2 *__restrict__ data
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     const float2 k = data[(size_t)j * N + i];
-    // one pass with a running minimum: when a nearer centre turns up the partial sum is rescaled
-    float dm = INFINITY, z = 0.f;
+    // two sweeps over the centres: the nearest squared distance first (no square root, no exponential), then the
+    // denominator -- one v_sqrt_f32 and one v_exp_f32 per pair, the quarter-rate instructions that bound this kernel
+    // (a single sweep with a running minimum computes a second exponential per pair for the rescaling)
+    float dm2 = INFINITY;
     for (int a = 0; a < Nc; ++a)
         for (int b = 0; b < Nc; ++b) {
             const float ex = k.x - (ph[a].x - ph[b].y), ey = k.y - (ph[a].y + ph[b].x);
-            const float d = __builtin_sqrtf(ex * ex + ey * ey);
-            if (d < dm) {
-                z *= __builtin_amdgcn_exp2f(-(dm - d) * inv_t * kLog2eEm);  // dm = inf the first time: z stays 0
-                dm = d;
-            }
-            z += __builtin_amdgcn_exp2f(-(d - dm) * inv_t * kLog2eEm);
+            dm2 = fminf(dm2, ex * ex + ey * ey);
+        }
+    const float dm = em_sqrt(dm2), sc = inv_t * kLog2eEm;
+    float z = 0.f;
+    for (int a = 0; a < Nc; ++a)
+        for (int b = 0; b < Nc; ++b) {
+            const float ex = k.x - (ph[a].x - ph[b].y), ey = k.y - (ph[a].y + ph[b].x);
+            z += __builtin_amdgcn_exp2f((dm - em_sqrt(ex * ex + ey * ey)) * sc);
         }
     dmin[(size_t)j * N + i] = dm;
     zsum[(size_t)j * N + i] = z;
@@ -74,6 +82,7 @@ __global__ __launch_bounds__(256) void k_em_accum(const float2 *__restrict__ dat
         cy = pa.y + pb.x;
     }
     float n = 0.f, sx = 0.f, sy = 0.f;
+    const float sc = inv_t * kLog2eEm;
     for (int t0 = 0; t0 < N; t0 += kEmTile) {
         const int cnt = min(kEmTile, N - t0);
         __syncthreads();
@@ -87,7 +96,7 @@ __global__ __launch_bounds__(256) void k_em_accum(const float2 *__restrict__ dat
             for (int x = 0; x < cnt; ++x) {
                 const float2 k = pts[x];
                 const float ex = k.x - cx, ey = k.y - cy;
-                const float w = __builtin_amdgcn_exp2f(-(__builtin_sqrtf(ex * ex + ey * ey) - nz[x].x) * inv_t * kLog2eEm) * nz[x].y;
+                const float w = __builtin_amdgcn_exp2f((nz[x].x - em_sqrt(ex * ex + ey * ey)) * sc) * nz[x].y;
                 n += w;
                 sx = __builtin_fmaf(w, k.x, sx);
                 sy = __builtin_fmaf(w, k.y, sy);
@@ -370,13 +379,13 @@ __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ d
         d2m = fminf(d2m, __shfl_xor(d2m, 8));
         d2m = fminf(d2m, __shfl_xor(d2m, 16));
         d2m = fminf(d2m, __shfl_xor(d2m, 32));
-        const float dm = __builtin_sqrtf(fmaxf(d2m, 0.f));
+        const float dm = em_sqrt(fmaxf(d2m, 0.f));
         float z = 0.f;
         for (int a = q; a < Nc; a += 8) {
             const float ua = ki + u[i * NS + a];
 #pragma unroll 4
             for (int b = 0; b < Nc; ++b) {
-                const float d = __builtin_sqrtf(fmaxf(ua + (v[i * NS + b] + xs[a * Nc + b]), 0.f));
+                const float d = em_sqrt(fmaxf(ua + (v[i * NS + b] + xs[a * Nc + b]), 0.f));
                 z += __builtin_amdgcn_exp2f(-(d - dm) * c);
             }
         }
@@ -408,7 +417,7 @@ __global__ __launch_bounds__(256) void k_ems_assign(const float2 *__restrict__ d
                 for (int e = 0; e < kEmMaxNc / 4; ++e) {
                     const int s2 = sq + 4 * e;
                     if (s2 < Nc) {
-                        const float d = __builtin_sqrtf(fmaxf(base + (other[i * NS + s2] + xr[e]), 0.f));
+                        const float d = em_sqrt(fmaxf(base + (other[i * NS + s2] + xr[e]), 0.f));
                         const float wi = __builtin_amdgcn_exp2f(-(d - dm) * c) * r;
                         nacc[e] += wi;
                         w += wi;
