@@ -419,6 +419,28 @@ def test_decode_attn_replays_from_a_hip_graph(gpu, idx):
     op.close()
 
 
+# ---------------------------------------------------------------- stage timing
+def test_stage_events_are_sampled_and_leave_the_result_alone(gpu):
+    import torch
+    import paper_2506_18879_amd as cv
+    w = synth.config(3, max_len=3000)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    plain = op(dw).clone()
+    cv.commvq_profile_enable(op.handle, 3)      # calls 1, 4 and 7 of the next seven are bracketed with events
+    for _ in range(7):
+        out = op(dw)
+    torch.cuda.synchronize()
+    ms, n = cv.commvq_profile_read(op.handle)
+    assert n == 3 and len(ms) == 3 and all(0.0 < t < 50.0 for t in ms), (ms, n)
+    assert torch.equal(out, plain)
+    cv.commvq_profile_enable(op.handle, 0)
+    op(dw)
+    torch.cuda.synchronize()
+    assert cv.commvq_profile_read(op.handle)[1] == 0
+    op.close()
+
+
 # ---------------------------------------------------------------- argument checking through the C ABI
 def test_error_statuses(gpu):
     import torch
