@@ -38,10 +38,11 @@ typedef enum {
     COMMVQ_OK = 0,
     COMMVQ_ERR_NULL = 1,      /* a required pointer is NULL */
     COMMVQ_ERR_CONFIG = 2,    /* unsupported head_dim / M / K / dtype / head counts */
-    COMMVQ_ERR_SHAPE = 3,     /* batch, total_tokens or max_seqlen inconsistent or < 1 */
+    COMMVQ_ERR_SHAPE = 3,     /* batch, total_tokens or max_seqlen inconsistent, < 1, or beyond what the
+                                 kernels' 32-bit offsets or the phase tables cover; misaligned buffers */
     COMMVQ_ERR_WORKSPACE = 4, /* workspace NULL, misaligned or too small */
     COMMVQ_ERR_LAUNCH = 5,    /* the HIP runtime reported an error (allocation, launch) */
-    COMMVQ_ERR_NO_DEVICE = 6  /* no usable gfx950 device */
+    COMMVQ_ERR_NO_DEVICE = 6  /* the current device is not a gfx950, or the handle is a planner handle */
 } commvq_status;
 
 typedef enum { COMMVQ_F32 = 0, COMMVQ_BF16 = 1 } commvq_dtype;
@@ -69,7 +70,7 @@ typedef struct {
     int32_t codebook_dtype;  /* commvq_dtype of both codebooks */
     double rope_base;        /* > 1; 500000 for LLaMA-3.1 */
     double softmax_scale;    /* 0 selects 1/sqrt(head_dim) (Eq. v1_formula) */
-    int32_t max_position;    /* largest |q_pos - key position| that will occur; sizes the phase tables */
+    int32_t max_position;    /* largest |q_pos - key position| that will occur, <= 2^24; sizes the phase tables */
     int32_t key_format;      /* commvq_key_format; 0 (indexed) keeps every field above as described */
     int32_t key_levels;      /* R, 1..21; COMMVQ_KEYS_PAIRED only (m_key is then ignored; bf16 tables, implicit key positions) */
     int32_t position_free;   /* 1: no rotation at all -- the case Sec. 4.2 sets aside ("R_i independent of i", e.g. keys
@@ -86,7 +87,9 @@ typedef struct {
     const int32_t *q_pos;      /* device [B]: position t of the query token (q <- q R_t) */
     const int32_t *key_pos;    /* device [T] or NULL; NULL means token i of a sequence sits at position i */
     int64_t total_tokens;      /* T = cu_seqlens[B] (host copy, sizes grids without a sync) */
-    int32_t max_seqlen;        /* host copy of max_b L_b */
+    int32_t max_seqlen;        /* host copy of max_b L_b.  With key_pos == NULL the keys sit at 0 .. L_b - 1, and a
+                                  query at or after the last of them is at least max_seqlen - 1 away from the first:
+                                  max_seqlen - 1 > max_position is refused (COMMVQ_ERR_SHAPE) */
 } commvq_positions;
 
 /* How one call is cut into workgroups (host struct, filled by commvq_plan_query). */
@@ -110,7 +113,19 @@ commvq_status commvq_destroy(commvq_handle *handle);
 /* Host-only check of a config (what commvq_create checks before touching the device). */
 commvq_status commvq_validate_config(const commvq_config *config);
 
-/* Host-only: work decomposition and workspace size for a batch shape. */
+/*
+ * A handle without device resources, for hosts that size buffers or vet arguments where no GPU is present
+ * (schedulers, admission checks, CPU-only tests).  commvq_plan_query, commvq_workspace_bytes,
+ * commvq_packed_key_codebook_bytes and commvq_encoder_table_bytes answer as for a full handle; every call that
+ * would launch kernels runs all of its argument checks (pointers are only compared with NULL and tested for
+ * alignment, never dereferenced), and returns COMMVQ_ERR_NO_DEVICE where a full handle would go on to launch.
+ * Freed with commvq_destroy.
+ */
+commvq_status commvq_create_planner(const commvq_config *config, commvq_handle **out);
+
+/* Host-only: work decomposition and workspace size for a batch shape.  COMMVQ_ERR_SHAPE if batch < 1,
+ * max_seqlen < 1, total_tokens outside [max_seqlen, batch * max_seqlen] or above 2^30, or if one (sequence,
+ * KV head) stream (max_seqlen * bytes per token of codes, unpacked pair indices or logits) passes 2^32 - 1 bytes. */
 commvq_status commvq_plan_query(const commvq_handle *handle, int32_t batch, int64_t total_tokens,
                                 int32_t max_seqlen, commvq_plan *plan);
 commvq_status commvq_workspace_bytes(const commvq_handle *handle, int32_t batch, int64_t total_tokens,
@@ -134,8 +149,9 @@ commvq_status commvq_workspace_bytes(const commvq_handle *handle, int32_t batch,
  *                  sequence of (x, y) first rows of its RoPE-commuting 2x2 blocks (Eq. C_struct).
  *                  COMMVQ_KEYS_PAIRED: the tied table [Hkv][R][64][d] bf16, same row convention
  *   val_codebooks  [Hkv][M_v][K][d]
- *   positions      host struct, see above; |q_pos - key position| must not exceed max_position
- *                  (larger distances are clamped: no fault, wrong rotation)
+ *   positions      host struct, see above; |q_pos - key position| must not exceed max_position.  What the host
+ *                  can see of that is checked (see max_seqlen); q_pos and key_pos live on the device, and a
+ *                  distance beyond the tables there is clamped to their last row: no fault, wrong rotation
  *   out            [B][Hq][d] fp32, fully overwritten
  *   workspace      >= commvq_workspace_bytes(...) bytes, 256-byte aligned, contents undefined after
  *   stream         a hipStream_t (NULL = the default stream)

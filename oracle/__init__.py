@@ -159,7 +159,9 @@ def paired_as_indexed(records, R, cu_seqlens, Hkv):
     """Flat packed records (per sequence [Hkv][L_b][PB]) -> flat index-form codes (per sequence [Hkv][L_b][2R]),
     index 2r = a_r, index 2r + 1 = b_r, matching tied_table_as_codebooks."""
     pb = (12 * R + 7) // 8
-    rec = np.ascontiguousarray(records, dtype=np.uint8).reshape(-1, pb)
+    rec = np.ascontiguousarray(records, dtype=np.uint8).reshape(-1)
+    assert rec.size == int(np.asarray(cu_seqlens)[-1]) * Hkv * pb, "records do not match cu_seqlens x Hkv x record bytes"
+    rec = rec.reshape(-1, pb)
     a, b = unpack_key_pairs(rec, R)
     out = np.empty((rec.shape[0], 2 * R), dtype=np.uint8)
     out[:, 0::2], out[:, 1::2] = a, b

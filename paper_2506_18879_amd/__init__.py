@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     Plan,
     Positions,
     commvq_create,
+    commvq_create_planner,
     commvq_decode_attn,
     commvq_destroy,
     commvq_em_shared_workspace_bytes,

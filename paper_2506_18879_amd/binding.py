@@ -37,7 +37,7 @@ class Plan(Structure):
 
 Handle = c_void_p
 
-EXPORTS = ("commvq_create", "commvq_destroy", "commvq_validate_config", "commvq_plan_query", "commvq_workspace_bytes",
+EXPORTS = ("commvq_create", "commvq_create_planner", "commvq_destroy", "commvq_validate_config", "commvq_plan_query", "commvq_workspace_bytes",
            "commvq_decode_attn", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
            "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
            "commvq_encoder_table_bytes", "commvq_encoder_prepare", "commvq_encode_keys",
@@ -61,6 +61,7 @@ def load_library():
     lib.commvq_status_string.argtypes = [ctypes.c_int]
     lib.commvq_validate_config.argtypes = [POINTER(Config)]
     lib.commvq_create.argtypes = [POINTER(Config), POINTER(c_void_p)]
+    lib.commvq_create_planner.argtypes = [POINTER(Config), POINTER(c_void_p)]
     lib.commvq_destroy.argtypes = [c_void_p]
     lib.commvq_plan_query.argtypes = [c_void_p, c_int32, c_int64, c_int32, POINTER(Plan)]
     lib.commvq_workspace_bytes.argtypes = [c_void_p, c_int32, c_int64, c_int32, POINTER(c_size_t)]
@@ -114,6 +115,12 @@ def commvq_validate_config(cfg: Config) -> int:
 def commvq_create(cfg: Config) -> Handle:
     h = c_void_p()
     _check(load_library().commvq_create(byref(cfg), byref(h)), "commvq_create")
+    return h
+
+
+def commvq_create_planner(cfg: Config) -> Handle:
+    h = c_void_p()
+    _check(load_library().commvq_create_planner(byref(cfg), byref(h)), "commvq_create_planner")
     return h
 
 

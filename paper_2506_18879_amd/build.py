@@ -19,8 +19,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 def build(verbose: bool = False) -> str:
     """Compile csrc/*.hip for gfx950 into paper_2506_18879_amd/libcommvq.so."""
-    extra = os.environ.get("COMMVQ_EXTRA_FLAGS", "").split()  # tuning experiments, e.g. -DCOMMVQ_SCORE_CHUNK=8
-    cmd = [HIPCC, *FLAGS, *extra, "-I" + os.path.join(ROOT, "include"), "-o", LIB, *SOURCES]
+    cmd = [HIPCC, *FLAGS, "-I" + os.path.join(ROOT, "include"), "-o", LIB, *SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))

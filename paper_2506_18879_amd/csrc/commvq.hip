@@ -24,6 +24,9 @@
 //     (q^j R_t^j) . (k^j R_p^j) = Re( q^j conj(k^j) exp(-i (t - p) theta_j) ),
 // i.e. only the relative position t - p enters, and the rotation can be applied to the
 // gather-summed codewords once per token (commutativity, Property 1).
+#include <algorithm>
+#include <cstring>
+
 #include "commvq_internal.hpp"
 
 namespace {
@@ -68,7 +71,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         // (about a quarter of the work of 1024 tokens), shorter ones fill the 256 compute units more evenly
         double best = -1.0;
         len = 1024;
-        for (int tpt = 1; tpt <= COMMVQ_SCORE_MAX_TPT; tpt *= 2) {
+        for (int tpt = 1; tpt <= kScoreMaxTpt; tpt *= 2) {
             if (tpt == 4 && h->G == 8 && (h->cfg.m_key == 16 || pair_keys(h->cfg))) break;  // those instantiations run out of registers
             const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt));
             const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
@@ -77,7 +80,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         }
     } else {
         len = 1024;
-        while (len > kScoreThreads && (long)units * ((max_seqlen + len - 1) / len) < COMMVQ_SCORE_MIN_WGS) len /= 2;
+        while (len > kScoreThreads && (long)units * ((max_seqlen + len - 1) / len) < kScoreMinWgs) len /= 2;
     }
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
@@ -164,9 +167,6 @@ __device__ __forceinline__ float row_sum16(float v)
 // inside the 16-lane rows (4 DPP steps per head), parked for 16 iterations and written as
 // one 256-byte run per head.  blockIdx.x % Hkv selects the KV head: consecutive workgroups
 // go to consecutive XCDs, so with 8 KV heads each XCD's L2 serves one head's codebook.
-#ifndef COMMVQ_SCORE_CHUNK
-#define COMMVQ_SCORE_CHUNK 4
-#endif
 
 template <int M, int G, bool BF16>
 __global__ __launch_bounds__(kScoreThreads) void k_score(
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     // Codeword loads are issued in chunks of CH codebooks into two register buffers; the chunk
     // after the one being summed is always in flight (across iterations too), and the codes
     // are fetched two iterations ahead.
-    constexpr int CH = BF16 ? COMMVQ_SCORE_CHUNK : COMMVQ_SCORE_CHUNK / 2;  // codebooks per chunk
+    constexpr int CH = BF16 ? 4 : 2;  // codebooks per chunk
     constexpr int LPC = BF16 ? CH : 2 * CH;                                  // 16-byte loads per chunk
     constexpr int NC = M / CH;
     static_assert(NC % 2 == 0, "buffer parity must repeat every iteration");
@@ -1634,28 +1634,45 @@ __global__ __launch_bounds__(kD * kFinalParts) void k_out_final(OutArgs a)
 }
 
 // ------------------------------------------------------------------ host side
-commvq_status check_positions(const commvq_positions *p)
+// What can be checked of a batch shape from host values alone.
+commvq_status check_shape(const commvq_handle *h, int32_t batch, int64_t total_tokens, int32_t max_seqlen, bool explicit_positions)
+{
+    if (batch < 1 || max_seqlen < 1) return COMMVQ_ERR_SHAPE;
+    if (total_tokens < max_seqlen) return COMMVQ_ERR_SHAPE;
+    if (total_tokens > (int64_t)batch * max_seqlen) return COMMVQ_ERR_SHAPE;
+    if (total_tokens > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
+    // the kernels address one (sequence, KV head)'s codes, unpacked pair indices and logits with 32-bit byte offsets
+    const commvq_config &c = h->cfg;
+    int64_t rec = c.m_val;
+    if (pair_keys(c)) rec = std::max<int64_t>(rec, 32 * pair_blocks(c));
+    else rec = std::max<int64_t>(rec, c.m_key);
+    rec = std::max<int64_t>(rec, 4 * h->G);
+    if ((int64_t)max_seqlen * rec > (int64_t)0xffffffffll) return COMMVQ_ERR_SHAPE;
+    // keys at positions 0 .. L - 1 and the query at or after the last of them: the farthest key is at least
+    // max_seqlen - 1 away, which the phase tables must cover (Eq. rope_ri is exact only inside them)
+    if (!explicit_positions && !c.position_free && (int64_t)max_seqlen - 1 > c.max_position) return COMMVQ_ERR_SHAPE;
+    return COMMVQ_OK;
+}
+
+commvq_status check_positions(const commvq_handle *h, const commvq_positions *p)
 {
     if (!p) return COMMVQ_ERR_NULL;
     if (!p->cu_seqlens || !p->q_pos) return COMMVQ_ERR_NULL;
-    if (p->batch < 1 || p->max_seqlen < 1) return COMMVQ_ERR_SHAPE;
-    if (p->total_tokens < p->max_seqlen) return COMMVQ_ERR_SHAPE;
-    if (p->total_tokens > (int64_t)p->batch * p->max_seqlen) return COMMVQ_ERR_SHAPE;
-    if (p->total_tokens > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
-    return COMMVQ_OK;
+    return check_shape(h, p->batch, p->total_tokens, p->max_seqlen, p->key_pos != nullptr);
 }
 
 commvq_status prep(const commvq_handle *h, const commvq_positions *pos, void *workspace, size_t workspace_bytes,
                    commvq_plan *plan, Workspace *w)
 {
     if (!h) return COMMVQ_ERR_NULL;
-    commvq_status st = check_positions(pos);
+    commvq_status st = check_positions(h, pos);
     if (st != COMMVQ_OK) return st;
     if (pair_keys(h->cfg) && pos->key_pos) return COMMVQ_ERR_CONFIG;  // paired-code keys: contiguous positions only
     make_plan(h, pos->batch, pos->max_seqlen, use_sliced(h, pos->key_pos != nullptr), plan);
     carve(h, pos->batch, pos->total_tokens, pos->max_seqlen, workspace, w);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < w->bytes)
         return COMMVQ_ERR_WORKSPACE;
+    if (h->device < 0) return COMMVQ_ERR_NO_DEVICE;  // planner handle: every argument was acceptable, nothing is launched
     return COMMVQ_OK;
 }
 
@@ -1698,13 +1715,8 @@ hipError_t launch_bins_mg(BinsArgs a, int Gtot, int grid, hipStream_t s)
     a.Gtot = Gtot;
     grid *= Gtot / G;
     const size_t lds = (size_t)G * M * kK * sizeof(unsigned);
-    static bool attr_set = false;  // per instantiation; raising the limit is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bins<M, G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
+    if (hipError_t e = allow_dynamic_lds(&k_bins<M, G>, (int)lds, lds_ok); e != hipSuccess) return e;
     hipLaunchKernelGGL((k_bins<M, G>), dim3(grid), dim3(kBinsThreads), lds, s, a);
     return hipGetLastError();
 }
@@ -1744,13 +1756,8 @@ struct SliceArgs {
 template <int M, int G, int TPT>
 hipError_t launch_sliced_mgt(const SliceArgs &a, int grid, hipStream_t s)
 {
-    static bool attr_set = false;  // per instantiation; raising the limit is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_mfma<M, G, TPT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kScoreLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
+    if (hipError_t e = allow_dynamic_lds(&k_score_mfma<M, G, TPT>, kScoreLds, lds_ok); e != hipSuccess) return e;
     hipLaunchKernelGGL((k_score_mfma<M, G, TPT>), dim3(grid), dim3(kSliceThreads), kScoreLds, s, a.q, a.key_codes,
                        a.packed, a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
     return hipGetLastError();
@@ -1779,13 +1786,8 @@ template <int NB, int G, int TPT>
 hipError_t launch_pair_bgt(const SliceArgs &a, int grid, hipStream_t s)
 {
     constexpr int lds = kPairPlanes * NB * kPairBlock + 8 * kLo * 16 + 8 * (TPT * kSliceThreads / kLo + 1) * 16 + kStatBytes;
-    static bool attr_set = false;  // per instantiation; raising the limit is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_pair<NB, G, TPT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
+    if (hipError_t e = allow_dynamic_lds(&k_score_pair<NB, G, TPT>, lds, lds_ok); e != hipSuccess) return e;
     hipLaunchKernelGGL((k_score_pair<NB, G, TPT>), dim3(grid), dim3(kSliceThreads), lds, s, a.q, a.key_codes, a.packed,
                        a.cu, a.q_pos, a.tbl_hi, a.tbl_lo, a.scores, a.sstat, a.d);
     return hipGetLastError();
@@ -1828,13 +1830,8 @@ hipError_t launch_lut_mgt(const float *lut, const uint8_t *key_codes, const int3
                           const SliceDims &d, int grid, hipStream_t s)
 {
     constexpr int lds = M * kK * (G < 4 ? G : 4) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_lut<M, G, TPT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
+    if (hipError_t e = allow_dynamic_lds(&k_score_lut<M, G, TPT>, lds, lds_ok); e != hipSuccess) return e;
     hipLaunchKernelGGL((k_score_lut<M, G, TPT>), dim3(grid), dim3(kSliceThreads), lds, s, lut, key_codes, cu, scores, sstat, d);
     return hipGetLastError();
 }
@@ -2002,6 +1999,31 @@ commvq_status commvq_validate_config(const commvq_config *c)
     return COMMVQ_OK;
 }
 
+static commvq_handle *new_handle(const commvq_config *config, int device)
+{
+    commvq_handle *h = new (std::nothrow) commvq_handle();
+    if (!h) return nullptr;
+    h->cfg = *config;
+    h->G = config->n_q_heads / config->n_kv_heads;
+    h->scale = (float)(config->softmax_scale > 0.0 ? config->softmax_scale : 1.0 / std::sqrt((double)kD));
+    h->n_hi = (config->max_position >> kLoBits) + 1;
+    h->device = device;
+    h->tbl_hi = h->tbl_lo = nullptr;
+    h->prof_every = 0; h->prof_calls = 0; h->prof_head = h->prof_count = 0; h->prof_ev_made = false;
+    return h;
+}
+
+commvq_status commvq_create_planner(const commvq_config *config, commvq_handle **out)
+{
+    if (!out) return COMMVQ_ERR_NULL;
+    commvq_status st = commvq_validate_config(config);
+    if (st != COMMVQ_OK) return st;
+    commvq_handle *h = new_handle(config, -1);
+    if (!h) return COMMVQ_ERR_LAUNCH;
+    *out = h;
+    return COMMVQ_OK;
+}
+
 commvq_status commvq_create(const commvq_config *config, commvq_handle **out)
 {
     if (!out) return COMMVQ_ERR_NULL;
@@ -2009,15 +2031,11 @@ commvq_status commvq_create(const commvq_config *config, commvq_handle **out)
     if (st != COMMVQ_OK) return st;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return COMMVQ_ERR_NO_DEVICE; }
-    commvq_handle *h = new (std::nothrow) commvq_handle();
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return COMMVQ_ERR_NO_DEVICE; }
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return COMMVQ_ERR_NO_DEVICE;  // the kernels are gfx950 code only
+    commvq_handle *h = new_handle(config, dev);
     if (!h) return COMMVQ_ERR_LAUNCH;
-    h->cfg = *config;
-    h->G = config->n_q_heads / config->n_kv_heads;
-    h->scale = (float)(config->softmax_scale > 0.0 ? config->softmax_scale : 1.0 / std::sqrt((double)kD));
-    h->n_hi = (config->max_position >> kLoBits) + 1;
-    h->device = dev;
-    h->tbl_hi = h->tbl_lo = nullptr;
-    h->prof_every = 0; h->prof_calls = 0; h->prof_head = h->prof_count = 0; h->prof_ev_made = false;
     // exact phases in fp64, rounded once to fp32
     std::vector<float2> hi((size_t)h->n_hi * kJ), lo((size_t)kLo * kJ);
     for (int j = 0; j < kJ; ++j) {
@@ -2052,8 +2070,8 @@ commvq_status commvq_destroy(commvq_handle *h)
     if (h->prof_ev_made)
         for (int i = 0; i < kProfRing; ++i)
             for (int k = 0; k < 4; ++k) (void)hipEventDestroy(h->prof_ev[i][k]);
-    (void)hipFree(h->tbl_hi);
-    (void)hipFree(h->tbl_lo);
+    if (h->tbl_hi) (void)hipFree(h->tbl_hi);
+    if (h->tbl_lo) (void)hipFree(h->tbl_lo);
     delete h;
     return COMMVQ_OK;
 }
@@ -2062,9 +2080,9 @@ commvq_status commvq_plan_query(const commvq_handle *h, int32_t batch, int64_t t
                                 commvq_plan *plan)
 {
     if (!h || !plan) return COMMVQ_ERR_NULL;
-    if (batch < 1 || max_seqlen < 1 || total_tokens < max_seqlen ||
-        total_tokens > (int64_t)batch * max_seqlen)
-        return COMMVQ_ERR_SHAPE;
+    // explicit key positions are not known here: the distance check belongs to the calls that see them
+    const commvq_status st = check_shape(h, batch, total_tokens, max_seqlen, true);
+    if (st != COMMVQ_OK) return st;
     make_plan(h, batch, max_seqlen, use_sliced(h, false), plan);
     return COMMVQ_OK;
 }
@@ -2095,6 +2113,7 @@ commvq_status commvq_pack_key_codebooks(commvq_handle *h, const void *key_cb, vo
     if (!h || !key_cb || !packed) return COMMVQ_ERR_NULL;
     if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
     if ((reinterpret_cast<uintptr_t>(key_cb) | reinterpret_cast<uintptr_t>(packed)) & 15u) return COMMVQ_ERR_SHAPE;
+    if (h->device < 0) return COMMVQ_ERR_NO_DEVICE;
     if (launch_prep(h->cfg, key_cb, static_cast<uint4 *>(packed), static_cast<hipStream_t>(stream)) != hipSuccess)
         return COMMVQ_ERR_LAUNCH;
     for (auto &e : h->packed_keys)

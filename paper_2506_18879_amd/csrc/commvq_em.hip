@@ -21,6 +21,7 @@
 #include <cstdint>
 
 #include "commvq.h"
+#include "commvq_launch.hpp"
 
 namespace {
 
@@ -554,7 +555,9 @@ extern "C" {
 commvq_status commvq_em_workspace_bytes(int32_t n_subspaces, int32_t n_points, int32_t n_centres, size_t *bytes)
 {
     if (!bytes) return COMMVQ_ERR_NULL;
-    if (n_subspaces < 1 || n_points < 1 || n_centres < 1 || n_centres > kEmMaxNc) return COMMVQ_ERR_SHAPE;
+    // sub-spaces are the y dimension of the launch grids (at most 65535); point indices are 32-bit
+    if (n_subspaces < 1 || n_subspaces > 65535 || n_points < 1 || n_points > (1 << 24) || n_centres < 1 || n_centres > kEmMaxNc)
+        return COMMVQ_ERR_SHAPE;
     const size_t pts = (size_t)n_subspaces * n_points, cen = (size_t)n_subspaces * n_centres * n_centres;
     *bytes = 2 * em_align(pts * 4) + em_align(cen * 4) + em_align(cen * 8);
     return COMMVQ_OK;
@@ -587,13 +590,9 @@ commvq_status commvq_em_step(const float *data, int32_t n_subspaces, int32_t n_p
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
     const int np = (2 * n_centres + 15) / 16 * 16;  // the system padded to whole 16-column blocks
     const int lds = (np * (np + 1) + np + np * 16) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_em_solve), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (2 * kEmMaxNc * (2 * kEmMaxNc + 1) + 2 * kEmMaxNc + 2 * kEmMaxNc * 16) * 4) != hipSuccess)
-            return COMMVQ_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(&k_em_solve, (2 * kEmMaxNc * (2 * kEmMaxNc + 1) + 2 * kEmMaxNc + 2 * kEmMaxNc * 16) * 4, lds_ok) != hipSuccess)
+        return COMMVQ_ERR_LAUNCH;
     hipLaunchKernelGGL(k_em_solve, dim3((unsigned)n_subspaces), dim3(256), lds, s, nab, sab, p2, n_centres);
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
@@ -631,15 +630,11 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
     const int lds_a = ((((J * Nc * 2 > Nc * Nc ? J * Nc * 2 : Nc * Nc) + 1) & ~1) + kEmsPts * (J + 1) * 2 + 2 * kEmsPts * (Nc + 1) + 3 * kEmsPts) * 4;
     const int np_s = (2 * Nc + 15) / 16 * 16;
     const int lds_s = (np_s * (np_s + 1) + np_s * kEmsSolveCols + np_s * 16) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const int max_a = (64 * 64 * 2 + kEmsPts * 65 * 2 + 2 * kEmsPts * 65 + 3 * kEmsPts) * 4;
-        const int max_s = (128 * 129 + 128 * kEmsSolveCols + 128 * 16) * 4;
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_assign), hipFuncAttributeMaxDynamicSharedMemorySize, max_a) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ems_solve), hipFuncAttributeMaxDynamicSharedMemorySize, max_s) != hipSuccess)
-            return COMMVQ_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok_a{0}, lds_ok_s{0};
+    const int max_a = (64 * 64 * 2 + kEmsPts * 65 * 2 + 2 * kEmsPts * 65 + 3 * kEmsPts) * 4;
+    const int max_s = (128 * 129 + 128 * kEmsSolveCols + 128 * 16) * 4;
+    if (allow_dynamic_lds(&k_ems_assign, max_a, lds_ok_a) != hipSuccess || allow_dynamic_lds(&k_ems_solve, max_s, lds_ok_s) != hipSuccess)
+        return COMMVQ_ERR_LAUNCH;
     hipLaunchKernelGGL(k_ems_assign, dim3((unsigned)l.n_wg), dim3(256), lds_a, s, d2, p2, xab, nn, nab_part, wa, wb, N, J, Nc,
                        kLog2eEm / temperature);
     if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;

@@ -641,6 +641,7 @@ commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void 
 {
     if (!h || !key_cb || !tables) return COMMVQ_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(tables) & 15u) return COMMVQ_ERR_SHAPE;
+    if (h->device < 0) return COMMVQ_ERR_NO_DEVICE;
     const commvq_config &c = h->cfg;
     const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
     const int levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
@@ -676,46 +677,27 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
     if (paired && !bf16) return COMMVQ_ERR_CONFIG;
+    if (h->device < 0) return COMMVQ_ERR_NO_DEVICE;
     if (paired && n_tokens >= kEbTokens) {  // many tokens: 64 per workgroup, dot products on the matrix cores
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_pair_batch), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kEpLds) != hipSuccess)
-                return COMMVQ_ERR_LAUNCH;
-            attr_set = true;
-        }
+        static std::atomic<uint64_t> lds_ok{0};
+        if (allow_dynamic_lds(&k_encode_pair_batch, kEpLds, lds_ok) != hipSuccess) return COMMVQ_ERR_LAUNCH;
         const dim3 bgrid((unsigned)((n_tokens + kEbTokens - 1) / kEbTokens * c.n_kv_heads));
         hipLaunchKernelGGL(k_encode_pair_batch, bgrid, dim3(256), kEpLds, s, keys, static_cast<const uint4 *>(key_cb), norms, cross,
                            codes_out, d, n_tokens);
     } else if (paired) {  // rows, norms and cross terms staged in LDS, next level prefetched
         const int lds = (2 * K * kEncRowDw + 2 * K * K + 2 * K + kD + 256 + 8 + 32) * 4;
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_lds<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-                return COMMVQ_ERR_LAUNCH;
-            attr_set = true;
-        }
+        static std::atomic<uint64_t> lds_ok{0};
+        if (allow_dynamic_lds(&k_encode_lds<true>, lds, lds_ok) != hipSuccess) return COMMVQ_ERR_LAUNCH;
         hipLaunchKernelGGL(k_encode_lds<true>, grid, dim3(256), lds, s, keys, static_cast<const unsigned *>(key_cb), norms, cross, codes_out, d);
     } else if (bf16 && n_tokens >= kEbTokens) {  // many tokens: rows staged once per 64 tokens, dot products on the matrix cores
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_batch), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kEbLds) != hipSuccess)
-                return COMMVQ_ERR_LAUNCH;
-            attr_set = true;
-        }
+        static std::atomic<uint64_t> lds_ok{0};
+        if (allow_dynamic_lds(&k_encode_batch, kEbLds, lds_ok) != hipSuccess) return COMMVQ_ERR_LAUNCH;
         const dim3 bgrid((unsigned)((n_tokens + kEbTokens - 1) / kEbTokens * c.n_kv_heads));
         hipLaunchKernelGGL(k_encode_batch, bgrid, dim3(256), kEbLds, s, keys, static_cast<const uint4 *>(key_cb), norms, codes_out, d,
                            n_tokens);
     } else if (bf16) {  // few tokens: next level's rows on their way into LDS while this level is searched
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_dma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kEdLds) != hipSuccess)
-                return COMMVQ_ERR_LAUNCH;
-            attr_set = true;
-        }
+        static std::atomic<uint64_t> lds_ok{0};
+        if (allow_dynamic_lds(&k_encode_dma, kEdLds, lds_ok) != hipSuccess) return COMMVQ_ERR_LAUNCH;
         hipLaunchKernelGGL(k_encode_dma, grid, dim3(256), kEdLds, s, keys, static_cast<const uint4 *>(key_cb), norms, codes_out, d);
     } else {
         hipLaunchKernelGGL(k_encode<false>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "commvq.h"
+#include "commvq_launch.hpp"
 
 namespace {
 
@@ -18,16 +19,9 @@ constexpr int kJ = 64;          // 2-D sub-spaces = lanes of a wavefront
 constexpr int kK = 256;         // codewords per codebook
 constexpr int kLoBits = 6;      // relative position = hi * 64 + lo
 constexpr int kLo = 1 << kLoBits;
-#ifndef COMMVQ_SCORE_MAX_TPT
-#define COMMVQ_SCORE_MAX_TPT 4
-#endif
-#ifndef COMMVQ_SCORE_MIN_WGS
-#define COMMVQ_SCORE_MIN_WGS 2048
-#endif
-#ifndef COMMVQ_SCORE_THREADS
-#define COMMVQ_SCORE_THREADS 256
-#endif
-constexpr int kScoreThreads = COMMVQ_SCORE_THREADS;
+constexpr int kScoreMaxTpt = 4;      // slice-streaming score tile: at most 4 x 1024 tokens
+constexpr int kScoreMinWgs = 2048;   // row-gather score kernel: tiles are halved until this many workgroups exist
+constexpr int kScoreThreads = 256;
 constexpr int kBinsThreads = 1024;
 constexpr int kOutThreads = 256;
 constexpr int kMaxValueSplits = 256;  // value_splits never exceeds 256 / (batch * KV heads), at least 1
@@ -46,7 +40,7 @@ struct commvq_handle {
     int G;
     float scale;
     int n_hi;
-    int device;
+    int device;      // device ordinal of the phase tables; -1 for a planner handle (no device resources)
     float2 *tbl_hi;  // [n_hi][64]  exp(i * theta_j * 64 * hi)
     float2 *tbl_lo;  // [64][64]    exp(i * theta_j * lo)
     int prof_every, prof_calls;  // stage events on every prof_every-th call (0: never)

@@ -87,3 +87,147 @@ def test_no_cpu_fallback():
     w = synth.make_workload("t", B=1, Hq=4, Hkv=1, seqlens=[8], Mk=16, Mv=16, dtype="bf16", seed=1)
     with pytest.raises(RuntimeError):
         DeviceWorkload(w)
+
+
+# ---------------------------------------------------------------- planner handle: host logic without a GPU
+@pytest.fixture()
+def planner():
+    made = []
+
+    def make(**kw):
+        h = cv.commvq_create_planner(good_cfg(**kw))
+        made.append(h)
+        return h
+
+    yield make
+    for h in made:
+        cv.commvq_destroy(h)
+
+
+def status_of(fn, *a, **kw):
+    try:
+        fn(*a, **kw)
+    except cv.CommVQError as e:
+        return e.status
+    return 0
+
+
+def test_planner_plans_the_five_configurations(planner):
+    # (config kwargs, batch, total tokens, longest sequence) -> tile of the slice-streaming kernel, one value
+    # workgroup per compute unit, bins x codebook chunks of 64 rows
+    cases = [
+        (dict(n_q_heads=1, n_kv_heads=1, m_key=32, m_val=32, q_dtype=0, codebook_dtype=0, max_position=4096), 1, 4096, 4096),
+        (dict(m_key=32, m_val=32), 1, 32768, 32768),
+        (dict(m_key=16, m_val=16), 1, 131072, 131072),
+        (dict(m_key=32, m_val=32), 8, 300000, 65536),
+        (dict(n_q_heads=64, m_key=32, m_val=16), 4, 4 * 131072, 131072),
+    ]
+    for kw, B, T, L in cases:
+        h = planner(**kw)
+        p = cv.commvq_plan_query(h, B, T, L)
+        assert p.score_split_len in (256, 512, 1024, 2048, 4096)
+        assert p.score_splits == -(-L // p.score_split_len)
+        assert p.value_splits == -(-L // p.value_split_len) and 1 <= p.value_splits <= 256
+        assert p.value_split_len % max(p.score_split_len, 1024) == 0 or p.score_kernel == 0
+        assert p.out_chunks == kw.get("m_val", 32) * 256 // 64
+        assert p.score_kernel == (0 if kw.get("codebook_dtype", 1) == 0 else 1)
+        ws = cv.commvq_workspace_bytes(h, B, T, L)
+        assert ws % 256 == 0 and ws >= 4 * T * kw.get("n_q_heads", 32)          # at least the logits
+    # the workspace grows with the batch
+    h = planner()
+    assert cv.commvq_workspace_bytes(h, 2, 20000, 10000) > cv.commvq_workspace_bytes(h, 1, 10000, 10000)
+
+
+@pytest.mark.parametrize("B,T,L", [(0, 10, 10), (1, 0, 0), (1, 10, 11), (2, 30, 10), (1, (1 << 30) + 1, (1 << 30) + 1)])
+def test_planner_rejects_inconsistent_shapes(planner, B, T, L):
+    h = planner(max_position=1 << 24)
+    assert status_of(cv.commvq_plan_query, h, B, T, L) == 3
+    assert status_of(cv.commvq_workspace_bytes, h, B, T, L) == 3
+
+
+def test_one_head_stream_must_fit_32_bit_offsets(planner):
+    # 2^27 tokens x 32 code bytes = 2^32: one past what a 32-bit byte offset reaches
+    h = planner(m_key=32, m_val=32, max_position=1 << 24)
+    assert status_of(cv.commvq_plan_query, h, 1, 1 << 27, 1 << 27) == 3
+    assert status_of(cv.commvq_plan_query, h, 1, (1 << 27) - 1, (1 << 27) - 1) == 0
+    h16 = planner(m_key=16, m_val=16, n_q_heads=8, n_kv_heads=8, max_position=1 << 24)
+    assert status_of(cv.commvq_plan_query, h16, 1, 1 << 27, 1 << 27) == 0
+    # eight heads of fp32 logits per token are 32 bytes as well
+    h8 = planner(m_key=16, m_val=16, n_q_heads=64, n_kv_heads=8, max_position=1 << 24)
+    assert status_of(cv.commvq_plan_query, h8, 1, 1 << 27, 1 << 27) == 3
+
+
+class _Buf:
+    """Stands in for a device buffer: the planner handle only looks at the address."""
+
+    def __init__(self, addr):
+        self.addr = addr
+
+    def data_ptr(self):
+        return self.addr
+
+
+def _call_args(h, B=1, T=5000, L=5000, key_pos=None, ws_slack=0, ws_addr=1 << 20, code_addr=1 << 21):
+    ws = cv.commvq_workspace_bytes(h, B, T, L)
+    pos = cv.binding.make_positions(B, _Buf(4096), _Buf(8192), key_pos, T, L)
+    return dict(q=_Buf(1 << 16), key_codes=_Buf(code_addr), val_codes=_Buf(1 << 22), key_codebooks=_Buf(1 << 23),
+                val_codebooks=_Buf(1 << 24), positions=pos, out=_Buf(1 << 25), workspace=_Buf(ws_addr),
+                workspace_bytes=ws + ws_slack)
+
+
+def test_decode_attn_argument_checks_run_before_any_launch(planner):
+    h = planner()
+    call = lambda **a: status_of(cv.commvq_decode_attn, h, a["q"], a["key_codes"], a["val_codes"], a["key_codebooks"],
+                                 a["val_codebooks"], a["positions"], a["out"], a["workspace"], a["workspace_bytes"])
+    assert call(**_call_args(h)) == 6                                   # all fine: a full handle would launch here
+    for missing in ("q", "key_codes", "val_codes", "key_codebooks", "val_codebooks", "out"):
+        a = _call_args(h)
+        a[missing] = None
+        assert call(**a) == 1, missing
+    a = _call_args(h)
+    a["positions"] = cv.binding.make_positions(1, None, _Buf(8192), None, 5000, 5000)
+    assert call(**a) == 1
+    assert call(**_call_args(h, code_addr=(1 << 21) + 8)) == 3          # codes not 16-byte aligned
+    assert call(**_call_args(h, ws_slack=-1)) == 4                      # one byte short
+    assert call(**_call_args(h, ws_addr=(1 << 20) + 128)) == 4          # not 256-byte aligned
+    a = _call_args(h)
+    a["workspace"] = None
+    assert call(**a) == 4
+    a = _call_args(h)
+    a["positions"] = cv.binding.make_positions(2, _Buf(4096), _Buf(8192), None, 5000, 2000)   # 5000 > 2 x 2000
+    assert call(**a) == 3
+
+
+def test_context_longer_than_the_phase_tables_is_refused(planner):
+    h = planner(max_position=4095)
+    call = lambda **a: status_of(cv.commvq_decode_attn, h, a["q"], a["key_codes"], a["val_codes"], a["key_codebooks"],
+                                 a["val_codebooks"], a["positions"], a["out"], a["workspace"], a["workspace_bytes"])
+    assert call(**_call_args(h, T=4096, L=4096)) == 6
+    assert call(**_call_args(h, T=4097, L=4097)) == 3                   # token 0 would be 4096 away from the query
+    # explicit key positions are the caller's to bound; the position-free variant has no rotation at all
+    assert call(**_call_args(h, T=4097, L=4097, key_pos=_Buf(1 << 26))) == 6
+    hf = planner(max_position=0, position_free=1)
+    assert status_of(cv.commvq_plan_query, hf, 1, 9000, 9000) == 0
+
+
+def test_paired_keys_refuse_explicit_positions_and_size_their_tables(planner):
+    h = planner(key_format=cv.COMMVQ_KEYS_PAIRED, key_levels=11, m_key=0)
+    a = _call_args(h, key_pos=_Buf(1 << 26))
+    assert status_of(cv.commvq_decode_attn, h, a["q"], a["key_codes"], a["val_codes"], a["key_codebooks"],
+                     a["val_codebooks"], a["positions"], a["out"], a["workspace"], a["workspace_bytes"]) == 2
+    assert cv.commvq_packed_key_codebook_bytes(h) == 8 * 16 * 1 * 64 * 256        # 16 planes x 1 block of 16 KiB per head
+    assert cv.commvq_encoder_table_bytes(h) == 8 * 11 * 64 * 4 * (1 + 64)         # norms + cross terms
+    hi = planner(m_key=16)
+    assert cv.commvq_packed_key_codebook_bytes(hi) == 8 * 16 * 256 * 128 * 2
+    assert cv.commvq_encoder_table_bytes(hi) == 8 * 16 * 256 * 4
+    assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 8, 16) == 3
+    assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 128, 16) == 6
+    assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 0, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 128, 16) == 3
+
+
+def test_em_sizes_are_bounded():
+    assert cv.commvq_em_workspace_bytes(64, 8192, 64) > 0
+    for bad in ((0, 10, 4), (65536, 10, 4), (4, 0, 4), (4, (1 << 24) + 1, 4), (4, 10, 0), (4, 10, 65)):
+        assert status_of(cv.commvq_em_workspace_bytes, *bad) == 3, bad
+    for bad in ((0, 10, 4), (65, 10, 4), (4, 0, 4), (4, 10, 65)):
+        assert status_of(cv.commvq_em_shared_workspace_bytes, *bad) == 3, bad

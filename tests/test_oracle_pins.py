@@ -420,6 +420,89 @@ def test_tied_table_decodes_to_appendix_centres(oracle):
     assert np.abs(blk @ Rm - Rm @ blk).max() < 1e-15
 
 
+def _pack_records_by_hand(a, b):
+    """Packs pairs with Python integers only (independent of synth's and the oracle's bit code): pair r of a
+    record is bits 12 r .. 12 r + 11, a in the low 6 bits (the byte layout chosen for App. A.1's s = {a, b})."""
+    a = np.asarray(a)
+    b = np.asarray(b)
+    R = a.shape[-1]
+    pb = (12 * R + 7) // 8
+    out = np.zeros(a.shape[:-1] + (pb,), np.uint8)
+    for idx in np.ndindex(*a.shape[:-1]):
+        word = 0
+        for r in range(R):
+            word |= (int(a[idx + (r,)]) | int(b[idx + (r,)]) << 6) << (12 * r)
+        out[idx] = list(word.to_bytes(pb, "little"))
+    return out
+
+
+def test_paired_as_indexed_hand_built_layout(oracle):
+    # 2 sequences (2 tokens and 1 token) x 2 KV heads, R = 2, every a and b different: the index form must be, per
+    # sequence, [Hkv][L_b][2R] with (a_0, b_0, a_1, b_1) per token -- a swapped a / b or a transposed head / token
+    # order changes the vector
+    Hkv, R, lens = 2, 2, [2, 1]
+    cu = np.array([0, 2, 3], np.int32)
+    flat_rec, want = [], []
+    nxt = 1
+    for L in lens:
+        a = np.zeros((Hkv, L, R), np.uint8)
+        b = np.zeros((Hkv, L, R), np.uint8)
+        for g in range(Hkv):
+            for i in range(L):
+                for r in range(R):
+                    a[g, i, r], b[g, i, r] = nxt, nxt + 1
+                    want += [nxt, nxt + 1]
+                    nxt += 2
+        flat_rec.append(_pack_records_by_hand(a, b).reshape(-1))
+    got = oracle.paired_as_indexed(np.concatenate(flat_rec), R, cu, Hkv)
+    assert got.dtype == np.uint8 and got.tolist() == want
+    assert want[:4] == [1, 2, 3, 4]          # token 0 of head 0 of sequence 0: a_0, b_0, a_1, b_1
+    with pytest.raises(AssertionError):      # a record count that does not match cu_seqlens x Hkv is refused
+        oracle.paired_as_indexed(np.concatenate(flat_rec)[:-3], R, cu, Hkv)
+
+
+def test_paired_records_attention_vs_complex_brute_force(oracle):
+    # The whole paired route (records -> paired_as_indexed + tied_table_as_codebooks -> the fp64 oracle) against
+    # a brute force that never leaves the paired form: a key is sum_r z[r][a_r] + i z[r][b_r] per sub-space
+    # (Eq. def_center, z = x + i y), RoPE is z e^{-i p theta_j} (Sec. 3.2, row vector times R), the logit is
+    # Re(q~ conj(k~)) / sqrt(d) summed over the sub-spaces (Eq. v1_formula).  z_a + i z_b != z_b + i z_a, so a
+    # swapped interleave fails; two ragged sequences and two KV heads make a wrong layout fail.
+    rng = np.random.default_rng(11)
+    Hq, Hkv, d, R, N, Mv, K = 4, 2, 8, 3, 64, 2, 256
+    lens = [5, 3]
+    cu = np.array([0, 5, 8], np.int32)
+    q_pos = np.array([9, 2], np.int32)
+    table = rng.standard_normal((Hkv, R, N, d))
+    val_cb = rng.standard_normal((Hkv, Mv, K, d))
+    q = rng.standard_normal((2, Hq, d))
+    recs, vcodes, ab = [], [], []
+    for L in lens:
+        a = rng.integers(0, N, (Hkv, L, R))
+        b = rng.integers(0, N, (Hkv, L, R))
+        ab.append((a, b))
+        recs.append(_pack_records_by_hand(a, b).reshape(-1))
+        vcodes.append(rng.integers(0, K, (Hkv, L, Mv)).astype(np.uint8))
+    got = oracle.decode_attn(q, oracle.paired_as_indexed(np.concatenate(recs), R, cu, Hkv),
+                             np.concatenate([v.reshape(-1) for v in vcodes]),
+                             oracle.tied_table_as_codebooks(table, K=K), val_cb, cu, q_pos, rope_base=BASE)
+    theta = BASE ** (-2.0 * np.arange(d // 2) / d)
+    z = table[..., 0::2] + 1j * table[..., 1::2]                                  # [Hkv][R][N][d/2]
+    for bi, L in enumerate(lens):
+        a, b = ab[bi]
+        for h in range(Hq):
+            g = h // (Hq // Hkv)
+            qz = (q[bi, h, 0::2] + 1j * q[bi, h, 1::2]) * np.exp(-1j * q_pos[bi] * theta)
+            logits = np.empty(L)
+            vals = np.empty((L, d))
+            for i in range(L):
+                kz = sum(z[g, r, a[g, i, r]] + 1j * z[g, r, b[g, i, r]] for r in range(R)) * np.exp(-1j * i * theta)
+                logits[i] = (qz * np.conj(kz)).real.sum() / math.sqrt(d)
+                vals[i] = sum(val_cb[g, m, vcodes[bi][g, i, m]] for m in range(Mv))
+            w = np.exp(logits - logits.max())
+            want = (w / w.sum()) @ vals
+            assert np.abs(got[bi, h] - want).max() < 1e-12
+
+
 # ---------------------------------------------------------------- key encoding (cache append)
 def test_encode_single_level_is_the_library_nearest_centre(oracle):
     # one level = plain vector quantization: scipy's vq returns the nearest code and its distance
@@ -498,9 +581,12 @@ def test_em_weights_are_a_softmax_and_centres_follow_def_center(oracle):
     hard, _ = oracle.em_step(data, phi, temperature=None)
     soft, _ = oracle.em_step(data, phi, temperature=1e-4)
     assert np.abs(hard - soft).max() < 1e-6
+    # the E step's weights (Eq. W) are the library softmax of -D / T, and one-hot on the nearest centre without T
     D = np.sqrt(((data[:, None] - cen[None]) ** 2).sum(-1))
-    W = softmax(-D / 0.3, axis=1)
-    assert np.abs(W.sum(axis=1) - 1).max() < 1e-14
+    W = oracle._em_assign(D.copy(), 0.3)
+    assert np.abs(W - softmax(-D / 0.3, axis=1)).max() < 1e-15
+    H = oracle._em_assign(D.copy(), None)
+    assert (H.sum(axis=1) == 1).all() and np.array_equal(H.argmax(axis=1), D.argmin(axis=1))
 
 
 def test_em_m_step_is_the_weighted_least_squares_minimum(oracle):
