@@ -1,7 +1,10 @@
 """GPU parity: libcommvq (through its C ABI) against the fp64 CPU oracle, element by element.
 
-Bar: per (sequence, head) row, max |out - ref| / max |ref| <= 2e-3 on the attention output;
-logits from the score stage within 2e-5 absolute (fp32 accumulation of ~4k terms of order 1).
+Contract: per (sequence, head) row, max |out - ref| / max |ref| <= 2e-3 on the attention output; logits from the
+score stage within 2e-5 absolute (fp32 accumulation of ~4k terms of order 1).  Beside the contract every case also
+has to stay within a regression bar ten times the error observed when the kernels were written (2e-6 per row):
+2e-5 per row, and 2e-2 element by element relative to max(|ref|, 1e-3 max|ref|) (outputs are sign-mixed and pass
+through zero, so a pure element-wise relative error is not defined).
 """
 import numpy as np
 import pytest
@@ -10,7 +13,10 @@ from paper_2506_18879_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-TOL_OUT = 2e-3
+TOL_OUT = 2e-3        # the contract
+TOL_REGRESS = 2e-5    # ten times the observed row error
+TOL_ELEM = 2e-2       # element-wise, with the floor below
+ELEM_FLOOR = 1e-3
 TOL_SCORE = 2e-5
 
 
@@ -35,6 +41,22 @@ def row_err(got, ref):
     return np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
 
 
+def elem_err(got, ref):
+    got = np.asarray(got, np.float64)
+    floor = ELEM_FLOOR * np.abs(ref).max(axis=-1, keepdims=True)
+    return np.abs(got - ref) / np.maximum(np.abs(ref), floor)
+
+
+def assert_rows(got, ref, what="", regress=TOL_REGRESS):
+    """The contract and the regression bars on a set of output rows; returns the largest row error."""
+    assert np.isfinite(np.asarray(got)).all(), what
+    e, el = float(row_err(got, ref).max()), float(elem_err(got, ref).max())
+    assert e <= TOL_OUT, (what, "contract", e)
+    assert e <= regress, (what, "regression bar", e)
+    assert el <= 1e3 * regress, (what, "element-wise regression bar", el)
+    return e
+
+
 def run_gpu(gpu, w, staged=False, **kw):
     import torch
     dw = gpu.DeviceWorkload(w)
@@ -46,14 +68,12 @@ def run_gpu(gpu, w, staged=False, **kw):
     return res
 
 
-def check(gpu, oracle, w, tol=TOL_OUT, **kw):
+def check(gpu, oracle, w, regress=TOL_REGRESS, **kw):
     print(f"case {w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} Mk={w.Mk} Mv={w.Mv} lens={np.diff(w.cu_seqlens)[:8]}", flush=True)
     got = run_gpu(gpu, w, **kw)
     ref = oracle_out(oracle, w)
-    assert np.isfinite(got).all()
-    err = row_err(got, ref)
-    print(f"  max row error {err.max():.3e}", flush=True)
-    assert err.max() <= tol, (w.name, err.max())
+    err = assert_rows(got, ref, w.name, regress)
+    print(f"  max row error {err:.3e}, element-wise (floor {ELEM_FLOOR:g}) {elem_err(got, ref).max():.3e}", flush=True)
     return got, ref
 
 
@@ -145,10 +165,7 @@ def test_every_combination_of_group_size_and_code_widths(gpu, oracle, dtype):
                 w = synth.make_workload(f"all_g{G}_k{Mk}_v{Mv}_{dtype}", B=2, Hq=G, Hkv=1, seqlens=[333, 1090], Mk=Mk, Mv=Mv,
                                         dtype=dtype, seed=1000 * G + 10 * Mk + Mv)
                 print(f"case {w.name}", flush=True)
-                got = run_gpu(gpu, w)
-                err = row_err(got, oracle_out(oracle, w)).max()
-                assert np.isfinite(got).all() and err <= TOL_OUT, (w.name, err)
-                worst = max(worst, err)
+                worst = max(worst, assert_rows(run_gpu(gpu, w), oracle_out(oracle, w), w.name))
     print(f"  worst row error {worst:.3e}", flush=True)
 
 
@@ -192,7 +209,7 @@ def test_batch_with_empty_sequences(gpu, oracle):
                              np.concatenate([[0], np.cumsum([lens[b] for b in keep])]).astype(np.int32), w.q_pos[keep],
                              rope_base=w.rope_base, n_threads=4)
     assert np.isfinite(got).all()
-    assert row_err(got[keep], ref).max() <= TOL_OUT
+    assert_rows(got[keep], ref, "empties")
     for b, L in enumerate(lens):
         if L == 0:
             assert not got[b].any()
@@ -270,16 +287,11 @@ def oracle_out_paired(oracle, w, **kw):
 @pytest.mark.parametrize("R", [11, 21, 3, 16, 17])
 @pytest.mark.parametrize("G,Hkv", [(4, 2), (1, 2), (8, 1), (2, 1)])
 def test_paired_keys_match_oracle(gpu, oracle, R, G, Hkv):
-    if R in (3, 16, 17) and G != 4:
-        pytest.skip("odd level counts are covered at G = 4")
     w = synth.make_pair_workload(f"pair_R{R}_g{G}", B=2, Hq=G * Hkv, Hkv=Hkv, seqlens=[1500, 333], R=R, Mv=16,
                                  seed=1000 + 10 * R + G)
     print(f"case {w.name}", flush=True)
-    got = run_gpu(gpu, w)
-    ref = oracle_out_paired(oracle, w)
-    err = row_err(got, ref)
-    print(f"  max row error {err.max():.3e}", flush=True)
-    assert np.isfinite(got).all() and err.max() <= TOL_OUT
+    err = assert_rows(run_gpu(gpu, w), oracle_out_paired(oracle, w), w.name)
+    print(f"  max row error {err:.3e}", flush=True)
 
 
 @pytest.mark.parametrize("R,L", [(11, 1), (11, 255), (11, 257), (21, 1025), (11, 5000), (21, 4097)])
@@ -294,7 +306,7 @@ def test_paired_keys_lengths_and_logits(gpu, oracle, R, L):
     torch.cuda.synchronize()
     ref, ref_scores, _ = oracle_out_paired(oracle, w, return_intermediates=True)
     assert np.abs(s.cpu().numpy().astype(np.float64) - ref_scores).max() <= TOL_SCORE
-    assert row_err(out.cpu().numpy(), ref).max() <= TOL_OUT
+    assert_rows(out.cpu().numpy(), ref, w.name)
     # packing the tied table ahead of time changes nothing
     op.pack_key_codebooks(dw)
     out2 = op(dw).clone()
@@ -308,7 +320,7 @@ def test_paired_keys_query_inside_context_and_rejections(gpu, oracle):
     w = synth.make_pair_workload("pair_qpos", B=2, Hq=8, Hkv=2, seqlens=[2100, 900], R=11, Mv=16, seed=5)
     w.q_pos = np.array([700, 60000], np.int32)
     got = run_gpu(gpu, w, max_position=70000)
-    assert row_err(got, oracle_out_paired(oracle, w)).max() <= TOL_OUT
+    assert_rows(got, oracle_out_paired(oracle, w), w.name)
     # explicit key positions are not supported with paired keys; neither are fp32 tables or R > 21
     dw = gpu.DeviceWorkload(w)
     op = gpu.DecodeAttention(w, max_position=70000)
@@ -344,9 +356,8 @@ def test_paired_keys_full_size_sampled_units(gpu, oracle, idx, units):
     worst = 0.0
     for u in np.flatnonzero(mask):
         b, g = divmod(int(u), w.Hkv)
-        worst = max(worst, row_err(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G]).max())
+        worst = max(worst, assert_rows(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G], f"{w.name} unit {u}"))
     print(f"  worst row error over {units} units: {worst:.3e}", flush=True)
-    assert worst <= TOL_OUT
 
 
 # ---------------------------------------------------------------- position-free keys (scalar look-up table)
@@ -359,7 +370,7 @@ def oracle_out_position_free(oracle, w, **kw):
 
 
 @pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 1), (4, 2), (8, 1)])
-@pytest.mark.parametrize("Mk,dtype", [(16, "bf16"), (32, "bf16"), (32, "f32")])
+@pytest.mark.parametrize("Mk,dtype", [(16, "bf16"), (32, "bf16"), (32, "f32"), (16, "f32")])
 def test_position_free_scalar_lut(gpu, oracle, G, Hkv, Mk, dtype):
     import torch
     w = synth.make_workload(f"lut_g{G}_m{Mk}_{dtype}", B=2, Hq=G * Hkv, Hkv=Hkv, seqlens=[2300, 517], Mk=Mk, Mv=16,
@@ -372,7 +383,7 @@ def test_position_free_scalar_lut(gpu, oracle, G, Hkv, Mk, dtype):
     torch.cuda.synchronize()
     ref, ref_scores, _ = oracle_out_position_free(oracle, w, return_intermediates=True)
     assert np.abs(s.cpu().numpy().astype(np.float64) - ref_scores).max() <= TOL_SCORE
-    assert row_err(out.cpu().numpy(), ref).max() <= TOL_OUT
+    assert_rows(out.cpu().numpy(), ref, w.name)
     op.close()
 
 
@@ -380,7 +391,7 @@ def test_position_free_scalar_lut(gpu, oracle, G, Hkv, Mk, dtype):
 def test_position_free_lengths(gpu, oracle, L):
     w = synth.make_workload(f"lut_L{L}", B=1, Hq=8, Hkv=2, seqlens=[L], Mk=16, Mv=32, dtype="bf16", seed=600 + L)
     got = run_gpu(gpu, w, position_free=True)
-    assert row_err(got, oracle_out_position_free(oracle, w)).max() <= TOL_OUT
+    assert_rows(got, oracle_out_position_free(oracle, w), w.name)
 
 
 # ---------------------------------------------------------------- HIP graph capture of the whole call
@@ -491,7 +502,5 @@ def test_full_size_sampled_units(gpu, oracle, idx, units):
     worst = 0.0
     for u in np.flatnonzero(mask):
         b, g = divmod(int(u), w.Hkv)
-        e = row_err(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G]).max()
-        worst = max(worst, e)
+        worst = max(worst, assert_rows(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G], f"{w.name} unit {u}"))
     print(f"  worst row error over {units} units: {worst:.3e}", flush=True)
-    assert worst <= TOL_OUT
