@@ -163,6 +163,25 @@ commvq_status commvq_decode_attn(commvq_handle *handle, const void *q, const uin
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * commvq_decode_attn for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results, but the workspace is a static device array inside the library (48 MiB on every GPU the library is
+ * loaded on, held until the process ends; commvq_static_scratch_bytes reports the size).  The call allocates
+ * nothing, creates no events (commvq_profile_enable is ignored here) and clears nothing with memset.
+ *   COMMVQ_ERR_WORKSPACE  the batch shape needs more than the array holds (commvq_workspace_bytes tells how much a
+ *                         shape needs; key codebooks packed ahead of time do not need their share of it, but the
+ *                         size check still counts it)
+ *   COMMVQ_ERR_NO_DEVICE  the current device is not the one the handle was created on
+ * Every call on a GPU uses that GPU's one array, and the array keeps the previous call's contents: calls that
+ * overlap in time on one GPU (two streams, two handles, two threads) race.  Run them one after the other, or use
+ * commvq_decode_attn with separate workspaces.
+ */
+commvq_status commvq_decode_attn_static(commvq_handle *handle, const void *q, const uint8_t *key_codes,
+                                        const uint8_t *val_codes, const void *key_codebooks, const void *val_codebooks,
+                                        const commvq_positions *positions, float *out, void *stream);
+commvq_status commvq_static_scratch_bytes(size_t *bytes /* host */);
+
+/*
  * Optional one-time preparation of static key codebooks (they are per-layer constants, Sec. 4.1).
  * The score kernel for bf16 codebooks streams the key codebook through LDS in slices of
  * 256 / M_k elements (Eq. new_attention is evaluated slice by slice) and wants it in that order.

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     commvq_create,
     commvq_create_planner,
     commvq_decode_attn,
+    commvq_decode_attn_static,
     commvq_destroy,
     commvq_em_shared_workspace_bytes,
     commvq_em_step,
@@ -35,6 +36,7 @@ from .binding import (  # noqa: F401
     commvq_stage_bins,
     commvq_stage_output,
     commvq_stage_scores,
+    commvq_static_scratch_bytes,
     commvq_status_string,
     commvq_validate_config,
     commvq_workspace_bytes,

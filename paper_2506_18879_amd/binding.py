@@ -38,7 +38,7 @@ class Plan(Structure):
 Handle = c_void_p
 
 EXPORTS = ("commvq_create", "commvq_create_planner", "commvq_destroy", "commvq_validate_config", "commvq_plan_query", "commvq_workspace_bytes",
-           "commvq_decode_attn", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
+           "commvq_decode_attn", "commvq_decode_attn_static", "commvq_static_scratch_bytes", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
            "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
            "commvq_encoder_table_bytes", "commvq_encoder_prepare", "commvq_encode_keys",
            "commvq_em_workspace_bytes", "commvq_em_step", "commvq_em_shared_workspace_bytes", "commvq_em_step_shared",
@@ -67,6 +67,9 @@ def load_library():
     lib.commvq_workspace_bytes.argtypes = [c_void_p, c_int32, c_int64, c_int32, POINTER(c_size_t)]
     lib.commvq_decode_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, POINTER(Positions),
                                        c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.commvq_decode_attn_static.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, POINTER(Positions),
+                                              c_void_p, c_void_p]
+    lib.commvq_static_scratch_bytes.argtypes = [POINTER(c_size_t)]
     lib.commvq_stage_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, POINTER(Positions), c_void_p, c_size_t,
                                         c_void_p, c_void_p]
     lib.commvq_stage_bins.argtypes = [c_void_p, c_void_p, POINTER(Positions), c_void_p, c_size_t, c_void_p]
@@ -150,6 +153,19 @@ def commvq_decode_attn(handle, q, key_codes, val_codes, key_codebooks, val_codeb
     _check(load_library().commvq_decode_attn(handle, _ptr(q), _ptr(key_codes), _ptr(val_codes), _ptr(key_codebooks),
                                              _ptr(val_codebooks), byref(positions), _ptr(out), _ptr(workspace),
                                              int(workspace_bytes), stream or None), "commvq_decode_attn")
+
+
+def commvq_decode_attn_static(handle, q, key_codes, val_codes, key_codebooks, val_codebooks, positions: Positions, out,
+                              stream: int = 0) -> None:
+    _check(load_library().commvq_decode_attn_static(handle, _ptr(q), _ptr(key_codes), _ptr(val_codes), _ptr(key_codebooks),
+                                                    _ptr(val_codebooks), byref(positions), _ptr(out), stream or None),
+           "commvq_decode_attn_static")
+
+
+def commvq_static_scratch_bytes() -> int:
+    n = c_size_t()
+    _check(load_library().commvq_static_scratch_bytes(byref(n)), "commvq_static_scratch_bytes")
+    return int(n.value)
 
 
 def commvq_packed_key_codebook_bytes(handle) -> int:

@@ -29,6 +29,13 @@
 
 #include "commvq_internal.hpp"
 
+// Scratch memory of commvq_decode_attn_static: the workspace of a call, held by the library itself so that the
+// entry point allocates nothing.  One copy per GPU the library is loaded on, for the life of the process.  In host
+// code this name is only a stand-in for the symbol: the device address is looked up once per device in
+// commvq_create (hipGetSymbolAddress) and kept in the handle; kernels receive that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 struct Workspace {
@@ -2009,6 +2016,7 @@ static commvq_handle *new_handle(const commvq_config *config, int device)
     h->n_hi = (config->max_position >> kLoBits) + 1;
     h->device = device;
     h->tbl_hi = h->tbl_lo = nullptr;
+    h->static_scratch = nullptr;
     h->prof_every = 0; h->prof_calls = 0; h->prof_head = h->prof_count = 0; h->prof_ev_made = false;
     return h;
 }
@@ -2053,6 +2061,10 @@ commvq_status commvq_create(const commvq_config *config, commvq_handle **out)
               hipMalloc(reinterpret_cast<void **>(&h->tbl_lo), lo.size() * sizeof(float2)) == hipSuccess &&
               hipMemcpy(h->tbl_hi, hi.data(), hi.size() * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->tbl_lo, lo.data(), lo.size() * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+    // this device's address of the static scratch array (every GPU holds its own copy at its own address)
+    void *sp = nullptr;
+    ok = ok && hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) == hipSuccess && sp != nullptr;
+    h->static_scratch = sp;
     if (!ok) {
         (void)hipGetLastError();
         if (h->tbl_hi) (void)hipFree(h->tbl_hi);
@@ -2218,6 +2230,35 @@ commvq_status commvq_decode_attn(commvq_handle *h, const void *q, const uint8_t 
         h->prof_head = (h->prof_head + 1) % kProfRing;
         if (h->prof_count < kProfRing) ++h->prof_count;
     }
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_decode_attn_static(commvq_handle *h, const void *q, const uint8_t *key_codes, const uint8_t *val_codes,
+                                        const void *key_cb, const void *val_cb, const commvq_positions *pos, float *out,
+                                        void *stream)
+{
+    if (!h || !q || !key_codes || !val_codes || !key_cb || !val_cb || !out) return COMMVQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(key_codes) | reinterpret_cast<uintptr_t>(val_codes)) & 15u) return COMMVQ_ERR_SHAPE;
+    commvq_plan plan;
+    Workspace w;
+    // the handle's copy of the scratch array is the workspace; a batch shape that needs more than the array holds
+    // comes back as COMMVQ_ERR_WORKSPACE from the same check that vets a caller's workspace
+    commvq_status st = prep(h, pos, h->device < 0 ? reinterpret_cast<void *>(256) : h->static_scratch, kStaticScratchBytes, &plan, &w);
+    if (st != COMMVQ_OK) return st;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != h->device) return COMMVQ_ERR_NO_DEVICE;  // the array of another GPU
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = run_scores(h, q, key_codes, key_cb, pos, plan, w, s);
+    if (st != COMMVQ_OK) return st;
+    st = run_bins(h, val_codes, pos, plan, w, s);
+    if (st != COMMVQ_OK) return st;
+    return run_output(h, val_cb, pos, plan, w, out, s);
+}
+
+commvq_status commvq_static_scratch_bytes(size_t *bytes)
+{
+    if (!bytes) return COMMVQ_ERR_NULL;
+    *bytes = kStaticScratchBytes;
     return COMMVQ_OK;
 }
 

@@ -43,6 +43,7 @@ struct commvq_handle {
     int device;      // device ordinal of the phase tables; -1 for a planner handle (no device resources)
     float2 *tbl_hi;  // [n_hi][64]  exp(i * theta_j * 64 * hi)
     float2 *tbl_lo;  // [64][64]    exp(i * theta_j * lo)
+    void *static_scratch;  // this device's copy of the library's static scratch array (commvq_decode_attn_static)
     int prof_every, prof_calls;  // stage events on every prof_every-th call (0: never)
     int prof_head, prof_count;
     hipEvent_t prof_ev[kProfRing][4];

@@ -231,3 +231,17 @@ def test_em_sizes_are_bounded():
         assert status_of(cv.commvq_em_workspace_bytes, *bad) == 3, bad
     for bad in ((0, 10, 4), (65, 10, 4), (4, 0, 4), (4, 10, 65)):
         assert status_of(cv.commvq_em_shared_workspace_bytes, *bad) == 3, bad
+
+
+def test_static_scratch_entry_point_checks_its_arguments(planner):
+    h = planner(max_position=1 << 23)
+    a = _call_args(h)
+    call = lambda pos, **kw: status_of(cv.commvq_decode_attn_static, h, kw.get("q", a["q"]), a["key_codes"], a["val_codes"],
+                                       a["key_codebooks"], a["val_codebooks"], pos, a["out"])
+    assert cv.commvq_static_scratch_bytes() == 48 << 20
+    assert call(a["positions"]) == 6                                     # acceptable: a full handle would launch
+    assert call(a["positions"], q=None) == 1
+    big = cv.binding.make_positions(1, _Buf(4096), _Buf(8192), None, 4_000_000, 4_000_000)
+    assert cv.commvq_workspace_bytes(h, 1, 4_000_000, 4_000_000) > cv.commvq_static_scratch_bytes()
+    assert call(big) == 4                                                # more than the static array holds
+    assert call(cv.binding.make_positions(1, _Buf(4096), _Buf(8192), None, 0, 0)) == 3
