@@ -345,13 +345,18 @@ def main():
     kname = "k_score_pair" if paired else ("k_score_mfma" if w.dtype == "bf16" else "k_score")
     if args.position_free:
         kname = "k_score_lut"
-    traffic = None
+    # HBM bytes per launch from rocprofv3 counter passes (FETCH_SIZE, WRITE_SIZE) of this same command: counters
+    # cannot be read from inside the process, so the figures are the stored ones of the committed passes
+    traffic, stored = None, {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(w.name, {}).get(kname)
+            stored = json.load(open(tpath)).get(w.name, {})
+            traffic = stored.get(kname)
         except Exception:
-            traffic = None
+            traffic, stored = None, {}
+    traffic_source = ("stored: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE passes over this command)"
+                      if traffic is not None else None)
     key_stream_gbs = w.key_codes.nbytes / score_s / 1e9 if score_s > 0 else 0.0
     # the pipes the kernel actually loads: codeword pieces gathered from LDS, and the matrix instructions that
     # sum them: 256 issued flop per 16-byte piece (mostly multiplications by zero), as one dense 16x16x32 bf16 MFMA
@@ -362,6 +367,7 @@ def main():
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if paired else 2.0 * MFMA_BF16_PEAK_TFLOPS
     roofline = {"kernel": kname, "bound": "alu", "achieved": round(achieved_tflops, 3), "peak": FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved_tflops / FP32_PEAK_TFLOPS, 4), "traffic": traffic,
+                "traffic_source": traffic_source,
                 "kernel_ms": round(stage_ms[0], 5), "launches_averaged": n_prof,
                 "launches_sampled": ("every call of a separate eager run" if args.graph else
                                      f"every {args.stage_event_interval}th call of the timed region"),
@@ -382,11 +388,28 @@ def main():
         roofline = {"kernel": kname, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel_ms": round(stage_ms[0], 5),
                     "launches_averaged": n_prof, "timed_region_includes": "k_lut_build + k_score_lut"}
+    # the two stages that can be judged against HBM: the value stage streams the value codes (and re-reads the
+    # logits), the output stage reads the bins of every value split and the value codebook once per sequence
+    bins_s, out_s = stage_ms[1] * 1e-3, stage_ms[2] * 1e-3
+    val_gbs = w.val_codes.nbytes / bins_s / 1e9 if bins_s > 0 else 0.0
+    bins_alg = w.val_codes.nbytes + T * w.Hq * 4
+    out_alg = op.plan.value_splits * w.B * w.Hq * w.Mv * w.K * 4 + w.B * w.val_codebooks.nbytes
+    stage_views = {
+        "value_stream_view": {"stage": "k_bins", "value_code_GBs": round(val_gbs, 1),
+                              "frac_of_hbm_peak": round(val_gbs / HBM_PEAK_GBS, 4),
+                              "with_logits_read_GBs": round(bins_alg / bins_s / 1e9, 1) if bins_s > 0 else 0.0,
+                              "counter_bytes": stored.get("k_bins"), "stage_ms": round(stage_ms[1], 5)},
+        "output_view": {"stage": "k_out + k_out_final", "bins_and_codebook_GBs": round(out_alg / out_s / 1e9, 1) if out_s > 0 else 0.0,
+                        "frac_of_hbm_peak": round(out_alg / out_s / 1e9 / HBM_PEAK_GBS, 4) if out_s > 0 else 0.0,
+                        "counter_bytes": (stored.get("k_out", 0) + stored.get("k_out_final", 0)) or None,
+                        "stage_ms": round(stage_ms[2], 5)}}
+    alg_bytes = per_copy + w.B * w.Hq * w.d * (esz + 4)
+    call_counter = sum(v for k, v in stored.items() if isinstance(v, (int, float)) and (k != "k_prep" or not prepacked)) or None
     result = {
         "metric": "decode-attention context tokens/sec per layer at 128K; % of HBM roofline",
         "value": round(tokens_per_s, 1), "unit": "context tokens/s per layer", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f32 arithmetic on bf16 storage" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "context_tokens": T, "m_key": w.Mk, "m_val": w.Mv, "codewords": w.K, "storage": w.dtype,
                    "key_format": w.key_format, "key_levels": w.key_levels, "position_free": bool(args.position_free),
@@ -396,10 +419,14 @@ def main():
         "whole_call": {"code_stream_GBs": round(code_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "algorithmic_GBs": round((per_copy + w.B * w.Hq * w.d * (esz + 4)) / (ms_per_step * 1e-3) / 1e9, 1),
                        "code_stream_frac_of_hbm_peak": round(code_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "algorithmic_bytes": alg_bytes, "counter_bytes": call_counter,
+                       "counter_over_algorithmic": round(call_counter / alg_bytes, 2) if call_counter else None,
+                       "counter_source": traffic_source,
                        "stage_ms": {"scores": round(stage_ms[0], 5), "bins": round(stage_ms[1], 5),
                                     "output": round(stage_ms[2], 5)}},
         "roofline": roofline,
     }
+    result["roofline"].update(stage_views)
 
     if not args.no_cpu_baseline:
         import oracle

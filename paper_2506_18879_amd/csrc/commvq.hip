@@ -406,7 +406,7 @@ constexpr int kSliceThreads = 1024;              // one workgroup per compute un
 constexpr int kSliceBytes = 128 * 1024;          // LDS bytes of one codebook slice
 constexpr int kPhaseBytes = (4 * 64 + 4 * 65) * 16;  // LDS bytes of the slice's phase factors (at most)
 constexpr int kStatBytes = (kSliceThreads / 64) * 8 * 8;  // per-wavefront (max, sum) of up to 8 heads
-constexpr int kScoreLds = kSliceBytes + kPhaseBytes + kStatBytes;
+constexpr int kScoreLds = kSliceBytes + 2 * kPhaseBytes + kStatBytes;  // the phase factors are double-buffered
 
 // Key codebook re-laid for k_score_mfma.
 //   packed[g][s][blk][c][col] : 16-byte pieces (8 bf16).  Slice s holds elements DS*s .. DS*s + DS-1 of
@@ -524,33 +524,46 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
     extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [2][K][16] 16-byte pieces, then the phase factors
     float4 *elo = reinterpret_cast<float4 *>(tab + kSliceBytes / 16);  // [PARTS][64]  exp(i theta_j lo), this slice's j
-    float4 *ehi = elo + PARTS * kLo;                                   // [PARTS][NHR] exp(i theta_j 64 H), H = Hmin + row
+    float4 *ehi = elo + PARTS * kLo;                                   // [NHR][PARTS] exp(i theta_j 64 H), H = Hmin + row
     // the slice sits at LDS address 0 (no static LDS in this kernel), so gather addresses need no base added
-    float2(*wstat)[G] = reinterpret_cast<float2(*)[G]>(reinterpret_cast<char *>(tab) + kSliceBytes + kPhaseBytes);  // [NW][G]
+    float2(*wstat)[G] = reinterpret_cast<float2(*)[G]>(reinterpret_cast<char *>(tab) + kSliceBytes + 2 * kPhaseBytes);  // [NW][G]
 
     int id = blockIdx.x;
     const int g = id % a.Hkv;
     id /= a.Hkv;
     const int tile = id % a.nsplit;
     const int b = id / a.nsplit;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // The first slice of the head's codebook depends on nothing but the workgroup index: it is requested before the
+    // sequence's bounds are even known, so that its (cold) fetch, that of the bounds and that of the tile's codes
+    // overlap.  Later slices are fetched into the same registers while the last pass of the current one finishes (its
+    // gather registers are dead by then).
+    constexpr int PIECES = P * M * kK;
+    constexpr int PPT = PIECES / kSliceThreads;
+    const uint4 *src = packed + (size_t)g * S * P * M * kK;
+    const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(src, (unsigned)S * PIECES * 16u);
+    uint4_t stage[PPT];
+    auto fetch_slice = [&](int sl) {
+#pragma unroll
+        for (int x = 0; x < PPT; ++x)
+            stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, (unsigned)sl * (PIECES * 16u), 0);
+    };
+    constexpr bool PREFETCH = !(M == 32 && G == 8 && TPT == 4);  // that instantiation has no registers to spare
+    if (PREFETCH) fetch_slice(0);
     const int cu0 = cu[b];
     const int L = cu[b + 1] - cu0;
     const int t0 = tile * TILE;
     if (t0 >= L) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, gk = lane >> 4;
     const int par = gk & 1;                                   // odd / even codebook of a gather step
     const int set = gk >> 1;                                  // M = 32: which 16-token set the lane gathers for
     const int el = M == 16 ? 4 * gk : 4 * par;                // first of the lane's 4 slice elements
     const int qpos = q_pos[b];
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
-    const uint4 *src = packed + (size_t)g * S * P * M * kK;
     const __amdgpu_buffer_rsrc_t cd_rs = make_rsrc(codes, (unsigned)L * M);
     const unsigned qesz = a.q_bf16 ? 2u : 4u;
     const __amdgpu_buffer_rsrc_t q_rs =
         make_rsrc(static_cast<const char *>(q) + ((size_t)b * a.Hq + (size_t)g * G) * kD * qesz, (unsigned)G * kD * qesz);
-    constexpr int PIECES = P * M * kK;
-    constexpr int PPT = PIECES / kSliceThreads;
 
     // Selection operand of v_smfmac_f32_16x16x64_bf16 (first operand structured-sparse: two of every four
     // consecutive k kept, 2-bit positions in an index register).  Its second operand takes two 16-byte pieces per
@@ -612,38 +625,113 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     // lane's first token (the one whose logits it ends up with); it is re-read through an opaque copy in every
     // slice so that nothing that depends on a token index (code loads, table offsets) is hoisted out of the slice
     // loop.  M = 32: the lane gathers for tokens tb - 16 set and tb - 16 set + 16.
-    int tb = t0 + wave * (16 * SETS) + n + 16 * (M == 16 ? 0 : set);
-    unsigned cw[2][CW];
+    int tb = t0 + 4 * wave + (n >> 2) + kLo * ((n & 3) + (M == 16 ? 0 : 4 * set));
+    constexpr int PSTRIDE = 4 * kLo * SETS;  // tokens between two passes of a lane: a whole number of coarse rows
+    // byte offset of the codes the lane gathers in pass 0 (M = 32: of the first of its two tokens, the second is
+    // 4 coarse rows further on); refreshed with tb in every slice
+    unsigned code_off = (unsigned)(tb - (M == 16 ? 0 : 4 * kLo * set)) * M + (M == 16 ? 8u * par : 16u * hi + 8u * par);
     auto fetch_codes = [&](int p, unsigned(&dst)[CW]) {
+        // tokens past the end of the sequence read zeros (the descriptor ends with the sequence): code 0, a valid row
         if (M == 16) {  // bytes 8 par .. + 7 of the token's codes
-            const int tok = min(tb + p * NW * 16, L - 1);
-            const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * M + 8u * par, 0, 0);
+            const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, code_off + (unsigned)(p * PSTRIDE * M), 0, 0);
             dst[0] = c2[0]; dst[1] = c2[1];
         } else {        // bytes 16 hi + 8 par .. + 7 of both tokens
 #pragma unroll
             for (int v = 0; v < 2; ++v) {
-                const int tok = min(tb - 16 * set + 16 * v + p * NW * 32, L - 1);
-                const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * M + 16u * hi + 8u * par, 0, 0);
+                const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, code_off + (unsigned)((p * PSTRIDE + 4 * kLo * v) * M), 0, 0);
                 dst[2 * v + 0] = c2[0]; dst[2 * v + 1] = c2[1];
             }
         }
     };
-    fetch_codes(0, cw[0]);
+    // cc[v][h]: rotated code bytes 4 h .. 4 h + 3 of token v (M = 16: one token, steps 0..3 only): what the gather
+    // addresses of a pass are made from.
+    constexpr int CV = M == 16 ? 1 : 2;
+    auto make_cc = [&](const unsigned(&c)[CW], unsigned(&cc)[CV][CV]) {
+        if (M == 16) {
+            cc[0][0] = __builtin_amdgcn_perm(c[1], c[0], rsel_lo);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                cc[v][0] = __builtin_amdgcn_perm(c[2 * v + 1], c[2 * v], rsel_lo);
+                cc[v][CV - 1] = __builtin_amdgcn_perm(c[2 * v + 1], c[2 * v], rsel_hi);
+            }
+        }
+    };
+    // The codes of the whole tile are read ONCE and stay in registers, in gather order (ccall[p] = cc of pass p), for
+    // all slices: a per-pass fetch has to cover the latency of a load that misses L1 in every slice (the tile's codes
+    // are 64 KiB or more), which a look-ahead of two passes does not, and it re-reads the tile's codes once per slice.
+    // Only the first slice streams them (STREAM0): its pass p turns the codes of pass p + 1 into ccall[p + 1] and
+    // requests those of pass p + 3, so that the cold fetch of the codes hides behind the first slice's arithmetic.
+    // Raw codes in flight: those of passes 0 and 1 (requested here) wait in the ccall slots of the LAST passes, which
+    // are not written until the raw values have long been used; later ones in the first registers of the slice
+    // staging buffer, idle between the slice's LDS write and the last pass.
+    constexpr bool STREAM0 = NPASS >= 4;
+    constexpr int RAWS = NPASS * CV * CV / CW;                // ccall slots that one pass's raw codes take (2 or 1)
+    unsigned ccall[NPASS][CV][CV];
+    auto raw_slot = [&](int k, unsigned(&dst)[CW]) {          // raw codes of pass k (0 or 1): copy out of their parking slots
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            const int flat = (NPASS * CV * CV - 2 * CW) + k * CW + i;
+            dst[i] = ccall[flat / (CV * CV)][(flat / CV) % CV][flat % CV];
+        }
+    };
+    if (STREAM0) {
+        unsigned r0[CW], r1[CW];
+        fetch_codes(0, r0);
+        fetch_codes(1, r1);
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            const int f0 = (NPASS * CV * CV - 2 * CW) + i, f1 = f0 + CW;
+            ccall[f0 / (CV * CV)][(f0 / CV) % CV][f0 % CV] = r0[i];
+            ccall[f1 / (CV * CV)][(f1 / CV) % CV][f1 % CV] = r1[i];
+        }
+    } else {
+        unsigned craw[NPASS][CW];
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) fetch_codes(p, craw[p]);
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) make_cc(craw[p], ccall[p]);
+    }
+    (void)RAWS;
     const int hmin = (qpos - (t0 + TILE - 1)) >> kLoBits;     // coarse row of the tile's last token (arithmetic shift)
     const unsigned elo_base = (unsigned)kSliceBytes + (unsigned)(M == 16 ? gk : par) * (kLo * 16u);
-    const unsigned ehi_base = (unsigned)kSliceBytes + (unsigned)(PARTS * kLo) * 16u + (unsigned)(M == 16 ? gk : par) * (NHR * 16u);
+    const unsigned ehi_base = (unsigned)kSliceBytes + (unsigned)(PARTS * kLo) * 16u + (unsigned)(M == 16 ? gk : par) * 16u;
 
-    // The next slice is fetched into registers while the last pass of the current one finishes (its
-    // gather registers are dead by then).
-    const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(src, (unsigned)S * PIECES * 16u);
-    uint4_t stage[PPT];
-    auto fetch_slice = [&](int sl) {
-#pragma unroll
-        for (int x = 0; x < PPT; ++x)
-            stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, (unsigned)sl * (PIECES * 16u), 0);
+    // Phase factors of a slice's sub-spaces, two buffers of [PARTS * 64 fine entries][NHR * PARTS coarse entries]:
+    // the fine table as it is, and the rows of the coarse table that the tile's distances q_pos - token can reach,
+    // row-major, so that the four coarse rows and the parts that the lanes of a read touch are 16 consecutive 16-byte
+    // pieces (no bank conflicts).  Thread t < PARTS * 64 moves fine entry t, the next PARTS * NHR threads one coarse
+    // entry each.  Where no distance of the tile is negative the entries go from memory straight into LDS, a whole
+    // slice ahead; a negative distance takes the conjugate of the row of its absolute value, which needs a register.
+    const bool DMA_OK = hmin >= 0;
+    auto phase_src = [&](int sl, bool &neg) -> const float2 * {
+        neg = false;
+        if (tid < PARTS * kLo) {
+            const int part = tid / kLo, lo = tid % kLo;
+            return tbl_lo + (size_t)lo * kJ + sl * NJ + 2 * part;
+        }
+        const int x = tid - PARTS * kLo;
+        const int part = x % PARTS, H = hmin + x / PARTS;
+        neg = H < 0;
+        return tbl_hi + (size_t)min(H < 0 ? -H : H, a.n_hi - 1) * kJ + sl * NJ + 2 * part;
     };
-    constexpr bool PREFETCH = !(M == 32 && G == 8 && TPT == 4);  // that instantiation has no registers to spare
-    if (PREFETCH) fetch_slice(0);
+    static_assert(PARTS * kLo + PARTS * NHR <= kSliceThreads && (PARTS * kLo) % 64 == 0, "one phase entry per thread");
+    auto dma_phase = [&](int sl, int buf) {
+        if (tid < PARTS * kLo + PARTS * NHR) {
+            bool neg;
+            const float2 *srcp = phase_src(sl, neg);
+            lds_dma16(srcp, __builtin_amdgcn_readfirstlane((unsigned)kSliceBytes + (unsigned)buf * kPhaseBytes + (unsigned)wave * 1024u));
+        }
+    };
+    auto stage_phase = [&](int sl, int buf) {
+        if (tid < PARTS * kLo + PARTS * NHR) {
+            bool neg;
+            float4 e = *reinterpret_cast<const float4 *>(phase_src(sl, neg));
+            if (neg) { e.y = -e.y; e.w = -e.w; }
+            elo[(size_t)buf * (kPhaseBytes / 16) + tid] = e;
+        }
+    };
+    if (DMA_OK) dma_phase(0, 0);
 
     for (int sl = 0; sl < S; ++sl) {
         if (!PREFETCH) fetch_slice(sl);
@@ -663,21 +751,14 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         __syncthreads();  // everyone is done reading the previous slice
 #pragma unroll
         for (int x = 0; x < PPT; ++x) reinterpret_cast<uint4_t *>(tab)[x * kSliceThreads + tid] = stage[x];
-        // phase factors of this slice's sub-spaces: the fine table as it is, and the rows of the coarse
-        // table that the tile's distances q_pos - token can reach, conjugated where the distance is negative
-        if (tid < PARTS * kLo) {
-            const int part = tid / kLo, lo = tid % kLo;
-            elo[tid] = *reinterpret_cast<const float4 *>(tbl_lo + (size_t)lo * kJ + sl * NJ + 2 * part);
-        }
-        for (int x = tid; x < PARTS * NHR; x += kSliceThreads) {
-            const int part = x / NHR, H = hmin + x % NHR;
-            const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
-            float4 e = *reinterpret_cast<const float4 *>(tbl_hi + (size_t)hi * kJ + sl * NJ + 2 * part);
-            if (H < 0) { e.y = -e.y; e.w = -e.w; }
-            ehi[x] = e;
-        }
+        if (!DMA_OK) stage_phase(sl, sl & 1);
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this slice's phase factors (sent a slice ago) are in LDS
         __syncthreads();
+        // the phase factors of the next slice travel into the other phase buffer while this slice is worked on
+        if (DMA_OK) dma_phase(min(sl + 1, S - 1), (sl + 1) & 1);
+        const unsigned ph_off = (unsigned)(sl & 1) * kPhaseBytes;
         asm volatile("" : "+v"(tb));
+        code_off = (unsigned)(tb - (M == 16 ? 0 : 4 * kLo * set)) * M + (M == 16 ? 8u * par : 16u * hi + 8u * par);
         // byte offsets (in the LDS phase tables) of the lane's part, and its distance to the query, times 16
         const int dist16 = (qpos - tb) * 16;
         // scaled queries of this slice
@@ -695,56 +776,109 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 }
             }
         }
-        // the passes of a lane are a whole number of coarse rows (64 tokens) apart: one fine phase factor serves
-        // them all, and the coarse row steps down by a constant
-        static_assert((NW * 16 * SETS) % kLo == 0, "pass stride in whole coarse rows");
-        const uint4_t elr = lds_read_b128(elo_base + (unsigned)(dist16 & ((kLo - 1) * 16)));
-        const unsigned ehi_last = ehi_base + (unsigned)(((dist16 >> (kLoBits + 4)) - hmin - (NPASS - 1) * (NW * 16 * SETS / kLo)) * 16);
+        // The tokens of a lane (one per pass) and of the four lanes of a 4-lane block are whole coarse rows (64
+        // tokens) apart: they share the fine phase factor E_lo, so it is folded into the block's query operand
+        // once per slice, q' = q conj(E_lo) (Re(conj(q) a E_hi E_lo) = Re(conj(q') a E_hi)), and a pass only rotates
+        // by the coarse factor, whose row steps down by a constant from pass to pass.
+        static_assert(PSTRIDE % kLo == 0, "pass stride in whole coarse rows");
+        {
+            const uint4_t elr = lds_read_b128(elo_base + ph_off + (unsigned)(dist16 & ((kLo - 1) * 16)));
+#pragma unroll
+            for (int x = 0; x < NGRP; ++x)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const unsigned lxr = elr[2 * u], lyr = elr[2 * u + 1];
+                    const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
+                    const float qx = qrow[x][2 * u], qy = qrow[x][2 * u + 1];
+                    qrow[x][2 * u] = qx * lx + qy * ly;
+                    qrow[x][2 * u + 1] = qy * lx - qx * ly;
+                }
+        }
+        const unsigned ehi_last = ehi_base + ph_off + (unsigned)(((dist16 >> (kLoBits + 4)) - hmin - (NPASS - 1) * (PSTRIDE / kLo)) * (16 * PARTS));
+        // per step two LDS reads (pieces A and B) and one sparse MFMA; reads in groups of RG steps, two groups in flight
+        constexpr int RG = (G == 8 && TPT == 4) ? 1 : 2, NG = NST / RG;  // fewer reads in flight where registers are short
+        uint4_t v[2][RG][2];
+        auto issue = [&](int grp, const unsigned(&cc)[CV][CV], uint4_t(&dst)[RG][2]) {
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                const int st = grp * RG + r;
+#pragma unroll
+                for (int ab = 0; ab < 2; ++ab) {
+                    // address bytes: [0] column, [1] code byte st % 4 of its dword, [2] block, [3] zero.  M = 16: block =
+                    // plane = ab (xreg bytes 2, 3 hold 0, 1); M = 32: block = hi (xreg byte 2), the code is token ab's
+                    const unsigned sel = 0x0c000000u | (unsigned)(M == 16 ? 2 + ab : 2) << 16 | (unsigned)(4 + st % 4) << 8;
+                    const unsigned addr = __builtin_amdgcn_perm(cc[M == 16 ? 0 : ab][M == 16 ? 0 : st / 4], xreg[st], sel);
+                    dst[r][ab] = lds_read_b128(addr);
+                }
+            }
+        };
+        // The passes are software-pipelined: the codes of pass k sit in cw[k & 1] (fetched two passes ahead; after the
+        // last passes of a slice, those of the first passes of the next one), and the LDS reads of a group of steps
+        // are issued as soon as the matrix instructions that consumed the group's registers have been issued -- for the
+        // last groups of a pass these are the first reads of the NEXT pass, which then travel while this pass is rotated
+        // and contracted with the queries.
+        unsigned cc[CV][CV];
+        if (STREAM0 && sl == 0) {
+            unsigned r[CW];
+            raw_slot(0, r);
+            make_cc(r, ccall[0]);
+            if (2 < NPASS) {
+                unsigned f[CW];
+                fetch_codes(2, f);
+#pragma unroll
+                for (int i = 0; i < CW; ++i) stage[0][i] = f[i];
+            }
+        }
+        // an opaque copy per slice: the gather addresses made from these must not be hoisted out of the slice loop
+        // (they would need eight registers per pass instead of one)
+#pragma unroll
+        for (int pp = 0; pp < NPASS; ++pp)
+#pragma unroll
+            for (int i = 0; i < CV; ++i)
+#pragma unroll
+                for (int j = 0; j < CV; ++j) asm volatile("" : "+v"(ccall[pp][i][j]));
+#pragma unroll
+        for (int i = 0; i < CV; ++i)
+#pragma unroll
+            for (int j = 0; j < CV; ++j) cc[i][j] = ccall[0][i][j];
+        issue(0, cc, v[0]);
+        if (NG > 1) issue(1, cc, v[1]);
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure flat
             // coarse phase factor of the lane's token and part, from LDS: a pass is a whole number of coarse rows
-            // further on (16 consecutive tokens read at most two rows: no bank conflicts)
-            const uint4_t ehr = lds_read_b128(ehi_last + (unsigned)((NPASS - 1 - p) * (NW * 16 * SETS / kLo) * 16));
-            __builtin_amdgcn_sched_barrier(0);
-            fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            // cc[v][h]: rotated code bytes 4 h .. 4 h + 3 of token v (M = 16: one token, steps 0..3 only)
-            unsigned cc[M == 16 ? 1 : 2][M == 16 ? 1 : 2];
-            if (M == 16) {
-                cc[0][0] = __builtin_amdgcn_perm(cw[p & 1][1], cw[p & 1][0], rsel_lo);
-            } else {
+            // further on
+            const uint4_t ehr = lds_read_b128(ehi_last + (unsigned)((NPASS - 1 - p) * (PSTRIDE / kLo) * (16 * PARTS)));
+            unsigned ccn[CV][CV];
+            if (p + 1 < NPASS) {
+                if (STREAM0 && sl == 0) {
+                    // first slice: the codes of pass p + 1 have arrived (raw, requested two passes ago); keep them in
+                    // gather order and request those of pass p + 3 into the buffer they leave
+                    unsigned r[CW];
+                    if (p == 0) {
+                        raw_slot(1, r);
+                    } else {
 #pragma unroll
-                for (int v = 0; v < 2; ++v) {
-                    cc[v][0] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_lo);
-                    cc[v][M == 16 ? 0 : 1] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_hi);
-                }
-            }
-
-            // 1. gather-sum on the matrix cores: per step two LDS reads (pieces A and B) and one sparse MFMA;
-            //    reads in groups of RG steps, two groups in flight
-            floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-            constexpr int RG = (G == 8 && TPT == 4) ? 1 : 2, NG = NST / RG;  // fewer reads in flight where registers are short
-            uint4_t v[2][RG][2];
-            auto issue = [&](int grp, uint4_t(&dst)[RG][2]) {
+                        for (int i = 0; i < CW; ++i) r[i] = stage[(p + 1) & 1][i];
+                    }
+                    make_cc(r, ccall[p + 1]);
+                    if (p + 3 < NPASS) {
+                        unsigned f[CW];
+                        fetch_codes(p + 3, f);
 #pragma unroll
-                for (int r = 0; r < RG; ++r) {
-                    const int st = grp * RG + r;
-#pragma unroll
-                    for (int ab = 0; ab < 2; ++ab) {
-                        // address bytes: [0] column, [1] code byte st % 4 of its dword, [2] block, [3] zero.  M = 16: block =
-                        // plane = ab (xreg bytes 2, 3 hold 0, 1); M = 32: block = hi (xreg byte 2), the code is token ab's
-                        const unsigned sel = 0x0c000000u | (unsigned)(M == 16 ? 2 + ab : 2) << 16 | (unsigned)(4 + st % 4) << 8;
-                        const unsigned addr = __builtin_amdgcn_perm(cc[M == 16 ? 0 : ab][M == 16 ? 0 : st / 4], xreg[st], sel);
-                        dst[r][ab] = lds_read_b128(addr);
+                        for (int i = 0; i < CW; ++i) stage[(p + 1) & 1][i] = f[i];
                     }
                 }
-            };
-            issue(0, v[0]);
+#pragma unroll
+                for (int i = 0; i < CV; ++i)
+#pragma unroll
+                    for (int j = 0; j < CV; ++j) ccn[i][j] = ccall[p + 1][i][j];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // 1. gather-sum on the matrix cores
+            floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int grp = 0; grp < NG; ++grp) {
-                if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
                     const uint4_t pa = v[grp & 1][r][0], pb = v[grp & 1][r][1];
@@ -752,18 +886,24 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                     acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(selv, __builtin_bit_cast(bf16x16_t, both), acc, (int)sidx, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                if (grp + 2 < NG) issue(grp + 2, cc, v[grp & 1]);
+                else if (p + 1 < NPASS) issue(grp + 2 - NG, ccn, v[grp & 1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
             if (PREFETCH && p == NPASS - 1) fetch_slice(min(sl + 1, S - 1));  // after the last slice: a harmless re-read
-            // 2. E = E_hi E_lo for the lane's two sub-spaces; rotated block = A E
+            if (p + 1 < NPASS) {
+#pragma unroll
+                for (int i = 0; i < CV; ++i)
+#pragma unroll
+                    for (int j = 0; j < CV; ++j) cc[i][j] = ccn[i][j];
+            }
+            // 2. the lane's two sub-spaces rotated by the coarse phase factor: A E_hi
             float val[4];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const unsigned hxr = ehr[2 * u], hyr = ehr[2 * u + 1], lxr = elr[2 * u], lyr = elr[2 * u + 1];
-                const float hx = __builtin_bit_cast(float, hxr);
-                const float hy = __builtin_bit_cast(float, hyr);
-                const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
-                const float ex = hx * lx - hy * ly;
-                const float ey = hx * ly + hy * lx;
+                const unsigned hxr = ehr[2 * u], hyr = ehr[2 * u + 1];
+                const float ex = __builtin_bit_cast(float, hxr);
+                const float ey = __builtin_bit_cast(float, hyr);
                 const float ax = acc[2 * u], ay = acc[2 * u + 1];
                 val[2 * u] = ax * ex - ay * ey;
                 val[2 * u + 1] = ax * ey + ay * ex;
@@ -784,33 +924,68 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         }
     }
 
-    // logits to memory and the tile's (max, sum of exp) per head.  sc[p][x][o] of lane (n, gk) is the logit
-    // of head 4 x + gk (M = 16) or 4 x + 2 o + par (M = 32) for the lane's token of pass p.
+    // The tile's (max, sum of exp) per head, and the logits to memory.  sc[p][x][o] of lane (n, gk) is the logit
+    // of head 4 x + gk (M = 16) or 4 x + 2 o + par (M = 32) for the lane's token of pass p.  The tokens of a
+    // wavefront are scattered over the tile (4 fine positions x 4 coarse rows per pass), so the logits of four
+    // heads at a time are transposed through the now idle slice area of LDS, [head][coarse row][68] floats (rows
+    // padded from 64, heads offset by 16 banks: the writes of a wavefront fall on 32 different banks), and leave
+    // as runs of 256 consecutive tokens per wavefront.
+    constexpr int SROW = 68, SHEAD = (TILE / kLo) * SROW + 16;
+    float *stg = reinterpret_cast<float *>(tab);
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    const int rel0 = tb - t0;
 #pragma unroll
-    for (int x = 0; x < NGRP; ++x)
+    for (int x = 0; x < NGRP; ++x) {
 #pragma unroll
         for (int o = 0; o < NOUT; ++o) {
             const int head = 4 * x + (M == 16 ? gk : 2 * o + par);
             float mx = -INFINITY;
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
-                const int tok = tb + p * NW * 16 * SETS;
-                if (head < G && tok < L) {
-                    srow[(size_t)head * L + tok] = sc[p][x][o];
-                    mx = fmaxf(mx, sc[p][x][o]);
-                }
+                const int tok = tb + p * PSTRIDE;
+                if (head < G && tok < L) mx = fmaxf(mx, sc[p][x][o]);
             }
             const float wm = head_lanes_max<M>(mx);
             float l = 0.f;
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
-                const int tok = tb + p * NW * 16 * SETS;
+                const int tok = tb + p * PSTRIDE;
                 if (head < G && tok < L) l += __builtin_amdgcn_exp2f((sc[p][x][o] - wm) * kLog2e);
             }
             l = head_lanes_sum<M>(l);
             if (n == 0 && head < G && (M == 16 || set == 0)) wstat[wave][head] = make_float2(wm, l);
         }
+        __syncthreads();  // the last slice (x = 0) or the previous group's logits have been read by everyone
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o) {
+            const int hl = M == 16 ? gk : 2 * o + par;
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int rel = rel0 + p * PSTRIDE;
+                stg[hl * SHEAD + (rel >> kLoBits) * SROW + (rel & (kLo - 1))] = sc[p][x][o];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < TPT; ++it) {
+            const int idx = it * kSliceThreads + tid;
+            const int hl = idx / (TILE / 4), rel = 4 * (idx % (TILE / 4));
+            const int head = 4 * x + hl, tok = t0 + rel;
+            if (head < G && tok < L) {
+                const float4 v = *reinterpret_cast<const float4 *>(stg + hl * SHEAD + (rel >> kLoBits) * SROW + (rel & (kLo - 1)));
+                float *dst = srow + (size_t)head * L + tok;
+                if (tok + 3 < L) {
+                    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // L need not be a multiple of 4
+                    const f4u vv = {v.x, v.y, v.z, v.w};
+                    *reinterpret_cast<f4u *>(dst) = vv;
+                } else {
+                    dst[0] = v.x;
+                    if (tok + 1 < L) dst[1] = v.y;
+                    if (tok + 2 < L) dst[2] = v.z;
+                }
+            }
+        }
+    }
     __syncthreads();
     if (tid < G) {
         float m = -INFINITY;

@@ -101,10 +101,6 @@ __global__ __launch_bounds__(256) void k_encode(const void *__restrict__ keys, c
 // at the top of the next level.  No static LDS: the images sit at LDS address 0.
 constexpr int kEdImg = 16 * 256;  // 16-byte pieces of one level's rows
 constexpr int kEdLds = 2 * kEdImg * 16 + kD * 4 + 8 * 4 + 8 * 4 + 32 * 4;
-__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_byte_addr_uniform)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte_addr_uniform), "v"(gptr) : "memory");
-}
 __global__ __launch_bounds__(256) void k_encode_dma(const void *__restrict__ keys, const uint4 *__restrict__ cb,
                                                     const float *__restrict__ norms, uint8_t *__restrict__ out, const EncodeDims a)
 {

@@ -105,6 +105,14 @@ __device__ __forceinline__ float cb_elem(const void *cb, size_t i)
     return static_cast<const float *>(cb)[i];
 }
 
+// 16 bytes per lane from global memory straight into LDS (no register destination): lane l of the wavefront lands at
+// LDS byte address lds_byte_addr_uniform + 16 l.  Issued from inline asm, so the compiler makes no later access wait
+// for it: the kernel waits itself (s_waitcnt vmcnt(0)) before the data is used.
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_byte_addr_uniform)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte_addr_uniform), "v"(gptr) : "memory");
+}
+
 __device__ __forceinline__ float bf16_lo(unsigned v) { return __builtin_bit_cast(float, v << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned v) { return __builtin_bit_cast(float, v & 0xffff0000u); }
 
