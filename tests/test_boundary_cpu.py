@@ -125,7 +125,7 @@ def test_planner_plans_the_five_configurations(planner):
     for kw, B, T, L in cases:
         h = planner(**kw)
         p = cv.commvq_plan_query(h, B, T, L)
-        assert p.score_split_len in (256, 512, 1024, 2048, 4096)
+        assert p.score_split_len in (64, 128, 256, 512, 1024, 2048, 4096)
         assert p.score_splits == -(-L // p.score_split_len)
         assert p.value_splits == -(-L // p.value_split_len) and 1 <= p.value_splits <= 256
         assert p.value_split_len % max(p.score_split_len, 1024) == 0 or p.score_kernel == 0
