@@ -224,6 +224,22 @@ commvq_status commvq_encode_keys(commvq_handle *handle, const void *keys, int32_
                                  void *stream);
 
 /*
+ * Value encoding for cache append -- a stand-in for the paper's value encoder.  Sec. 4.1 encodes a value vector with a
+ * small trained network E (x -> binary code s) whose weights come out of the training of Sec. 4.1 and are not part
+ * of this library; what IS fixed by the cache format is the decoder (Eq. vanilla_decode in index form: the sum of the
+ * m_val selected rows).  These calls produce codes for that decoder by the same greedy residual assignment as the
+ * key encoder -- level m takes the row of value codebook m nearest to what the earlier levels left -- so that a
+ * cache can be appended to end to end without the trained network.  Arguments, layouts, tie rule and status codes as
+ * commvq_encoder_table_bytes / commvq_encoder_prepare / commvq_encode_keys in index form, with val_codebooks
+ * [Hkv][m_val][K][d] and m_val index bytes per record.
+ */
+commvq_status commvq_value_encoder_table_bytes(const commvq_handle *handle, size_t *bytes);
+commvq_status commvq_value_encoder_prepare(commvq_handle *handle, const void *val_codebooks, void *tables, void *stream);
+commvq_status commvq_encode_values(commvq_handle *handle, const void *values, int32_t n_tokens, const void *val_codebooks,
+                                   const void *tables, uint8_t *codes_out, int64_t token_stride, int64_t head_stride,
+                                   void *stream);
+
+/*
  * Offline: one iteration of the EM-like learner of the RoPE-commutative key codebook (Sec. 4.2,
  * Algorithm 1; App. A.2), for n_subspaces independent 2-D sub-spaces at once.  Needs no handle.
  *   data         device [n_subspaces][n_points][2] fp32: the calibration points of every sub-space

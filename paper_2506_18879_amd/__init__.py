@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     commvq_em_step_shared,
     commvq_em_workspace_bytes,
     commvq_encode_keys,
+    commvq_encode_values,
     commvq_encoder_prepare,
     commvq_encoder_table_bytes,
     commvq_forget_packed_key_codebooks,
@@ -39,6 +40,8 @@ from .binding import (  # noqa: F401
     commvq_static_scratch_bytes,
     commvq_status_string,
     commvq_validate_config,
+    commvq_value_encoder_prepare,
+    commvq_value_encoder_table_bytes,
     commvq_workspace_bytes,
     library_path,
     load_library,

@@ -41,6 +41,7 @@ EXPORTS = ("commvq_create", "commvq_create_planner", "commvq_destroy", "commvq_v
            "commvq_decode_attn", "commvq_decode_attn_static", "commvq_static_scratch_bytes", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
            "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
            "commvq_encoder_table_bytes", "commvq_encoder_prepare", "commvq_encode_keys",
+           "commvq_value_encoder_table_bytes", "commvq_value_encoder_prepare", "commvq_encode_values",
            "commvq_em_workspace_bytes", "commvq_em_step", "commvq_em_shared_workspace_bytes", "commvq_em_step_shared",
            "commvq_profile_enable", "commvq_profile_read", "commvq_status_string")
 
@@ -80,6 +81,9 @@ def load_library():
     lib.commvq_encoder_table_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.commvq_encoder_prepare.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     lib.commvq_encode_keys.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p]
+    lib.commvq_value_encoder_table_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
+    lib.commvq_value_encoder_prepare.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.commvq_encode_values.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p]
     lib.commvq_em_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, POINTER(c_size_t)]
     lib.commvq_em_step.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.commvq_em_shared_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, POINTER(c_size_t)]
@@ -200,6 +204,24 @@ def commvq_encode_keys(handle, keys, n_tokens: int, key_codebooks, tables, codes
     _check(load_library().commvq_encode_keys(handle, _ptr(keys), int(n_tokens), _ptr(key_codebooks), _ptr(tables),
                                              _ptr(codes_out), int(token_stride), int(head_stride), stream or None),
            "commvq_encode_keys")
+
+
+def commvq_value_encoder_table_bytes(handle) -> int:
+    n = c_size_t()
+    _check(load_library().commvq_value_encoder_table_bytes(handle, byref(n)), "commvq_value_encoder_table_bytes")
+    return int(n.value)
+
+
+def commvq_value_encoder_prepare(handle, val_codebooks, tables, stream: int = 0) -> None:
+    _check(load_library().commvq_value_encoder_prepare(handle, _ptr(val_codebooks), _ptr(tables), stream or None),
+           "commvq_value_encoder_prepare")
+
+
+def commvq_encode_values(handle, values, n_tokens: int, val_codebooks, tables, codes_out, token_stride: int,
+                         head_stride: int, stream: int = 0) -> None:
+    _check(load_library().commvq_encode_values(handle, _ptr(values), int(n_tokens), _ptr(val_codebooks), _ptr(tables),
+                                               _ptr(codes_out), int(token_stride), int(head_stride), stream or None),
+           "commvq_encode_values")
 
 
 def commvq_em_workspace_bytes(n_subspaces: int, n_points: int, n_centres: int) -> int:

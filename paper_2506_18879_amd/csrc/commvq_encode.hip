@@ -621,45 +621,57 @@ __global__ __launch_bounds__(256) void k_encode_lds(const void *__restrict__ key
 
 }  // namespace
 
-extern "C" {
+namespace {
 
-commvq_status commvq_encoder_table_bytes(const commvq_handle *h, size_t *bytes)
+// What is encoded: the keys (the configured key format) or the values (always index form, m_val codebooks).
+struct EncodeWhat {
+    bool paired;
+    int levels, K, rec;
+};
+EncodeWhat encode_what(const commvq_config &c, bool values)
+{
+    EncodeWhat w;
+    w.paired = !values && c.key_format == COMMVQ_KEYS_PAIRED;
+    w.levels = values ? c.m_val : w.paired ? c.key_levels : c.m_key;
+    w.K = w.paired ? 64 : kK;
+    w.rec = w.paired ? (12 * w.levels + 7) / 8 : w.levels;
+    return w;
+}
+
+commvq_status encoder_table_bytes(const commvq_handle *h, bool values, size_t *bytes)
 {
     if (!h || !bytes) return COMMVQ_ERR_NULL;
-    const commvq_config &c = h->cfg;
-    const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
-    const size_t levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
-    *bytes = (size_t)c.n_kv_heads * levels * K * sizeof(float) * (paired ? 1 + K : 1);
+    const EncodeWhat w = encode_what(h->cfg, values);
+    *bytes = (size_t)h->cfg.n_kv_heads * w.levels * w.K * sizeof(float) * (w.paired ? 1 + w.K : 1);
     return COMMVQ_OK;
 }
 
-commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void *tables, void *stream)
+commvq_status encoder_prepare(commvq_handle *h, bool values, const void *cb, void *tables, void *stream)
 {
-    if (!h || !key_cb || !tables) return COMMVQ_ERR_NULL;
+    if (!h || !cb || !tables) return COMMVQ_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(tables) & 15u) return COMMVQ_ERR_SHAPE;
     if (h->device < 0) return COMMVQ_ERR_NO_DEVICE;
     const commvq_config &c = h->cfg;
-    const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
-    const int levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
-    const int rows = c.n_kv_heads * levels * K;
+    const EncodeWhat w = encode_what(c, values);
+    const int rows = c.n_kv_heads * w.levels * w.K;
     float *norms = static_cast<float *>(tables), *cross = norms + rows;
-    const size_t n = paired ? (size_t)rows * K : (size_t)rows;
+    const size_t n = w.paired ? (size_t)rows * w.K : (size_t)rows;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (c.codebook_dtype == COMMVQ_BF16)
-        hipLaunchKernelGGL(k_encode_tables<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, key_cb, norms, cross, rows, K, paired ? 1 : 0);
+        hipLaunchKernelGGL(k_encode_tables<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, cb, norms, cross, rows, w.K, w.paired ? 1 : 0);
     else
-        hipLaunchKernelGGL(k_encode_tables<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, key_cb, norms, cross, rows, K, paired ? 1 : 0);
+        hipLaunchKernelGGL(k_encode_tables<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, cb, norms, cross, rows, w.K, w.paired ? 1 : 0);
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
 }
 
-commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_tokens, const void *key_cb, const void *tables,
-                                 uint8_t *codes_out, int64_t token_stride, int64_t head_stride, void *stream)
+commvq_status encode_vectors(commvq_handle *h, bool values, const void *keys, int32_t n_tokens, const void *key_cb, const void *tables,
+                             uint8_t *codes_out, int64_t token_stride, int64_t head_stride, void *stream)
 {
     if (!h || !keys || !key_cb || !tables || !codes_out) return COMMVQ_ERR_NULL;
     const commvq_config &c = h->cfg;
-    const bool paired = c.key_format == COMMVQ_KEYS_PAIRED;
-    const int levels = paired ? c.key_levels : c.m_key, K = paired ? 64 : kK;
-    const int rec = paired ? (12 * levels + 7) / 8 : levels;
+    const EncodeWhat w = encode_what(c, values);
+    const bool paired = w.paired;
+    const int levels = w.levels, K = w.K, rec = w.rec;
     if (n_tokens < 1 || (int64_t)n_tokens * c.n_kv_heads > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
     if (head_stride < rec || token_stride < rec) return COMMVQ_ERR_SHAPE;  // records must not overlap
     if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(keys) | reinterpret_cast<uintptr_t>(key_cb)) & 15u)
@@ -699,6 +711,33 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
         hipLaunchKernelGGL(k_encode<false>, grid, dim3(256), 0, s, keys, key_cb, norms, codes_out, d);
     }
     return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+commvq_status commvq_encoder_table_bytes(const commvq_handle *h, size_t *bytes) { return encoder_table_bytes(h, false, bytes); }
+commvq_status commvq_value_encoder_table_bytes(const commvq_handle *h, size_t *bytes) { return encoder_table_bytes(h, true, bytes); }
+
+commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void *tables, void *stream)
+{
+    return encoder_prepare(h, false, key_cb, tables, stream);
+}
+commvq_status commvq_value_encoder_prepare(commvq_handle *h, const void *val_cb, void *tables, void *stream)
+{
+    return encoder_prepare(h, true, val_cb, tables, stream);
+}
+
+commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_tokens, const void *key_cb, const void *tables,
+                                 uint8_t *codes_out, int64_t token_stride, int64_t head_stride, void *stream)
+{
+    return encode_vectors(h, false, keys, n_tokens, key_cb, tables, codes_out, token_stride, head_stride, stream);
+}
+commvq_status commvq_encode_values(commvq_handle *h, const void *values, int32_t n_tokens, const void *val_cb, const void *tables,
+                                   uint8_t *codes_out, int64_t token_stride, int64_t head_stride, void *stream)
+{
+    return encode_vectors(h, true, values, n_tokens, val_cb, tables, codes_out, token_stride, head_stride, stream);
 }
 
 }  // extern "C"

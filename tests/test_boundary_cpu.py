@@ -217,12 +217,18 @@ def test_paired_keys_refuse_explicit_positions_and_size_their_tables(planner):
                      a["val_codebooks"], a["positions"], a["out"], a["workspace"], a["workspace_bytes"]) == 2
     assert cv.commvq_packed_key_codebook_bytes(h) == 8 * 16 * 1 * 64 * 256        # 16 planes x 1 block of 16 KiB per head
     assert cv.commvq_encoder_table_bytes(h) == 8 * 11 * 64 * 4 * (1 + 64)         # norms + cross terms
+    assert cv.commvq_value_encoder_table_bytes(h) == 8 * 32 * 256 * 4              # values are in index form whatever the keys
     hi = planner(m_key=16)
     assert cv.commvq_packed_key_codebook_bytes(hi) == 8 * 16 * 256 * 128 * 2
     assert cv.commvq_encoder_table_bytes(hi) == 8 * 16 * 256 * 4
     assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 8, 16) == 3
     assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 128, 16) == 6
     assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 0, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 128, 16) == 3
+    hv = planner(m_key=16, m_val=32)
+    assert cv.commvq_value_encoder_table_bytes(hv) == 8 * 32 * 256 * 4
+    assert status_of(cv.commvq_encode_values, hv, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 256, 16) == 3   # 32-byte records
+    assert status_of(cv.commvq_encode_values, hv, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 256, 32) == 6
+    assert status_of(cv.commvq_value_encoder_prepare, hv, _Buf(1 << 21), _Buf((1 << 22) + 4)) == 3
 
 
 def test_em_sizes_are_bounded():

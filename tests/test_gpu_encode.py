@@ -179,6 +179,39 @@ def test_encode_recovers_exact_centres_and_feeds_attention(gpu, oracle):
     op.close()
 
 
+@pytest.mark.parametrize("dtype,Mv,n", [("bf16", 16, 7), ("bf16", 32, 150), ("f32", 32, 40)])
+def test_encode_values_greedy_residual_assignment(gpu, oracle, dtype, Mv, n):
+    """The stand-in value encoder: same residual nearest-row search as the key encoder in index form, over the VALUE
+    codebooks (which have no block structure); and the records it writes are what commvq_decode_attn reads."""
+    import torch
+    import paper_2506_18879_amd as cv
+    w = synth.make_workload(f"encv_{dtype}_{Mv}", B=1, Hq=4, Hkv=2, seqlens=[n], Mk=16, Mv=Mv, dtype=dtype, seed=900 + Mv + n)
+    bf = dtype == "bf16"
+    rng = np.random.default_rng(Mv + n)
+    vals, vf = _keys(rng, n, w)
+    op = gpu.DecodeAttention(w)
+    vcb = gpu.to_device(w.val_codebooks, bf)
+    tables = torch.empty(cv.commvq_value_encoder_table_bytes(op.handle), dtype=torch.uint8, device="cuda")
+    cache = torch.full((w.Hkv, n, Mv), 0xEE, dtype=torch.uint8, device="cuda")
+    cv.commvq_value_encoder_prepare(op.handle, vcb, tables)
+    cv.commvq_encode_values(op.handle, gpu.to_device(vals, bf), n, vcb, tables, cache, Mv, n * Mv)
+    torch.cuda.synchronize()
+    got = cache.cpu().numpy()
+    cb = w.as_f64("val_codebooks")
+    same = np.concatenate([judge(oracle, vf[:, g], cb[g], got[g], False) for g in range(w.Hkv)])
+    assert same.mean() >= 0.99
+    # append -> attend: the cache's value codes are the encoder's records
+    w.val_codes = np.ascontiguousarray(got).reshape(-1)
+    dw = gpu.DeviceWorkload(w)
+    out = op(dw)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attn(w.as_f64("q"), w.key_codes, w.val_codes, w.as_f64("key_codebooks"), cb, w.cu_seqlens, w.q_pos,
+                             rope_base=w.rope_base)
+    err = np.abs(out.cpu().numpy() - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+    assert err.max() <= 2e-5
+    op.close()
+
+
 def test_encode_rejects_overlapping_records(gpu):
     import torch
     import paper_2506_18879_amd as cv
