@@ -101,6 +101,8 @@ typedef struct {
     int32_t out_chunks;       /* codebook-row chunks per (sequence, KV head) in the bins x codebook product */
     int32_t score_kernel;     /* 0: rows gathered through L1 (fp32 codebooks or explicit key positions);
                                  1: codebook slices streamed through LDS (or the look-up table of position_free) */
+    int32_t score_slice_groups; /* score workgroups per tile: contexts too short to fill the chip are also cut along the
+                                 codebook slices, and the groups' partial logits are added by a small kernel; 1 otherwise */
 } commvq_plan;
 
 typedef struct commvq_handle commvq_handle;

@@ -32,7 +32,8 @@ class Positions(Structure):
 
 class Plan(Structure):
     _fields_ = [("score_split_len", c_int32), ("score_splits", c_int32), ("value_split_len", c_int32),
-                ("value_splits", c_int32), ("out_chunks", c_int32), ("score_kernel", c_int32)]
+                ("value_splits", c_int32), ("out_chunks", c_int32), ("score_kernel", c_int32),
+                ("score_slice_groups", c_int32)]
 
 
 Handle = c_void_p

@@ -42,12 +42,13 @@ struct Workspace {
     float *scores;    // [T * Hq] scaled logits
     float2 *sstat;    // [B * Hq * score_splits] (max, sum of exp(logit - max)) of each score split
     float *vscale;    // [B * Hq * value_splits] 2^-S: value of one fixed-point unit of that split's bins
-    float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over that value split
+    float *lsum;      // [B * Hq * value_splits] sum of exp(logit - sequence max) over the score tiles that begin in that value split
     unsigned *bins;   // [B * Hkv * value_splits][K][Mv][G] fixed-point bins (codeword-major: see k_bins)
     float *partial;   // [B * Hq * out_chunks][d]
     uint4 *packed;    // key codebook re-laid slice-major for k_score_mfma / k_score_pair
     uint8_t *pair_bytes;  // paired-code keys: one byte per index, [T * Hkv][32 * blocks]
     float *lut;           // position-free keys: scale * q . C, [B * Hkv][M_k * K][G]
+    float *scores_part;   // [slice groups][T * Hq] partial logits when the score tiles are also cut along the slices
     size_t bytes;
 };
 
@@ -72,18 +73,28 @@ inline size_t packed_key_bytes(const commvq_config &c)
 void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commvq_plan *p)
 {
     const int units = B * h->cfg.n_kv_heads;
-    int len;
+    int len, groups = 1;
     if (sliced) {
-        // tile = 1024, 2048 or 4096 tokens: longer tiles amortise the LDS refill of each codebook slice
-        // (about a quarter of the work of 1024 tokens), shorter ones fill the 256 compute units more evenly
-        double best = -1.0;
+        // Tile = 1024, 2048 or 4096 tokens of one (sequence, KV head); a context too short to fill the 256 compute
+        // units with such tiles is also cut along the codebook slices, `groups` workgroups per tile that each stream
+        // S / groups slices and leave partial logits for k_score_combine to add.  Cost model of a workgroup, in
+        // microseconds as measured on the five configurations: a fixed start (first fetches, write-out), per slice a
+        // switch (LDS refill, barriers) and the passes themselves.
+        const bool splittable = !pair_keys(h->cfg) && !h->cfg.position_free;
+        const int S = pair_keys(h->cfg) ? 4 : h->cfg.m_key / 2;                       // slices per tile
+        const double c1024 = h->cfg.m_key == 16 && !pair_keys(h->cfg) ? 2.1 : 1.85;  // passes of 1024 tokens over one slice
+        double best = 1e30;
         len = 1024;
+        groups = 1;
         for (int tpt = 1; tpt <= kScoreMaxTpt; tpt *= 2) {
             if (tpt == 4 && h->G == 8 && (h->cfg.m_key == 16 || pair_keys(h->cfg))) break;  // those instantiations run out of registers
-            const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt));
-            const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
-            const double eff = fill / (1.0 + 0.25 / tpt);
-            if (eff > best * 1.0001) { best = eff; len = 1024 * tpt; }
+            for (int e = 1; e <= (splittable ? S : 1); e *= 2) {
+                const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt)) * e;
+                // cut along the slices: every group fetches the tile's codes again, the partial logits take a trip through
+                // memory, and k_score_combine is one more launch
+                const double t = (double)((wgs + 255) / 256) * (9.0 + (double)(S / e) * (1.3 + tpt * c1024)) + (e > 1 ? 18.0 : 0.0);
+                if (t < best * 0.9999) { best = t; len = 1024 * tpt; groups = e; }
+            }
         }
     } else {
         len = 1024;
@@ -95,13 +106,28 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
     int nv = 256 / units;  // about one value workgroup per compute unit
     if (nv < 1) nv = 1;
     int vlen = (max_seqlen + nv - 1) / nv;
-    const int round_to = len > 1024 ? len : 1024;  // whole score splits, so their statistics can be summed
-    vlen = (vlen + round_to - 1) / round_to * round_to;
+    // a value split is a whole number of statistics tiles (score tiles; 1024 tokens when k_score_combine writes the
+    // statistics), or a power-of-two fraction of one (never less than 1024 tokens): k_bins takes its exp-sums from them
+    const int slen = groups > 1 ? 1024 : len;
+    if (vlen >= slen || slen <= 1024) {
+        const int round_to = slen > 1024 ? slen : 1024;
+        vlen = (vlen + round_to - 1) / round_to * round_to;
+    } else {
+        int part = 1024;
+        while (part < vlen) part *= 2;
+        vlen = part;  // 1024 or 2048 inside a 2048- or 4096-token tile
+    }
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
     p->out_chunks = h->cfg.m_val * kK / kOutRows;
     p->score_kernel = sliced ? 1 : 0;
+    p->score_slice_groups = groups;
 }
+
+// Granularity of the (max, sum of exp) statistics that the score stage leaves for k_bins: the score tile, except that
+// k_score_combine (tiles cut along the slices) writes them per 1024 tokens.
+inline int stat_len(const commvq_plan &p) { return p.score_kernel && p.score_slice_groups > 1 ? 1024 : p.score_split_len; }
+inline int stat_splits(const commvq_plan &p, int max_seqlen) { return (max_seqlen + stat_len(p) - 1) / stat_len(p); }
 
 // Carves the workspace.  Array sizes are the larger of what the two score kernels need, so one
 // workspace size serves a batch shape whether or not explicit positions are passed.
@@ -111,7 +137,7 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     commvq_plan pa, pb;
     make_plan(h, B, max_seqlen, true, &pa);
     make_plan(h, B, max_seqlen, false, &pb);
-    const size_t ssplits = pa.score_splits > pb.score_splits ? pa.score_splits : pb.score_splits;
+    const size_t ssplits = std::max<size_t>(std::max(pa.score_splits, pb.score_splits), (size_t)stat_splits(pa, max_seqlen));
     const size_t vsplits = pa.value_splits > pb.value_splits ? pa.value_splits : pb.value_splits;
     size_t off = 0;
     auto take = [&](size_t n_floats) {
@@ -128,6 +154,7 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     w->packed = reinterpret_cast<uint4 *>(take(packed_key_bytes(c) / 4));
     w->pair_bytes = pair_keys(c) ? reinterpret_cast<uint8_t *>(take((size_t)T * c.n_kv_heads * 8 * pair_blocks(c))) : nullptr;
     w->lut = c.position_free ? take((size_t)B * c.n_q_heads * c.m_key * kK) : nullptr;
+    w->scores_part = pa.score_slice_groups > 1 ? take((size_t)pa.score_slice_groups * T * c.n_q_heads) : nullptr;
     w->bytes = off;
 }
 
@@ -438,6 +465,8 @@ __global__ __launch_bounds__(256) void k_prep(const uint4 *__restrict__ key_cb, 
 struct SliceDims {
     int Hq, Hkv, nsplit, n_hi, q_bf16;
     float scale;
+    int groups;            // workgroups per tile, each with S / groups of the codebook slices (k_score_mfma)
+    long long part_stride; // floats between the partial logit arrays of two slice groups
 };
 
 // ------------------------------------------------------------------ k_score_mfma
@@ -533,7 +562,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const int g = id % a.Hkv;
     id /= a.Hkv;
     const int tile = id % a.nsplit;
-    const int b = id / a.nsplit;
+    id /= a.nsplit;
+    const int eg = id % a.groups;                             // which group of slices (0 when tiles are not cut along them)
+    const int b = id / a.groups;
+    const int s_begin = eg * (S / a.groups), s_end = s_begin + S / a.groups;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // The first slice of the head's codebook depends on nothing but the workgroup index: it is requested before the
     // sequence's bounds are even known, so that its (cold) fetch, that of the bounds and that of the tile's codes
@@ -550,7 +582,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, (unsigned)sl * (PIECES * 16u), 0);
     };
     constexpr bool PREFETCH = !(M == 32 && G == 8 && TPT == 4);  // that instantiation has no registers to spare
-    if (PREFETCH) fetch_slice(0);
+    if (PREFETCH) fetch_slice(s_begin);
     const int cu0 = cu[b];
     const int L = cu[b + 1] - cu0;
     const int t0 = tile * TILE;
@@ -666,7 +698,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     // Raw codes in flight: those of passes 0 and 1 (requested here) wait in the ccall slots of the LAST passes, which
     // are not written until the raw values have long been used; later ones in the first registers of the slice
     // staging buffer, idle between the slice's LDS write and the last pass.
-    constexpr bool STREAM0 = NPASS >= 4;
+    constexpr bool STREAM0 = M == 16 && NPASS >= 4;  // (with 32 codebooks the stream's two loads per pass do not hide)
     constexpr int RAWS = NPASS * CV * CV / CW;                // ccall slots that one pass's raw codes take (2 or 1)
     unsigned ccall[NPASS][CV][CV];
     auto raw_slot = [&](int k, unsigned(&dst)[CW]) {          // raw codes of pass k (0 or 1): copy out of their parking slots
@@ -732,9 +764,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             elo[(size_t)buf * (kPhaseBytes / 16) + tid] = e;
         }
     };
-    if (DMA_OK) dma_phase(0, 0);
+    if (DMA_OK) dma_phase(s_begin, s_begin & 1);
 
-    for (int sl = 0; sl < S; ++sl) {
+    for (int si = 0; si < s_end - s_begin; ++si) {  // (counted from 0, so that the first slice's extra work can be peeled off)
+        const int sl = s_begin + si;
         if (!PREFETCH) fetch_slice(sl);
         // queries of this slice (head 4 grp + n % 4, the lane's 4 elements): requested before the barriers, so
         // that they have arrived when the first pass needs them
@@ -819,7 +852,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         // last groups of a pass these are the first reads of the NEXT pass, which then travel while this pass is rotated
         // and contracted with the queries.
         unsigned cc[CV][CV];
-        if (STREAM0 && sl == 0) {
+        if (STREAM0 && si == 0) {
             unsigned r[CW];
             raw_slot(0, r);
             make_cc(r, ccall[0]);
@@ -852,7 +885,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             const uint4_t ehr = lds_read_b128(ehi_last + (unsigned)((NPASS - 1 - p) * (PSTRIDE / kLo) * (16 * PARTS)));
             unsigned ccn[CV][CV];
             if (p + 1 < NPASS) {
-                if (STREAM0 && sl == 0) {
+                if (STREAM0 && si == 0) {
                     // first slice: the codes of pass p + 1 have arrived (raw, requested two passes ago); keep them in
                     // gather order and request those of pass p + 3 into the buffer they leave
                     unsigned r[CW];
@@ -933,7 +966,8 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     // as runs of 256 consecutive tokens per wavefront.
     constexpr int SROW = 68, SHEAD = (TILE / kLo) * SROW + 16;
     float *stg = reinterpret_cast<float *>(tab);
-    float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
+    // a slice group leaves partial logits in its own array; the tile statistics then come from k_score_combine
+    float *srow = scores + (size_t)eg * a.part_stride + (size_t)cu0 * a.Hq + (size_t)g * G * L;
     const int rel0 = tb - t0;
 #pragma unroll
     for (int x = 0; x < NGRP; ++x) {
@@ -988,7 +1022,7 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         }
     }
     __syncthreads();
-    if (tid < G) {
+    if (tid < G && a.groups == 1) {
         float m = -INFINITY;
         for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
         float l = 0.f;
@@ -997,6 +1031,70 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
             if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
         }
         sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
+    }
+}
+
+// ------------------------------------------------------------------ k_score_combine
+// Score tiles that were also cut along the codebook slices (short contexts): the logit of a token is the sum of the
+// partial logits of the slice groups (Eq. new_attention's sum over the sub-spaces, split in `groups` parts).  One
+// workgroup per (sequence, query head, 1024 tokens): adds the parts in a fixed order, writes the logits and the
+// (max, sum of exp) of its 1024 tokens.
+constexpr int kCombineThreads = 256;
+__global__ __launch_bounds__(kCombineThreads) void k_score_combine(const float *__restrict__ part, float *__restrict__ scores,
+                                                                  float2 *__restrict__ sstat, const int32_t *__restrict__ cu,
+                                                                  int Hq, int nsplit, int tile_len, int groups, long long part_stride)
+{
+    __shared__ float red[kCombineThreads / 64];
+    int id = blockIdx.x;
+    const int tile = id % nsplit;
+    id /= nsplit;
+    const int h = id % Hq, b = id / Hq;
+    const int cu0 = cu[b], L = cu[b + 1] - cu0;
+    const int t0 = tile * tile_len;
+    if (t0 >= L) return;
+    const int t1 = min(t0 + tile_len, L);
+    const size_t row = (size_t)cu0 * Hq + (size_t)h * L;
+    constexpr int MAXV = 1024 / kCombineThreads;  // statistics tiles of 1024 tokens
+    float v[MAXV];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+        const int tok = t0 + k * kCombineThreads + (int)threadIdx.x;
+        v[k] = -INFINITY;
+        if (k * kCombineThreads < tile_len && tok < t1) {
+            // all parts requested at once (at most 16 slice groups), added in a fixed order
+            float pv[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) pv[e] = e < groups ? part[(size_t)e * part_stride + row + tok] : 0.f;
+            float acc = pv[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) acc += pv[e];
+            scores[row + tok] = acc;
+            v[k] = acc;
+            mx = fmaxf(mx, acc);
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    mx = wave_max(mx);
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    {
+        float m2 = red[0];
+        for (int w = 1; w < kCombineThreads / 64; ++w) m2 = fmaxf(m2, red[w]);
+        mx = m2;
+    }
+    __syncthreads();
+    float l = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k)
+        if (v[k] != -INFINITY) l += __builtin_amdgcn_exp2f((v[k] - mx) * kLog2e);
+    l = wave_sum(l);
+    if (lane == 0) red[wave] = l;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float lt = 0.f;
+        for (int w = 0; w < kCombineThreads / 64; ++w) lt += red[w];  // fixed order
+        sstat[((size_t)b * Hq + h) * nsplit + tile] = make_float2(mx, lt);
     }
 }
 
@@ -1569,18 +1667,30 @@ __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)
         float mx = first.x;  // maximum logit of head h0 + wave over the whole sequence
         for (int s = lane + 64; s < ns; s += 64) mx = fmaxf(mx, st[s].x);
         mx = wave_max(mx);
+        // Sum of exp(logit - mx) over the score tiles that this value split touches: it bounds every bin of the split
+        // (it IS the split's own sum when the split is a whole number of tiles) and fixes the fixed-point unit.  What
+        // the split reports towards the softmax denominator (lown) are the tiles that BEGIN inside it, so that a tile
+        // shared by several value splits is counted once.
         const int sa = v0 / a.split_len, sb = min((v1 + a.split_len - 1) / a.split_len, ns);
-        float l = 0.f;  // sum of exp(logit - mx) over this value split
-        if (lane >= sa && lane < sb) l = first.y * __builtin_amdgcn_exp2f((first.x - mx) * kLog2e);
+        float l = 0.f, lown = 0.f;
+        if (lane >= sa && lane < sb) {
+            l = first.y * __builtin_amdgcn_exp2f((first.x - mx) * kLog2e);
+            if (lane * a.split_len >= v0) lown = l;
+        }
         for (int s = lane + 64; s < sb; s += 64)
-            if (s >= sa) l += st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
+            if (s >= sa) {
+                const float t = st[s].y * __builtin_amdgcn_exp2f((st[s].x - mx) * kLog2e);
+                l += t;
+                if (s * a.split_len >= v0) lown += t;
+            }
         l = wave_sum(l);
+        lown = wave_sum(lown);
         int S = 0;
         if (l >= 1e-30f) S = min(30 - ilogbf(l), 120);
         if (lane == 0) {
             eoff_s[wave] = (float)S - mx * kLog2e;
             a.vscale[((size_t)b * a.Hq + h0 + wave) * a.nvsplit + vs] = ldexpf(1.f, -S);
-            a.lsum[((size_t)b * a.Hq + h0 + wave) * a.nvsplit + vs] = l;
+            a.lsum[((size_t)b * a.Hq + h0 + wave) * a.nvsplit + vs] = lown;
         }
     }
     __syncthreads();
@@ -2051,7 +2161,7 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
     if (c.position_free) {  // scalar look-up table: build T = scale q C^T, then M look-ups per token
         SliceDims d;
         d.Hq = c.n_q_heads; d.Hkv = c.n_kv_heads; d.nsplit = plan.score_splits; d.n_hi = h->n_hi;
-        d.q_bf16 = c.q_dtype == COMMVQ_BF16; d.scale = h->scale;
+        d.q_bf16 = c.q_dtype == COMMVQ_BF16; d.scale = h->scale; d.groups = 1; d.part_stride = 0;
         const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
         const int tpt = plan.score_split_len / kSliceThreads;
         const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
@@ -2072,7 +2182,10 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
         sa.tbl_hi = h->tbl_hi; sa.tbl_lo = h->tbl_lo; sa.scores = w.scores; sa.sstat = w.sstat;
         sa.d.Hq = c.n_q_heads; sa.d.Hkv = c.n_kv_heads; sa.d.nsplit = plan.score_splits; sa.d.n_hi = h->n_hi;
         sa.d.q_bf16 = c.q_dtype == COMMVQ_BF16; sa.d.scale = h->scale;
-        const int grid = pos->batch * c.n_kv_heads * plan.score_splits;
+        const int groups = pair_keys(c) ? 1 : plan.score_slice_groups;
+        sa.d.groups = groups; sa.d.part_stride = (long long)pos->total_tokens * c.n_q_heads;
+        if (groups > 1) sa.scores = w.scores_part;
+        const int grid = pos->batch * c.n_kv_heads * plan.score_splits * groups;
         const int tpt = plan.score_split_len / kSliceThreads;
         hipError_t e;
         if (pair_keys(c)) {
@@ -2085,6 +2198,13 @@ commvq_status run_scores(commvq_handle *h, const void *q, const uint8_t *key_cod
             e = pair_blocks(c) == 1 ? launch_pair_b<1>(sa, h->G, tpt, grid, s) : launch_pair_b<2>(sa, h->G, tpt, grid, s);
         } else {
             e = c.m_key == 16 ? launch_sliced_m<16>(sa, h->G, tpt, grid, s) : launch_sliced_m<32>(sa, h->G, tpt, grid, s);
+            if (e == hipSuccess && groups > 1) {
+                const int ns = stat_splits(plan, pos->max_seqlen);
+                hipLaunchKernelGGL(k_score_combine, dim3((unsigned)(pos->batch * c.n_q_heads * ns)), dim3(kCombineThreads), 0, s,
+                                   w.scores_part, w.scores, w.sstat, pos->cu_seqlens, c.n_q_heads, ns, stat_len(plan), groups,
+                                   sa.d.part_stride);
+                e = hipGetLastError();
+            }
         }
         return e == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
     }
@@ -2108,7 +2228,7 @@ commvq_status run_bins(commvq_handle *h, const uint8_t *val_codes, const commvq_
     BinsArgs a;
     a.val_codes = val_codes; a.cu = pos->cu_seqlens; a.scores = w.scores; a.sstat = w.sstat;
     a.bins = w.bins; a.vscale = w.vscale; a.lsum = w.lsum;
-    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = plan.score_splits; a.split_len = plan.score_split_len;
+    a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.nsplit = stat_splits(plan, pos->max_seqlen); a.split_len = stat_len(plan);
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
     const int grid = pos->batch * c.n_kv_heads * plan.value_splits;
     hipError_t e = c.m_val == 16 ? launch_bins_m<16>(a, h->G, grid, s) : launch_bins_m<32>(a, h->G, grid, s);
