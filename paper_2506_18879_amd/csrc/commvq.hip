@@ -5,8 +5,9 @@
 //               codewords, rotate once by the RoPE matrix of the relative position, contract
 //               with the G query heads of the group -> scaled logits + per-split (max, sum exp).
 //               bf16 codebooks with contiguous key positions: k_prep (codebook re-laid in
-//               LDS-image order, queries scaled) + k_score_mfma (codebook slices streamed
-//               through LDS, gather-sum and query contraction on the matrix cores);
+//               LDS-image order) + k_score_mfma (codebook slices streamed through LDS, tile codes
+//               resident in registers, gather-sum and query contraction on the matrix cores), for
+//               short contexts with the tiles also cut along the slices + k_score_combine;
 //               fp32 codebooks or explicit key positions: k_score (rows gathered through L1).
 //   k_bins      Softmax(A) S_V of Eq. optimized_v (unnormalised): exp(logit - max) is
 //               scatter-added into LDS bins (one per head, value codebook and codeword; written out
@@ -515,23 +516,43 @@ __device__ __forceinline__ float swap32_add(float x, float y)
 // Works on the key codebook repacked by k_prep: slice sl (DS = 256 / M consecutive elements of
 // every codeword) sits in LDS as tab[P][M][K] 16-byte pieces while all tokens of the tile pass by.
 //
+// Tokens.  A tile of TILE = 1024 TPT tokens is 64 fine positions (token mod 64) x TILE / 64 coarse rows.  A
+// wavefront owns 4 fine positions; in a pass, lane n of its 16 token lanes takes fine position n / 4 and
+// coarse row n % 4 of the pass's block of rows (M = 32: a second set of 16 tokens, 4 rows further on).
+// So the 4 lanes of a 4-lane block, and all passes of a lane, are whole coarse rows apart: they share the
+// fine phase factor E_lo of the relative position 64 H + lo, which is therefore folded into the block's
+// query operand once per slice, and a pass only rotates by the coarse factor E_hi.
+//
+// Codes.  The tile's codes are read once and stay in registers for all slices, already in the byte order
+// of the lane's gather steps (M = 16: streamed in during the first slice; see STREAM0).
+//
+// Per slice and pass:
 //  1. Gather-sum: v_smfmac_f32_16x16x64_bf16 (structured-sparse first operand) with a constant 0/1
 //     selection matrix as first operand and 128 gathered pieces as second: lane n + 16 g supplies two
 //     pieces, A and B, for column n.  Products with 1.0 are exact, so this is the plain fp32 sum of the
 //     M codeword slices.  Rows 0..7 of the result are the elements of the four lanes' A pieces added up,
 //     rows 8..15 those of their B pieces:
 //       M = 16 (two planes): a pass covers 16 tokens; A / B = plane 0 / plane 1 of one codebook;
-//               lane (n, g) receives elements 4g .. 4g+3 of the slice for token n;
-//       M = 32 (one plane):  a pass covers 32 tokens in two sets; A / B = the same codebook for tokens
-//               n and n + 16; lane (n, g) receives elements 4 (g & 1) .. +3 for token n + 16 (g >> 1).
-//  2. Each lane rotates its two (x, y) sub-spaces by the token's relative position (two-level
-//     phase tables) -- the only per-token vector arithmetic left on the vector ALUs.
+//               lane (n, g) receives elements 4g .. 4g+3 of the slice for its token;
+//       M = 32 (one plane):  a pass covers 32 tokens in two sets; A / B = the same codebook for the
+//               lane's token of set 0 and of set 1; lane (n, g) receives elements 4 (g & 1) .. +3 for
+//               its token of set g >> 1.
+//     The LDS reads of a group of steps are issued right after the matrix instructions that consumed the
+//     group's registers, so the first reads of the next pass travel while this pass is finished.
+//  2. Each lane rotates its two (x, y) sub-spaces by the coarse phase factor of its token.
 //  3. Contraction with the queries: four v_mfma_f32_4x4x1_16b_f32 per group of 4 heads.  In each
-//     block of 4 lanes, lane i supplies q[head i][the block's r-th element] and every lane its own
-//     rotated r-th element, so register i of a lane receives the partial logit of head i for the
-//     lane's own token over the lane's 4 elements.  The 4 (M = 16) or 2 (M = 32) lanes of a token
+//     block of 4 lanes, lane i supplies q'[head i][the block's r-th element] (q' = q conj(E_lo)) and every
+//     lane its own rotated r-th element, so register i of a lane receives the partial logit of head i for
+//     the lane's own token over the lane's 4 elements.  The 4 (M = 16) or 2 (M = 32) lanes of a token
 //     are then combined with row / half swaps so that each keeps the total of one (two) heads:
-//     lane (n, g) holds head g of token n (M = 16), heads g & 1 and 2 + (g & 1) (M = 32).
+//     lane (n, g) holds head g of its token (M = 16), heads g & 1 and 2 + (g & 1) (M = 32).
+// On gfx950 the vector and matrix instructions of a SIMD do not overlap (measured again on this kernel:
+// interleaving the next pass's gather-sum with this pass's vector work changes nothing), so a pass costs the
+// sum of its instruction issue: 4 (8) sparse MFMA of 16 clk, 4 small ones of 8 per head group, ~28 vector
+// instructions.
+//
+// Short contexts: a launch may cut every tile along the slices as well (SliceDims::groups workgroups per
+// tile); each then writes partial logits, which k_score_combine adds.
 template <int M, int G, int TPT>
 __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const void *__restrict__ q, const uint8_t *__restrict__ key_codes, const uint4 *__restrict__ packed,
@@ -653,11 +674,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         rsel_hi |= (unsigned)((x + 4 + n) & 7) << (8 * x);
     }
 
-    // Codes are fetched one pass ahead (the fetch for pass 0 of the next slice rides on the last
-    // pass of this one), so that their latency hides behind a whole pass of gather work.  tb is the
-    // lane's first token (the one whose logits it ends up with); it is re-read through an opaque copy in every
-    // slice so that nothing that depends on a token index (code loads, table offsets) is hoisted out of the slice
-    // loop.  M = 32: the lane gathers for tokens tb - 16 set and tb - 16 set + 16.
+    // tb is the lane's token of pass 0 (the one whose logits it ends up with; pass p: tb + p PSTRIDE); it is re-read
+    // through an opaque copy in every slice so that nothing that depends on a token index (table offsets) is hoisted
+    // out of the slice loop.  M = 32: the lane gathers for the set-0 token tb - 256 set and the set-1 token 256 further.
     int tb = t0 + 4 * wave + (n >> 2) + kLo * ((n & 3) + (M == 16 ? 0 : 4 * set));
     constexpr int PSTRIDE = 4 * kLo * SETS;  // tokens between two passes of a lane: a whole number of coarse rows
     // byte offset of the codes the lane gathers in pass 0 (M = 32: of the first of its two tokens, the second is
@@ -846,11 +865,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
                 }
             }
         };
-        // The passes are software-pipelined: the codes of pass k sit in cw[k & 1] (fetched two passes ahead; after the
-        // last passes of a slice, those of the first passes of the next one), and the LDS reads of a group of steps
-        // are issued as soon as the matrix instructions that consumed the group's registers have been issued -- for the
-        // last groups of a pass these are the first reads of the NEXT pass, which then travel while this pass is rotated
-        // and contracted with the queries.
+        // The passes are software-pipelined: the LDS reads of a group of steps are issued as soon as the matrix
+        // instructions that consumed the group's registers have been issued -- for the last groups of a pass these are
+        // the first reads of the NEXT pass, which then travel while this pass is rotated and contracted with the queries.
         unsigned cc[CV][CV];
         if (STREAM0 && si == 0) {
             unsigned r[CW];

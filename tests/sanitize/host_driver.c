@@ -51,6 +51,15 @@ static int drive(commvq_config c, int32_t B, int64_t T, int32_t L)
     EXPECT(commvq_encode_keys(h, fake(1 << 16), 3, fake(1 << 22), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 64, NULL),
            COMMVQ_ERR_NO_DEVICE);
     EXPECT(commvq_encode_keys(h, fake(1 << 16), 3, fake(1 << 22), fake(1 << 27), (uint8_t *)fake(1 << 28), 1, 1, NULL), COMMVQ_ERR_SHAPE);
+    EXPECT(commvq_decode_attn_static(h, fake(1 << 16), (const uint8_t *)fake(1 << 20), (const uint8_t *)fake(1 << 21), fake(1 << 22),
+                                     fake(1 << 23), &pos, (float *)fake(1 << 24), NULL),
+           ws <= ((size_t)48 << 20) ? COMMVQ_ERR_NO_DEVICE : COMMVQ_ERR_WORKSPACE);
+    EXPECT(commvq_value_encoder_table_bytes(h, &nb), COMMVQ_OK);
+    EXPECT(commvq_value_encoder_prepare(h, fake(1 << 23), fake(1 << 27), NULL), COMMVQ_ERR_NO_DEVICE);
+    EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 64, NULL),
+           COMMVQ_ERR_NO_DEVICE);
+    EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 8, NULL),
+           COMMVQ_ERR_SHAPE);
     EXPECT(commvq_profile_enable(h, 4), COMMVQ_OK);
     float ms[3];
     int32_t n = -1;
@@ -76,6 +85,8 @@ int main(void)
         if (!commvq_status_string((commvq_status)i)) return 1;
 
     if (drive(base, 1, 131072, 131072)) return 1;                       /* the benchmark layer at 128K */
+    if (drive(base, 1, 8192, 8192)) return 1;                           /* short context: tiles cut along the slices */
+    if (drive(base, 3, 20000, 9000)) return 1;
     c = base; c.m_key = 32; c.m_val = 32;
     if (drive(c, 8, 300001, 65536)) return 1;                           /* ragged batch */
     c = base; c.n_q_heads = 64; c.m_key = 32;
@@ -92,6 +103,7 @@ int main(void)
     if (drive(c, 1, 1, 1)) return 1;                                    /* one token */
 
     size_t nb = 0;
+    EXPECT(commvq_static_scratch_bytes(&nb), COMMVQ_OK);
     EXPECT(commvq_em_workspace_bytes(65535, 1 << 24, 64, &nb), COMMVQ_OK);
     EXPECT(commvq_em_workspace_bytes(65536, 16, 4, &nb), COMMVQ_ERR_SHAPE);
     EXPECT(commvq_em_shared_workspace_bytes(64, 1 << 24, 64, &nb), COMMVQ_OK);

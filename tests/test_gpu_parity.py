@@ -178,6 +178,39 @@ def test_one_bit_keys_group_sizes_and_tile_lengths(gpu, oracle, G, Hkv, L):
     check(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("Mk,G,lens", [(16, 4, [3000]), (32, 4, [8192]), (32, 8, [5000, 700]), (16, 1, [4097, 1, 2049]), (32, 2, [1500])])
+def test_short_contexts_cut_along_the_codebook_slices(gpu, oracle, Mk, G, lens):
+    # contexts too short to fill the chip with whole score tiles: several workgroups per tile, each with a group of
+    # the codebook slices, partial logits added by k_score_combine (which also writes the 1024-token statistics)
+    import torch
+    w = synth.make_workload(f"groups_m{Mk}_g{G}", B=len(lens), Hq=2 * G, Hkv=2, seqlens=lens, Mk=Mk, Mv=16, dtype="bf16",
+                            seed=4000 + Mk + G + lens[0])
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    assert op.plan.score_kernel == 1 and op.plan.score_slice_groups > 1, (op.plan.score_split_len, op.plan.score_slice_groups)
+    print(f"case {w.name}: tiles of {op.plan.score_split_len} tokens, {op.plan.score_slice_groups} slice groups", flush=True)
+    s = op.scores(dw)
+    out = op(dw)
+    torch.cuda.synchronize()
+    ref, ref_scores, _ = oracle_out(oracle, w, return_intermediates=True)
+    assert np.abs(s.cpu().numpy().astype(np.float64) - ref_scores).max() <= TOL_SCORE
+    assert_rows(out.cpu().numpy(), ref, w.name)
+    op.close()
+
+
+def test_slice_groups_on_the_8b_layer_at_16k(gpu, oracle):
+    # the 8B-shaped layer at a 16K context, 2-bit keys: 4096-token tiles in 8 slice groups of two slices each
+    import torch
+    w = synth.make_workload("groups_8b_16k", B=1, Hq=32, Hkv=8, seqlens=[16384], Mk=32, Mv=32, dtype="bf16", seed=616)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    assert (op.plan.score_split_len, op.plan.score_slice_groups) == (4096, 8)
+    out = op(dw)
+    torch.cuda.synchronize()
+    assert_rows(out.cpu().numpy(), oracle_out(oracle, w), w.name)
+    op.close()
+
+
 @pytest.mark.parametrize("Mk", [16, 32])
 @pytest.mark.parametrize("qpos", [0, 1234, 70000])
 def test_contiguous_keys_with_query_inside_or_far_beyond_the_context(gpu, oracle, Mk, qpos):
