@@ -511,6 +511,88 @@ __device__ __forceinline__ float swap32_add(float x, float y)
     return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
 }
 
+// The tile's (max, sum of exp) per head, and the logits to memory, for the slice-streaming score kernels.
+// sc[p][x][o] of lane (n, gk) is the logit of head 4 x + gk (M = 16) or 4 x + 2 o + par (M = 32) for the lane's token
+// of pass p, tb + p * 4 * 64 * (sets of the pass).  The tokens of a wavefront are scattered over the tile (4 fine
+// positions x 4 coarse rows per pass), so the logits of four heads at a time are transposed through the now idle
+// slice area of LDS (stg), [head][coarse row][68] floats (rows padded from 64, heads offset by 16 banks: the writes
+// of a wavefront fall on 32 different banks), and leave as runs of 256 consecutive tokens per wavefront.
+// stat_dst: where the tile's statistics of head 0 go (stride nsplit per head), or null.
+template <int M, int G, int TPT, int NPASS, int NGRP, int NOUT>
+__device__ __forceinline__ void write_tile_logits(const float (&sc)[NPASS][NGRP][NOUT], float *stg, float2 (*wstat)[G],
+                                                  float *srow, float2 *stat_dst, int nsplit, int tb, int t0, int L)
+{
+    constexpr int TILE = TPT * kSliceThreads, NW = kSliceThreads / 64;
+    constexpr int PSTRIDE = 4 * kLo * (M == 16 ? 1 : 2);
+    constexpr int SROW = 68, SHEAD = (TILE / kLo) * SROW + 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gk = lane >> 4, par = gk & 1, set = gk >> 1;
+    const int rel0 = tb - t0;
+#pragma unroll
+    for (int x = 0; x < NGRP; ++x) {
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o) {
+            const int head = 4 * x + (M == 16 ? gk : 2 * o + par);
+            float mx = -INFINITY;
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int tok = tb + p * PSTRIDE;
+                if (head < G && tok < L) mx = fmaxf(mx, sc[p][x][o]);
+            }
+            const float wm = head_lanes_max<M>(mx);
+            float l = 0.f;
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int tok = tb + p * PSTRIDE;
+                if (head < G && tok < L) l += __builtin_amdgcn_exp2f((sc[p][x][o] - wm) * kLog2e);
+            }
+            l = head_lanes_sum<M>(l);
+            if (n == 0 && head < G && (M == 16 || set == 0)) wstat[wave][head] = make_float2(wm, l);
+        }
+        __syncthreads();  // the last slice (x = 0) or the previous group's logits have been read by everyone
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o) {
+            const int hl = M == 16 ? gk : 2 * o + par;
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int rel = rel0 + p * PSTRIDE;
+                stg[hl * SHEAD + (rel >> kLoBits) * SROW + (rel & (kLo - 1))] = sc[p][x][o];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < TPT; ++it) {
+            const int idx = it * kSliceThreads + tid;
+            const int hl = idx / (TILE / 4), rel = 4 * (idx % (TILE / 4));
+            const int head = 4 * x + hl, tok = t0 + rel;
+            if (head < G && tok < L) {
+                const float4 v = *reinterpret_cast<const float4 *>(stg + hl * SHEAD + (rel >> kLoBits) * SROW + (rel & (kLo - 1)));
+                float *dst = srow + (size_t)head * L + tok;
+                if (tok + 3 < L) {
+                    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // L need not be a multiple of 4
+                    const f4u vv = {v.x, v.y, v.z, v.w};
+                    *reinterpret_cast<f4u *>(dst) = vv;
+                } else {
+                    dst[0] = v.x;
+                    if (tok + 1 < L) dst[1] = v.y;
+                    if (tok + 2 < L) dst[2] = v.z;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < G && stat_dst) {
+        float m = -INFINITY;
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
+        float l = 0.f;
+        for (int w = 0; w < NW; ++w) {
+            const float2 st = wstat[w][tid];
+            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+        }
+        stat_dst[(size_t)tid * nsplit] = make_float2(m, l);
+    }
+}
+
 // Slice-streaming score kernel with both contractions on the matrix cores (Eq. new_attention,
 // re-bracketed: gather-sum the codeword blocks first, rotate once, contract with the G queries).
 // Works on the key codebook repacked by k_prep: slice sl (DS = 256 / M consecutive elements of
@@ -975,80 +1057,10 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
         }
     }
 
-    // The tile's (max, sum of exp) per head, and the logits to memory.  sc[p][x][o] of lane (n, gk) is the logit
-    // of head 4 x + gk (M = 16) or 4 x + 2 o + par (M = 32) for the lane's token of pass p.  The tokens of a
-    // wavefront are scattered over the tile (4 fine positions x 4 coarse rows per pass), so the logits of four
-    // heads at a time are transposed through the now idle slice area of LDS, [head][coarse row][68] floats (rows
-    // padded from 64, heads offset by 16 banks: the writes of a wavefront fall on 32 different banks), and leave
-    // as runs of 256 consecutive tokens per wavefront.
-    constexpr int SROW = 68, SHEAD = (TILE / kLo) * SROW + 16;
-    float *stg = reinterpret_cast<float *>(tab);
     // a slice group leaves partial logits in its own array; the tile statistics then come from k_score_combine
     float *srow = scores + (size_t)eg * a.part_stride + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-    const int rel0 = tb - t0;
-#pragma unroll
-    for (int x = 0; x < NGRP; ++x) {
-#pragma unroll
-        for (int o = 0; o < NOUT; ++o) {
-            const int head = 4 * x + (M == 16 ? gk : 2 * o + par);
-            float mx = -INFINITY;
-#pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                const int tok = tb + p * PSTRIDE;
-                if (head < G && tok < L) mx = fmaxf(mx, sc[p][x][o]);
-            }
-            const float wm = head_lanes_max<M>(mx);
-            float l = 0.f;
-#pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                const int tok = tb + p * PSTRIDE;
-                if (head < G && tok < L) l += __builtin_amdgcn_exp2f((sc[p][x][o] - wm) * kLog2e);
-            }
-            l = head_lanes_sum<M>(l);
-            if (n == 0 && head < G && (M == 16 || set == 0)) wstat[wave][head] = make_float2(wm, l);
-        }
-        __syncthreads();  // the last slice (x = 0) or the previous group's logits have been read by everyone
-#pragma unroll
-        for (int o = 0; o < NOUT; ++o) {
-            const int hl = M == 16 ? gk : 2 * o + par;
-#pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                const int rel = rel0 + p * PSTRIDE;
-                stg[hl * SHEAD + (rel >> kLoBits) * SROW + (rel & (kLo - 1))] = sc[p][x][o];
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < TPT; ++it) {
-            const int idx = it * kSliceThreads + tid;
-            const int hl = idx / (TILE / 4), rel = 4 * (idx % (TILE / 4));
-            const int head = 4 * x + hl, tok = t0 + rel;
-            if (head < G && tok < L) {
-                const float4 v = *reinterpret_cast<const float4 *>(stg + hl * SHEAD + (rel >> kLoBits) * SROW + (rel & (kLo - 1)));
-                float *dst = srow + (size_t)head * L + tok;
-                if (tok + 3 < L) {
-                    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // L need not be a multiple of 4
-                    const f4u vv = {v.x, v.y, v.z, v.w};
-                    *reinterpret_cast<f4u *>(dst) = vv;
-                } else {
-                    dst[0] = v.x;
-                    if (tok + 1 < L) dst[1] = v.y;
-                    if (tok + 2 < L) dst[2] = v.z;
-                }
-            }
-        }
-    }
-    __syncthreads();
-    if (tid < G && a.groups == 1) {
-        float m = -INFINITY;
-        for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
-        float l = 0.f;
-        for (int w = 0; w < NW; ++w) {
-            const float2 st = wstat[w][tid];
-            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
-        }
-        sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
-    }
+    float2 *stat_dst = a.groups == 1 ? sstat + ((size_t)b * a.Hq + (size_t)g * G) * a.nsplit + tile : nullptr;
+    write_tile_logits<M, G, TPT, NPASS, NGRP, NOUT>(sc, reinterpret_cast<float *>(tab), wstat, srow, stat_dst, a.nsplit, tb, t0, L);
 }
 
 // ------------------------------------------------------------------ k_score_combine
@@ -1374,11 +1386,13 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
     constexpr int NHR = TILE / kLo + 1;
     constexpr int NGRP = (G + 3) / 4;
     constexpr int PARTS = 8;                          // (sub-space of a plane) x (planes 0,1 | 2,3)
+    constexpr int HROW = 12;                          // 16-byte entries per coarse phase row (8 used: conflict-free reads)
     static_assert(NPASS % 2 == 0, "code double-buffer parity assumes an even number of passes");
     extern __shared__ __attribute__((aligned(16))) uint4 tab[];  // [PL][NB][64][16] pieces, then the phase factors
     float4 *elo = reinterpret_cast<float4 *>(reinterpret_cast<char *>(tab) + SLICE);  // [PARTS][64]
-    float4 *ehi = elo + PARTS * kLo;                                                   // [PARTS][NHR]
-    float2(*wstat)[G] = reinterpret_cast<float2(*)[G]>(ehi + PARTS * NHR);            // [NW][G]
+    float4 *ehi = elo + PARTS * kLo;                                                   // [NHR][HROW]
+    float2(*wstat)[G] = reinterpret_cast<float2(*)[G]>(ehi + HROW * NHR);             // [NW][G]
+    static_assert(4 * ((TILE / kLo) * 68 + 16) * 4 <= SLICE + (PARTS * kLo + HROW * NHR) * 16, "the write-out stages its logits below the statistics");
 
     int id = blockIdx.x;
     const int g = id % a.Hkv;
@@ -1420,11 +1434,11 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
     }
     const bf16x8_t selv = __builtin_bit_cast(bf16x8_t, sel);
 
-    float sc[NPASS][NGRP];
+    float sc[NPASS][NGRP][1];
 #pragma unroll
     for (int p = 0; p < NPASS; ++p)
 #pragma unroll
-        for (int x = 0; x < NGRP; ++x) sc[p][x] = 0.f;
+        for (int x = 0; x < NGRP; ++x) sc[p][x][0] = 0.f;
 
     // xreg[st]: byte 0 = 16 * bank column (= level within the block) read at step st, byte 2 = 0, byte 3 = 1;
     // a byte permute splices the centre index in as byte 1: address = 256 c + 16 col (+ 65536 via byte 3)
@@ -1438,20 +1452,32 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
         rsel_hi |= (unsigned)((x + 4 + n) & 7) << (8 * x);
     }
 
-    int tb = t0 + wave * 16 + n;
+    // Token mapping as in k_score_mfma (M = 16): lane n of a wavefront's 16 token lanes takes fine position
+    // 4 wave + n / 4 and coarse row n % 4 of the pass's block of four rows, so the lanes of a 4-lane block and all
+    // passes of a lane are whole coarse rows apart and share the fine phase factor, which is folded into the query.
+    int tb = t0 + 4 * wave + (n >> 2) + kLo * (n & 3);
+    constexpr int PSTRIDE = 4 * kLo;
     unsigned cw[2][2 * NB];
     auto fetch_codes = [&](int p, unsigned(&dst)[2 * NB]) {
-        const int tok = min(tb + p * NW * 16, L - 1);
+        const int tok = min(tb + p * PSTRIDE, L - 1);
 #pragma unroll
         for (int v = 0; v < NB; ++v) {  // bytes 32 v + 16 type + 8 half .. + 7 of the token's indices
             const uint2_t c2 = __builtin_amdgcn_raw_buffer_load_b64(cd_rs, (unsigned)tok * CB + 32u * v + 16u * type + 8u * half, 0, 0);
             dst[2 * v + 0] = c2[0]; dst[2 * v + 1] = c2[1];
         }
     };
+    // rotated index bytes of a pass: what its gather addresses are made from
+    auto make_cc = [&](const unsigned(&c)[2 * NB], unsigned(&cc)[2 * NB]) {
+#pragma unroll
+        for (int v = 0; v < NB; ++v) {
+            cc[2 * v + 0] = __builtin_amdgcn_perm(c[2 * v + 1], c[2 * v], rsel_lo);
+            cc[2 * v + 1] = __builtin_amdgcn_perm(c[2 * v + 1], c[2 * v], rsel_hi);
+        }
+    };
     fetch_codes(0, cw[0]);
     const int hmin = (qpos - (t0 + TILE - 1)) >> kLoBits;
     const unsigned elo_base = (unsigned)SLICE + (unsigned)(2 * gk) * (kLo * 16u);
-    const unsigned ehi_base = (unsigned)SLICE + (unsigned)(PARTS * kLo) * 16u + (unsigned)(2 * gk) * (NHR * 16u);
+    const unsigned ehi_base = (unsigned)SLICE + (unsigned)(PARTS * kLo) * 16u + (unsigned)gk * 16u;
 
     for (int sl = 0; sl < S; ++sl) {
         // queries of this slice (head 4 grp + n % 4, sub-space gk of each of the 4 planes): requested ahead of the
@@ -1477,7 +1503,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
 #pragma unroll
             for (int x = 0; x < PPT; ++x) tab[x * kSliceThreads + tid] = stage[x];
         }
-        // phase factors of this slice's 16 sub-spaces: part (s, h) holds sub-space s of planes 2h and 2h + 1
+        // phase factors of this slice's 16 sub-spaces: an entry (s, h) holds sub-space s of planes 2h and 2h + 1;
+        // fine table [2 s + h][64 positions], coarse table [row][4 h + s] (rows padded to 12 entries, so that the four
+        // rows x four sub-spaces that the lanes of a read touch are 16 different 16-byte bank groups)
         if (tid < PARTS * kLo) {
             const int part = tid / kLo, lo = tid % kLo;
             const int j0 = 16 * sl + 8 * (part & 1) + (part >> 1);
@@ -1485,83 +1513,101 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
             elo[tid] = make_float4(e0.x, e0.y, e1.x, e1.y);
         }
         for (int x = tid; x < PARTS * NHR; x += kSliceThreads) {
-            const int part = x / NHR, H = hmin + x % NHR;
+            const int c = x % PARTS, H = hmin + x / PARTS;
             const int hi = min(H < 0 ? -H : H, a.n_hi - 1);
-            const int j0 = 16 * sl + 8 * (part & 1) + (part >> 1);
+            const int j0 = 16 * sl + 8 * (c >> 2) + (c & 3);
             const float2 e0 = tbl_hi[(size_t)hi * kJ + j0], e1 = tbl_hi[(size_t)hi * kJ + j0 + 4];
             const float sg = H < 0 ? -1.f : 1.f;
-            ehi[x] = make_float4(e0.x, sg * e0.y, e1.x, sg * e1.y);
+            ehi[(x / PARTS) * HROW + c] = make_float4(e0.x, sg * e0.y, e1.x, sg * e1.y);
         }
         __syncthreads();
         asm volatile("" : "+v"(tb));
         const int dist16 = (qpos - tb) * 16;
-        // scaled queries of this slice
+        // scaled queries of this slice, times the conjugate of the fine phase factor (shared by the lane's tokens of all
+        // passes and by the four lanes of its block): q' = q conj(E_lo), Re(conj(q) k E_hi E_lo) = Re(conj(q') k E_hi)
         float qrow[NGRP][PL][2];
+        {
+            uint4_t elr[2];
 #pragma unroll
-        for (int x = 0; x < NGRP; ++x)
+            for (int h = 0; h < 2; ++h) elr[h] = lds_read_b128(elo_base + (unsigned)(dist16 & ((kLo - 1) * 16)) + (unsigned)(h * (kLo * 16)));
 #pragma unroll
-            for (int pl = 0; pl < PL; ++pl) {
-                const unsigned u0 = qraw[x][pl][0], u1 = qraw[x][pl][1];
-                if (a.q_bf16) {
-                    qrow[x][pl][0] = bf16_lo(u0) * a.scale; qrow[x][pl][1] = bf16_hi(u0) * a.scale;
-                } else {
-                    qrow[x][pl][0] = __builtin_bit_cast(float, u0) * a.scale; qrow[x][pl][1] = __builtin_bit_cast(float, u1) * a.scale;
+            for (int x = 0; x < NGRP; ++x)
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl) {
+                    const unsigned u0 = qraw[x][pl][0], u1 = qraw[x][pl][1];
+                    float qx, qy;
+                    if (a.q_bf16) {
+                        qx = bf16_lo(u0) * a.scale; qy = bf16_hi(u0) * a.scale;
+                    } else {
+                        qx = __builtin_bit_cast(float, u0) * a.scale; qy = __builtin_bit_cast(float, u1) * a.scale;
+                    }
+                    const unsigned lxr = elr[pl / 2][2 * (pl & 1)], lyr = elr[pl / 2][2 * (pl & 1) + 1];
+                    const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
+                    qrow[x][pl][0] = qx * lx + qy * ly;
+                    qrow[x][pl][1] = qy * lx - qx * ly;
                 }
+        }
+        // coarse phase row of the lane's token of the LAST pass; a pass is a whole number of rows further on
+        const unsigned ehi_last = ehi_base + (unsigned)(((dist16 >> (kLoBits + 4)) - hmin - (NPASS - 1) * (PSTRIDE / kLo)) * (16 * HROW));
+        // Gather: 8 NB pieces per lane and plane, in groups of RG reads; the groups of all planes of a pass form one
+        // sequence, and a group's reads are issued before the matrix instructions of the group before it -- across
+        // planes and passes, so that the first reads of the next plane (pass) travel while this one is rotated and
+        // contracted with the queries.
+        constexpr int NS = 8 * NB, RG = (NB == 2 || G == 8) ? 2 : 4, NG = NS / RG, NFLAT = PL * NG;  // fewer reads in flight where registers are short
+        static_assert(NFLAT % 2 == 0, "read buffers alternate across passes");
+        uint4_t v[2][RG];
+        auto issue = [&](int flat, const unsigned(&cc)[2 * NB], uint4_t(&dst)[RG]) {
+            const int pl = flat / NG, grp = flat % NG;
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                const int st = grp * RG + r;       // level 16 (st / 8) + 8 half + (n + st) mod 8
+                const int idx = pl * NB + st / 8;  // (plane, block) image of 16 KiB
+                const unsigned selb = 0x0c000000u | (unsigned)(2 + idx / 4) << 16 | (unsigned)(4 + st % 4) << 8;
+                const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], selb);
+                dst[r] = lds_read_b128((unsigned)((idx % 4) * kPairBlock) + addr);
             }
+        };
+        unsigned cc[2 * NB];
+        make_cc(cw[0], cc);  // (the last pass of the previous slice requested the codes of pass 0 again)
+        issue(0, cc, v[0]);
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure flat
-            const int d16 = dist16 - p * (NW * 16 * 16);
-            const unsigned lo_off = elo_base + (unsigned)(d16 & ((kLo - 1) * 16));
-            const unsigned hi_off = ehi_base + (unsigned)(((d16 >> (kLoBits + 4)) - hmin) * 16);
             fetch_codes((p + 1) % NPASS, cw[(p + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            unsigned cc[2 * NB];
+            uint4_t ehr[2];
 #pragma unroll
-            for (int v = 0; v < NB; ++v) {
-                cc[2 * v + 0] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_lo);
-                cc[2 * v + 1] = __builtin_amdgcn_perm(cw[p & 1][2 * v + 1], cw[p & 1][2 * v], rsel_hi);
-            }
+            for (int h = 0; h < 2; ++h)
+                ehr[h] = lds_read_b128(ehi_last + (unsigned)((NPASS - 1 - p) * (PSTRIDE / kLo) * (16 * HROW) + h * 64));
+            __builtin_amdgcn_sched_barrier(0);
+            unsigned ccn[2 * NB];
             floatx4_t t[NGRP];
 #pragma unroll
             for (int x = 0; x < NGRP; ++x) t[x] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int pl = 0; pl < PL; ++pl) {
-                // 1. gather-sum of the plane: 8 NB pieces per lane, in groups of 4 reads
+                // 1. gather-sum of the plane
                 floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-                constexpr int NS = 8 * NB, RG = (NB == 2 || G == 8) ? 2 : 4, NG = NS / RG;  // fewer reads in flight where registers are short
-                uint4_t v[2][RG];
-                auto issue = [&](int grp, uint4_t(&dst)[RG]) {
-#pragma unroll
-                    for (int r = 0; r < RG; ++r) {
-                        const int st = grp * RG + r;       // level 16 (st / 8) + 8 half + (n + st) mod 8
-                        const int idx = pl * NB + st / 8;  // (plane, block) image of 16 KiB
-                        const unsigned selb = 0x0c000000u | (unsigned)(2 + idx / 4) << 16 | (unsigned)(4 + st % 4) << 8;
-                        const unsigned addr = __builtin_amdgcn_perm(cc[st / 4], xreg[st % 8], selb);
-                        dst[r] = lds_read_b128((unsigned)((idx % 4) * kPairBlock) + addr);
-                    }
-                };
-                issue(0, v[0]);
 #pragma unroll
                 for (int grp = 0; grp < NG; ++grp) {
-                    if (grp + 1 < NG) issue(grp + 1, v[(grp + 1) & 1]);
+                    const int flat = pl * NG + grp;
+                    if (flat + 1 < NFLAT) {
+                        issue(flat + 1, cc, v[(flat + 1) & 1]);
+                    } else if (p + 1 < NPASS) {
+                        make_cc(cw[(p + 1) & 1], ccn);
+                        issue(0, ccn, v[(flat + 1) & 1]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int r = 0; r < RG; r += 2) {
-                        const uint4_t pa = v[grp & 1][r], pb = v[grp & 1][r + 1];
+                        const uint4_t pa = v[flat & 1][r], pb = v[flat & 1][r + 1];
                         const uint8v_t both = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
                         acc = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(selv, __builtin_bit_cast(bf16x16_t, both), acc, (int)sidx, 0, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // 2. decoded block of sub-space gk (Eq. def_center), rotated by E = E_hi E_lo
-                const uint4_t elr = lds_read_b128(lo_off + (unsigned)((pl / 2) * (kLo * 16)));
-                const uint4_t ehr = lds_read_b128(hi_off + (unsigned)((pl / 2) * (NHR * 16)));
-                const unsigned hxr = ehr[2 * (pl & 1)], hyr = ehr[2 * (pl & 1) + 1], lxr = elr[2 * (pl & 1)], lyr = elr[2 * (pl & 1) + 1];
-                const float hx = __builtin_bit_cast(float, hxr), hy = __builtin_bit_cast(float, hyr);
-                const float lx = __builtin_bit_cast(float, lxr), ly = __builtin_bit_cast(float, lyr);
-                const float ex = hx * lx - hy * ly;
-                const float ey = hx * ly + hy * lx;
+                // 2. decoded block of sub-space gk (Eq. def_center), rotated by the coarse phase factor
+                const unsigned hxr = ehr[pl / 2][2 * (pl & 1)], hyr = ehr[pl / 2][2 * (pl & 1) + 1];
+                const float ex = __builtin_bit_cast(float, hxr), ey = __builtin_bit_cast(float, hyr);
                 const float kx = acc[0] - acc[3], ky = acc[1] + acc[2];
                 const float bx = kx * ex - ky * ey;
                 const float by = kx * ey + ky * ex;
@@ -1574,44 +1620,17 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_pair(
             }
             // totals over the 4 lanes of the token: lane (n, gk) keeps head 4 grp + gk
 #pragma unroll
-            for (int x = 0; x < NGRP; ++x) sc[p][x] += swap16_add(swap32_add(t[x][0], t[x][2]), swap32_add(t[x][1], t[x][3]));
+            for (int x = 0; x < NGRP; ++x) sc[p][x][0] += swap16_add(swap32_add(t[x][0], t[x][2]), swap32_add(t[x][1], t[x][3]));
+            if (p + 1 < NPASS) {
+#pragma unroll
+                for (int i = 0; i < 2 * NB; ++i) cc[i] = ccn[i];
+            }
         }
     }
 
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-#pragma unroll
-    for (int x = 0; x < NGRP; ++x) {
-        const int head = 4 * x + gk;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int tok = tb + p * NW * 16;
-            if (head < G && tok < L) {
-                srow[(size_t)head * L + tok] = sc[p][x];
-                mx = fmaxf(mx, sc[p][x]);
-            }
-        }
-        const float wm = row_max16(mx);
-        float l = 0.f;
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int tok = tb + p * NW * 16;
-            if (head < G && tok < L) l += __builtin_amdgcn_exp2f((sc[p][x] - wm) * kLog2e);
-        }
-        l = row_sum16(l);
-        if (n == 0 && head < G) wstat[wave][head] = make_float2(wm, l);
-    }
-    __syncthreads();
-    if (tid < G) {
-        float m = -INFINITY;
-        for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
-        float l = 0.f;
-        for (int w = 0; w < NW; ++w) {
-            const float2 st = wstat[w][tid];
-            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
-        }
-        sstat[((size_t)b * a.Hq + (size_t)g * G + tid) * a.nsplit + tile] = make_float2(m, l);
-    }
+    float2 *stat_dst = sstat + ((size_t)b * a.Hq + (size_t)g * G) * a.nsplit + tile;
+    write_tile_logits<16, G, TPT, NPASS, NGRP, 1>(sc, reinterpret_cast<float *>(tab), wstat, srow, stat_dst, a.nsplit, tb, t0, L);
 }
 
 // ------------------------------------------------------------------ k_bins
@@ -2095,7 +2114,12 @@ hipError_t launch_sliced_m(const SliceArgs &a, int G, int tpt, int grid, hipStre
 template <int NB, int G, int TPT>
 hipError_t launch_pair_bgt(const SliceArgs &a, int grid, hipStream_t s)
 {
-    constexpr int lds = kPairPlanes * NB * kPairBlock + 8 * kLo * 16 + 8 * (TPT * kSliceThreads / kLo + 1) * 16 + kStatBytes;
+    constexpr int tile = TPT * kSliceThreads;
+    // slice + fine phase factors + coarse rows (12 entries each) + per-wavefront statistics; the write-out stages four
+    // heads of the tile's logits, [64 positions padded to 68] per coarse row, over the slice and the phase factors
+    constexpr int work = kPairPlanes * NB * kPairBlock + 8 * kLo * 16 + 12 * (tile / kLo + 1) * 16;
+    constexpr int stg = 4 * ((tile / kLo) * 68 + 16) * 4;
+    constexpr int lds = (work > stg ? work : stg) + kStatBytes;
     static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
     if (hipError_t e = allow_dynamic_lds(&k_score_pair<NB, G, TPT>, lds, lds_ok); e != hipSuccess) return e;
     hipLaunchKernelGGL((k_score_pair<NB, G, TPT>), dim3(grid), dim3(kSliceThreads), lds, s, a.q, a.key_codes, a.packed,
