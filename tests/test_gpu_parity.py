@@ -211,6 +211,47 @@ def test_slice_groups_on_the_8b_layer_at_16k(gpu, oracle):
     op.close()
 
 
+def _random_shape(case):
+    """One seeded shape within the documented limits: group size, code widths, storage, key format, batch and lengths."""
+    rng = np.random.Generator(np.random.PCG64(9100 + case))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.integers(1, 4))
+    kind = ["short", "mixed", "many", "long"][case % 4]
+    if kind == "short":
+        lens = rng.integers(1, 700, size=int(rng.integers(1, 7)))
+    elif kind == "mixed":
+        lens = rng.integers(1, 6000, size=int(rng.integers(2, 6)))
+    elif kind == "many":     # a serving batch: many short sequences
+        lens = rng.integers(1, 300, size=int(rng.integers(20, 40)))
+    else:
+        lens = rng.integers(5000, 14000, size=int(rng.integers(1, 3)))
+    lens = [int(x) for x in lens]
+    if max(lens) < 1:
+        lens[0] = 1
+    return G, Hkv, lens, rng
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_shapes_index_form(gpu, oracle, case):
+    G, Hkv, lens, rng = _random_shape(case)
+    Mk, Mv = int(rng.choice([16, 32])), int(rng.choice([16, 32]))
+    dtype = "f32" if case % 5 == 4 else "bf16"
+    w = synth.make_workload(f"rnd{case}", B=len(lens), Hq=G * Hkv, Hkv=Hkv, seqlens=lens, Mk=Mk, Mv=Mv, dtype=dtype,
+                            seed=9200 + case, code_dist="zipf" if case % 3 == 0 else "uniform")
+    check(gpu, oracle, w)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_random_shapes_paired_keys(gpu, oracle, case):
+    G, Hkv, lens, rng = _random_shape(case + 100)
+    R = int(rng.integers(1, 22))
+    w = synth.make_pair_workload(f"rndp{case}", B=len(lens), Hq=G * Hkv, Hkv=Hkv, seqlens=lens, R=R, Mv=int(rng.choice([16, 32])),
+                                 seed=9300 + case)
+    print(f"case {w.name} R={R} G={G} Hkv={Hkv} lens={lens[:8]}", flush=True)
+    got = run_gpu(gpu, w)
+    assert_rows(got, oracle_out_paired(oracle, w), w.name)
+
+
 @pytest.mark.parametrize("Mk", [16, 32])
 @pytest.mark.parametrize("qpos", [0, 1234, 70000])
 def test_contiguous_keys_with_query_inside_or_far_beyond_the_context(gpu, oracle, Mk, qpos):
