@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--config", type=int, default=3,
                     help="workload 1..7 (3 = 8B-shaped layer, 128K context, 1-bit; 6, 7 = the same layer with keys in "
                          "the paper's paired format, R = 11 / 21)")
+    ap.add_argument("--context-tokens", type=int, default=None,
+                    help="shrink every context of the workload to at most this many tokens (short-context plans: score "
+                         "tiles cut along the codebook slices); the workload name then ends in _ctx<N>")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-resident numbers)")
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
@@ -267,7 +270,9 @@ def main():
     from paper_2506_18879_amd.device import DecodeAttention, DeviceWorkload
 
     torch.cuda.set_device(0)
-    w = synth.config(args.config)
+    w = synth.config(args.config, max_len=args.context_tokens)
+    if args.context_tokens is not None:
+        w.name = f"{w.name}_ctx{args.context_tokens}"
     T, G = w.total_tokens, w.Hq // w.Hkv
     esz = 2 if w.dtype == "bf16" else 4
     code_bytes = w.key_codes.nbytes + w.val_codes.nbytes
@@ -372,6 +377,7 @@ def main():
                 "launches_sampled": ("every call of a separate eager run" if args.graph else
                                      f"every {args.stage_event_interval}th call of the timed region"),
                 "timed_region_includes": ("index unpacking (k_unpack_pairs) + k_score_pair" if paired else
+                                          "k_score_mfma + k_score_combine" if prepacked and op.plan.score_slice_groups > 1 else
                                           "k_score_mfma only" if prepacked else "codebook re-layout (k_prep) + score kernel"),
                 "lds_gather_view": {"codeword_bytes_TBs": round(gather_tbs, 2), "peak_TBs": LDS_PEAK_TBS,
                                     "frac": round(gather_tbs / LDS_PEAK_TBS, 4)},
@@ -413,7 +419,9 @@ def main():
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "context_tokens": T, "m_key": w.Mk, "m_val": w.Mv, "codewords": w.K, "storage": w.dtype,
                    "key_format": w.key_format, "key_levels": w.key_levels, "position_free": bool(args.position_free),
-                   "codes": w.code_dist, "buffer_copies_rotated": n_copies,
+                   "codes": w.code_dist, "score_tile_tokens": op.plan.score_split_len,
+                   "score_slice_groups": op.plan.score_slice_groups, "value_split_tokens": op.plan.value_split_len,
+                   "buffer_copies_rotated": n_copies,
                    "key_codebooks_packed_before_timed_region": prepacked, "hip_graph_replay": bool(args.graph),
                    "cache_state": "warm" if args.warm else "cold (rotating copies > 256 MB LLC)"},
         "whole_call": {"code_stream_GBs": round(code_bytes / (ms_per_step * 1e-3) / 1e9, 1),

@@ -93,7 +93,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
                 const long wgs = (long)units * ((max_seqlen + 1024 * tpt - 1) / (1024 * tpt)) * e;
                 // cut along the slices: every group fetches the tile's codes again, the partial logits take a trip through
                 // memory, and k_score_combine is one more launch
-                const double t = (double)((wgs + 255) / 256) * (9.0 + (double)(S / e) * (1.3 + tpt * c1024)) + (e > 1 ? 18.0 : 0.0);
+                const double t = (double)((wgs + 255) / 256) * (9.0 + (double)(S / e) * (1.3 + tpt * c1024)) + (e > 1 ? 12.0 : 0.0);
                 if (t < best * 0.9999) { best = t; len = 1024 * tpt; groups = e; }
             }
         }

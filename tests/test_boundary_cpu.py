@@ -128,7 +128,11 @@ def test_planner_plans_the_five_configurations(planner):
         assert p.score_split_len in (64, 128, 256, 512, 1024, 2048, 4096)
         assert p.score_splits == -(-L // p.score_split_len)
         assert p.value_splits == -(-L // p.value_split_len) and 1 <= p.value_splits <= 256
-        assert p.value_split_len % max(p.score_split_len, 1024) == 0 or p.score_kernel == 0
+        # a value split is a whole number of statistics tiles (score tiles, or 1024 tokens when the tiles are also cut
+        # along the slices) or a power-of-two fraction of one, never under 1024 tokens
+        stat = 1024 if p.score_slice_groups > 1 else p.score_split_len
+        assert (p.value_split_len % max(stat, 1024) == 0 or p.score_kernel == 0
+                or (stat % p.value_split_len == 0 and p.value_split_len >= 1024))
         assert p.out_chunks == kw.get("m_val", 32) * 256 // 64
         assert p.score_kernel == (0 if kw.get("codebook_dtype", 1) == 0 else 1)
         ws = cv.commvq_workspace_bytes(h, B, T, L)
