@@ -680,9 +680,12 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_mfma(
     const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(src, (unsigned)S * PIECES * 16u);
     uint4_t stage[PPT];
     auto fetch_slice = [&](int sl) {
+        // the slice index is the same in every lane; said so explicitly, or the loads may be wrapped in a loop over
+        // the distinct values of what the compiler holds in a vector register
+        const unsigned soff = __builtin_amdgcn_readfirstlane((unsigned)sl * (PIECES * 16u));
 #pragma unroll
         for (int x = 0; x < PPT; ++x)
-            stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, (unsigned)sl * (PIECES * 16u), 0);
+            stage[x] = __builtin_amdgcn_raw_buffer_load_b128(src_rs, (unsigned)(x * kSliceThreads + tid) * 16u, soff, 0);
     };
     constexpr bool PREFETCH = !(M == 32 && G == 8 && TPT == 4);  // that instantiation has no registers to spare
     if (PREFETCH) fetch_slice(s_begin);
