@@ -578,3 +578,23 @@ def test_full_size_sampled_units(gpu, oracle, idx, units):
         b, g = divmod(int(u), w.Hkv)
         worst = max(worst, assert_rows(got[b, g * G:(g + 1) * G], ref[b, g * G:(g + 1) * G], f"{w.name} unit {u}"))
     print(f"  worst row error over {units} units: {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("path", ["sliced", "row_gather", "paired", "position_free"])
+def test_rope_base_and_softmax_scale_from_the_configuration(gpu, oracle, path):
+    # theta_j = base^(-2j/d) with a base other than the workloads' 500000, and a logit scale other than 1/sqrt(d):
+    # both are fields of the configuration and reach every score path through the handle's phase tables / scale
+    import torch
+    base, scale = 10000.0, 0.05
+    kw = dict(B=2, Hq=8, Hkv=2, seqlens=[2100, 700], Mv=16, seed=8800, rope_base=base)
+    if path == "paired":
+        w = synth.make_pair_workload("cfg_paired", R=11, **kw)
+    else:
+        w = synth.make_workload(f"cfg_{path}", Mk=16, dtype="f32" if path == "row_gather" else "bf16", **kw)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w, softmax_scale=scale, position_free=path == "position_free")
+    got = op(dw)
+    torch.cuda.synchronize()
+    ref_fn = {"paired": oracle_out_paired, "position_free": oracle_out_position_free}.get(path, oracle_out)
+    assert_rows(got.cpu().numpy(), ref_fn(oracle, w, scale=scale), w.name)
+    op.close()
