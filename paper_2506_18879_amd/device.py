@@ -45,13 +45,15 @@ class DeviceWorkload:
 class DecodeAttention:
     """Owns a libcommvq handle, a workspace and an output buffer for one batch shape."""
 
-    def __init__(self, w, max_position: Optional[int] = None, softmax_scale: float = 0.0, position_free: bool = False):
+    def __init__(self, w, max_position: Optional[int] = None, softmax_scale: float = 0.0, position_free: bool = False,
+                 q_dtype: Optional[str] = None):
         torch = _torch()
         dt = B.COMMVQ_BF16 if w.dtype == "bf16" else B.COMMVQ_F32
+        qdt = dt if q_dtype is None else (B.COMMVQ_BF16 if q_dtype == "bf16" else B.COMMVQ_F32)
         if max_position is None:
             max_position = max(int(w.q_pos.max()), w.max_seqlen, 0 if w.key_pos is None else int(w.key_pos.max()))
         paired = getattr(w, "key_format", "indexed") == "paired"
-        self.cfg = B.Config(w.Hq, w.Hkv, w.d, 16 if paired else w.Mk, w.Mv, w.K, dt, dt, float(w.rope_base),
+        self.cfg = B.Config(w.Hq, w.Hkv, w.d, 16 if paired else w.Mk, w.Mv, w.K, qdt, dt, float(w.rope_base),
                             float(softmax_scale), int(max_position),
                             B.COMMVQ_KEYS_PAIRED if paired else B.COMMVQ_KEYS_INDEXED, w.key_levels if paired else 0,
                             1 if position_free else 0)

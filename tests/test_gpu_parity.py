@@ -598,3 +598,29 @@ def test_rope_base_and_softmax_scale_from_the_configuration(gpu, oracle, path):
     ref_fn = {"paired": oracle_out_paired, "position_free": oracle_out_position_free}.get(path, oracle_out)
     assert_rows(got.cpu().numpy(), ref_fn(oracle, w, scale=scale), w.name)
     op.close()
+
+
+@pytest.mark.parametrize("path", ["sliced", "row_gather", "paired", "position_free"])
+def test_query_type_independent_of_the_codebook_type(gpu, oracle, path):
+    # q_dtype and codebook_dtype are separate fields: fp32 queries on bf16 codebooks (and bf16 queries on fp32 ones).
+    # The query values stay those of the workload (widened or already representable), so the oracle result is the same.
+    import torch
+    kw = dict(B=2, Hq=8, Hkv=2, seqlens=[1900, 640], Mv=16, seed=8900)
+    if path == "paired":
+        w = synth.make_pair_workload("qt_paired", R=11, **kw)
+    else:
+        w = synth.make_workload(f"qt_{path}", Mk=32, dtype="f32" if path == "row_gather" else "bf16", **kw)
+    dw = gpu.DeviceWorkload(w)
+    if w.dtype == "bf16":
+        dw.q = dw.q.float().contiguous()                       # exact widening
+        q_dtype = "f32"
+    else:
+        w.q = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(w.q))  # representable in bf16, before either side sees it
+        dw.q = gpu.to_device(synth.f32_to_bf16_bits(w.q), bf16=True)
+        q_dtype = "bf16"
+    op = gpu.DecodeAttention(w, q_dtype=q_dtype, position_free=path == "position_free")
+    got = op(dw)
+    torch.cuda.synchronize()
+    ref_fn = {"paired": oracle_out_paired, "position_free": oracle_out_position_free}.get(path, oracle_out)
+    assert_rows(got.cpu().numpy(), ref_fn(oracle, w), w.name)
+    op.close()
