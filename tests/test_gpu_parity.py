@@ -108,9 +108,10 @@ def test_staged_entry_points_equal_fused_call(gpu):
     assert np.array_equal(a, b)
 
 
-def test_prepacked_key_codebooks_give_identical_bits(gpu):
+@pytest.mark.parametrize("idx", [3, 2, 6, 7])
+def test_prepacked_key_codebooks_give_identical_bits(gpu, idx):
     import torch
-    w = synth.config(3, max_len=5000)
+    w = synth.config(idx, max_len=5000)     # index form with 16 / 32 codebooks, paired format with one / two level blocks
     dw = gpu.DeviceWorkload(w)
     op = gpu.DecodeAttention(w)
     a = op(dw).clone()
