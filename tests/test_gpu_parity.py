@@ -625,3 +625,27 @@ def test_query_type_independent_of_the_codebook_type(gpu, oracle, path):
     ref_fn = {"paired": oracle_out_paired, "position_free": oracle_out_position_free}.get(path, oracle_out)
     assert_rows(got.cpu().numpy(), ref_fn(oracle, w), w.name)
     op.close()
+
+
+def test_two_handles_on_two_streams_do_not_disturb_each_other(gpu):
+    # independent handles, workspaces and streams: calls that overlap on the GPU give the bits of calls run alone
+    import torch
+    wa = synth.config(3, max_len=20000)
+    wb = synth.make_pair_workload("conc_paired", B=2, Hq=8, Hkv=2, seqlens=[3000, 1200], R=21, Mv=32, seed=77)
+    dwa, dwb = gpu.DeviceWorkload(wa), gpu.DeviceWorkload(wb)
+    opa, opb = gpu.DecodeAttention(wa), gpu.DecodeAttention(wb)
+    ref_a, ref_b = opa(dwa).clone(), opb(dwb).clone()
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs_a = [torch.empty_like(ref_a) for _ in range(8)]
+    outs_b = [torch.empty_like(ref_b) for _ in range(8)]
+    for k in range(8):
+        with torch.cuda.stream(sa):
+            opa(dwa, out=outs_a[k])
+        with torch.cuda.stream(sb):
+            opb(dwb, out=outs_b[k])
+    torch.cuda.synchronize()
+    for k in range(8):
+        assert torch.equal(outs_a[k], ref_a) and torch.equal(outs_b[k], ref_b), k
+    opa.close()
+    opb.close()
