@@ -1852,63 +1852,71 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
     // bins: [split][K][Mv][G]; the chunk's 64 rows are kOutRows / Mv consecutive codewords of every codebook, one
     // contiguous run of 64 * G bins per split; local row r = (codeword - first) * Mv + codebook.  A thread reads
     // the G bins of its row with one vector load and takes every fourth split.
+    constexpr int NSG = kOutThreads / kOutRows;
+    constexpr int NCR = kOutRows / (kOutThreads / 64);  // codebook rows per wavefront
+    const int r1 = tid % kOutRows, sg = tid / kOutRows;
+    const unsigned *src = a.bins + (size_t)(b * a.Hkv + g) * a.nvsplit * G * MK + (size_t)(chunk * kOutRows + r1) * G;
+    auto load_bins = [&](int v, unsigned(&bv)[G]) {
+        const unsigned *pv = src + (size_t)v * G * MK;
+        if (G >= 4) {
+#pragma unroll
+            for (int q4 = 0; q4 < G / 4; ++q4) {
+                const uint4 t4 = reinterpret_cast<const uint4 *>(pv)[q4];
+                bv[4 * q4 + 0] = t4.x; bv[4 * q4 + 1 < G ? 4 * q4 + 1 : 0] = t4.y; bv[4 * q4 + 2 < G ? 4 * q4 + 2 : 0] = t4.z; bv[4 * q4 + 3 < G ? 4 * q4 + 3 : 0] = t4.w;
+            }
+        } else if (G == 2) {
+            const uint2 t2 = *reinterpret_cast<const uint2 *>(pv);
+            bv[0] = t2.x; bv[G - 1] = t2.y;
+        } else {
+            bv[0] = pv[0];
+        }
+    };
+    // a wavefront takes a quarter of the codebooks and the chunk's codewords of each: runs of consecutive rows
+    const int cpc = kOutRows / a.Mv, mpw = a.Mv / (kOutThreads / 64);  // codewords per chunk, codebooks per wavefront
+    auto load_row = [&](int i) -> float2 {
+        const int m = wave * mpw + i / cpc, cl = i % cpc;
+        const size_t row = (size_t)g * MK + (size_t)m * kK + (size_t)chunk * cpc + cl;
+        if (BF16) {
+            const unsigned v = static_cast<const unsigned *>(a.val_cb)[row * kJ + lane];
+            return make_float2(bf16_lo(v), bf16_hi(v));
+        }
+        return static_cast<const float2 *>(a.val_cb)[row * kJ + lane];
+    };
     for (int x = tid; x < G * nvs; x += kOutThreads)
         scl[x / nvs][x % nvs] = a.vscale[((size_t)b * a.Hq + (size_t)g * G + x / nvs) * a.nvsplit + x % nvs];
     __syncthreads();
     {
-        constexpr int NSG = kOutThreads / kOutRows;
-        const int r = tid % kOutRows, sg = tid / kOutRows;
-        const unsigned *src = a.bins + (size_t)(b * a.Hkv + g) * a.nvsplit * G * MK + (size_t)(chunk * kOutRows + r) * G;
         float s[G];
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) s[hh] = 0.f;
 #pragma unroll 4
         for (int v = sg; v < nvs; v += NSG) {
             unsigned bv[G];
-            const unsigned *pv = src + (size_t)v * G * MK;
-            if (G >= 4) {
-#pragma unroll
-                for (int q4 = 0; q4 < G / 4; ++q4) {
-                    const uint4 t4 = reinterpret_cast<const uint4 *>(pv)[q4];
-                    bv[4 * q4 + 0] = t4.x; bv[4 * q4 + 1 < G ? 4 * q4 + 1 : 0] = t4.y; bv[4 * q4 + 2 < G ? 4 * q4 + 2 : 0] = t4.z; bv[4 * q4 + 3 < G ? 4 * q4 + 3 : 0] = t4.w;
-                }
-            } else if (G == 2) {
-                const uint2 t2 = *reinterpret_cast<const uint2 *>(pv);
-                bv[0] = t2.x; bv[G - 1] = t2.y;
-            } else {
-                bv[0] = pv[0];
-            }
+            load_bins(v, bv);
 #pragma unroll
             for (int hh = 0; hh < G; ++hh) s[hh] += (float)bv[hh] * scl[hh][v];
         }
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) part[sg][r][hh] = s[hh];
+        for (int hh = 0; hh < G; ++hh) part[sg][r1][hh] = s[hh];
     }
     __syncthreads();
     for (int x = tid; x < G * kOutRows; x += kOutThreads) {
         const int hh = x % G, r = x / G;
         float s = 0.f;
 #pragma unroll
-        for (int sg = 0; sg < kOutThreads / kOutRows; ++sg) s += part[sg][r][hh];
+        for (int q = 0; q < NSG; ++q) s += part[q][r][hh];
         wsum[hh][r] = s;
     }
     __syncthreads();
     float2 acc[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) acc[hh] = make_float2(0.f, 0.f);
-    // a wavefront takes a quarter of the codebooks and the chunk's codewords of each: runs of consecutive rows
-    const int cpc = kOutRows / a.Mv, mpw = a.Mv / (kOutThreads / 64);  // codewords per chunk, codebooks per wavefront
-    for (int i = 0; i < kOutRows / (kOutThreads / 64); ++i) {
+    // (unrolled: the wavefront's 16 row loads are requested together)
+#pragma unroll
+    for (int i = 0; i < NCR; ++i) {
         const int m = wave * mpw + i / cpc, cl = i % cpc;
         const int r = cl * a.Mv + m;
-        const size_t row = (size_t)g * MK + (size_t)m * kK + (size_t)chunk * cpc + cl;
-        float2 c;
-        if (BF16) {
-            const unsigned v = static_cast<const unsigned *>(a.val_cb)[row * kJ + lane];
-            c = make_float2(bf16_lo(v), bf16_hi(v));
-        } else {
-            c = static_cast<const float2 *>(a.val_cb)[row * kJ + lane];
-        }
+        const float2 c = load_row(i);
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
             const float w = wsum[hh][r];
