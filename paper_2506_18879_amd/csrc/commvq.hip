@@ -1889,8 +1889,22 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
         float s[G];
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) s[hh] = 0.f;
+        // eight splits' bins in flight where a thread has that many and the registers allow, else four (same order of
+        // additions either way)
+        int v = sg;
+        if (G <= 4 && nvs >= 8 * NSG) {
+            for (; v + 7 * NSG < nvs; v += 8 * NSG) {
+                unsigned bv[8][G];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) load_bins(v + k * NSG, bv[k]);
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+#pragma unroll
+                    for (int hh = 0; hh < G; ++hh) s[hh] += (float)bv[k][hh] * scl[hh][v + k * NSG];
+            }
+        }
 #pragma unroll 4
-        for (int v = sg; v < nvs; v += NSG) {
+        for (; v < nvs; v += NSG) {
             unsigned bv[G];
             load_bins(v, bv);
 #pragma unroll
