@@ -435,6 +435,26 @@ def main():
         "roofline": roofline,
     }
     result["roofline"].update(stage_views)
+    # what the memory system of this machine delivers to a plain streaming kernel: a device-to-device copy of 1 GiB (torch's
+    # copy kernel; every byte read once and written once), as a measured companion to the published 8 TB/s
+    try:
+        n = 1 << 30
+        src, dst = torch.empty(n, dtype=torch.uint8, device="cuda"), torch.empty(n, dtype=torch.uint8, device="cuda")
+        src.zero_()
+        for _ in range(2):
+            dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+        result["whole_call"]["measured_copy_GBs"] = round(copy_gbs, 1)
+        result["whole_call"]["code_stream_frac_of_measured_copy"] = round(result["whole_call"]["code_stream_GBs"] / copy_gbs, 4)
+    except Exception:  # (a box without 2 GiB to spare: the figure is a companion, not part of the metric)
+        result["whole_call"]["measured_copy_GBs"] = None
 
     if not args.no_cpu_baseline:
         import oracle
