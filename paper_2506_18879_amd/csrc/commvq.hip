@@ -99,8 +99,8 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         }
     } else {
         len = 1024;
-        // down to 16 tokens per wavefront (four iterations of four tokens): a short context still spreads over the chip
-        while (len > kScoreThreads / 4 && (long)units * ((max_seqlen + len - 1) / len) < kScoreMinWgs) len /= 2;
+        // down to 4 tokens per wavefront (one iteration of four tokens): a short context still spreads over the chip
+        while (len > 16 && (long)units * ((max_seqlen + len - 1) / len) < kScoreMinWgs) len /= 2;
     }
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int r = lane >> 4, sub = lane & 15;
-    const int wlen = a.split_len / (kScoreThreads / 64);  // 16, 32 or a multiple of 64 tokens per wavefront
+    const int wlen = a.split_len / (kScoreThreads / 64);  // 4, 8, 16, 32 or a multiple of 64 tokens per wavefront
     const int t0 = s0 + wave * wlen;
     const int t1 = min(min(t0 + wlen, s0 + a.split_len), L);
     const int n_it = t1 > t0 ? (t1 - t0 + 3) / 4 : 0;

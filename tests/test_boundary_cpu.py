@@ -125,7 +125,7 @@ def test_planner_plans_the_five_configurations(planner):
     for kw, B, T, L in cases:
         h = planner(**kw)
         p = cv.commvq_plan_query(h, B, T, L)
-        assert p.score_split_len in (64, 128, 256, 512, 1024, 2048, 4096)
+        assert p.score_split_len in (16, 32, 64, 128, 256, 512, 1024, 2048, 4096)
         assert p.score_splits == -(-L // p.score_split_len)
         assert p.value_splits == -(-L // p.value_split_len) and 1 <= p.value_splits <= 256
         # a value split is a whole number of statistics tiles (score tiles, or 1024 tokens when the tiles are also cut
