@@ -296,6 +296,7 @@ def main():
     if prepacked:
         for c in copies:
             op.pack_key_codebooks(c)
+            op.pack_value_codebooks(c)   # (used by the batched output kernel only: 16 or more output rows per KV head)
         torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -422,7 +423,7 @@ def main():
                    "codes": w.code_dist, "score_tile_tokens": op.plan.score_split_len,
                    "score_slice_groups": op.plan.score_slice_groups, "value_split_tokens": op.plan.value_split_len,
                    "buffer_copies_rotated": n_copies,
-                   "key_codebooks_packed_before_timed_region": prepacked, "hip_graph_replay": bool(args.graph),
+                   "key_codebooks_packed_before_timed_region": prepacked, "value_codebooks_packed_before_timed_region": prepacked, "hip_graph_replay": bool(args.graph),
                    "cache_state": "warm" if args.warm else "cold (rotating copies > 256 MB LLC)"},
         "whole_call": {"code_stream_GBs": round(code_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "algorithmic_GBs": round((per_copy + w.B * w.Hq * w.d * (esz + 4)) / (ms_per_step * 1e-3) / 1e9, 1),

@@ -204,6 +204,20 @@ commvq_status commvq_pack_key_codebooks(commvq_handle *handle, const void *key_c
 commvq_status commvq_forget_packed_key_codebooks(commvq_handle *handle, const void *key_codebooks);
 
 /*
+ * The same for the value codebooks (Eq. optimized_v: bins x C_V).  For batches of several sequences (16 or more
+ * output rows = sequences x query heads per KV head, bf16 codebooks) the product with the value codebook runs on the
+ * matrix cores and reads the codebook in k-step order ([KV head][32 rows][dimension][32] with rows ordered
+ * codeword * M_v + codebook).  Without preparation every such call re-lays the value codebook into its workspace first;
+ * commvq_pack_value_codebooks does it once and remembers (val_codebooks -> packed) in the handle, exactly as above:
+ *   val_codebooks  [Hkv][M_v][K][d] bf16, as for commvq_decode_attn
+ *   packed         device buffer of commvq_packed_value_codebook_bytes() bytes, 16-byte aligned, caller-owned
+ * Results are bit-identical either way; smaller batches do not use it.  COMMVQ_ERR_CONFIG for fp32 codebooks.
+ */
+commvq_status commvq_packed_value_codebook_bytes(const commvq_handle *handle, size_t *bytes);
+commvq_status commvq_pack_value_codebooks(commvq_handle *handle, const void *val_codebooks, void *packed, void *stream);
+commvq_status commvq_forget_packed_value_codebooks(commvq_handle *handle, const void *val_codebooks);
+
+/*
  * Key encoding for cache append: the step before the attention call in every decode iteration.
  * Each new (pre-RoPE) key vector is assigned to its nearest clustering centre (the E step of Sec. 4.2),
  * level by level on the error left by the previous levels (residual refinement, Sec. 4.2); a centre of

@@ -41,6 +41,7 @@ Handle = c_void_p
 EXPORTS = ("commvq_create", "commvq_create_planner", "commvq_destroy", "commvq_validate_config", "commvq_plan_query", "commvq_workspace_bytes",
            "commvq_decode_attn", "commvq_decode_attn_static", "commvq_static_scratch_bytes", "commvq_stage_scores", "commvq_stage_bins", "commvq_stage_output",
            "commvq_packed_key_codebook_bytes", "commvq_pack_key_codebooks", "commvq_forget_packed_key_codebooks",
+           "commvq_packed_value_codebook_bytes", "commvq_pack_value_codebooks", "commvq_forget_packed_value_codebooks",
            "commvq_encoder_table_bytes", "commvq_encoder_prepare", "commvq_encode_keys",
            "commvq_value_encoder_table_bytes", "commvq_value_encoder_prepare", "commvq_encode_values",
            "commvq_em_workspace_bytes", "commvq_em_step", "commvq_em_shared_workspace_bytes", "commvq_em_step_shared",
@@ -79,6 +80,9 @@ def load_library():
     lib.commvq_packed_key_codebook_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.commvq_pack_key_codebooks.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     lib.commvq_forget_packed_key_codebooks.argtypes = [c_void_p, c_void_p]
+    lib.commvq_packed_value_codebook_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
+    lib.commvq_pack_value_codebooks.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.commvq_forget_packed_value_codebooks.argtypes = [c_void_p, c_void_p]
     lib.commvq_encoder_table_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.commvq_encoder_prepare.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     lib.commvq_encode_keys.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p]
@@ -187,6 +191,22 @@ def commvq_pack_key_codebooks(handle, key_codebooks, packed, stream: int = 0) ->
 def commvq_forget_packed_key_codebooks(handle, key_codebooks=None) -> None:
     _check(load_library().commvq_forget_packed_key_codebooks(handle, _ptr(key_codebooks)),
            "commvq_forget_packed_key_codebooks")
+
+
+def commvq_packed_value_codebook_bytes(handle) -> int:
+    n = c_size_t(0)
+    _check(load_library().commvq_packed_value_codebook_bytes(handle, byref(n)), "commvq_packed_value_codebook_bytes")
+    return int(n.value)
+
+
+def commvq_pack_value_codebooks(handle, val_codebooks, packed, stream: int = 0) -> None:
+    _check(load_library().commvq_pack_value_codebooks(handle, _ptr(val_codebooks), _ptr(packed), stream or None),
+           "commvq_pack_value_codebooks")
+
+
+def commvq_forget_packed_value_codebooks(handle, val_codebooks=None) -> None:
+    _check(load_library().commvq_forget_packed_value_codebooks(handle, _ptr(val_codebooks)),
+           "commvq_forget_packed_value_codebooks")
 
 
 def commvq_encoder_table_bytes(handle) -> int:

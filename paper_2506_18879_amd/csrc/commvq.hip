@@ -50,6 +50,7 @@ struct Workspace {
     uint8_t *pair_bytes;  // paired-code keys: one byte per index, [T * Hkv][32 * blocks]
     float *lut;           // position-free keys: scale * q . C, [B * Hkv][M_k * K][G]
     float *scores_part;   // [slice groups][T * Hq] partial logits when the score tiles are also cut along the slices
+    uint4 *packed_val;    // value codebook re-laid for k_out_mfma (batches; only if the caller has not packed it)
     size_t bytes;
 };
 
@@ -59,6 +60,13 @@ bool use_sliced(const commvq_handle *h, bool explicit_positions)
 {
     if (h->cfg.position_free) return true;  // scalar look-up table kernel: same tiling, positions play no role
     return h->cfg.codebook_dtype == COMMVQ_BF16 && !explicit_positions;
+}
+
+// The batched output kernel (value codebook on the matrix cores) serves bf16 codebooks from 16 output rows
+// (sequences x query heads of a KV head) on.
+inline bool use_out_mfma(const commvq_handle *h, int batch)
+{
+    return h->cfg.codebook_dtype == COMMVQ_BF16 && batch * h->G >= kOutMfmaMinRows;
 }
 
 // Paired-code key format: blocks of 16 levels, bytes of one packed record, bytes of the unpacked indices of a token.
@@ -156,6 +164,7 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     w->pair_bytes = pair_keys(c) ? reinterpret_cast<uint8_t *>(take((size_t)T * c.n_kv_heads * 8 * pair_blocks(c))) : nullptr;
     w->lut = c.position_free ? take((size_t)B * c.n_q_heads * c.m_key * kK) : nullptr;
     w->scores_part = pa.score_slice_groups > 1 ? take((size_t)pa.score_slice_groups * T * c.n_q_heads) : nullptr;
+    w->packed_val = use_out_mfma(h, B) ? reinterpret_cast<uint4 *>(take((size_t)c.n_kv_heads * c.m_val * kK * kD * 2 / 4)) : nullptr;
     w->bytes = off;
 }
 
@@ -1827,6 +1836,7 @@ struct OutArgs {
     const float *vscale, *lsum;
     float *partial, *out;
     int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
+    int batch;
 };
 
 // Workgroup = (sequence, KV head, chunk of codebook rows): sums the chunk's bins over the
@@ -1949,6 +1959,118 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
         float s = 0.f;
         for (int w = 0; w < kOutThreads / 64; ++w) s += red[w][hh][e];
         a.partial[(((size_t)b * a.Hq + (size_t)g * G + hh) * a.nchunk + chunk) * kD + e] = s;
+    }
+}
+
+// Value codebook re-laid for k_out_mfma: vp[g][kt][dim][32] bf16, where row 32 kt + j of head g is codeword
+// (32 kt + j) / M_v of codebook (32 kt + j) % M_v (the row order of the bins) -- the 32 rows of a k-step of the matrix
+// instruction contiguous per output dimension.  One thread per 16-byte piece of the output (static data, done once).
+__global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict__ val_cb, uint4 *__restrict__ vp, int Hkv, int Mv)
+{
+    const int MK = Mv * kK;
+    const size_t n = (size_t)Hkv * (MK / 32) * kD * 4;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n) return;
+    const int kg = (int)(t & 3), dim = (int)((t >> 2) % kD);
+    const size_t rest = (t >> 2) / kD;
+    const int kt = (int)(rest % (MK / 32)), g = (int)(rest / (MK / 32));
+    unsigned w[4];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int r = 32 * kt + 8 * kg + e;
+        const unsigned v = val_cb[(((size_t)g * Mv + r % Mv) * kK + r / Mv) * kD + dim];
+        if (e & 1) w[e / 2] |= v << 16; else w[e / 2] = v;
+    }
+    vp[t] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// The output stage for batches (Eq. optimized_v's bins x C_V as what it is for several sequences, a matrix product):
+// per KV head, [sequences x query heads] x [M_v K rows] times [rows] x [d].  A workgroup takes 16 output rows
+// (16 / G sequences), kOutMfmaRows codebook rows and all d columns: it sums the fixed-point bins of its rows over the
+// value splits (fp32, each split's unit applied), splits every fp32 weight EXACTLY into three bf16 parts (24 mantissa
+// bits = 8 + 8 + 8) and multiplies them with the bf16 codebook by v_mfma_f32_16x16x32_bf16, accumulating in fp32: the
+// fp32 product up to summation order, at a tenth of the vector instructions.  Each wavefront takes 32 of the 128 columns;
+// the codebook comes straight from memory in the k_prep_values order (16 bytes per lane = 8 consecutive rows of one
+// column), read once per 16 output rows instead of once per sequence.
+template <int G>
+__global__ __launch_bounds__(kOutThreads) void k_out_mfma(OutArgs a, const uint4 *__restrict__ vp)
+{
+    constexpr int KC = kOutMfmaRows, SPT = 16 / G, WS = KC + 8;  // (row stride padded: the 16 rows fall on different banks)
+    __shared__ __attribute__((aligned(16))) uint16_t Wl[3][16][WS];
+    int id = blockIdx.x;
+    const int chunk = id % a.nchunk;
+    id /= a.nchunk;
+    const int g = id % a.Hkv;
+    const int b0 = (id / a.Hkv) * SPT;
+    const int MK = a.Mv * kK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int it = tid; it < SPT * KC; it += kOutThreads) {
+        const int sq = it / KC, k = it % KC, b = b0 + sq;
+        float w[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) w[hh] = 0.f;
+        if (b < a.batch) {
+            const int L = a.cu[b + 1] - a.cu[b];
+            const int nvs = min((L + a.vsplit_len - 1) / a.vsplit_len, a.nvsplit);
+            const unsigned *src = a.bins + (size_t)(b * a.Hkv + g) * a.nvsplit * G * MK + (size_t)(chunk * KC + k) * G;
+            const float *scl = a.vscale + ((size_t)b * a.Hq + (size_t)g * G) * a.nvsplit;
+#pragma unroll 4
+            for (int v = 0; v < nvs; ++v) {
+                const unsigned *pv = src + (size_t)v * G * MK;
+                unsigned bv[G];
+                if (G >= 4) {
+#pragma unroll
+                    for (int q4 = 0; q4 < G / 4; ++q4) {
+                        const uint4 t4 = reinterpret_cast<const uint4 *>(pv)[q4];
+                        bv[4 * q4 + 0] = t4.x; bv[4 * q4 + 1 < G ? 4 * q4 + 1 : 0] = t4.y; bv[4 * q4 + 2 < G ? 4 * q4 + 2 : 0] = t4.z; bv[4 * q4 + 3 < G ? 4 * q4 + 3 : 0] = t4.w;
+                    }
+                } else if (G == 2) {
+                    const uint2 t2 = *reinterpret_cast<const uint2 *>(pv);
+                    bv[0] = t2.x; bv[G - 1] = t2.y;
+                } else {
+                    bv[0] = pv[0];
+                }
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) w[hh] += (float)bv[hh] * scl[(size_t)hh * a.nvsplit + v];
+            }
+        }
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            // hi = the top 16 bits, mid = the top 16 bits of what is left, lo = the rest (exact: 8 + 8 + 8 mantissa bits)
+            const unsigned u0 = __builtin_bit_cast(unsigned, w[hh]) & 0xffff0000u;
+            const float r1 = w[hh] - __builtin_bit_cast(float, u0);
+            const unsigned u1 = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
+            const float r2 = r1 - __builtin_bit_cast(float, u1);
+            const unsigned u2 = __builtin_bit_cast(unsigned, r2) & 0xffff0000u;
+            Wl[0][sq * G + hh][k] = (uint16_t)(u0 >> 16);
+            Wl[1][sq * G + hh][k] = (uint16_t)(u1 >> 16);
+            Wl[2][sq * G + hh][k] = (uint16_t)(u2 >> 16);
+        }
+    }
+    __syncthreads();
+    // first operand: lane (i = lane % 16, kg = lane / 16) supplies weights of output row i for rows 8 kg .. 8 kg + 7 of the
+    // k-step; second: lane (n, kg) the same rows of column n; result: lane (n, rg) holds rows 4 rg .. 4 rg + 3 of column n
+    const int n = lane & 15, kg = lane >> 4;
+    floatx4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    const uint4 *bsrc = vp + (((size_t)g * (MK / 32) + (size_t)chunk * (KC / 32)) * kD + 32 * wave + n) * 4 + kg;
+#pragma unroll
+    for (int kt = 0; kt < KC / 32; ++kt) {
+        const uint4 B0 = bsrc[(size_t)(kt * kD) * 4], B1 = bsrc[(size_t)(kt * kD + 16) * 4];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const uint4 A = *reinterpret_cast<const uint4 *>(&Wl[p][n][32 * kt + 8 * kg]);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B0), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B1), acc[1], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = 4 * kg + r, b = b0 + i / G, hh = i % G;
+        if (b < a.batch) {
+            float *dst = a.partial + (((size_t)b * a.Hq + (size_t)g * G + hh) * a.nchunk + chunk) * kD + 32 * wave + n;
+            dst[0] = acc[0][r];
+            dst[16] = acc[1][r];
+        }
     }
 }
 
@@ -2184,6 +2306,14 @@ hipError_t launch_prep(const commvq_config &c, const void *key_cb, uint4 *packed
     return hipGetLastError();
 }
 
+hipError_t launch_prep_values(const commvq_config &c, const void *val_cb, uint4 *vp, hipStream_t s)
+{
+    const size_t n = (size_t)c.n_kv_heads * c.m_val * kK * kD * 2 / 16;
+    hipLaunchKernelGGL(k_prep_values, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const uint16_t *>(val_cb), vp,
+                       c.n_kv_heads, c.m_val);
+    return hipGetLastError();
+}
+
 template <int M, int G, int TPT>
 hipError_t launch_lut_mgt(const float *lut, const uint8_t *key_codes, const int32_t *cu, float *scores, float2 *sstat,
                           const SliceDims &d, int grid, hipStream_t s)
@@ -2310,10 +2440,31 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
     a.partial = w.partial; a.out = out;
     a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
-    a.nchunk = plan.out_chunks; a.Mv = c.m_val;
+    a.nchunk = plan.out_chunks; a.Mv = c.m_val; a.batch = pos->batch;
     const int grid = pos->batch * c.n_kv_heads * plan.out_chunks;
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
     hipError_t e;
+    if (use_out_mfma(h, pos->batch)) {  // several sequences: the product with the value codebook on the matrix cores
+        const uint4 *vp = nullptr;
+        for (const auto &pv : h->packed_vals)
+            if (pv.first == val_cb) vp = pv.second;
+        if (!vp) {  // not packed ahead of time: re-lay the value codebook into the workspace on every call
+            if (launch_prep_values(c, val_cb, w.packed_val, s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
+            vp = w.packed_val;
+        }
+        a.nchunk = c.m_val * kK / kOutMfmaRows;
+        const int spt = 16 / h->G;
+        const int mgrid = ((pos->batch + spt - 1) / spt) * c.n_kv_heads * a.nchunk;
+        switch (h->G) {
+        case 1: hipLaunchKernelGGL(k_out_mfma<1>, dim3(mgrid), dim3(kOutThreads), 0, s, a, vp); break;
+        case 2: hipLaunchKernelGGL(k_out_mfma<2>, dim3(mgrid), dim3(kOutThreads), 0, s, a, vp); break;
+        case 4: hipLaunchKernelGGL(k_out_mfma<4>, dim3(mgrid), dim3(kOutThreads), 0, s, a, vp); break;
+        default: hipLaunchKernelGGL(k_out_mfma<8>, dim3(mgrid), dim3(kOutThreads), 0, s, a, vp); break;
+        }
+        if (hipGetLastError() != hipSuccess) return COMMVQ_ERR_LAUNCH;
+        hipLaunchKernelGGL(k_out_final, dim3(pos->batch * c.n_q_heads), dim3(kD * kFinalParts), 0, s, a);
+        return hipGetLastError() == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+    }
     switch (h->G) {
     case 1: e = launch_out_g<1>(a, bf16, grid, s); break;
     case 2: e = launch_out_g<2>(a, bf16, grid, s); break;
@@ -2500,6 +2651,46 @@ commvq_status commvq_pack_key_codebooks(commvq_handle *h, const void *key_cb, vo
     } catch (...) {
         return COMMVQ_ERR_LAUNCH;
     }
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_packed_value_codebook_bytes(const commvq_handle *h, size_t *bytes)
+{
+    if (!h || !bytes) return COMMVQ_ERR_NULL;
+    if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    *bytes = (size_t)h->cfg.n_kv_heads * h->cfg.m_val * kK * kD * 2;
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_pack_value_codebooks(commvq_handle *h, const void *val_cb, void *packed, void *stream)
+{
+    if (!h || !val_cb || !packed) return COMMVQ_ERR_NULL;
+    if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
+    if ((reinterpret_cast<uintptr_t>(val_cb) | reinterpret_cast<uintptr_t>(packed)) & 15u) return COMMVQ_ERR_SHAPE;
+    if (h->device < 0) return COMMVQ_ERR_NO_DEVICE;
+    if (launch_prep_values(h->cfg, val_cb, static_cast<uint4 *>(packed), static_cast<hipStream_t>(stream)) != hipSuccess)
+        return COMMVQ_ERR_LAUNCH;
+    for (auto &e : h->packed_vals)
+        if (e.first == val_cb) {
+            e.second = static_cast<const uint4 *>(packed);
+            return COMMVQ_OK;
+        }
+    try {
+        h->packed_vals.emplace_back(val_cb, static_cast<const uint4 *>(packed));
+    } catch (...) {
+        return COMMVQ_ERR_LAUNCH;
+    }
+    return COMMVQ_OK;
+}
+
+commvq_status commvq_forget_packed_value_codebooks(commvq_handle *h, const void *val_cb)
+{
+    if (!h) return COMMVQ_ERR_NULL;
+    for (size_t i = 0; i < h->packed_vals.size(); ++i)
+        if (!val_cb || h->packed_vals[i].first == val_cb) {
+            h->packed_vals.erase(h->packed_vals.begin() + (long)i);
+            --i;
+        }
     return COMMVQ_OK;
 }
 

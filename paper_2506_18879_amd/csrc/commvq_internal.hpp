@@ -26,6 +26,8 @@ constexpr int kBinsThreads = 1024;
 constexpr int kOutThreads = 256;
 constexpr int kMaxValueSplits = 256;  // value_splits never exceeds 256 / (batch * KV heads), at least 1
 constexpr int kOutRows = 64;    // codebook rows per k_out workgroup
+constexpr int kOutMfmaRows = 256;   // codebook rows per k_out_mfma workgroup (batched output stage)
+constexpr int kOutMfmaMinRows = 16;  // batch * (query heads per KV head) from which the batched output kernel is used
 constexpr int kProfRing = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -50,6 +52,8 @@ struct commvq_handle {
     bool prof_ev_made;
     // key codebooks that the caller has had re-laid once (commvq_pack_key_codebooks): source pointer -> packed copy
     std::vector<std::pair<const void *, const uint4 *>> packed_keys;
+    // value codebooks re-laid once for the batched output kernel (commvq_pack_value_codebooks): source -> packed copy
+    std::vector<std::pair<const void *, const uint4 *>> packed_vals;
 };
 
 namespace {

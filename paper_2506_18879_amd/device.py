@@ -73,6 +73,13 @@ class DecodeAttention:
         B.commvq_pack_key_codebooks(self.handle, dw.key_codebooks, buf, self.stream_ptr())
         self._packed[dw.key_codebooks.data_ptr()] = (buf, dw.key_codebooks)  # keep both alive while registered
 
+    def pack_value_codebooks(self, dw: DeviceWorkload):
+        """One-time re-layout of dw's (static) value codebooks for the batched output kernel."""
+        torch = _torch()
+        buf = torch.empty(B.commvq_packed_value_codebook_bytes(self.handle), dtype=torch.uint8, device="cuda")
+        B.commvq_pack_value_codebooks(self.handle, dw.val_codebooks, buf, self.stream_ptr())
+        self._packed[("v", dw.val_codebooks.data_ptr())] = (buf, dw.val_codebooks)
+
     def close(self):
         if self.handle is not None:
             B.commvq_destroy(self.handle)

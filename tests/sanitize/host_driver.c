@@ -42,10 +42,16 @@ static int drive(commvq_config c, int32_t B, int64_t T, int32_t L)
         EXPECT(commvq_packed_key_codebook_bytes(h, &nb), COMMVQ_OK);
         EXPECT(commvq_pack_key_codebooks(h, fake(1 << 22), fake(1 << 26), NULL), COMMVQ_ERR_NO_DEVICE);
         EXPECT(commvq_pack_key_codebooks(h, fake((1 << 22) + 4), fake(1 << 26), NULL), COMMVQ_ERR_SHAPE);
+        EXPECT(commvq_packed_value_codebook_bytes(h, &nb), COMMVQ_OK);
+        EXPECT(commvq_pack_value_codebooks(h, fake(1 << 22), fake(1 << 26), NULL), COMMVQ_ERR_NO_DEVICE);
+        EXPECT(commvq_pack_value_codebooks(h, fake(1 << 22), fake((1 << 26) + 8), NULL), COMMVQ_ERR_SHAPE);
+        EXPECT(commvq_pack_value_codebooks(h, NULL, fake(1 << 26), NULL), COMMVQ_ERR_NULL);
     } else {
         EXPECT(commvq_packed_key_codebook_bytes(h, &nb), COMMVQ_ERR_CONFIG);
+        EXPECT(commvq_packed_value_codebook_bytes(h, &nb), COMMVQ_ERR_CONFIG);
     }
     EXPECT(commvq_forget_packed_key_codebooks(h, NULL), COMMVQ_OK);
+    EXPECT(commvq_forget_packed_value_codebooks(h, NULL), COMMVQ_OK);
     EXPECT(commvq_encoder_table_bytes(h, &nb), COMMVQ_OK);
     EXPECT(commvq_encoder_prepare(h, fake(1 << 22), fake(1 << 27), NULL), COMMVQ_ERR_NO_DEVICE);
     EXPECT(commvq_encode_keys(h, fake(1 << 16), 3, fake(1 << 22), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 64, NULL),

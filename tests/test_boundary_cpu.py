@@ -230,6 +230,16 @@ def test_paired_keys_refuse_explicit_positions_and_size_their_tables(planner):
     assert status_of(cv.commvq_encode_keys, hi, _Buf(1 << 20), 0, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 128, 16) == 3
     hv = planner(m_key=16, m_val=32)
     assert cv.commvq_value_encoder_table_bytes(hv) == 8 * 32 * 256 * 4
+    # value codebooks re-laid for the batched output kernel: the size of the codebook itself; bf16 only; a batch with 16 or
+    # more output rows per KV head reserves room for the per-call re-layout in its workspace
+    assert cv.commvq_packed_value_codebook_bytes(hv) == 8 * 32 * 256 * 128 * 2
+    assert cv.commvq_packed_value_codebook_bytes(hi) == 8 * 32 * 256 * 128 * 2
+    h32 = planner(n_q_heads=1, n_kv_heads=1, q_dtype=0, codebook_dtype=0)
+    assert status_of(cv.commvq_packed_value_codebook_bytes, h32) == 2
+    assert status_of(cv.commvq_pack_value_codebooks, hv, _Buf(1 << 22), _Buf(1 << 26)) == 6
+    cv.commvq_forget_packed_value_codebooks(hv)
+    assert (cv.commvq_workspace_bytes(hv, 4, 4000, 1000) - cv.commvq_workspace_bytes(hv, 3, 3000, 1000)) > 8 * 32 * 256 * 128 * 2
+
     assert status_of(cv.commvq_encode_values, hv, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 256, 16) == 3   # 32-byte records
     assert status_of(cv.commvq_encode_values, hv, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 256, 32) == 6
     assert status_of(cv.commvq_value_encoder_prepare, hv, _Buf(1 << 21), _Buf((1 << 22) + 4)) == 3

@@ -649,3 +649,34 @@ def test_two_handles_on_two_streams_do_not_disturb_each_other(gpu):
         assert torch.equal(outs_a[k], ref_a) and torch.equal(outs_b[k], ref_b), k
     opa.close()
     opb.close()
+
+
+@pytest.mark.parametrize("G,Hkv,Mv,lens", [(4, 2, 16, [900, 40, 2100, 0, 333]), (8, 1, 32, [1500, 700]), (1, 2, 32, [300] * 17),
+                                           (2, 2, 16, [64, 1, 5000, 129, 77, 2048, 3, 999, 12])])
+def test_batched_output_stage_on_the_matrix_cores(gpu, oracle, G, Hkv, Mv, lens):
+    # 16 or more output rows (sequences x query heads of a KV head): bins x value codebook as a matrix product
+    # (k_out_mfma), with the value codebook re-laid per call or once (commvq_pack_value_codebooks): identical bits
+    import torch
+    import paper_2506_18879_amd as cv
+    assert len(lens) * G >= 16
+    w = synth.make_workload(f"outmfma_g{G}_v{Mv}", B=len(lens), Hq=G * Hkv, Hkv=Hkv, seqlens=lens, Mk=16, Mv=Mv, dtype="bf16",
+                            seed=6100 + G + Mv)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    a = op(dw).clone()
+    op.pack_value_codebooks(dw)
+    b = op(dw).clone()
+    cv.commvq_forget_packed_value_codebooks(op.handle, dw.val_codebooks)
+    c = op(dw).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    keep = [i for i, n in enumerate(lens) if n > 0]       # (the oracle rejects empty sequences; their rows are zeros)
+    got = a.cpu().numpy()
+    ref = oracle.decode_attn(w.as_f64("q")[keep], w.key_codes, w.val_codes, w.as_f64("key_codebooks"), w.as_f64("val_codebooks"),
+                             np.concatenate([[0], np.cumsum([lens[i] for i in keep])]).astype(np.int32), w.q_pos[keep],
+                             rope_base=w.rope_base, n_threads=8)
+    assert_rows(got[keep], ref, w.name)
+    for i, n in enumerate(lens):
+        if n == 0:
+            assert not got[i].any()
+    op.close()
