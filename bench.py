@@ -406,9 +406,9 @@ def main():
                               "frac_of_hbm_peak": round(val_gbs / HBM_PEAK_GBS, 4),
                               "with_logits_read_GBs": round(bins_alg / bins_s / 1e9, 1) if bins_s > 0 else 0.0,
                               "counter_bytes": stored.get("k_bins"), "stage_ms": round(stage_ms[1], 5)},
-        "output_view": {"stage": "k_out + k_out_final", "bins_and_codebook_GBs": round(out_alg / out_s / 1e9, 1) if out_s > 0 else 0.0,
+        "output_view": {"stage": "k_out (k_out_mfma for batches) + k_out_final", "bins_and_codebook_GBs": round(out_alg / out_s / 1e9, 1) if out_s > 0 else 0.0,
                         "frac_of_hbm_peak": round(out_alg / out_s / 1e9 / HBM_PEAK_GBS, 4) if out_s > 0 else 0.0,
-                        "counter_bytes": (stored.get("k_out", 0) + stored.get("k_out_final", 0)) or None,
+                        "counter_bytes": sum(v for k, v in stored.items() if k.startswith("k_out") and isinstance(v, (int, float))) or None,
                         "stage_ms": round(stage_ms[2], 5)}}
     alg_bytes = per_copy + w.B * w.Hq * w.d * (esz + 4)
     call_counter = sum(v for k, v in stored.items() if isinstance(v, (int, float)) and (k != "k_prep" or not prepacked)) or None
