@@ -411,7 +411,7 @@ def main():
                         "counter_bytes": sum(v for k, v in stored.items() if k.startswith("k_out") and isinstance(v, (int, float))) or None,
                         "stage_ms": round(stage_ms[2], 5)}}
     alg_bytes = per_copy + w.B * w.Hq * w.d * (esz + 4)
-    call_counter = sum(v for k, v in stored.items() if isinstance(v, (int, float)) and (k != "k_prep" or not prepacked)) or None
+    call_counter = sum(v for k, v in stored.items() if isinstance(v, (int, float)) and (not k.startswith("k_prep") or not prepacked)) or None
     result = {
         "metric": "decode-attention context tokens/sec per layer at 128K; % of HBM roofline",
         "value": round(tokens_per_s, 1), "unit": "context tokens/s per layer", "n_gpus": 1, "steps": args.steps,
