@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--context-tokens", type=int, default=None,
                     help="shrink every context of the workload to at most this many tokens (short-context plans: score "
                          "tiles cut along the codebook slices); the workload name then ends in _ctx<N>")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="with --context-tokens N: a serving-like batch of this many sequences of the workload's layer, "
+                         "lengths uniform on [N/2, N] (index-form configurations 2..5); the workload name then ends in _b<B>_ctx<N>")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-resident numbers)")
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
@@ -273,6 +276,13 @@ def main():
     w = synth.config(args.config, max_len=args.context_tokens)
     if args.context_tokens is not None:
         w.name = f"{w.name}_ctx{args.context_tokens}"
+    if args.batch is not None:
+        assert args.context_tokens is not None and w.key_format == "indexed" and w.dtype == "bf16", "--batch: configurations 2..5 with --context-tokens"
+        lens = np.random.Generator(np.random.PCG64(args.batch * 1000003 + args.context_tokens)).integers(
+            max(1, args.context_tokens // 2), args.context_tokens, size=args.batch, endpoint=True)
+        base = w.name.split("_ctx")[0]
+        w = synth.make_workload(f"{base}_b{args.batch}_ctx{args.context_tokens}", B=args.batch, Hq=w.Hq, Hkv=w.Hkv, seqlens=lens,
+                                Mk=w.Mk, Mv=w.Mv, dtype=w.dtype, seed=250618879 + 100 * args.config, code_dist=w.code_dist)
     T, G = w.total_tokens, w.Hq // w.Hkv
     esz = 2 if w.dtype == "bf16" else 4
     code_bytes = w.key_codes.nbytes + w.val_codes.nbytes
