@@ -265,3 +265,12 @@ def test_static_scratch_entry_point_checks_its_arguments(planner):
     assert cv.commvq_workspace_bytes(h, 1, 4_000_000, 4_000_000) > cv.commvq_static_scratch_bytes()
     assert call(big) == 4                                                # more than the static array holds
     assert call(cv.binding.make_positions(1, _Buf(4096), _Buf(8192), None, 0, 0)) == 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU per box in this build: --gpus N > 1 exits with a message and prints no result line
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and not r.stdout.strip()
