@@ -43,6 +43,10 @@ def _load():
             [ctypes.c_int] * 7 + [ctypes.c_void_p] * 8 + [ctypes.c_double] * 2 + [ctypes.c_void_p] * 4 + [ctypes.c_int]
         )
         lib.commvq_oracle_decode_attn.restype = ctypes.c_int
+        lib.commvq_oracle_decode_attn_bits.argtypes = lib.commvq_oracle_decode_attn.argtypes
+        lib.commvq_oracle_decode_attn_bits.restype = ctypes.c_int
+        lib.commvq_oracle_decode_bits.argtypes = [ctypes.c_void_p, dp] + [ctypes.c_int] * 4 + [dp]
+        lib.commvq_oracle_decode_bits.restype = None
         lib.commvq_oracle_encode_keys.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 6
         lib.commvq_oracle_encode_keys.restype = ctypes.c_int
         _lib = lib
@@ -118,6 +122,63 @@ def decode_attn(q, key_codes, val_codes, key_codebooks, val_codebooks, cu_seqlen
         float(rope_base), float(scale), _ptr(out), _ptr(scores), _ptr(weights), _ptr(um), int(n_threads))
     if rc != 0:
         raise ValueError(f"commvq_oracle_decode_attn failed with code {rc}")
+    if return_intermediates:
+        return out, scores, weights
+    return out
+
+
+def decode_bits(bits, codebook, first=0, n=None):
+    """Return columns first .. first + n - 1 of s C for a binary code s (Sec. 4.1, Eq. vanilla_decode).
+
+    bits: uint8[Nc / 8], bit c of the code = bit c % 8 of byte c / 8; codebook: [Nc][width].
+    """
+    cb = _f64(codebook)
+    Nc, width = cb.shape
+    n = width - first if n is None else n
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    assert Nc % 8 == 0 and bits.shape == (Nc // 8,) and 0 <= first and first + n <= width
+    out = np.empty(n, dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    _load().commvq_oracle_decode_bits(_ptr(bits), cb.ctypes.data_as(dp), Nc, width, int(first), int(n), out.ctypes.data_as(dp))
+    return out
+
+
+def decode_attn_binary_values(q, key_codes, val_bits, key_codebooks, val_codebook, cu_seqlens, q_pos,
+                              key_pos=None, rope_base=500000.0, scale=None, unit_mask=None, n_threads=1,
+                              return_intermediates=False):
+    """decode_attn with the values in the paper's own binary form (Sec. 4.1; Eq. decode_v, Eq. v1_formula).
+
+    val_bits flat uint8, per sequence [L_b][Nc / 8]: one record per token for all KV heads together;
+    val_codebook [Nc][Hkv * d]: the token's whole value vector (the KV heads' values side by side) is the sum of
+    the rows whose bit is set, and query head h attends over columns g d .. g d + d - 1 of it, g = h / (Hq / Hkv).
+    Everything else as decode_attn.
+    """
+    q = _f64(q)
+    kcb, vcb = _f64(key_codebooks), _f64(val_codebook)
+    B, Hq, d = q.shape
+    Hkv, Mk, K, d2 = kcb.shape
+    Nc = vcb.shape[0]
+    assert d2 == d and vcb.shape == (Nc, Hkv * d) and Nc % 8 == 0
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    qp = np.ascontiguousarray(q_pos, dtype=np.int32)
+    assert cu.shape == (B + 1,) and qp.shape == (B,) and cu[0] == 0
+    T = int(cu[-1])
+    kc = np.ascontiguousarray(key_codes, dtype=np.uint8).reshape(-1)
+    vb = np.ascontiguousarray(val_bits, dtype=np.uint8).reshape(-1)
+    assert kc.size == T * Hkv * Mk and vb.size == T * (Nc // 8)
+    kp = None if key_pos is None else np.ascontiguousarray(key_pos, dtype=np.int32)
+    assert kp is None or kp.shape == (T,)
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.full((B, Hq, d), np.nan, dtype=np.float64)
+    scores = np.full(T * Hq, np.nan, dtype=np.float64) if return_intermediates else None
+    weights = np.full(T * Hq, np.nan, dtype=np.float64) if return_intermediates else None
+    um = None if unit_mask is None else np.ascontiguousarray(unit_mask, dtype=np.uint8).reshape(B * Hkv)
+    rc = _load().commvq_oracle_decode_attn_bits(
+        B, Hq, Hkv, d, Mk, Nc, K, _ptr(q), _ptr(kc), _ptr(vb), _ptr(kcb), _ptr(vcb), _ptr(cu), _ptr(qp), _ptr(kp),
+        float(rope_base), float(scale), _ptr(out), _ptr(scores), _ptr(weights), _ptr(um), int(n_threads))
+    if rc != 0:
+        raise ValueError(f"commvq_oracle_decode_attn_bits failed with code {rc}")
     if return_intermediates:
         return out, scores, weights
     return out

@@ -60,6 +60,23 @@ void commvq_oracle_decode(const uint8_t *codes, const double *codebooks, /* [M][
     }
 }
 
+/*
+ * The paper's own value code (Sec. 4.1): the encoder turns the whole value vector of a token -- all KV heads
+ * side by side, `width` = Hkv * d scalars -- into a binary sequence s of length Nc with any number of ones, and the
+ * decoder is the matrix product s C with C [Nc][width] (Eq. vanilla_decode): the sum of the rows whose bit is set.
+ * Bit c of a record is bit c % 8 of its byte c / 8.  Writes columns first .. first + n - 1 of s C to t_hat.
+ */
+void commvq_oracle_decode_bits(const uint8_t *bits, const double *codebook, /* [Nc][width] */
+                               int Nc, int width, int first, int n, double *t_hat)
+{
+    for (int e = 0; e < n; ++e) t_hat[e] = 0.0;
+    for (int c = 0; c < Nc; ++c)
+        if ((bits[c / 8] >> (c % 8)) & 1) {
+            const double *row = codebook + (size_t)c * width + first;
+            for (int e = 0; e < n; ++e) t_hat[e] += row[e];
+        }
+}
+
 typedef struct {
     int B, Hq, Hkv, d, Mk, Mv, K;
     const double *q;
@@ -69,6 +86,7 @@ typedef struct {
     double rope_base, scale;
     double *out, *scores_out, *weights_out;
     const uint8_t *unit_mask; /* [B*Hkv] or NULL: which (b, g) units to compute */
+    int Nc;                   /* > 0: values in the binary form of Sec. 4.1 (see commvq_oracle_decode_attn_bits) */
 } job_t;
 
 /* One (sequence b, KV head g) unit: all query heads of the group. */
@@ -78,9 +96,10 @@ static int run_unit(const job_t *J, int b, int g)
     const int64_t off = J->cu_seqlens[b];
     const int64_t L = J->cu_seqlens[b + 1] - off;
     const uint8_t *kc = J->key_codes + ((size_t)off * J->Hkv + (size_t)g * L) * J->Mk;
-    const uint8_t *vc = J->val_codes + ((size_t)off * J->Hkv + (size_t)g * L) * J->Mv;
+    const uint8_t *vc = J->Nc > 0 ? J->val_codes + (size_t)off * (size_t)(J->Nc / 8)
+                                  : J->val_codes + ((size_t)off * J->Hkv + (size_t)g * L) * J->Mv;
     const double *kcb = J->key_cb + (size_t)g * J->Mk * J->K * d;
-    const double *vcb = J->val_cb + (size_t)g * J->Mv * J->K * d;
+    const double *vcb = J->Nc > 0 ? J->val_cb : J->val_cb + (size_t)g * J->Mv * J->K * d;
 
     double *qr = (double *)malloc(sizeof(double) * (size_t)G * d);
     double *s = (double *)malloc(sizeof(double) * (size_t)G * L);
@@ -122,7 +141,8 @@ static int run_unit(const job_t *J, int b, int g)
         for (int e = 0; e < d; ++e) o[e] = 0.0;
     }
     for (int64_t i = 0; i < L; ++i) {
-        commvq_oracle_decode(vc + (size_t)i * J->Mv, vcb, J->Mv, J->K, d, kv);
+        if (J->Nc > 0) commvq_oracle_decode_bits(vc + (size_t)i * (size_t)(J->Nc / 8), vcb, J->Nc, J->Hkv * d, g * d, d, kv);
+        else commvq_oracle_decode(vc + (size_t)i * J->Mv, vcb, J->Mv, J->K, d, kv);
         for (int hh = 0; hh < G; ++hh) {
             double w = s[(size_t)hh * L + i];
             double *o = J->out + ((size_t)b * J->Hq + (size_t)g * G + hh) * d;
@@ -146,6 +166,8 @@ static void *worker(void *arg)
     }
     return NULL;
 }
+
+static int run_job(const job_t *J, int n_threads);
 
 /*
  * Layouts (all host memory):
@@ -173,7 +195,14 @@ int commvq_oracle_decode_attn(int B, int Hq, int Hkv, int d, int Mk, int Mv, int
     if (!q || !key_codes || !val_codes || !key_cb || !val_cb || !cu_seqlens || !q_pos || !out) return 1;
     for (int b = 0; b < B; ++b) if (cu_seqlens[b + 1] - cu_seqlens[b] < 1) return 1;
     job_t J = { B, Hq, Hkv, d, Mk, Mv, K, q, key_codes, val_codes, key_cb, val_cb, cu_seqlens,
-                q_pos, key_pos, rope_base, scale, out, scores_out, weights_out, unit_mask };
+                q_pos, key_pos, rope_base, scale, out, scores_out, weights_out, unit_mask, 0 };
+    return run_job(&J, n_threads);
+}
+
+static int run_job(const job_t *Jp, int n_threads)
+{
+    job_t J = *Jp;
+    const int B = J.B, Hkv = J.Hkv;
     if (n_threads < 1) n_threads = 1;
     if (n_threads > B * Hkv) n_threads = B * Hkv;
     pthread_t *th = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)n_threads);
@@ -189,6 +218,30 @@ int commvq_oracle_decode_attn(int B, int Hq, int Hkv, int d, int Mk, int Mv, int
     for (int t = 0; t < n_threads; ++t) if (ws[t].rc) rc = 2;
     free(th); free(ws);
     return rc;
+}
+
+/*
+ * The same attention with the values in the paper's binary form (Sec. 4.1, Eq. vanilla_decode; Eq. decode_v):
+ *   val_bits  per sequence b: [L_b][Nc / 8] bytes, one record per token for ALL KV heads together, sequences
+ *             concatenated (offset cu_seqlens[b] * Nc / 8)
+ *   val_cb    [Nc][Hkv * d]: row c is added to the token's whole value vector when bit c of its record is set;
+ *             the value of KV head g is columns g d .. g d + d - 1 of that vector (the heads' values side by side)
+ * Keys, positions, outputs and return codes as commvq_oracle_decode_attn.  Nc must be a multiple of 8.
+ */
+int commvq_oracle_decode_attn_bits(int B, int Hq, int Hkv, int d, int Mk, int Nc, int K,
+                                   const double *q, const uint8_t *key_codes, const uint8_t *val_bits,
+                                   const double *key_cb, const double *val_cb,
+                                   const int32_t *cu_seqlens, const int32_t *q_pos, const int32_t *key_pos,
+                                   double rope_base, double scale, double *out, double *scores_out,
+                                   double *weights_out, const uint8_t *unit_mask, int n_threads)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 2 || d % 2 || Mk < 1 || Nc < 8 || Nc % 8 || K < 1 || K > 256)
+        return 1;
+    if (!q || !key_codes || !val_bits || !key_cb || !val_cb || !cu_seqlens || !q_pos || !out) return 1;
+    for (int b = 0; b < B; ++b) if (cu_seqlens[b + 1] - cu_seqlens[b] < 1) return 1;
+    job_t J = { B, Hq, Hkv, d, Mk, 0, K, q, key_codes, val_bits, key_cb, val_cb, cu_seqlens,
+                q_pos, key_pos, rope_base, scale, out, scores_out, weights_out, unit_mask, Nc };
+    return run_job(&J, n_threads);
 }
 
 /*

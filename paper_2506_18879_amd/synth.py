@@ -18,6 +18,9 @@ Storage conventions
     of 6-bit indices, packed little endian into ``ceil(12 R / 8)`` bytes with
     pair ``r`` at bits ``12 r .. 12 r + 11`` (``a`` low, ``b`` high); one tied
     table ``[Hkv][R][64][d]`` serves both indices of a level.
+  * binary value format (Sec. 4.1): per token ONE record of ``Nc / 8`` bytes for all KV
+    heads together (bit ``c`` = bit ``c % 8`` of byte ``c // 8``), sequence ``b`` holds
+    ``[L_b][Nc / 8]``; one value codebook ``[Nc][Hkv * d]``.
 """
 from __future__ import annotations
 
@@ -67,6 +70,8 @@ class Workload:
     extras: dict = field(default_factory=dict)
     key_format: str = "indexed"  # "indexed": Mk uint8 indices per token; "paired": key_levels packed 12-bit pairs
     key_levels: int = 0          # R of the paired format (then key_codebooks is the tied table [Hkv][R][64][d])
+    val_format: str = "indexed"  # "indexed": Mv uint8 indices per token and KV head; "binary": val_bits bits per token
+    val_bits: int = 0            # N_c of the binary format (then val_codebooks is [Nc][Hkv * d] and Mv is unused)
 
     @property
     def total_tokens(self) -> int:
@@ -84,7 +89,7 @@ class Workload:
         return a.astype(np.float64)
 
     def seq_codes(self, which: str, b: int) -> np.ndarray:
-        """View of one sequence's codes as [Hkv][L_b][M]."""
+        """View of one sequence's codes as [Hkv][L_b][M] (index-form keys or values only)."""
         M = self.Mk if which == "key" else self.Mv
         flat = self.key_codes if which == "key" else self.val_codes
         o, e = int(self.cu_seqlens[b]), int(self.cu_seqlens[b + 1])
@@ -193,6 +198,26 @@ def make_pair_workload(name: str, *, B: int, Hq: int, Hkv: int, seqlens, R: int,
     return base
 
 
+def with_binary_values(base: Workload, Nc: int, *, density: float = 0.5, seed: Optional[int] = None) -> Workload:
+    """Replace base's values by the paper's binary value code: every token stores Nc bits for all KV heads
+    together, each bit set with probability `density` (the trained encoder's statistics are not published), and
+    one codebook [Nc][Hkv * d] with entries ~ N(0, (density Nc)^-1/2), so that a decoded coordinate has about unit
+    variance."""
+    assert Nc % 8 == 0 and 0.0 <= density <= 1.0
+    rng = np.random.Generator(np.random.PCG64((base.seed if seed is None else seed) ^ 0xB175))
+    T = base.total_tokens
+    rows = []
+    for lo in range(0, T, 1 << 16):  # in pieces: the unpacked bits of a long context would not fit comfortably
+        n = min(1 << 16, T - lo)
+        rows.append(np.packbits(rng.random((n, Nc)) < density, axis=1, bitorder="little"))
+    base.val_codes = np.concatenate(rows).reshape(-1) if rows else np.zeros(0, np.uint8)
+    cb = rng.standard_normal((Nc, base.Hkv * base.d), dtype=np.float32) * np.float32(max(density * Nc, 1.0) ** -0.5)
+    base.val_codebooks = f32_to_bf16_bits(cb) if base.dtype == "bf16" else cb
+    base.val_format, base.val_bits, base.Mv = "binary", Nc, 0
+    base.name += f"_vbits{Nc}"
+    return base
+
+
 def config(idx: int, *, seed: Optional[int] = None, max_len: Optional[int] = None) -> Workload:
     """The five benchmark configurations (1-based ``idx``).
 
@@ -227,4 +252,8 @@ def config(idx: int, *, seed: Optional[int] = None, max_len: Optional[int] = Non
         R = 11 if idx == 6 else 21
         return make_pair_workload(f"c{idx}_8b_L131072_paired_R{R}", B=1, Hq=32, Hkv=8, seqlens=[cap(131072)], R=R,
                                   Mv=16 if idx == 6 else 32, seed=s)
-    raise ValueError(f"config index {idx} not in 1..7")
+    if idx in (8, 9):  # 8B-shaped layer, 128K, values in the paper's binary form: N_c = 1024 (1 bit) / 2048 (2 bit)
+        base = make_workload(f"c{idx}_8b_L131072", B=1, Hq=32, Hkv=8, seqlens=[cap(131072)], Mk=16 if idx == 8 else 32,
+                             Mv=16, dtype="bf16", seed=s)
+        return with_binary_values(base, 1024 if idx == 8 else 2048)
+    raise ValueError(f"config index {idx} not in 1..9")

@@ -687,3 +687,124 @@ def test_em_shared_hard_assignment_is_the_paired_encoder_choice(oracle):
     table = phi.transpose(1, 0, 2).reshape(1, Nc, 2 * g)                            # one level [Nc][d] of rows C[a]
     codes, _, _ = oracle.encode_keys(cen.reshape(Nc * Nc, 2 * g), table, paired=True)
     assert np.array_equal(codes[:, 0, 0] * Nc + codes[:, 0, 1], np.arange(Nc * Nc))
+
+
+# ---------------------------------------------------------------- the paper's binary value code (Sec. 4.1)
+def _tiny_bits(rng, lens, Nc, density=0.5):
+    return np.concatenate([np.packbits(rng.random((L, Nc)) < density, axis=1, bitorder="little").reshape(-1) for L in lens])
+
+
+def test_binary_decode_is_the_matrix_product_s_times_C(oracle):
+    # Eq. vanilla_decode: t_hat = s C with s in {0,1}^Nc -- numpy's unpackbits + matmul as the library route
+    rng = np.random.default_rng(61)
+    Nc, width = 24, 10
+    C = rng.standard_normal((Nc, width))
+    for density in (0.0, 0.1, 0.5, 1.0):
+        bits = np.packbits(rng.random(Nc) < density, bitorder="little")
+        s = np.unpackbits(bits, bitorder="little")[:Nc].astype(np.float64)
+        np.testing.assert_allclose(oracle.decode_bits(bits, C), s @ C, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(oracle.decode_bits(bits, C, first=3, n=4), (s @ C)[3:7], rtol=0, atol=1e-13)
+    # one bit set selects exactly that row; bit c lives in byte c // 8 at position c % 8
+    for c in (0, 1, 7, 8, 13, 23):
+        bits = np.zeros(Nc // 8, np.uint8)
+        bits[c // 8] = 1 << (c % 8)
+        np.testing.assert_array_equal(oracle.decode_bits(bits, C), C[c])
+
+
+def test_binary_values_reduce_to_index_form_when_block_one_hot(oracle):
+    # A binary code that has exactly one bit per (KV head, codebook) block, with a codebook whose row (g, m, k) is
+    # non-zero only in head g's columns, IS the index form (Eq. vanilla_decode with one 1 per codebook): both oracle
+    # entry points must agree.  Fixes the record layout of a ragged batch, the bit order and the head's column range.
+    rng = np.random.default_rng(62)
+    p = tiny(rng, B=2, Hq=4, Hkv=2, d=8, Mk=3, Mv=2, K=4, lens=(5, 3))
+    Hkv, Mv, K, d = p["Hkv"], p["Mv"], p["K"], p["d"]
+    Nc = Hkv * Mv * K
+    C = np.zeros((Nc, Hkv * d))
+    for g in range(Hkv):
+        C[g * Mv * K:(g + 1) * Mv * K, g * d:(g + 1) * d] = p["val_cb"][g].reshape(Mv * K, d)
+    recs = []
+    off = 0
+    for L in p["lens"]:
+        codes = p["val_codes"][off * Hkv * Mv:(off + L) * Hkv * Mv].reshape(Hkv, L, Mv)
+        s = np.zeros((L, Nc), np.uint8)
+        for g in range(Hkv):
+            for i in range(L):
+                for m in range(Mv):
+                    s[i, (g * Mv + m) * K + codes[g, i, m]] = 1
+        recs.append(np.packbits(s, axis=1, bitorder="little").reshape(-1))
+        off += L
+    want = run(oracle, p)
+    got = oracle.decode_attn_binary_values(p["q"], p["key_codes"], np.concatenate(recs), p["key_cb"], C, p["cu"], p["q_pos"],
+                                           rope_base=BASE)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+
+
+def test_binary_values_against_torch_sdpa_with_equal_positions(oracle):
+    # all keys at the query's position: the rotations cancel and Eq. v1_formula is plain attention over the decoded
+    # tensors -- K_hat from the index-form key decode, V_hat = S_V C_V (Eq. decode_v) by unpackbits + matmul, heads
+    # mapped h -> h // G; torch's fp64 scaled_dot_product_attention as the library routine
+    rng = np.random.default_rng(63)
+    p = tiny(rng, B=2, Hq=4, Hkv=2, d=8, Mk=3, Mv=2, K=4, lens=(7, 4))
+    Hq, Hkv, d, Mk, K = p["Hq"], p["Hkv"], p["d"], p["Mk"], p["K"]
+    Nc = 40
+    C = rng.standard_normal((Nc, Hkv * d))
+    vb = _tiny_bits(rng, p["lens"], Nc)
+    key_pos = np.concatenate([np.full(L, qp, np.int32) for L, qp in zip(p["lens"], p["q_pos"])])
+    got = oracle.decode_attn_binary_values(p["q"], p["key_codes"], vb, p["key_cb"], C, p["cu"], p["q_pos"], key_pos=key_pos,
+                                           rope_base=BASE)
+    G = Hq // Hkv
+    off = 0
+    for b, L in enumerate(p["lens"]):
+        kc = p["key_codes"][off * Hkv * Mk:(off + L) * Hkv * Mk].reshape(Hkv, L, Mk)
+        S = np.unpackbits(vb[off * (Nc // 8):(off + L) * (Nc // 8)].reshape(L, Nc // 8), axis=1, bitorder="little")[:, :Nc]
+        V = S.astype(np.float64) @ C                                               # [L][Hkv * d]
+        for h in range(Hq):
+            g = h // G
+            Kh = np.stack([sum(p["key_cb"][g, m, kc[g, i, m]] for m in range(Mk)) for i in range(L)])
+            want = torch.nn.functional.scaled_dot_product_attention(
+                torch.from_numpy(p["q"][b, h][None, None]), torch.from_numpy(Kh[None]), torch.from_numpy(V[None, :, g * d:(g + 1) * d].copy()))
+            np.testing.assert_allclose(got[b, h], want[0, 0].numpy(), rtol=0, atol=1e-12)
+        off += L
+
+
+def test_binary_values_zero_query_closed_form_and_unit_mask(oracle):
+    # q = 0: uniform weights, so out = (1 / L) (column sums of S_V) C_V restricted to the head's columns
+    # (Eq. optimized_v with Softmax(A) = 1 / L)
+    rng = np.random.default_rng(64)
+    p = tiny(rng, B=1, Hq=4, Hkv=2, d=8, Mk=2, Mv=2, K=4, lens=(9,))
+    Nc, L, d = 16, 9, p["d"]
+    C = rng.standard_normal((Nc, p["Hkv"] * d))
+    vb = _tiny_bits(rng, p["lens"], Nc, density=0.3)
+    S = np.unpackbits(vb.reshape(L, Nc // 8), axis=1, bitorder="little").astype(np.float64)
+    q0 = np.zeros_like(p["q"])
+    got = oracle.decode_attn_binary_values(q0, p["key_codes"], vb, p["key_cb"], C, p["cu"], p["q_pos"], rope_base=BASE)
+    full = (S.sum(axis=0) / L) @ C
+    for h in range(4):
+        g = h // 2
+        np.testing.assert_allclose(got[0, h], full[g * d:(g + 1) * d], rtol=0, atol=1e-13)
+    # no bit set anywhere: every value is the zero vector
+    z = oracle.decode_attn_binary_values(p["q"], p["key_codes"], np.zeros_like(vb), p["key_cb"], C, p["cu"], p["q_pos"], rope_base=BASE)
+    np.testing.assert_array_equal(z, np.zeros_like(z))
+    # the scores do not depend on the value format
+    _, sc, wt = oracle.decode_attn_binary_values(p["q"], p["key_codes"], vb, p["key_cb"], C, p["cu"], p["q_pos"], rope_base=BASE,
+                                                 return_intermediates=True)
+    _, sc2, wt2 = oracle.decode_attn(p["q"], p["key_codes"], p["val_codes"], p["key_cb"], p["val_cb"], p["cu"], p["q_pos"],
+                                     rope_base=BASE, return_intermediates=True)
+    np.testing.assert_array_equal(sc, sc2)
+    np.testing.assert_array_equal(wt, wt2)
+    # masked units are left untouched (NaN), computed units are not affected by the mask
+    m = oracle.decode_attn_binary_values(p["q"], p["key_codes"], vb, p["key_cb"], C, p["cu"], p["q_pos"], rope_base=BASE,
+                                         unit_mask=np.array([[False, True]]), n_threads=2)
+    ref = oracle.decode_attn_binary_values(p["q"], p["key_codes"], vb, p["key_cb"], C, p["cu"], p["q_pos"], rope_base=BASE)
+    assert np.isnan(m[0, :2]).all()
+    np.testing.assert_array_equal(m[0, 2:], ref[0, 2:])
+
+
+def test_synth_binary_value_workload_shapes():
+    w = synth.with_binary_values(synth.make_workload("t", B=2, Hq=4, Hkv=2, seqlens=[5, 9], Mk=16, Mv=16, dtype="bf16", seed=5), 1024,
+                                 density=0.25)
+    assert w.val_format == "binary" and w.val_bits == 1024
+    assert w.val_codes.dtype == np.uint8 and w.val_codes.size == 14 * 128
+    assert w.val_codebooks.shape == (1024, 2 * 128) and w.val_codebooks.dtype == np.uint16
+    frac = np.unpackbits(w.val_codes).mean()
+    assert 0.2 < frac < 0.3
