@@ -58,6 +58,20 @@ typedef enum { COMMVQ_F32 = 0, COMMVQ_BF16 = 1 } commvq_dtype;
  */
 typedef enum { COMMVQ_KEYS_INDEXED = 0, COMMVQ_KEYS_PAIRED = 1 } commvq_key_format;
 
+/*
+ * How the values are stored.
+ *   COMMVQ_VALUES_INDEXED  m_val independent codebooks of K = 256 codewords per KV head, one uint8 index per codebook
+ *                          (Eq. vanilla_decode with exactly one 1 per codebook).
+ *   COMMVQ_VALUES_BINARY   the paper's own value code (Sec. 4.1): the encoder maps a token's whole value vector -- the
+ *                          n_kv_heads heads side by side, n_kv_heads * head_dim scalars -- to a binary sequence s of
+ *                          value_bits = N_c bits with ANY number of ones, and the vector decodes to s C_V with ONE
+ *                          codebook C_V [N_c][n_kv_heads * head_dim] (Eq. vanilla_decode); N_c = 1024 is the paper's
+ *                          1-bit setting for an 8-KV-head model, 2048 its 2-bit setting (App., Table codebook_conf).
+ *                          Softmax(A) S_V of Eq. optimized_v is then a dense product over the context and runs on the
+ *                          matrix cores.
+ */
+typedef enum { COMMVQ_VALUES_INDEXED = 0, COMMVQ_VALUES_BINARY = 1 } commvq_value_format;
+
 /* Host struct, copied by commvq_create. */
 typedef struct {
     int32_t n_q_heads;       /* Hq */
@@ -77,6 +91,8 @@ typedef struct {
                                 quantized after RoPE): scores are (q . k_hat_i) * scale, computed with a scalar look-up
                                 table T[m][c] = scale * q . C[m][c] and M_k look-ups per token; q_pos / key_pos are
                                 ignored.  Indexed keys only.  0: RoPE as described above. */
+    int32_t value_format;    /* commvq_value_format; 0 (indexed) keeps every field above as described */
+    int32_t value_bits;      /* N_c: 1024, 2048 or 4096; COMMVQ_VALUES_BINARY only (m_val is then ignored) */
 } commvq_config;
 
 /* Host struct of device pointers: where the tokens sit (ragged batch). */
@@ -146,11 +162,14 @@ commvq_status commvq_workspace_bytes(const commvq_handle *handle, int32_t batch,
  *                  COMMVQ_KEYS_PAIRED: [Hkv][L_b][PB] with PB = ceil(12 R / 8) bytes per record; pair r of a
  *                  token is bits 12 r .. 12 r + 11 of its record (little endian), a_r the low 6 bits, b_r the
  *                  high 6 bits; sequence offset cu_seqlens[b] * Hkv * PB
- *   val_codes      uint8; same with M_v
+ *   val_codes      uint8; same with M_v.
+ *                  COMMVQ_VALUES_BINARY: sequence b holds [L_b][N_c / 8], ONE record per token for all KV heads (byte
+ *                  offset of sequence b = cu_seqlens[b] * N_c / 8); bit c of a record is bit c % 8 of its byte c / 8
  *   key_codebooks  [Hkv][M_k][K][d], codebook_dtype, row-major; a key codeword row is the
  *                  sequence of (x, y) first rows of its RoPE-commuting 2x2 blocks (Eq. C_struct).
  *                  COMMVQ_KEYS_PAIRED: the tied table [Hkv][R][64][d] bf16, same row convention
- *   val_codebooks  [Hkv][M_v][K][d]
+ *   val_codebooks  [Hkv][M_v][K][d].  COMMVQ_VALUES_BINARY: [N_c][Hkv * d]; query head h attends over columns
+ *                  (h / G) d .. (h / G) d + d - 1 of the decoded vectors
  *   positions      host struct, see above; |q_pos - key position| must not exceed max_position.  What the host
  *                  can see of that is checked (see max_seqlen); q_pos and key_pos live on the device, and a
  *                  distance beyond the tables there is clamped to their last row: no fault, wrong rotation
@@ -212,6 +231,8 @@ commvq_status commvq_forget_packed_key_codebooks(commvq_handle *handle, const vo
  *   val_codebooks  [Hkv][M_v][K][d] bf16, as for commvq_decode_attn
  *   packed         device buffer of commvq_packed_value_codebook_bytes() bytes, 16-byte aligned, caller-owned
  * Results are bit-identical either way; smaller batches do not use it.  COMMVQ_ERR_CONFIG for fp32 codebooks.
+ * COMMVQ_VALUES_BINARY: val_codebooks is [N_c][Hkv * d]; row 32 kt + j of head g is then code bit 256 ((32 kt + j) %
+ * (N_c / 256)) + (32 kt + j) / (N_c / 256), restricted to the head's columns.
  */
 commvq_status commvq_packed_value_codebook_bytes(const commvq_handle *handle, size_t *bytes);
 commvq_status commvq_pack_value_codebooks(commvq_handle *handle, const void *val_codebooks, void *packed, void *stream);
@@ -247,7 +268,8 @@ commvq_status commvq_encode_keys(commvq_handle *handle, const void *keys, int32_
  * key encoder -- level m takes the row of value codebook m nearest to what the earlier levels left -- so that a
  * cache can be appended to end to end without the trained network.  Arguments, layouts, tie rule and status codes as
  * commvq_encoder_table_bytes / commvq_encoder_prepare / commvq_encode_keys in index form, with val_codebooks
- * [Hkv][m_val][K][d] and m_val index bytes per record.
+ * [Hkv][m_val][K][d] and m_val index bytes per record.  COMMVQ_ERR_CONFIG for COMMVQ_VALUES_BINARY (no greedy
+ * stand-in exists for a free binary code; the trained encoder is the only producer of such records).
  */
 commvq_status commvq_value_encoder_table_bytes(const commvq_handle *handle, size_t *bytes);
 commvq_status commvq_value_encoder_prepare(commvq_handle *handle, const void *val_codebooks, void *tables, void *stream);
@@ -300,6 +322,8 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
  *                        accumulated per (head, value codebook, codeword) in 32-bit fixed point
  *                        (unit chosen per context split from its exp-sum; error below
  *                        tokens-per-split * 2^-32 of the split's weight), plus the exp sums.
+ *                        COMMVQ_VALUES_BINARY: per (head, code bit), as an 8-bit integer matrix product over
+ *                        four signed digits of the same fixed-point weights (error below tokens * 2^-31).
  *   commvq_stage_output  (bins C_V) / sum of Eq. optimized_v -> out.
  */
 commvq_status commvq_stage_scores(commvq_handle *handle, const void *q, const uint8_t *key_codes,

@@ -9,6 +9,7 @@ from . import build as _build
 
 COMMVQ_F32, COMMVQ_BF16 = 0, 1
 COMMVQ_KEYS_INDEXED, COMMVQ_KEYS_PAIRED = 0, 1
+COMMVQ_VALUES_INDEXED, COMMVQ_VALUES_BINARY = 0, 1
 _lib = None
 
 
@@ -22,7 +23,8 @@ class Config(Structure):
     _fields_ = [("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32), ("m_key", c_int32),
                 ("m_val", c_int32), ("k", c_int32), ("q_dtype", c_int32), ("codebook_dtype", c_int32),
                 ("rope_base", c_double), ("softmax_scale", c_double), ("max_position", c_int32),
-                ("key_format", c_int32), ("key_levels", c_int32), ("position_free", c_int32)]
+                ("key_format", c_int32), ("key_levels", c_int32), ("position_free", c_int32),
+                ("value_format", c_int32), ("value_bits", c_int32)]
 
 
 class Positions(Structure):

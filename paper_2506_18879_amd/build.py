@@ -7,7 +7,8 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 SRC = os.path.join(PKG, "csrc", "commvq.hip")
-SOURCES = [SRC, os.path.join(PKG, "csrc", "commvq_encode.hip"), os.path.join(PKG, "csrc", "commvq_em.hip")]
+SOURCES = [SRC, os.path.join(PKG, "csrc", "commvq_encode.hip"), os.path.join(PKG, "csrc", "commvq_em.hip"),
+           os.path.join(PKG, "csrc", "commvq_vbits.hip")]
 LIB = os.path.join(PKG, "libcommvq.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

@@ -29,6 +29,7 @@
 #include <cstring>
 
 #include "commvq_internal.hpp"
+#include "commvq_vbits.hpp"
 
 // Scratch memory of commvq_decode_attn_static: the workspace of a call, held by the library itself so that the
 // entry point allocates nothing.  One copy per GPU the library is loaded on, for the life of the process.  In host
@@ -68,6 +69,11 @@ inline bool use_out_mfma(const commvq_handle *h, int batch)
 {
     return h->cfg.codebook_dtype == COMMVQ_BF16 && batch * h->G >= kOutMfmaMinRows;
 }
+
+// Binary value code: N_c code bits per token for all KV heads, one codebook [N_c][Hkv * d].  Towards the output kernels a
+// KV head's N_c bins look like N_c / 256 value codebooks of 256 rows (code bit c = codebook c / 256, codeword c % 256).
+inline bool bin_values(const commvq_config &c) { return c.value_format == COMMVQ_VALUES_BINARY; }
+inline int val_books(const commvq_config &c) { return bin_values(c) ? c.value_bits / kK : c.m_val; }
 
 // Paired-code key format: blocks of 16 levels, bytes of one packed record, bytes of the unpacked indices of a token.
 inline bool pair_keys(const commvq_config &c) { return c.key_format == COMMVQ_KEYS_PAIRED; }
@@ -113,6 +119,8 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
     int nv = 256 / units;  // about one value workgroup per compute unit
+    if (bin_values(h->cfg))  // a workgroup of the binary-code value kernel: 32 query heads x 512 code bits of one token range
+        nv = 256 / (B * ((h->cfg.n_q_heads + kVbitsHeads - 1) / kVbitsHeads) * (h->cfg.value_bits / kVbitsCols));
     if (nv < 1) nv = 1;
     int vlen = (max_seqlen + nv - 1) / nv;
     // a value split is a whole number of statistics tiles (score tiles; 1024 tokens when k_score_combine writes the
@@ -128,7 +136,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
     }
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
-    p->out_chunks = h->cfg.m_val * kK / kOutRows;
+    p->out_chunks = val_books(h->cfg) * kK / kOutRows;
     p->score_kernel = sliced ? 1 : 0;
     p->score_slice_groups = groups;
 }
@@ -158,13 +166,13 @@ void carve(const commvq_handle *h, int B, int64_t T, int max_seqlen, void *base,
     w->sstat = reinterpret_cast<float2 *>(take((size_t)B * c.n_q_heads * ssplits * 2));
     w->vscale = take((size_t)B * c.n_q_heads * vsplits);
     w->lsum = take((size_t)B * c.n_q_heads * vsplits);
-    w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * vsplits * h->G * c.m_val * kK));
+    w->bins = reinterpret_cast<unsigned *>(take((size_t)B * c.n_kv_heads * vsplits * h->G * val_books(c) * kK));
     w->partial = take((size_t)B * c.n_q_heads * pa.out_chunks * kD);
     w->packed = reinterpret_cast<uint4 *>(take(packed_key_bytes(c) / 4));
     w->pair_bytes = pair_keys(c) ? reinterpret_cast<uint8_t *>(take((size_t)T * c.n_kv_heads * 8 * pair_blocks(c))) : nullptr;
     w->lut = c.position_free ? take((size_t)B * c.n_q_heads * c.m_key * kK) : nullptr;
     w->scores_part = pa.score_slice_groups > 1 ? take((size_t)pa.score_slice_groups * T * c.n_q_heads) : nullptr;
-    w->packed_val = use_out_mfma(h, B) ? reinterpret_cast<uint4 *>(take((size_t)c.n_kv_heads * c.m_val * kK * kD * 2 / 4)) : nullptr;
+    w->packed_val = use_out_mfma(h, B) ? reinterpret_cast<uint4 *>(take((size_t)c.n_kv_heads * val_books(c) * kK * kD * 2 / 4)) : nullptr;
     w->bytes = off;
 }
 
@@ -1837,6 +1845,9 @@ struct OutArgs {
     float *partial, *out;
     int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
     int batch;
+    // value-codebook row of (KV head g, codebook m, codeword c) = (m * K + c) * cb_row_mul + g * cb_head_mul, in rows of
+    // d elements: index form [Hkv][M_v][K][d] -> (1, M_v K); binary code [N_c][Hkv * d] -> (Hkv, 1)
+    int cb_row_mul, cb_head_mul;
 };
 
 // Workgroup = (sequence, KV head, chunk of codebook rows): sums the chunk's bins over the
@@ -1885,7 +1896,7 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
     const int cpc = kOutRows / a.Mv, mpw = a.Mv / (kOutThreads / 64);  // codewords per chunk, codebooks per wavefront
     auto load_row = [&](int i) -> float2 {
         const int m = wave * mpw + i / cpc, cl = i % cpc;
-        const size_t row = (size_t)g * MK + (size_t)m * kK + (size_t)chunk * cpc + cl;
+        const size_t row = ((size_t)m * kK + (size_t)chunk * cpc + cl) * a.cb_row_mul + (size_t)g * a.cb_head_mul;
         if (BF16) {
             const unsigned v = static_cast<const unsigned *>(a.val_cb)[row * kJ + lane];
             return make_float2(bf16_lo(v), bf16_hi(v));
@@ -1965,7 +1976,8 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
 // Value codebook re-laid for k_out_mfma: vp[g][kt][dim][32] bf16, where row 32 kt + j of head g is codeword
 // (32 kt + j) / M_v of codebook (32 kt + j) % M_v (the row order of the bins) -- the 32 rows of a k-step of the matrix
 // instruction contiguous per output dimension.  One thread per 16-byte piece of the output (static data, done once).
-__global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict__ val_cb, uint4 *__restrict__ vp, int Hkv, int Mv)
+__global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict__ val_cb, uint4 *__restrict__ vp, int Hkv, int Mv,
+                                                     int row_mul, int head_mul)
 {
     const int MK = Mv * kK;
     const size_t n = (size_t)Hkv * (MK / 32) * kD * 4;
@@ -1978,7 +1990,7 @@ __global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict_
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int r = 32 * kt + 8 * kg + e;
-        const unsigned v = val_cb[(((size_t)g * Mv + r % Mv) * kK + r / Mv) * kD + dim];
+        const unsigned v = val_cb[(((size_t)(r % Mv) * kK + r / Mv) * row_mul + (size_t)g * head_mul) * kD + dim];
         if (e & 1) w[e / 2] |= v << 16; else w[e / 2] = v;
     }
     vp[t] = make_uint4(w[0], w[1], w[2], w[3]);
@@ -2119,7 +2131,7 @@ commvq_status check_shape(const commvq_handle *h, int32_t batch, int64_t total_t
     if (total_tokens > (int64_t)1 << 30) return COMMVQ_ERR_SHAPE;
     // the kernels address one (sequence, KV head)'s codes, unpacked pair indices and logits with 32-bit byte offsets
     const commvq_config &c = h->cfg;
-    int64_t rec = c.m_val;
+    int64_t rec = bin_values(c) ? c.value_bits / 8 : c.m_val;
     if (pair_keys(c)) rec = std::max<int64_t>(rec, 32 * pair_blocks(c));
     else rec = std::max<int64_t>(rec, c.m_key);
     rec = std::max<int64_t>(rec, 4 * h->G);
@@ -2308,9 +2320,9 @@ hipError_t launch_prep(const commvq_config &c, const void *key_cb, uint4 *packed
 
 hipError_t launch_prep_values(const commvq_config &c, const void *val_cb, uint4 *vp, hipStream_t s)
 {
-    const size_t n = (size_t)c.n_kv_heads * c.m_val * kK * kD * 2 / 16;
+    const size_t n = (size_t)c.n_kv_heads * val_books(c) * kK * kD * 2 / 16;
     hipLaunchKernelGGL(k_prep_values, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const uint16_t *>(val_cb), vp,
-                       c.n_kv_heads, c.m_val);
+                       c.n_kv_heads, val_books(c), bin_values(c) ? c.n_kv_heads : 1, bin_values(c) ? 1 : c.m_val * kK);
     return hipGetLastError();
 }
 
@@ -2421,6 +2433,16 @@ commvq_status run_bins(commvq_handle *h, const uint8_t *val_codes, const commvq_
                        const commvq_plan &plan, const Workspace &w, hipStream_t s)
 {
     const commvq_config &c = h->cfg;
+    if (bin_values(c)) {  // free binary code: Softmax(A) S_V as an integer matrix product (commvq_vbits.hip)
+        VbitsArgs v;
+        v.val_bits = val_codes; v.cu = pos->cu_seqlens; v.scores = w.scores; v.sstat = w.sstat;
+        v.bins = w.bins; v.vscale = w.vscale; v.lsum = w.lsum;
+        v.Hq = c.n_q_heads; v.Hkv = c.n_kv_heads; v.G = h->G;
+        v.nsplit = stat_splits(plan, pos->max_seqlen); v.split_len = stat_len(plan);
+        v.nvsplit = plan.value_splits; v.vsplit_len = plan.value_split_len;
+        v.Nc = c.value_bits; v.batch = pos->batch;
+        return commvq_launch_vbits(v, s) == hipSuccess ? COMMVQ_OK : COMMVQ_ERR_LAUNCH;
+    }
     BinsArgs a;
     a.val_codes = val_codes; a.cu = pos->cu_seqlens; a.scores = w.scores; a.sstat = w.sstat;
     a.bins = w.bins; a.vscale = w.vscale; a.lsum = w.lsum;
@@ -2440,7 +2462,9 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
     a.partial = w.partial; a.out = out;
     a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
-    a.nchunk = plan.out_chunks; a.Mv = c.m_val; a.batch = pos->batch;
+    a.nchunk = plan.out_chunks; a.Mv = val_books(c); a.batch = pos->batch;
+    a.cb_row_mul = bin_values(c) ? c.n_kv_heads : 1;
+    a.cb_head_mul = bin_values(c) ? 1 : c.m_val * kK;
     const int grid = pos->batch * c.n_kv_heads * plan.out_chunks;
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
     hipError_t e;
@@ -2452,7 +2476,7 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
             if (launch_prep_values(c, val_cb, w.packed_val, s) != hipSuccess) return COMMVQ_ERR_LAUNCH;
             vp = w.packed_val;
         }
-        a.nchunk = c.m_val * kK / kOutMfmaRows;
+        a.nchunk = val_books(c) * kK / kOutMfmaRows;
         const int spt = 16 / h->G;
         const int mgrid = ((pos->batch + spt - 1) / spt) * c.n_kv_heads * a.nchunk;
         switch (h->G) {
@@ -2502,7 +2526,14 @@ commvq_status commvq_validate_config(const commvq_config *c)
     if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return COMMVQ_ERR_CONFIG;
     const int G = c->n_q_heads / c->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return COMMVQ_ERR_CONFIG;
-    if (c->m_val != 16 && c->m_val != 32) return COMMVQ_ERR_CONFIG;
+    if (c->value_format == COMMVQ_VALUES_INDEXED) {
+        if (c->m_val != 16 && c->m_val != 32) return COMMVQ_ERR_CONFIG;
+    } else if (c->value_format == COMMVQ_VALUES_BINARY) {
+        // towards the output kernels N_c / 256 stands in for the number of value codebooks: 4, 8 or 16
+        if (c->value_bits != 1024 && c->value_bits != 2048 && c->value_bits != 4096) return COMMVQ_ERR_CONFIG;
+    } else {
+        return COMMVQ_ERR_CONFIG;
+    }
     if (c->key_format == COMMVQ_KEYS_INDEXED) {
         if (c->m_key != 16 && c->m_key != 32) return COMMVQ_ERR_CONFIG;
     } else if (c->key_format == COMMVQ_KEYS_PAIRED) {
@@ -2658,7 +2689,7 @@ commvq_status commvq_packed_value_codebook_bytes(const commvq_handle *h, size_t 
 {
     if (!h || !bytes) return COMMVQ_ERR_NULL;
     if (h->cfg.codebook_dtype != COMMVQ_BF16) return COMMVQ_ERR_CONFIG;
-    *bytes = (size_t)h->cfg.n_kv_heads * h->cfg.m_val * kK * kD * 2;
+    *bytes = (size_t)h->cfg.n_kv_heads * val_books(h->cfg) * kK * kD * 2;
     return COMMVQ_OK;
 }
 

@@ -718,7 +718,14 @@ commvq_status encode_vectors(commvq_handle *h, bool values, const void *keys, in
 extern "C" {
 
 commvq_status commvq_encoder_table_bytes(const commvq_handle *h, size_t *bytes) { return encoder_table_bytes(h, false, bytes); }
-commvq_status commvq_value_encoder_table_bytes(const commvq_handle *h, size_t *bytes) { return encoder_table_bytes(h, true, bytes); }
+// a free binary value code has no greedy stand-in here: its only producer is the trained encoder of Sec. 4.1
+static bool binary_values(const commvq_handle *h) { return h && h->cfg.value_format == COMMVQ_VALUES_BINARY; }
+
+commvq_status commvq_value_encoder_table_bytes(const commvq_handle *h, size_t *bytes)
+{
+    if (binary_values(h)) return COMMVQ_ERR_CONFIG;
+    return encoder_table_bytes(h, true, bytes);
+}
 
 commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void *tables, void *stream)
 {
@@ -726,6 +733,7 @@ commvq_status commvq_encoder_prepare(commvq_handle *h, const void *key_cb, void 
 }
 commvq_status commvq_value_encoder_prepare(commvq_handle *h, const void *val_cb, void *tables, void *stream)
 {
+    if (binary_values(h)) return COMMVQ_ERR_CONFIG;
     return encoder_prepare(h, true, val_cb, tables, stream);
 }
 
@@ -737,6 +745,7 @@ commvq_status commvq_encode_keys(commvq_handle *h, const void *keys, int32_t n_t
 commvq_status commvq_encode_values(commvq_handle *h, const void *values, int32_t n_tokens, const void *val_cb, const void *tables,
                                    uint8_t *codes_out, int64_t token_stride, int64_t head_stride, void *stream)
 {
+    if (binary_values(h)) return COMMVQ_ERR_CONFIG;
     return encode_vectors(h, true, values, n_tokens, val_cb, tables, codes_out, token_stride, head_stride, stream);
 }
 

@@ -53,10 +53,12 @@ class DecodeAttention:
         if max_position is None:
             max_position = max(int(w.q_pos.max()), w.max_seqlen, 0 if w.key_pos is None else int(w.key_pos.max()))
         paired = getattr(w, "key_format", "indexed") == "paired"
-        self.cfg = B.Config(w.Hq, w.Hkv, w.d, 16 if paired else w.Mk, w.Mv, w.K, qdt, dt, float(w.rope_base),
+        vbin = getattr(w, "val_format", "indexed") == "binary"
+        self.cfg = B.Config(w.Hq, w.Hkv, w.d, 16 if paired else w.Mk, 16 if vbin else w.Mv, w.K, qdt, dt, float(w.rope_base),
                             float(softmax_scale), int(max_position),
                             B.COMMVQ_KEYS_PAIRED if paired else B.COMMVQ_KEYS_INDEXED, w.key_levels if paired else 0,
-                            1 if position_free else 0)
+                            1 if position_free else 0,
+                            B.COMMVQ_VALUES_BINARY if vbin else B.COMMVQ_VALUES_INDEXED, w.val_bits if vbin else 0)
         self.handle = B.commvq_create(self.cfg)
         self.plan = B.commvq_plan_query(self.handle, w.B, w.total_tokens, w.max_seqlen)
         self.workspace_bytes = B.commvq_workspace_bytes(self.handle, w.B, w.total_tokens, w.max_seqlen)

@@ -274,3 +274,34 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_binary_value_format_config_plan_and_sizes(planner):
+    ok = dict(value_format=cv.COMMVQ_VALUES_BINARY, value_bits=1024, m_val=0)   # m_val is ignored with binary values
+    assert cv.commvq_validate_config(good_cfg(**ok)) == 0
+    for bits in (2048, 4096):
+        assert cv.commvq_validate_config(good_cfg(**dict(ok, value_bits=bits))) == 0
+    for bad in (dict(ok, value_bits=0), dict(ok, value_bits=512), dict(ok, value_bits=1000), dict(ok, value_bits=8192),
+                dict(value_format=2, value_bits=1024)):
+        assert cv.commvq_validate_config(good_cfg(**bad)) == 2
+    # the 8B-shaped layer at 128K: a value workgroup is 32 heads x 512 code bits of a token range -> 2 column groups,
+    # 128 ranges of 1024 tokens; the output stage sees N_c / 256 = 4 "codebooks" of 256 rows (16 chunks of 64 rows)
+    h = planner(**ok)
+    p = cv.commvq_plan_query(h, 1, 131072, 131072)
+    assert (p.value_splits, p.value_split_len, p.out_chunks) == (128, 1024, 16)
+    h70 = planner(**dict(ok, n_q_heads=64, m_key=32, value_bits=2048))
+    p = cv.commvq_plan_query(h70, 4, 4 * 131072, 131072)
+    assert p.value_splits * 4 * 2 * 4 <= 256 and p.value_splits * p.value_split_len >= 131072 and p.out_chunks == 32
+    # bins: [B * Hkv * ranges][G * N_c] words are part of the workspace
+    assert cv.commvq_workspace_bytes(h, 1, 131072, 131072) >= 131072 * 32 * 4 + 8 * 128 * 4 * 1024 * 4
+    # records of N_c / 8 bytes per token must stay inside 32-bit offsets: 2^23 tokens x 512 bytes = 2^32
+    h4k = planner(**dict(ok, value_bits=4096, max_position=1 << 24))
+    assert status_of(cv.commvq_plan_query, h4k, 1, 1 << 23, 1 << 23) == 3
+    assert status_of(cv.commvq_plan_query, h4k, 1, (1 << 23) - 1, (1 << 23) - 1) == 0
+    # the packed value codebook has the size of the codebook; the greedy value encoder does not apply
+    assert cv.commvq_packed_value_codebook_bytes(h) == 1024 * 8 * 128 * 2
+    assert status_of(cv.commvq_value_encoder_table_bytes, h) == 2
+    assert status_of(cv.commvq_encode_values, h, _Buf(1 << 20), 4, _Buf(1 << 21), _Buf(1 << 22), _Buf(1 << 23), 256, 32) == 2
+    a = _call_args(h)
+    assert status_of(cv.commvq_decode_attn, h, a["q"], a["key_codes"], a["val_codes"], a["key_codebooks"], a["val_codebooks"],
+                     a["positions"], a["out"], a["workspace"], a["workspace_bytes"]) == 6
