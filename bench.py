@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 peak (vector, and equally the fp32 matrix instructions)
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
+MFMA_I8_PEAK_TOPS = 5000.0      # MI355X published dense int8 matrix peak
 LDS_PEAK_TBS = 157.3        # 256 CUs x 256 B/clk (ds_read_b128 without bank conflicts) x 2.4 GHz
 COLD_FOOTPRINT = 640 << 20  # rotate through at least this many bytes of codes + codebooks
 
@@ -29,8 +30,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--config", type=int, default=3,
-                    help="workload 1..7 (3 = 8B-shaped layer, 128K context, 1-bit; 6, 7 = the same layer with keys in "
-                         "the paper's paired format, R = 11 / 21)")
+                    help="workload 1..9 (3 = 8B-shaped layer, 128K context, 1-bit; 6, 7 = the same layer with keys in "
+                         "the paper's paired format, R = 11 / 21; 8, 9 = the same layer with values in the paper's binary "
+                         "form, N_c = 1024 / 2048)")
     ap.add_argument("--context-tokens", type=int, default=None,
                     help="shrink every context of the workload to at most this many tokens (short-context plans: score "
                          "tiles cut along the codebook slices); the workload name then ends in _ctx<N>")
@@ -410,16 +412,27 @@ def main():
     bins_s, out_s = stage_ms[1] * 1e-3, stage_ms[2] * 1e-3
     val_gbs = w.val_codes.nbytes / bins_s / 1e9 if bins_s > 0 else 0.0
     bins_alg = w.val_codes.nbytes + T * w.Hq * 4
-    out_alg = op.plan.value_splits * w.B * w.Hq * w.Mv * w.K * 4 + w.B * w.val_codebooks.nbytes
+    vbin = w.val_format == "binary"
+    val_rows = w.val_bits if vbin else w.Mv * w.K            # bins per query head
+    out_alg = op.plan.value_splits * w.B * w.Hq * val_rows * 4 + w.B * w.val_codebooks.nbytes
     stage_views = {
-        "value_stream_view": {"stage": "k_bins", "value_code_GBs": round(val_gbs, 1),
+        "value_stream_view": {"stage": "k_vbits" if vbin else "k_bins", "value_code_GBs": round(val_gbs, 1),
                               "frac_of_hbm_peak": round(val_gbs / HBM_PEAK_GBS, 4),
                               "with_logits_read_GBs": round(bins_alg / bins_s / 1e9, 1) if bins_s > 0 else 0.0,
-                              "counter_bytes": stored.get("k_bins"), "stage_ms": round(stage_ms[1], 5)},
+                              "with_logits_read_and_bins_written_GBs": round((bins_alg + op.plan.value_splits * w.B * w.Hq * val_rows * 4) / bins_s / 1e9, 1) if bins_s > 0 else 0.0,
+                              "counter_bytes": stored.get("k_vbits" if vbin else "k_bins"), "stage_ms": round(stage_ms[1], 5)},
         "output_view": {"stage": "k_out (k_out_mfma for batches) + k_out_final", "bins_and_codebook_GBs": round(out_alg / out_s / 1e9, 1) if out_s > 0 else 0.0,
                         "frac_of_hbm_peak": round(out_alg / out_s / 1e9 / HBM_PEAK_GBS, 4) if out_s > 0 else 0.0,
                         "counter_bytes": sum(v for k, v in stored.items() if k.startswith("k_out") and isinstance(v, (int, float))) or None,
                         "stage_ms": round(stage_ms[2], 5)}}
+    if vbin and bins_s > 0:
+        # Softmax(A) S_V as a dense product: heads (padded to 32 per workgroup) x N_c x tokens, four 8-bit digits
+        heads = -(-w.Hq // 32) * 32
+        i8_tops = 2.0 * 4 * heads * w.val_bits * T / bins_s / 1e12
+        stage_views["value_stream_view"]["mfma_view"] = {
+            "issued_int8_TOPs": round(i8_tops, 1), "peak_TOPs": MFMA_I8_PEAK_TOPS, "instruction": "v_mfma_i32_16x16x64_i8",
+            "frac": round(i8_tops / MFMA_I8_PEAK_TOPS, 4),
+            "algorithmic_TOPs": round(2.0 * w.Hq * w.val_bits * T / bins_s / 1e12, 1)}
     alg_bytes = per_copy + w.B * w.Hq * w.d * (esz + 4)
     call_counter = sum(v for k, v in stored.items() if isinstance(v, (int, float)) and (not k.startswith("k_prep") or not prepacked)) or None
     result = {
@@ -429,7 +442,8 @@ def main():
         "vs_baseline": None, "dtype": "f32 arithmetic on bf16 storage" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "context_tokens": T, "m_key": w.Mk, "m_val": w.Mv, "codewords": w.K, "storage": w.dtype,
-                   "key_format": w.key_format, "key_levels": w.key_levels, "position_free": bool(args.position_free),
+                   "key_format": w.key_format, "key_levels": w.key_levels, "value_format": w.val_format,
+                   "value_bits": w.val_bits, "position_free": bool(args.position_free),
                    "codes": w.code_dist, "score_tile_tokens": op.plan.score_split_len,
                    "score_slice_groups": op.plan.score_slice_groups, "value_split_tokens": op.plan.value_split_len,
                    "buffer_copies_rotated": n_copies,
@@ -487,8 +501,9 @@ def main():
         reps = 0
         c0 = time.perf_counter()
         while reps < 8 and (reps == 0 or time.perf_counter() - c0 < 2.0):  # about 10-30 core-seconds
-            oracle.decode_attn(o_q, o_codes, w.val_codes, o_kcb, o_vcb, w.cu_seqlens, w.q_pos, key_pos=o_pos,
-                               rope_base=w.rope_base, unit_mask=mask.reshape(w.B, w.Hkv), n_threads=n_threads)
+            o_fn = oracle.decode_attn_binary_values if vbin else oracle.decode_attn
+            o_fn(o_q, o_codes, w.val_codes, o_kcb, o_vcb, w.cu_seqlens, w.q_pos, key_pos=o_pos,
+                 rope_base=w.rope_base, unit_mask=mask.reshape(w.B, w.Hkv), n_threads=n_threads)
             reps += 1
         c1 = time.perf_counter()
         sample_tokens *= reps

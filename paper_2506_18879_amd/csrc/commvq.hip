@@ -71,7 +71,7 @@ inline bool use_out_mfma(const commvq_handle *h, int batch)
 }
 
 // Binary value code: N_c code bits per token for all KV heads, one codebook [N_c][Hkv * d].  Towards the output kernels a
-// KV head's N_c bins look like N_c / 256 value codebooks of 256 rows (code bit c = codebook c / 256, codeword c % 256).
+// KV head's N_c bins stand in for N_c / 256 value codebooks of 256 rows; bins row r is code bit r.
 inline bool bin_values(const commvq_config &c) { return c.value_format == COMMVQ_VALUES_BINARY; }
 inline int val_books(const commvq_config &c) { return bin_values(c) ? c.value_bits / kK : c.m_val; }
 
@@ -1845,9 +1845,10 @@ struct OutArgs {
     float *partial, *out;
     int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
     int batch;
-    // value-codebook row of (KV head g, codebook m, codeword c) = (m * K + c) * cb_row_mul + g * cb_head_mul, in rows of
-    // d elements: index form [Hkv][M_v][K][d] -> (1, M_v K); binary code [N_c][Hkv * d] -> (Hkv, 1)
-    int cb_row_mul, cb_head_mul;
+    // Index form: bins row r of a KV head = codeword r / M_v of codebook r % M_v, whose value-codebook row (of d
+    // elements) is g * M_v K + (r % M_v) * K + r / M_v.  Binary code (cb_linear): bins row r = code bit r, codebook
+    // [N_c][Hkv * d], row of d elements r * Hkv + g.
+    int cb_linear;
 };
 
 // Workgroup = (sequence, KV head, chunk of codebook rows): sums the chunk's bins over the
@@ -1896,7 +1897,8 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
     const int cpc = kOutRows / a.Mv, mpw = a.Mv / (kOutThreads / 64);  // codewords per chunk, codebooks per wavefront
     auto load_row = [&](int i) -> float2 {
         const int m = wave * mpw + i / cpc, cl = i % cpc;
-        const size_t row = ((size_t)m * kK + (size_t)chunk * cpc + cl) * a.cb_row_mul + (size_t)g * a.cb_head_mul;
+        const size_t row = a.cb_linear ? ((size_t)chunk * kOutRows + (size_t)(cl * a.Mv + m)) * a.Hkv + g
+                                       : (size_t)g * MK + (size_t)m * kK + (size_t)chunk * cpc + cl;
         if (BF16) {
             const unsigned v = static_cast<const unsigned *>(a.val_cb)[row * kJ + lane];
             return make_float2(bf16_lo(v), bf16_hi(v));
@@ -1977,7 +1979,7 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
 // (32 kt + j) / M_v of codebook (32 kt + j) % M_v (the row order of the bins) -- the 32 rows of a k-step of the matrix
 // instruction contiguous per output dimension.  One thread per 16-byte piece of the output (static data, done once).
 __global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict__ val_cb, uint4 *__restrict__ vp, int Hkv, int Mv,
-                                                     int row_mul, int head_mul)
+                                                     int linear)
 {
     const int MK = Mv * kK;
     const size_t n = (size_t)Hkv * (MK / 32) * kD * 4;
@@ -1990,7 +1992,8 @@ __global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict_
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int r = 32 * kt + 8 * kg + e;
-        const unsigned v = val_cb[(((size_t)(r % Mv) * kK + r / Mv) * row_mul + (size_t)g * head_mul) * kD + dim];
+        const unsigned v = linear ? val_cb[((size_t)r * Hkv + g) * kD + dim]  // binary code: row r = code bit r of [N_c][Hkv * d]
+                                  : val_cb[(((size_t)g * Mv + r % Mv) * kK + r / Mv) * kD + dim];
         if (e & 1) w[e / 2] |= v << 16; else w[e / 2] = v;
     }
     vp[t] = make_uint4(w[0], w[1], w[2], w[3]);
@@ -2322,7 +2325,7 @@ hipError_t launch_prep_values(const commvq_config &c, const void *val_cb, uint4 
 {
     const size_t n = (size_t)c.n_kv_heads * val_books(c) * kK * kD * 2 / 16;
     hipLaunchKernelGGL(k_prep_values, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const uint16_t *>(val_cb), vp,
-                       c.n_kv_heads, val_books(c), bin_values(c) ? c.n_kv_heads : 1, bin_values(c) ? 1 : c.m_val * kK);
+                       c.n_kv_heads, val_books(c), bin_values(c) ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -2463,8 +2466,7 @@ commvq_status run_output(commvq_handle *h, const void *val_cb, const commvq_posi
     a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
     a.nvsplit = plan.value_splits; a.vsplit_len = plan.value_split_len;
     a.nchunk = plan.out_chunks; a.Mv = val_books(c); a.batch = pos->batch;
-    a.cb_row_mul = bin_values(c) ? c.n_kv_heads : 1;
-    a.cb_head_mul = bin_values(c) ? 1 : c.m_val * kK;
+    a.cb_linear = bin_values(c) ? 1 : 0;
     const int grid = pos->batch * c.n_kv_heads * plan.out_chunks;
     const bool bf16 = c.codebook_dtype == COMMVQ_BF16;
     hipError_t e;

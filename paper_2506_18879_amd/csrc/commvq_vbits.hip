@@ -13,7 +13,8 @@ namespace {
 constexpr int kVbThreads = 512;                // 8 wavefronts: each takes 64 of the workgroup's 512 code bits
 constexpr int kVbStage = 128;                  // tokens per LDS stage = two 64-token steps of the matrix instruction
 constexpr int kVbSStride = kVbStage + 4;       // dwords per row of the transposed bit stage (rows 16-byte aligned)
-constexpr int kVbAStride = kVbStage / 4 + 4;   // dwords per (digit, head) row of the weight stage
+constexpr int kVbAStride = kVbStage / 4 + 8;   // dwords per (digit, head) row of the weight stage: 10 bank columns of 16 bytes, so that
+                                               // the lanes a 16-byte LDS read serves together (l % 8, (l / 16) % 2) fall on 16 different columns
 typedef int intx4_t __attribute__((ext_vector_type(4)));
 
 // One workgroup = (sequence, token range, 32 query heads, 512 code bits).
@@ -60,9 +61,13 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
     const uint8_t *rec = a.val_bits + (size_t)cu0 * NB + cg * (kVbitsCols / 8);
     const float *srow = a.scores + (size_t)cu0 * a.Hq;
     const int tt = tid >> 2, jq = tid & 3;  // bit stage: token of the stage, 16-byte piece of the record part
-    uint4 sreg;
-    float wreg[2][4];                       // weight stage: two (head, token quad) items per thread
-    auto fetch = [&](int t0) {
+    // two sets of staging registers: a stage's loads are requested two stages ahead (one compute phase does not cover
+    // the latency of memory)
+    uint4 sreg2[2];
+    float wreg2[2][2][4];                   // weight stage: two (head, token quad) items per thread
+    auto fetch = [&](int t0, int set) {
+        uint4 &sreg = sreg2[set];
+        float(&wreg)[2][4] = wreg2[set];
         const int t = t0 + tt;
         sreg = t < v1 ? *reinterpret_cast<const uint4 *>(rec + (size_t)t * NB + 16 * jq) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
@@ -75,27 +80,35 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
             }
         }
     };
-    fetch(v0);
+    fetch(v0, 0);
+    if (v0 + kVbStage < v1) fetch(v0 + kVbStage, 1);
 
     // Statistics, per head as in the index-form stage: the sequence maximum, the exp-sum of the score tiles that the range
     // touches (bounds every bin, fixes the fixed-point unit), and the exp-sum of the tiles that begin inside the range
     // (what it reports towards the softmax denominator).
-    for (int u = 0; u < kVbitsHeads / (kVbThreads / 64); ++u) {
+    constexpr int HPW = kVbitsHeads / (kVbThreads / 64);  // heads per wavefront
+    const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
+    float2 first[HPW];  // the first 64 tiles' statistics of every head, requested together
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+        const int h = h0 + wave + (kVbThreads / 64) * u;
+        first[u] = (h < a.Hq && lane < ns) ? a.sstat[((size_t)b * a.Hq + h) * a.nsplit + lane] : make_float2(-INFINITY, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
         const int hl = wave + (kVbThreads / 64) * u, h = h0 + hl;
         if (h >= a.Hq) {
             if (lane == 0) eoff_s[hl] = 0.f;
             continue;
         }
-        const int ns = min((L + a.split_len - 1) / a.split_len, a.nsplit);
         const float2 *st = a.sstat + ((size_t)b * a.Hq + h) * a.nsplit;
-        const float2 first = lane < ns ? st[lane] : make_float2(-INFINITY, 0.f);
-        float mx = first.x;
+        float mx = first[u].x;
         for (int s = lane + 64; s < ns; s += 64) mx = fmaxf(mx, st[s].x);
         mx = wave_max(mx);
         const int sa = v0 / a.split_len, sb = min((v1 + a.split_len - 1) / a.split_len, ns);
         float l = 0.f, lown = 0.f;
         if (lane >= sa && lane < sb) {
-            l = first.y * __builtin_amdgcn_exp2f((first.x - mx) * kLog2e);
+            l = first[u].y * __builtin_amdgcn_exp2f((first[u].x - mx) * kLog2e);
             if (lane * a.split_len >= v0) lown = l;
         }
         for (int s = lane + 64; s < sb; s += 64)
@@ -118,7 +131,9 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
     }
     __syncthreads();
 
-    auto stage_write = [&](int buf) {
+    auto stage_write = [&](int buf, int set) {
+        const uint4 sreg = sreg2[set];
+        const float(&wreg)[2][4] = wreg2[set];
         unsigned *sd = s_lds[buf];
         sd[(4 * jq + 0) * kVbSStride + tt] = sreg.x;
         sd[(4 * jq + 1) * kVbSStride + tt] = sreg.y;
@@ -188,26 +203,27 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
         }
     };
 
-    stage_write(0);
+    stage_write(0, 0);
     __syncthreads();
-    int buf = 0;
-    for (int t0 = v0; t0 < v1; t0 += kVbStage) {
-        const bool more = t0 + kVbStage < v1;  // uniform over the workgroup
-        if (more) fetch(t0 + kVbStage);
-        compute(buf);
-        if (more) stage_write(buf ^ 1);
+    // iteration of stage s (buffer and register set s % 2): request stage s + 2, multiply stage s, stage s + 1 to LDS
+    auto iteration = [&](int t0, int par) {
+        if (t0 + 2 * kVbStage < v1) fetch(t0 + 2 * kVbStage, par);  // (all conditions uniform over the workgroup)
+        compute(par);
+        if (t0 + kVbStage < v1) stage_write(par ^ 1, par ^ 1);
         __syncthreads();
-        buf ^= 1;
+    };
+    for (int t0 = v0; t0 < v1; t0 += 2 * kVbStage) {
+        iteration(t0, 0);
+        if (t0 + kVbStage < v1) iteration(t0 + kVbStage, 1);
     }
 
-    // digits -> integer bins, stored where the index-form output kernels expect them: [256][Nc / 256][G] per
-    // (sequence, KV head, range), code bit c at row (c % 256) * (Nc / 256) + c / 256
-    const int Mvp = a.Nc >> 8;
+    // digits -> integer bins [Nc][G] per (sequence, KV head, range): a wavefront's 64 code bits x the G heads of a KV
+    // head are one contiguous run
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int bit = bit0 + 2 * p;
         const int c = 32 * (cg * (kVbitsCols / 32) + 2 * wave + (n >> 3)) + 8 * (int)bn + bit;
-        const size_t row = (size_t)((c & 255) * Mvp + (c >> 8));
+        const size_t row = (size_t)c;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             unsigned val[4];

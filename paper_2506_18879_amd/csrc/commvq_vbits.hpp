@@ -14,7 +14,7 @@ struct VbitsArgs {
     const int32_t *cu;        // [B + 1]
     const float *scores;      // scaled logits, (b, h, i) at cu[b] * Hq + h * L_b + i
     const float2 *sstat;      // [B * Hq][nsplit] (max, sum of exp(logit - max)) of the score-stage tiles
-    unsigned *bins;           // [B * Hkv][nvsplit][256][Nc / 256][G]: bin of code bit c at row (c % 256) * (Nc / 256) + c / 256
+    unsigned *bins;           // [B * Hkv][nvsplit][Nc][G]
     float *vscale, *lsum;     // [B * Hq][nvsplit]
     int Hq, Hkv, G;
     int nsplit, split_len;    // statistics tiles of the score stage
