@@ -231,8 +231,8 @@ commvq_status commvq_forget_packed_key_codebooks(commvq_handle *handle, const vo
  *   val_codebooks  [Hkv][M_v][K][d] bf16, as for commvq_decode_attn
  *   packed         device buffer of commvq_packed_value_codebook_bytes() bytes, 16-byte aligned, caller-owned
  * Results are bit-identical either way; smaller batches do not use it.  COMMVQ_ERR_CONFIG for fp32 codebooks.
- * COMMVQ_VALUES_BINARY: val_codebooks is [N_c][Hkv * d]; row r of head g is then code bit r, restricted to the
- * head's columns.
+ * COMMVQ_VALUES_BINARY: val_codebooks is [N_c][Hkv * d]; row r of head g is then the code bit that the value stage
+ * keeps in row r of its bins (the six low bits of r permuted), restricted to the head's columns.
  */
 commvq_status commvq_packed_value_codebook_bytes(const commvq_handle *handle, size_t *bytes);
 commvq_status commvq_pack_value_codebooks(commvq_handle *handle, const void *val_codebooks, void *packed, void *stream);

@@ -71,7 +71,7 @@ inline bool use_out_mfma(const commvq_handle *h, int batch)
 }
 
 // Binary value code: N_c code bits per token for all KV heads, one codebook [N_c][Hkv * d].  Towards the output kernels a
-// KV head's N_c bins stand in for N_c / 256 value codebooks of 256 rows; bins row r is code bit r.
+// KV head's N_c bins stand in for N_c / 256 value codebooks of 256 rows; bins row r is code bit vbits_code_bit(r).
 inline bool bin_values(const commvq_config &c) { return c.value_format == COMMVQ_VALUES_BINARY; }
 inline int val_books(const commvq_config &c) { return bin_values(c) ? c.value_bits / kK : c.m_val; }
 
@@ -134,6 +134,9 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         while (part < vlen) part *= 2;
         vlen = part;  // 1024 or 2048 inside a 2048- or 4096-token tile
     }
+    // the binary-code value kernel sums signed digit x bit products in 32-bit accumulators: |digit| <= 2^7, bit byte <= 2^6,
+    // so a range of at most 2^17 tokens stays below 2^30
+    if (bin_values(h->cfg) && vlen > (1 << 17)) vlen = 1 << 17;
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
     p->out_chunks = val_books(h->cfg) * kK / kOutRows;
@@ -1846,8 +1849,8 @@ struct OutArgs {
     int Hq, Hkv, nvsplit, vsplit_len, nchunk, Mv;
     int batch;
     // Index form: bins row r of a KV head = codeword r / M_v of codebook r % M_v, whose value-codebook row (of d
-    // elements) is g * M_v K + (r % M_v) * K + r / M_v.  Binary code (cb_linear): bins row r = code bit r, codebook
-    // [N_c][Hkv * d], row of d elements r * Hkv + g.
+    // elements) is g * M_v K + (r % M_v) * K + r / M_v.  Binary code (cb_linear): bins row r = code bit c =
+    // vbits_code_bit(r), codebook [N_c][Hkv * d], row of d elements c * Hkv + g.
     int cb_linear;
 };
 
@@ -1897,7 +1900,7 @@ __global__ __launch_bounds__(kOutThreads) void k_out(OutArgs a)
     const int cpc = kOutRows / a.Mv, mpw = a.Mv / (kOutThreads / 64);  // codewords per chunk, codebooks per wavefront
     auto load_row = [&](int i) -> float2 {
         const int m = wave * mpw + i / cpc, cl = i % cpc;
-        const size_t row = a.cb_linear ? ((size_t)chunk * kOutRows + (size_t)(cl * a.Mv + m)) * a.Hkv + g
+        const size_t row = a.cb_linear ? (size_t)vbits_code_bit(chunk * kOutRows + cl * a.Mv + m) * a.Hkv + g
                                        : (size_t)g * MK + (size_t)m * kK + (size_t)chunk * cpc + cl;
         if (BF16) {
             const unsigned v = static_cast<const unsigned *>(a.val_cb)[row * kJ + lane];
@@ -1992,7 +1995,7 @@ __global__ __launch_bounds__(256) void k_prep_values(const uint16_t *__restrict_
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int r = 32 * kt + 8 * kg + e;
-        const unsigned v = linear ? val_cb[((size_t)r * Hkv + g) * kD + dim]  // binary code: row r = code bit r of [N_c][Hkv * d]
+        const unsigned v = linear ? val_cb[((size_t)vbits_code_bit(r) * Hkv + g) * kD + dim]  // binary code: [N_c][Hkv * d]
                                   : val_cb[(((size_t)g * Mv + r % Mv) * kK + r / Mv) * kD + dim];
         if (e & 1) w[e / 2] |= v << 16; else w[e / 2] = v;
     }

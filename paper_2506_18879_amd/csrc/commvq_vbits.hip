@@ -16,23 +16,24 @@ constexpr int kVbSStride = kVbStage + 4;       // dwords per row of the transpos
 constexpr int kVbAStride = kVbStage / 4 + 8;   // dwords per (digit, head) row of the weight stage: 10 bank columns of 16 bytes, so that
                                                // the lanes a 16-byte LDS read serves together (l % 8, (l / 16) % 2) fall on 16 different columns
 typedef int intx4_t __attribute__((ext_vector_type(4)));
+typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));  // four floats at any 4-byte boundary
 
 // One workgroup = (sequence, token range, 32 query heads, 512 code bits).
 //
 // Exactness.  As in the index-form value stage the weights are added in fixed point: w = exp(logit - max) is taken
 // as the integer W = round(w 2^S), with S chosen from the known exp-sum of the range so that the sum of all W stays
 // below 2^30.  W + 0x80808080 has the bytes u'_k with W = sum_k (u'_k - 128) 256^k: four signed 8-bit digits, which
-// is what v_mfma_i32_16x16x64_i8 multiplies.  The code bits enter as the bytes 2^bit (a mask instead of a shift; bit 7
-// reads as -128), the four digit sums are integers in 32-bit accumulators (|digit| x 128 x tokens of a range < 2^31),
-// and sum_k (acc_k / +-2^bit) 256^k modulo 2^32 is the exact integer sum_i W_i S_V[i][c] whatever the order of
+// is what v_mfma_i32_16x16x64_i8 multiplies.  The code bits enter as the bytes 4^p in pass p (a mask on the record byte
+// instead of a shift per bit), the four digit sums are integers in 32-bit accumulators (|digit| x 64 x tokens of a range
+// < 2^31), and sum_k (acc_k / 4^p) 256^k modulo 2^32 is the exact integer sum_i W_i S_V[i][c] whatever the order of
 // additions: results are bit-reproducible and carry a rounding error below (tokens of the range) x 2^-31 of its weight.
 //
 // Data flow per stage of 128 tokens: the records' 64 bytes that hold the workgroup's code bits are loaded coalesced and
 // written to LDS transposed ([dword of the record][token]); the 32 x 128 logits become digit bytes (4 x 4 byte
 // transpose per head and token quad: one digit of four consecutive tokens per dword) in LDS [digit][head][token].
 // A wavefront then reads, per 64-token step, its two record dwords for 16 tokens per lane, picks its byte with two
-// byte permutes per token quad, masks its bit (lane n of a 16-lane row: dword n / 8, byte n % 4, bits (n / 4) % 2 + 2 p in
-// four passes p), and issues 4 digits x 2 head blocks x 4 passes matrix instructions over them.  The next stage's
+// byte permutes per token quad, shifts it down by its bit parity (n / 4) % 2 and masks bit 2 p in pass p (lane n of a
+// 16-lane row: dword n / 8, byte n % 4, record bits (n / 4) % 2 + 2 p in four passes p), and issues 4 digits x 2 head blocks x 4 passes matrix instructions over them.  The next stage's
 // global loads are in flight meanwhile.
 __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
 {
@@ -68,6 +69,17 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
     auto fetch = [&](int t0, int set) {
         uint4 &sreg = sreg2[set];
         float(&wreg)[2][4] = wreg2[set];
+        if (t0 + kVbStage <= v1 && h0 + kVbitsHeads <= a.Hq) {  // (uniform) a whole stage: no bounds to watch
+            sreg = *reinterpret_cast<const uint4 *>(rec + (size_t)(t0 + tt) * NB + 16 * jq);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int it = tid + kVbThreads * u;
+                // (a logit row starts wherever the previous one ended: 4-byte alignment is all that is known)
+                const f4u_t v = *reinterpret_cast<const f4u_t *>(srow + (size_t)(h0 + (it >> 5)) * L + t0 + 4 * (it & 31));
+                wreg[u][0] = v.x; wreg[u][1] = v.y; wreg[u][2] = v.z; wreg[u][3] = v.w;
+            }
+            return;
+        }
         const int t = t0 + tt;
         sreg = t < v1 ? *reinterpret_cast<const uint4 *>(rec + (size_t)t * NB + 16 * jq) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
@@ -178,11 +190,11 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
         const unsigned *ad = a_lds[buf];
 #pragma unroll
         for (int kb = 0; kb < kVbStage / 64; ++kb) {
-            unsigned Y[4];
+            unsigned Y[4];  // byte j = the lane's record byte of token 4 r + j, shifted down by the lane's bit parity
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const uint4 X = *reinterpret_cast<const uint4 *>(sd + 64 * kb + 16 * q + 4 * r);
-                Y[r] = __builtin_amdgcn_perm(X.y, X.x, sel01) | __builtin_amdgcn_perm(X.w, X.z, sel23);
+                Y[r] = (__builtin_amdgcn_perm(X.y, X.x, sel01) | __builtin_amdgcn_perm(X.w, X.z, sel23)) >> bit0;
             }
             intx4_t A[4][2];
 #pragma unroll
@@ -192,7 +204,7 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
                     A[k][mb] = *reinterpret_cast<const intx4_t *>(ad + (k * kVbitsHeads + 16 * mb + n) * kVbAStride + 16 * kb + 4 * q);
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const unsigned mask = 0x01010101u << (bit0 + 2 * p);
+                const unsigned mask = 0x01010101u << (2 * p);  // bit 2 p of the shifted byte = bit 2 p + parity of the record
                 const intx4_t B = {(int)(Y[0] & mask), (int)(Y[1] & mask), (int)(Y[2] & mask), (int)(Y[3] & mask)};
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
@@ -217,25 +229,20 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
         if (t0 + kVbStage < v1) iteration(t0 + kVbStage, 1);
     }
 
-    // digits -> integer bins [Nc][G] per (sequence, KV head, range): a wavefront's 64 code bits x the G heads of a KV
-    // head are one contiguous run
+    // digits -> integer bins [Nc rows][G] per (sequence, KV head, range); row 64 W + 16 p + n for the wavefront's W-th
+    // run of 64 code bits (vbits_code_bit gives the code bit of a row): the 16 lanes of a pass store 16 consecutive rows
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const int bit = bit0 + 2 * p;
-        const int c = 32 * (cg * (kVbitsCols / 32) + 2 * wave + (n >> 3)) + 8 * (int)bn + bit;
-        const size_t row = (size_t)c;
+        const size_t row = (size_t)(64 * (cg * (kVbitsCols / 64) + wave) + 16 * p + n);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             unsigned val[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                unsigned tot = 0;
+                // sum_k (acc_k / 4^p) 256^k modulo 2^32; every acc_k is a multiple of 4^p
+                unsigned tot = (unsigned)(acc[0][mb][p][i] >> (2 * p));
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    int v = acc[k][mb][p][i];
-                    if (bit == 7) v = -v;
-                    tot += (unsigned)(v >> bit) << (8 * k);
-                }
+                for (int k = 1; k < 4; ++k) tot += (unsigned)acc[k][mb][p][i] << (8 * k - 2 * p);
                 val[i] = tot;
             }
             const int h = h0 + 16 * mb + 4 * q;  // heads h .. h + 3

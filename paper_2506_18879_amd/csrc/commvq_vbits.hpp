@@ -9,12 +9,20 @@
 constexpr int kVbitsHeads = 32;
 constexpr int kVbitsCols = 512;
 
+// Row r of a KV head's bins holds code bit vbits_code_bit(r): within every run of 64 rows the six low bits are permuted
+// so that the 16 lanes of a matrix-instruction result column block (lane n, pass p -> dword n / 8 of the wavefront's
+// pair, byte n % 4, bit (n / 4) % 2 + 2 p) own 16 consecutive rows r = 16 p + n and store them as one contiguous run.
+__host__ __device__ inline int vbits_code_bit(int r)
+{
+    return (r & ~63) | (((r >> 3) & 1) << 5) | ((r & 3) << 3) | (((r >> 4) & 3) << 1) | ((r >> 2) & 1);
+}
+
 struct VbitsArgs {
     const uint8_t *val_bits;  // sequence b: [L_b][Nc / 8] at byte offset cu[b] * Nc / 8
     const int32_t *cu;        // [B + 1]
     const float *scores;      // scaled logits, (b, h, i) at cu[b] * Hq + h * L_b + i
     const float2 *sstat;      // [B * Hq][nsplit] (max, sum of exp(logit - max)) of the score-stage tiles
-    unsigned *bins;           // [B * Hkv][nvsplit][Nc][G]
+    unsigned *bins;           // [B * Hkv][nvsplit][Nc rows][G], row r = code bit vbits_code_bit(r)
     float *vscale, *lsum;     // [B * Hq][nvsplit]
     int Hq, Hkv, G;
     int nsplit, split_len;    // statistics tiles of the score stage

@@ -305,3 +305,10 @@ def test_binary_value_format_config_plan_and_sizes(planner):
     a = _call_args(h)
     assert status_of(cv.commvq_decode_attn, h, a["q"], a["key_codes"], a["val_codes"], a["key_codebooks"], a["val_codebooks"],
                      a["positions"], a["out"], a["workspace"], a["workspace_bytes"]) == 6
+
+
+def test_binary_value_ranges_stay_within_the_32_bit_digit_sums(planner):
+    # one sequence per workgroup-row of a big batch would give ranges as long as the context; they are capped at 2^17 tokens
+    h = planner(value_format=cv.COMMVQ_VALUES_BINARY, value_bits=1024, m_val=0, max_position=1 << 24)
+    p = cv.commvq_plan_query(h, 512, 512 << 20 >> 9 << 9, 1 << 20)
+    assert p.value_split_len == 1 << 17 and p.value_splits == 8

@@ -100,6 +100,12 @@ def test_binary_values_many_splits_and_empty_sequences(gpu, oracle):
         assert row <= TOL_REGRESS and el <= 1e3 * TOL_REGRESS, (b, row, el)
 
 
+def test_binary_values_one_long_range_per_sequence(gpu, oracle):
+    # 130 sequences: more than the chip has workgroup slots, so every sequence is ONE token range; the long one runs
+    # 47 stages through the same accumulators
+    check(gpu, oracle, make(130, 32, 8, [6000] + [3] * 129, 1024, seed=81))
+
+
 def synth_without_empty(w):
     """The same workload without its empty sequences (the oracle's softmax needs at least one token)."""
     import copy
