@@ -30,9 +30,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--config", type=int, default=3,
-                    help="workload 1..9 (3 = 8B-shaped layer, 128K context, 1-bit; 6, 7 = the same layer with keys in "
+                    help="workload 1..11 (3 = 8B-shaped layer, 128K context, 1-bit; 6, 7 = the same layer with keys in "
                          "the paper's paired format, R = 11 / 21; 8, 9 = the same layer with values in the paper's binary "
-                         "form, N_c = 1024 / 2048)")
+                         "form, N_c = 1024 / 2048; 10, 11 = both: the paper's 1-bit and 2-bit settings)")
     ap.add_argument("--context-tokens", type=int, default=None,
                     help="shrink every context of the workload to at most this many tokens (short-context plans: score "
                          "tiles cut along the codebook slices); the workload name then ends in _ctx<N>")

@@ -43,11 +43,12 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
 
     const int ncg = a.Nc / kVbitsCols;
     const int nhg = (a.Hq + kVbitsHeads - 1) / kVbitsHeads;
-    int id = blockIdx.x;
-    const int cg = id % ncg;
-    id /= ncg;
-    const int hg = id % nhg;
-    id /= nhg;
+    // The column groups (and head groups) of one token range read the same records and logits.  Workgroups go to the
+    // chip's eight L2 domains round robin by index, so the group is the SLOW index: with a multiple of eight ranges the
+    // readers of a range share one L2 and the second read of a line is a hit there.
+    const int nrange = (int)gridDim.x / (ncg * nhg);
+    const int id = blockIdx.x % nrange, grp = blockIdx.x / nrange;
+    const int hg = grp % nhg, cg = grp / nhg;
     const int vs = id % a.nvsplit;
     const int b = id / a.nvsplit;
     const int cu0 = a.cu[b];

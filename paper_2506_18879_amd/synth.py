@@ -256,4 +256,8 @@ def config(idx: int, *, seed: Optional[int] = None, max_len: Optional[int] = Non
         base = make_workload(f"c{idx}_8b_L131072", B=1, Hq=32, Hkv=8, seqlens=[cap(131072)], Mk=16 if idx == 8 else 32,
                              Mv=16, dtype="bf16", seed=s)
         return with_binary_values(base, 1024 if idx == 8 else 2048)
-    raise ValueError(f"config index {idx} not in 1..9")
+    if idx in (10, 11):  # the paper's own formats on both sides (App., Table codebook_conf): 1 bit = (R 11, N_c 1024), 2 bit = (21, 2048)
+        R, Nc = (11, 1024) if idx == 10 else (21, 2048)
+        base = make_pair_workload(f"c{idx}_8b_L131072_paired_R{R}", B=1, Hq=32, Hkv=8, seqlens=[cap(131072)], R=R, Mv=16, seed=s)
+        return with_binary_values(base, Nc)
+    raise ValueError(f"config index {idx} not in 1..11")
