@@ -199,3 +199,37 @@ def test_binary_values_full_size_sampled_heads(gpu, oracle):
     row, el = errors(got[0, rows], ref[0, rows])
     print(f"  full size: max row error {row:.3e}, element-wise {el:.3e}", flush=True)
     assert row <= TOL_REGRESS and el <= 1e3 * TOL_REGRESS
+
+
+def test_binary_values_static_scratch_entry_and_graph_replay(gpu):
+    # the entry point that allocates nothing, and a captured call, must give the eager call's bits
+    import torch
+    import paper_2506_18879_amd as cv
+    w = synth.config(8, max_len=20000)
+    dw = gpu.DeviceWorkload(w)
+    op = gpu.DecodeAttention(w)
+    eager = op(dw).clone()
+    torch.cuda.synchronize()
+    out = torch.full_like(eager, float("nan"))
+    cv.commvq_decode_attn_static(op.handle, dw.q, dw.key_codes, dw.val_codes, dw.key_codebooks, dw.val_codebooks,
+                                 dw.positions, out, op.stream_ptr())
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        op(dw)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            op(dw)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        op.out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = op.out.clone()
+        again = op(dw).clone()      # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, eager) and torch.equal(again, eager), rep
+    op.close()
