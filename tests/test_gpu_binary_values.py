@@ -233,3 +233,19 @@ def test_binary_values_static_scratch_entry_and_graph_replay(gpu):
         torch.cuda.synchronize()
         assert torch.equal(replayed, eager) and torch.equal(again, eager), rep
     op.close()
+
+
+def test_paper_one_bit_setting_full_size_sampled_head(gpu, oracle):
+    # workload 10: the paper's 1-bit setting on both sides (paired keys R = 11, 1024 value bits) at 131072 tokens, in the
+    # launch configuration bench.py times; the oracle computes one of the eight KV heads (4 of the 32 output rows)
+    w = synth.config(10)
+    got = run_gpu(gpu, w)
+    kc = oracle.paired_as_indexed(w.key_codes, w.key_levels, w.cu_seqlens, w.Hkv)
+    kcb = oracle.tied_table_as_codebooks(w.as_f64("key_codebooks"), K=256)
+    mask = np.zeros((1, 8), bool)
+    mask[0, 5] = True
+    ref = oracle.decode_attn_binary_values(w.as_f64("q"), kc, w.val_codes, kcb, w.as_f64("val_codebooks"), w.cu_seqlens,
+                                           w.q_pos, rope_base=w.rope_base, unit_mask=mask, n_threads=1)
+    row, el = errors(got[0, 20:24], ref[0, 20:24])
+    print(f"  c10 full size: max row error {row:.3e}, element-wise {el:.3e}", flush=True)
+    assert row <= TOL_REGRESS and el <= 1e3 * TOL_REGRESS
