@@ -249,3 +249,31 @@ def test_paper_one_bit_setting_full_size_sampled_head(gpu, oracle):
     row, el = errors(got[0, 20:24], ref[0, 20:24])
     print(f"  c10 full size: max row error {row:.3e}, element-wise {el:.3e}", flush=True)
     assert row <= TOL_REGRESS and el <= 1e3 * TOL_REGRESS
+
+
+def _random_shape(case):
+    """One seeded shape within the documented limits (as the index-form random-shape test draws them)."""
+    rng = np.random.Generator(np.random.PCG64(9500 + case))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.integers(1, 9))
+    kind = ["short", "mixed", "many", "long"][case % 4]
+    if kind == "short":
+        lens = rng.integers(1, 700, size=int(rng.integers(1, 7)))
+    elif kind == "mixed":
+        lens = rng.integers(1, 6000, size=int(rng.integers(2, 6)))
+    elif kind == "many":     # a serving batch: many short sequences
+        lens = rng.integers(1, 300, size=int(rng.integers(20, 40)))
+    else:
+        lens = rng.integers(5000, 14000, size=int(rng.integers(1, 3)))
+    return G, Hkv, [int(x) for x in lens], rng
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_shapes_binary_values(gpu, oracle, case):
+    G, Hkv, lens, rng = _random_shape(case)
+    Nc = int(rng.choice([1024, 2048, 4096]))
+    density = float(rng.choice([0.05, 0.3, 0.5, 0.8]))
+    w = make(len(lens), G * Hkv, Hkv, lens, Nc, Mk=int(rng.choice([16, 32])), dtype="f32" if case % 5 == 4 else "bf16",
+             seed=9600 + case, density=density, code_dist="zipf" if case % 3 == 0 else "uniform")
+    print(f"G={G} Hkv={Hkv} Nc={Nc} density={density}", flush=True)
+    check(gpu, oracle, w)
