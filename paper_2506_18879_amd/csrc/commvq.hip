@@ -119,7 +119,7 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
     p->score_split_len = len;
     p->score_splits = (max_seqlen + len - 1) / len;
     int nv = 256 / units;  // about one value workgroup per compute unit
-    if (bin_values(h->cfg))  // a workgroup of the binary-code value kernel: 32 query heads x 512 code bits of one token range
+    if (bin_values(h->cfg))  // a workgroup of the binary-code value kernel: 16 query heads x 1024 code bits of one token range
         nv = 256 / (B * ((h->cfg.n_q_heads + kVbitsHeads - 1) / kVbitsHeads) * (h->cfg.value_bits / kVbitsCols));
     if (nv < 1) nv = 1;
     int vlen = (max_seqlen + nv - 1) / nv;
@@ -134,9 +134,9 @@ void make_plan(const commvq_handle *h, int B, int max_seqlen, bool sliced, commv
         while (part < vlen) part *= 2;
         vlen = part;  // 1024 or 2048 inside a 2048- or 4096-token tile
     }
-    // the binary-code value kernel sums signed digit x bit products in 32-bit accumulators: |digit| <= 2^7, bit byte <= 2^6,
-    // so a range of at most 2^17 tokens stays below 2^30
-    if (bin_values(h->cfg) && vlen > (1 << 17)) vlen = 1 << 17;
+    // the binary-code value kernel sums signed digit x bit products in 32-bit accumulators: |digit| <= 2^7, |bit byte| <= 2^7,
+    // so a range of at most 2^16 tokens stays within 2^30
+    if (bin_values(h->cfg) && vlen > (1 << 16)) vlen = 1 << 16;
     p->value_split_len = vlen;
     p->value_splits = (max_seqlen + vlen - 1) / vlen;
     p->out_chunks = val_books(h->cfg) * kK / kOutRows;

@@ -10,40 +10,42 @@
 
 namespace {
 
-constexpr int kVbThreads = 512;                // 8 wavefronts: each takes 64 of the workgroup's 512 code bits
+constexpr int kVbThreads = 512;                // 8 wavefronts: each takes 128 of the workgroup's 1024 code bits
 constexpr int kVbStage = 128;                  // tokens per LDS stage = two 64-token steps of the matrix instruction
+constexpr int kVbSRows = kVbitsCols / 32;      // record dwords of a workgroup
 constexpr int kVbSStride = kVbStage + 4;       // dwords per row of the transposed bit stage (rows 16-byte aligned)
 constexpr int kVbAStride = kVbStage / 4 + 8;   // dwords per (digit, head) row of the weight stage: 10 bank columns of 16 bytes, so that
                                                // the lanes a 16-byte LDS read serves together (l % 8, (l / 16) % 2) fall on 16 different columns
 typedef int intx4_t __attribute__((ext_vector_type(4)));
 typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));  // four floats at any 4-byte boundary
 
-// One workgroup = (sequence, token range, 32 query heads, 512 code bits).
+// One workgroup = (sequence, token range, 16 query heads, 1024 code bits).
 //
 // Exactness.  As in the index-form value stage the weights are added in fixed point: w = exp(logit - max) is taken
 // as the integer W = round(w 2^S), with S chosen from the known exp-sum of the range so that the sum of all W stays
 // below 2^30.  W + 0x80808080 has the bytes u'_k with W = sum_k (u'_k - 128) 256^k: four signed 8-bit digits, which
-// is what v_mfma_i32_16x16x64_i8 multiplies.  The code bits enter as the bytes 4^p in pass p (a mask on the record byte
-// instead of a shift per bit), the four digit sums are integers in 32-bit accumulators (|digit| x 64 x tokens of a range
-// < 2^31), and sum_k (acc_k / 4^p) 256^k modulo 2^32 is the exact integer sum_i W_i S_V[i][c] whatever the order of
-// additions: results are bit-reproducible and carry a rounding error below (tokens of the range) x 2^-31 of its weight.
+// is what v_mfma_i32_16x16x64_i8 multiplies.  The code bits enter as the bytes 2^p in pass p (a mask on the record byte
+// instead of a shift per bit; 2^7 reads as -128), the four digit sums are integers in 32-bit accumulators (|digit| x 128 x
+// tokens of a range <= 2^30), and sum_k (acc_k / +-2^p) 256^k modulo 2^32 is the exact integer sum_i W_i S_V[i][c] whatever
+// the order of additions: results are bit-reproducible and carry a rounding error below (tokens of the range) x 2^-31 of
+// its weight.
 //
-// Data flow per stage of 128 tokens: the records' 64 bytes that hold the workgroup's code bits are loaded coalesced and
-// written to LDS transposed ([dword of the record][token]); the 32 x 128 logits become digit bytes (4 x 4 byte
-// transpose per head and token quad: one digit of four consecutive tokens per dword) in LDS [digit][head][token].
-// A wavefront then reads, per 64-token step, its two record dwords for 16 tokens per lane, picks its byte with two
-// byte permutes per token quad, shifts it down by its bit parity (n / 4) % 2 and masks bit 2 p in pass p (lane n of a
-// 16-lane row: dword n / 8, byte n % 4, record bits (n / 4) % 2 + 2 p in four passes p), and issues 4 digits x 2 head blocks x 4 passes matrix instructions over them.  The next stage's
-// global loads are in flight meanwhile.
+// Data flow per stage of 128 tokens: the records' 128 bytes that hold the workgroup's code bits are loaded coalesced and
+// written to LDS transposed ([dword of the record][token]); the 16 x 128 logits become digit bytes (one 4 x 4 byte
+// transpose per thread: one digit of four consecutive tokens per dword) in LDS [digit][head][token].  A wavefront then
+// reads, per 64-token step, one record dword for 16 tokens per lane (lane n of a 16-lane row: dword n / 4 of the
+// wavefront's four, byte n % 4), picks its byte with two byte permutes per token quad, and issues 8 passes (one record
+// bit each, the same for all lanes: a constant mask) x 4 digits matrix instructions over them.  The global loads run two
+// stages ahead.
 __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned s_lds[2][16 * kVbSStride];
+    __shared__ __attribute__((aligned(16))) unsigned s_lds[2][kVbSRows * kVbSStride];
     __shared__ __attribute__((aligned(16))) unsigned a_lds[2][4 * kVbitsHeads * kVbAStride];
     __shared__ float eoff_s[kVbitsHeads];
 
     const int ncg = a.Nc / kVbitsCols;
     const int nhg = (a.Hq + kVbitsHeads - 1) / kVbitsHeads;
-    // The column groups (and head groups) of one token range read the same records and logits.  Workgroups go to the
+    // The head groups (and column groups) of one token range read the same records and logits.  Workgroups go to the
     // chip's eight L2 domains round robin by index, so the group is the SLOW index: with a multiple of eight ranges the
     // readers of a range share one L2 and the second read of a line is a hit there.
     const int nrange = (int)gridDim.x / (ncg * nhg);
@@ -62,35 +64,35 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
     const int NB = a.Nc / 8;
     const uint8_t *rec = a.val_bits + (size_t)cu0 * NB + cg * (kVbitsCols / 8);
     const float *srow = a.scores + (size_t)cu0 * a.Hq;
-    const int tt = tid >> 2, jq = tid & 3;  // bit stage: token of the stage, 16-byte piece of the record part
+    // bit stage: two (token, 16-byte piece of the record part) items per thread; weight stage: one (head, token quad)
+    const int wh = tid >> 5, wq = tid & 31;
     // two sets of staging registers: a stage's loads are requested two stages ahead (one compute phase does not cover
     // the latency of memory)
-    uint4 sreg2[2];
-    float wreg2[2][2][4];                   // weight stage: two (head, token quad) items per thread
+    uint4 sreg2[2][2];
+    float wreg2[2][4];
     auto fetch = [&](int t0, int set) {
-        uint4 &sreg = sreg2[set];
-        float(&wreg)[2][4] = wreg2[set];
+        uint4(&sreg)[2] = sreg2[set];
+        float(&wreg)[4] = wreg2[set];
         if (t0 + kVbStage <= v1 && h0 + kVbitsHeads <= a.Hq) {  // (uniform) a whole stage: no bounds to watch
-            sreg = *reinterpret_cast<const uint4 *>(rec + (size_t)(t0 + tt) * NB + 16 * jq);
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int it = tid + kVbThreads * u;
-                // (a logit row starts wherever the previous one ended: 4-byte alignment is all that is known)
-                const f4u_t v = *reinterpret_cast<const f4u_t *>(srow + (size_t)(h0 + (it >> 5)) * L + t0 + 4 * (it & 31));
-                wreg[u][0] = v.x; wreg[u][1] = v.y; wreg[u][2] = v.z; wreg[u][3] = v.w;
+                sreg[u] = *reinterpret_cast<const uint4 *>(rec + (size_t)(t0 + (it >> 3)) * NB + 16 * (it & 7));
             }
+            // (a logit row starts wherever the previous one ended: 4-byte alignment is all that is known)
+            const f4u_t v = *reinterpret_cast<const f4u_t *>(srow + (size_t)(h0 + wh) * L + t0 + 4 * wq);
+            wreg[0] = v.x; wreg[1] = v.y; wreg[2] = v.z; wreg[3] = v.w;
             return;
         }
-        const int t = t0 + tt;
-        sreg = t < v1 ? *reinterpret_cast<const uint4 *>(rec + (size_t)t * NB + 16 * jq) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int it = tid + kVbThreads * u, h = h0 + (it >> 5), tq = it & 31;
+            const int it = tid + kVbThreads * u, t = t0 + (it >> 3);
+            sreg[u] = t < v1 ? *reinterpret_cast<const uint4 *>(rec + (size_t)t * NB + 16 * (it & 7)) : make_uint4(0u, 0u, 0u, 0u);
+        }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int ti = t0 + 4 * tq + j;
-                wreg[u][j] = (h < a.Hq && ti < v1) ? srow[(size_t)h * L + ti] : -INFINITY;  // exp -> 0: no weight
-            }
+        for (int j = 0; j < 4; ++j) {
+            const int ti = t0 + 4 * wq + j;
+            wreg[j] = (h0 + wh < a.Hq && ti < v1) ? srow[(size_t)(h0 + wh) * L + ti] : -INFINITY;  // exp -> 0: no weight
         }
     };
     fetch(v0, 0);
@@ -145,73 +147,64 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
     __syncthreads();
 
     auto stage_write = [&](int buf, int set) {
-        const uint4 sreg = sreg2[set];
-        const float(&wreg)[2][4] = wreg2[set];
         unsigned *sd = s_lds[buf];
-        sd[(4 * jq + 0) * kVbSStride + tt] = sreg.x;
-        sd[(4 * jq + 1) * kVbSStride + tt] = sreg.y;
-        sd[(4 * jq + 2) * kVbSStride + tt] = sreg.z;
-        sd[(4 * jq + 3) * kVbSStride + tt] = sreg.w;
-        unsigned *ad = a_lds[buf];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int it = tid + kVbThreads * u, hl = it >> 5, tq = it & 31;
-            const float eo = eoff_s[hl];
-            unsigned wp[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const unsigned W = (unsigned)(__builtin_amdgcn_exp2f(wreg[u][j] * kLog2e + eo) + 0.5f);
-                wp[j] = (W + 0x80808080u) ^ 0x80808080u;  // bytes = signed digits
-            }
-            // 4 x 4 byte transpose: digit k of the four tokens in one dword
-            const unsigned lo01 = __builtin_amdgcn_perm(wp[1], wp[0], 0x05010400u), hi01 = __builtin_amdgcn_perm(wp[1], wp[0], 0x07030602u);
-            const unsigned lo23 = __builtin_amdgcn_perm(wp[3], wp[2], 0x05010400u), hi23 = __builtin_amdgcn_perm(wp[3], wp[2], 0x07030602u);
-            ad[(0 * kVbitsHeads + hl) * kVbAStride + tq] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
-            ad[(1 * kVbitsHeads + hl) * kVbAStride + tq] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
-            ad[(2 * kVbitsHeads + hl) * kVbAStride + tq] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
-            ad[(3 * kVbitsHeads + hl) * kVbAStride + tq] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+            const int it = tid + kVbThreads * u, tt = it >> 3, jq = it & 7;
+            const uint4 sreg = sreg2[set][u];
+            sd[(4 * jq + 0) * kVbSStride + tt] = sreg.x;
+            sd[(4 * jq + 1) * kVbSStride + tt] = sreg.y;
+            sd[(4 * jq + 2) * kVbSStride + tt] = sreg.z;
+            sd[(4 * jq + 3) * kVbSStride + tt] = sreg.w;
         }
+        unsigned *ad = a_lds[buf];
+        const float eo = eoff_s[wh];
+        unsigned wp[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned W = (unsigned)(__builtin_amdgcn_exp2f(wreg2[set][j] * kLog2e + eo) + 0.5f);
+            wp[j] = (W + 0x80808080u) ^ 0x80808080u;  // bytes = signed digits
+        }
+        // 4 x 4 byte transpose: digit k of the four tokens in one dword
+        const unsigned lo01 = __builtin_amdgcn_perm(wp[1], wp[0], 0x05010400u), hi01 = __builtin_amdgcn_perm(wp[1], wp[0], 0x07030602u);
+        const unsigned lo23 = __builtin_amdgcn_perm(wp[3], wp[2], 0x05010400u), hi23 = __builtin_amdgcn_perm(wp[3], wp[2], 0x07030602u);
+        ad[(0 * kVbitsHeads + wh) * kVbAStride + wq] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+        ad[(1 * kVbitsHeads + wh) * kVbAStride + wq] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+        ad[(2 * kVbitsHeads + wh) * kVbAStride + wq] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+        ad[(3 * kVbitsHeads + wh) * kVbAStride + wq] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
     };
 
     const int n = lane & 15, q = lane >> 4;
     const unsigned bn = (unsigned)n & 3u;
     const unsigned sel01 = 0x0c0c0000u | ((4u + bn) << 8) | bn;           // byte bn of two dwords -> bytes 0, 1
     const unsigned sel23 = ((4u + bn) << 24) | (bn << 16) | 0x00000c0cu;  // ... -> bytes 2, 3
-    const int bit0 = (n >> 2) & 1;
-    intx4_t acc[4][2][4];
+    intx4_t acc[4][8];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int p = 0; p < 4; ++p) acc[k][mb][p] = intx4_t{0, 0, 0, 0};
+        for (int p = 0; p < 8; ++p) acc[k][p] = intx4_t{0, 0, 0, 0};
 
     auto compute = [&](int buf) {
-        const unsigned *sd = s_lds[buf] + (2 * wave + (n >> 3)) * kVbSStride;
+        const unsigned *sd = s_lds[buf] + (4 * wave + (n >> 2)) * kVbSStride;
         const unsigned *ad = a_lds[buf];
 #pragma unroll
         for (int kb = 0; kb < kVbStage / 64; ++kb) {
-            unsigned Y[4];  // byte j = the lane's record byte of token 4 r + j, shifted down by the lane's bit parity
+            unsigned Y[4];  // byte j = the lane's record byte of token 4 r + j
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const uint4 X = *reinterpret_cast<const uint4 *>(sd + 64 * kb + 16 * q + 4 * r);
-                Y[r] = (__builtin_amdgcn_perm(X.y, X.x, sel01) | __builtin_amdgcn_perm(X.w, X.z, sel23)) >> bit0;
+                Y[r] = __builtin_amdgcn_perm(X.y, X.x, sel01) | __builtin_amdgcn_perm(X.w, X.z, sel23);
             }
-            intx4_t A[4][2];
+            intx4_t A[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k)
+                A[k] = *reinterpret_cast<const intx4_t *>(ad + (k * kVbitsHeads + n) * kVbAStride + 16 * kb + 4 * q);
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-                    A[k][mb] = *reinterpret_cast<const intx4_t *>(ad + (k * kVbitsHeads + 16 * mb + n) * kVbAStride + 16 * kb + 4 * q);
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const unsigned mask = 0x01010101u << (2 * p);  // bit 2 p of the shifted byte = bit 2 p + parity of the record
+            for (int p = 0; p < 8; ++p) {
+                const unsigned mask = 0x01010101u << p;
                 const intx4_t B = {(int)(Y[0] & mask), (int)(Y[1] & mask), (int)(Y[2] & mask), (int)(Y[3] & mask)};
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-                        acc[k][mb][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[k][mb], B, acc[k][mb][p], 0, 0, 0);
+                for (int k = 0; k < 4; ++k) acc[k][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[k], B, acc[k][p], 0, 0, 0);
             }
         }
     };
@@ -230,37 +223,34 @@ __global__ __launch_bounds__(kVbThreads) void k_vbits(VbitsArgs a)
         if (t0 + kVbStage < v1) iteration(t0 + kVbStage, 1);
     }
 
-    // digits -> integer bins [Nc rows][G] per (sequence, KV head, range); row 64 W + 16 p + n for the wavefront's W-th
-    // run of 64 code bits (vbits_code_bit gives the code bit of a row): the 16 lanes of a pass store 16 consecutive rows
+    // digits -> integer bins [Nc rows][G] per (sequence, KV head, range); row 128 W + 16 p + n for the wavefront's W-th
+    // run of 128 code bits (vbits_code_bit gives the code bit of a row): the 16 lanes of a pass store 16 consecutive rows
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const size_t row = (size_t)(64 * (cg * (kVbitsCols / 64) + wave) + 16 * p + n);
+    for (int p = 0; p < 8; ++p) {
+        const size_t row = (size_t)(128 * (cg * (kVbitsCols / 128) + wave) + 16 * p + n);
+        unsigned val[4];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            unsigned val[4];
+        for (int i = 0; i < 4; ++i) {
+            // sum_k (acc_k / 2^p) 256^k modulo 2^32; every acc_k is a multiple of 2^p (pass 7 multiplied by -2^7)
+            unsigned tot = (unsigned)(acc[0][p][i] >> p);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                // sum_k (acc_k / 4^p) 256^k modulo 2^32; every acc_k is a multiple of 4^p
-                unsigned tot = (unsigned)(acc[0][mb][p][i] >> (2 * p));
-#pragma unroll
-                for (int k = 1; k < 4; ++k) tot += (unsigned)acc[k][mb][p][i] << (8 * k - 2 * p);
-                val[i] = tot;
+            for (int k = 1; k < 4; ++k) tot += (unsigned)acc[k][p][i] << (8 * k - p);
+            val[i] = p == 7 ? 0u - tot : tot;
+        }
+        const int h = h0 + 4 * q;  // heads h .. h + 3
+        if ((a.G & 3) == 0) {
+            if (h < a.Hq) {
+                const int g = h / a.G, hh = h % a.G;
+                unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * ((size_t)a.G * a.Nc) + row * a.G + hh;
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(val[0], val[1], val[2], val[3]);
             }
-            const int h = h0 + 16 * mb + 4 * q;  // heads h .. h + 3
-            if ((a.G & 3) == 0) {
-                if (h < a.Hq) {
-                    const int g = h / a.G, hh = h % a.G;
-                    unsigned *dst = a.bins + ((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * ((size_t)a.G * a.Nc) + row * a.G + hh;
-                    *reinterpret_cast<uint4 *>(dst) = make_uint4(val[0], val[1], val[2], val[3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (h + i < a.Hq) {
+                    const int g = (h + i) / a.G, hh = (h + i) % a.G;
+                    a.bins[((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * ((size_t)a.G * a.Nc) + row * a.G + hh] = val[i];
                 }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (h + i < a.Hq) {
-                        const int g = (h + i) / a.G, hh = (h + i) % a.G;
-                        a.bins[((size_t)(b * a.Hkv + g) * a.nvsplit + vs) * ((size_t)a.G * a.Nc) + row * a.G + hh] = val[i];
-                    }
-            }
         }
     }
 }

@@ -6,15 +6,15 @@
 
 // Geometry shared by the planner and the kernel: a workgroup takes kVbitsHeads query heads x kVbitsCols code bits of
 // one token range.
-constexpr int kVbitsHeads = 32;
-constexpr int kVbitsCols = 512;
+constexpr int kVbitsHeads = 16;
+constexpr int kVbitsCols = 1024;
 
-// Row r of a KV head's bins holds code bit vbits_code_bit(r): within every run of 64 rows the six low bits are permuted
-// so that the 16 lanes of a matrix-instruction result column block (lane n, pass p -> dword n / 8 of the wavefront's
-// pair, byte n % 4, bit (n / 4) % 2 + 2 p) own 16 consecutive rows r = 16 p + n and store them as one contiguous run.
+// Row r of a KV head's bins holds code bit vbits_code_bit(r): within every run of 128 rows the seven low bits are
+// permuted so that the 16 lanes of a matrix-instruction result column block (lane n, pass p -> dword n / 4 of the
+// wavefront's four, byte n % 4, bit p) own 16 consecutive rows r = 16 p + n and store them as one contiguous run.
 __host__ __device__ inline int vbits_code_bit(int r)
 {
-    return (r & ~63) | (((r >> 3) & 1) << 5) | ((r & 3) << 3) | (((r >> 4) & 3) << 1) | ((r >> 2) & 1);
+    return (r & ~127) | (((r >> 2) & 3) << 5) | ((r & 3) << 3) | ((r >> 4) & 7);
 }
 
 struct VbitsArgs {

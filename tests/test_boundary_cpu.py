@@ -284,7 +284,7 @@ def test_binary_value_format_config_plan_and_sizes(planner):
     for bad in (dict(ok, value_bits=0), dict(ok, value_bits=512), dict(ok, value_bits=1000), dict(ok, value_bits=8192),
                 dict(value_format=2, value_bits=1024)):
         assert cv.commvq_validate_config(good_cfg(**bad)) == 2
-    # the 8B-shaped layer at 128K: a value workgroup is 32 heads x 512 code bits of a token range -> 2 column groups,
+    # the 8B-shaped layer at 128K: a value workgroup is 16 heads x 1024 code bits of a token range -> 2 head groups,
     # 128 ranges of 1024 tokens; the output stage sees N_c / 256 = 4 "codebooks" of 256 rows (16 chunks of 64 rows)
     h = planner(**ok)
     p = cv.commvq_plan_query(h, 1, 131072, 131072)
@@ -308,7 +308,7 @@ def test_binary_value_format_config_plan_and_sizes(planner):
 
 
 def test_binary_value_ranges_stay_within_the_32_bit_digit_sums(planner):
-    # one sequence per workgroup-row of a big batch would give ranges as long as the context; they are capped at 2^17 tokens
+    # one sequence per workgroup-row of a big batch would give ranges as long as the context; they are capped at 2^16 tokens
     h = planner(value_format=cv.COMMVQ_VALUES_BINARY, value_bits=1024, m_val=0, max_position=1 << 24)
     p = cv.commvq_plan_query(h, 512, 512 << 20 >> 9 << 9, 1 << 20)
-    assert p.value_split_len == 1 << 17 and p.value_splits == 8
+    assert p.value_split_len == 1 << 16 and p.value_splits == 16
