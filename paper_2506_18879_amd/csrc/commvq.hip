@@ -1188,8 +1188,8 @@ __global__ __launch_bounds__(256) void k_lut_build(const void *__restrict__ q, c
     for (int h = 0; h < G; ++h) dst[h] = acc[h];
 }
 
-// k_score_lut: one workgroup per (sequence, KV head, tile of TPT * 1024 tokens); the head group's table
-// (M * 256 * HG floats, HG = min(G, 4) heads at a time) sits in LDS, a lane owns TPT tokens: M code bytes
+// k_score_lut: one workgroup per (sequence, KV head, group of HG = min(G, 4) heads, tile of TPT * 1024 tokens); the
+// head group's table (M * 256 * HG floats) sits in LDS, a lane owns TPT tokens: M code bytes
 // in, M look-ups of HG floats, HG logits out.  Bound by the code stream and the logit writes (HBM).
 template <int M, int G, int TPT>
 __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__restrict__ lut, const uint8_t *__restrict__ key_codes,
@@ -1205,6 +1205,8 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
     int id = blockIdx.x;
     const int g = id % a.Hkv;
     id /= a.Hkv;
+    const int grp = id % NGRP;  // a workgroup takes one group of HG heads (eight heads: two workgroups per tile, each with its own table)
+    id /= NGRP;
     const int tile = id % a.nsplit;
     const int b = id / a.nsplit;
     const int cu0 = cu[b];
@@ -1215,18 +1217,20 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
     const float *src = lut + ((size_t)b * a.Hkv + g) * (M * kK) * G;
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-#pragma unroll 1
-    for (int grp = 0; grp < NGRP; ++grp) {
-        __syncthreads();
-        for (int x = tid; x < M * kK; x += kSliceThreads)
+    {
+        for (int x = tid; x < M * kK; x += kSliceThreads) {
+            if (HG == 4) {  // one 16-byte piece per table row
+                reinterpret_cast<float4 *>(tabf)[x] = *reinterpret_cast<const float4 *>(src + (size_t)x * G + grp * HG);
+            } else {
 #pragma unroll
-            for (int h = 0; h < HG; ++h) tabf[x * HG + h] = src[(size_t)x * G + grp * HG + h];
+                for (int h = 0; h < HG; ++h) tabf[x * HG + h] = src[(size_t)x * G + grp * HG + h];
+            }
+        }
         __syncthreads();
         float mx[HG], sc[TPT][HG];
 #pragma unroll
         for (int h = 0; h < HG; ++h) mx[h] = -INFINITY;
-        int tfirst = t0 + tid;
-        asm volatile("" : "+v"(tfirst));  // per head group: keeps the code loads and table addresses inside this loop
+        const int tfirst = t0 + tid;
 #pragma unroll
         for (int k = 0; k < TPT; ++k) {
             const int tok = tfirst + k * kSliceThreads;
@@ -2339,6 +2343,7 @@ hipError_t launch_lut_mgt(const float *lut, const uint8_t *key_codes, const int3
     constexpr int lds = M * kK * (G < 4 ? G : 4) * 4;
     static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
     if (hipError_t e = allow_dynamic_lds(&k_score_lut<M, G, TPT>, lds, lds_ok); e != hipSuccess) return e;
+    grid *= G < 4 ? 1 : G / 4;  // one workgroup per group of four heads
     hipLaunchKernelGGL((k_score_lut<M, G, TPT>), dim3(grid), dim3(kSliceThreads), lds, s, lut, key_codes, cu, scores, sstat, d);
     return hipGetLastError();
 }
