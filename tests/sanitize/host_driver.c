@@ -60,12 +60,19 @@ static int drive(commvq_config c, int32_t B, int64_t T, int32_t L)
     EXPECT(commvq_decode_attn_static(h, fake(1 << 16), (const uint8_t *)fake(1 << 20), (const uint8_t *)fake(1 << 21), fake(1 << 22),
                                      fake(1 << 23), &pos, (float *)fake(1 << 24), NULL),
            ws <= ((size_t)48 << 20) ? COMMVQ_ERR_NO_DEVICE : COMMVQ_ERR_WORKSPACE);
-    EXPECT(commvq_value_encoder_table_bytes(h, &nb), COMMVQ_OK);
-    EXPECT(commvq_value_encoder_prepare(h, fake(1 << 23), fake(1 << 27), NULL), COMMVQ_ERR_NO_DEVICE);
-    EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 64, NULL),
-           COMMVQ_ERR_NO_DEVICE);
-    EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 8, NULL),
-           COMMVQ_ERR_SHAPE);
+    if (c.value_format == COMMVQ_VALUES_BINARY) {  /* no greedy stand-in for a free binary code */
+        EXPECT(commvq_value_encoder_table_bytes(h, &nb), COMMVQ_ERR_CONFIG);
+        EXPECT(commvq_value_encoder_prepare(h, fake(1 << 23), fake(1 << 27), NULL), COMMVQ_ERR_CONFIG);
+        EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 64, NULL),
+               COMMVQ_ERR_CONFIG);
+    } else {
+        EXPECT(commvq_value_encoder_table_bytes(h, &nb), COMMVQ_OK);
+        EXPECT(commvq_value_encoder_prepare(h, fake(1 << 23), fake(1 << 27), NULL), COMMVQ_ERR_NO_DEVICE);
+        EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 64, NULL),
+               COMMVQ_ERR_NO_DEVICE);
+        EXPECT(commvq_encode_values(h, fake(1 << 16), 3, fake(1 << 23), fake(1 << 27), (uint8_t *)fake(1 << 28), 1024, 8, NULL),
+               COMMVQ_ERR_SHAPE);
+    }
     EXPECT(commvq_profile_enable(h, 4), COMMVQ_OK);
     float ms[3];
     int32_t n = -1;
@@ -107,6 +114,17 @@ int main(void)
     if (drive(c, 3, 7000, 3000)) return 1;                              /* scalar look-up table variant */
     c = base; c.n_q_heads = 8;
     if (drive(c, 1, 1, 1)) return 1;                                    /* one token */
+    c = base; c.value_format = COMMVQ_VALUES_BINARY; c.value_bits = 1024; c.m_val = 0;
+    if (drive(c, 1, 131072, 131072)) return 1;                          /* binary values, the paper's 1-bit width */
+    if (drive(c, 300, 300 * 70000, 70000)) return 1;                    /* one token range per sequence, capped in length */
+    c.value_bits = 4096; c.n_q_heads = 64; c.m_key = 32;
+    if (drive(c, 4, 4 * 131072, 131072)) return 1;
+    c = base; c.key_format = COMMVQ_KEYS_PAIRED; c.key_levels = 11; c.value_format = COMMVQ_VALUES_BINARY; c.value_bits = 1024;
+    if (drive(c, 2, 3000, 2000)) return 1;                              /* the paper's formats on both sides */
+    c = base; c.value_format = COMMVQ_VALUES_BINARY; c.value_bits = 1000;
+    EXPECT(commvq_validate_config(&c), COMMVQ_ERR_CONFIG);
+    c.value_format = 2; c.value_bits = 1024;
+    EXPECT(commvq_validate_config(&c), COMMVQ_ERR_CONFIG);
 
     size_t nb = 0;
     EXPECT(commvq_static_scratch_bytes(&nb), COMMVQ_OK);

@@ -17,6 +17,12 @@ int commvq_oracle_decode_attn(int B, int Hq, int Hkv, int d, int Mk, int Mv, int
                               const double *val_cb, const int32_t *cu_seqlens, const int32_t *q_pos,
                               const int32_t *key_pos, double rope_base, double scale, double *out,
                               double *scores_out, double *weights_out, const uint8_t *unit_mask, int n_threads);
+void commvq_oracle_decode_bits(const uint8_t *bits, const double *codebook, int Nc, int width, int first, int n, double *t_hat);
+int commvq_oracle_decode_attn_bits(int B, int Hq, int Hkv, int d, int Mk, int Nc, int K, const double *q,
+                                   const uint8_t *key_codes, const uint8_t *val_bits, const double *key_cb, const double *val_cb,
+                                   const int32_t *cu_seqlens, const int32_t *q_pos, const int32_t *key_pos, double rope_base,
+                                   double scale, double *out, double *scores_out, double *weights_out, const uint8_t *unit_mask,
+                                   int n_threads);
 int commvq_oracle_encode_keys(int n, int d, int levels, int K, int paired, const double *keys, const double *cb,
                               const uint8_t *given, uint8_t *codes, double *best, double *taken);
 
@@ -67,6 +73,21 @@ int main(void)
                                     1.0, out, NULL, NULL, NULL, 2) == 1);
     CHECK(commvq_oracle_decode_attn(B, Hq, 3, d, Mk, Mv, K, q, kc, vc, kcb, vcb, cu, q_pos, NULL, 500000.0, 1.0, out,
                                     NULL, NULL, NULL, 2) == 1);
+
+    /* binary value code: exactly-sized record and codebook buffers (Nc / 8 bytes per token, Nc rows of Hkv * d) */
+    enum { NC = 24 };
+    uint8_t *vb = rand_bytes((size_t)T * (NC / 8), 256);
+    double *vfull = rand_doubles((size_t)NC * Hkv * d);
+    commvq_oracle_decode_bits(vb + (size_t)(T - 1) * (NC / 8), vfull, NC, Hkv * d, (Hkv - 1) * d, d, dec);
+    CHECK(commvq_oracle_decode_attn_bits(B, Hq, Hkv, d, Mk, NC, K, q, kc, vb, kcb, vfull, cu, q_pos, NULL, 500000.0,
+                                         1.0 / sqrt((double)d), out, scores, weights, NULL, 1) == 0);
+    CHECK(commvq_oracle_decode_attn_bits(B, Hq, Hkv, d, Mk, NC, K, q, kc, vb, kcb, vfull, cu, q_pos, key_pos, 10000.0,
+                                         0.5, out, NULL, NULL, mask, 16) == 0);
+    CHECK(commvq_oracle_decode_attn_bits(B, Hq, Hkv, d, Mk, 20, K, q, kc, vb, kcb, vfull, cu, q_pos, NULL, 500000.0,
+                                         1.0, out, NULL, NULL, NULL, 2) == 1);
+    CHECK(commvq_oracle_decode_attn_bits(B, Hq, Hkv, d, Mk, NC, K, q, kc, NULL, kcb, vfull, cu, q_pos, NULL, 500000.0,
+                                         1.0, out, NULL, NULL, NULL, 2) == 1);
+    free(vb); free(vfull);
 
     /* encoder: index form, paired form, replay of given codes, a bad given code */
     enum { N = 7, LEV = 3 };

@@ -32,7 +32,7 @@ def test_library_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_
     if not (os.path.exists(HIPCC) and os.path.exists(CLANG)):
         pytest.skip("no hipcc")
     lib = str(tmp_path / "libcommvq_san.so")
-    src = [os.path.join(ROOT, "paper_2506_18879_amd", "csrc", f) for f in ("commvq.hip", "commvq_encode.hip", "commvq_em.hip")]
+    src = [os.path.join(ROOT, "paper_2506_18879_amd", "csrc", f) for f in ("commvq.hip", "commvq_encode.hip", "commvq_em.hip", "commvq_vbits.hip")]
     _run([HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-shared",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all",
