@@ -3,7 +3,8 @@
  * CommVQ-compressed KV cache, for AMD MI355X (gfx950).
  *
  * Every cached key and value is stored as M uint8 code indices into learned
- * codebooks (additive quantization, paper Sec. 4.1, Eq. vanilla_decode).  The
+ * codebooks (additive quantization, paper Sec. 4.1, Eq. vanilla_decode), or in
+ * the paper's own record formats (commvq_key_format, commvq_value_format).  The
  * library never decompresses the cache.  Scores follow the commutative
  * reformulation of Sec. 4.2 (Eq. new_attention): the selected key codewords are
  * gather-summed, rotated once by the RoPE matrix of the relative position and
