@@ -42,10 +42,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-resident numbers)")
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket the stages with HIP events")
-    ap.add_argument("--stage-event-interval", type=int, default=4,
+    ap.add_argument("--stage-event-interval", type=int, default=8,
                     help="bracket the stages of every N-th timed call with HIP events (an event between two kernels "
                          "costs ~5 us of GPU time, 11 us per call with all four: N = 1 times every launch and "
-                         "lowers the whole-call rate by 8 %%)")
+                         "lowers the whole-call rate by 8 %%, N = 8 by 1 %%)")
     ap.add_argument("--no-prepack", action="store_true",
                     help="re-lay the key codebook inside every call instead of once before the timed region")
     ap.add_argument("--graph", action="store_true",
