@@ -1155,7 +1155,8 @@ __global__ __launch_bounds__(kCombineThreads) void k_score_combine(const float *
 // after RoPE, or no positional rotation at all), (q C^T) could be computed once and every token's
 // score would be M scalar look-ups:  s_i = sum_m T[m][code_i,m],  T[m][c] = scale * q . C[m][c].
 //
-// k_lut_build: T[b][g][m][c][G] fp32, one thread per (b, g, m, c) row; the G queries sit in LDS.
+// k_lut_build: T[b][g][m][c][G] fp32 (G < 4; for G >= 4 in the LDS-image order of k_score_lut, see below), one thread
+// per (b, g, m, c) row; the G queries sit in LDS.
 template <int G, bool BF16>
 __global__ __launch_bounds__(256) void k_lut_build(const void *__restrict__ q, const void *__restrict__ cb,
                                                    float *__restrict__ lut, int Hkv, int M, int q_bf16, float scale)
@@ -1183,9 +1184,76 @@ __global__ __launch_bounds__(256) void k_lut_build(const void *__restrict__ q, c
 #pragma unroll
         for (int h = 0; h < G; ++h) acc[h] = __builtin_fmaf(qs[h][e], v, acc[h]);
     }
-    float *dst = lut + ((size_t)bg * rows_per_head + row) * G;
+    if (G >= 4) {
+        // groups of four heads: the table leaves in the order k_score_lut keeps it in LDS, [b][g][head group][block of 16
+        // codebooks][codeword][codebook of the block][4 heads] -- one 16-byte bank column per codebook
+        const int m = row / kK, c = row % kK;
 #pragma unroll
-    for (int h = 0; h < G; ++h) dst[h] = acc[h];
+        for (int grp = 0; grp < G / 4; ++grp) {
+            float4 *dst = reinterpret_cast<float4 *>(lut) +
+                          (((size_t)bg * (G / 4) + grp) * (M / 16) + m / 16) * (kK * 16) + (size_t)c * 16 + (m & 15);
+            *dst = make_float4(acc[(4 * grp + 0) % G], acc[(4 * grp + 1) % G], acc[(4 * grp + 2) % G], acc[(4 * grp + 3) % G]);
+        }
+    } else {
+        float *dst = lut + ((size_t)bg * rows_per_head + row) * G;
+#pragma unroll
+        for (int h = 0; h < G; ++h) dst[h] = acc[h];
+    }
+}
+
+// k_lut_build_mfma: the same table for bf16 codebooks and four or eight heads per KV head, where T = scale q C^T is the
+// one dense (heads x M K x d) contraction of these paths: a wavefront takes 16 codebook rows, v_mfma_f32_16x16x32_bf16 with
+// the queries as first operand (row = head; a bf16 query as it is, an fp32 query split exactly into three bf16 parts)
+// and 16 bytes of a codebook row per lane as second.  Result lane (n, rg) holds heads 4 rg .. 4 rg + 3 of row n: one
+// 16-byte entry of head group rg, stored in the LDS-image order of k_score_lut.
+template <int G>
+__global__ __launch_bounds__(256) void k_lut_build_mfma(const void *__restrict__ q, const uint16_t *__restrict__ cb,
+                                                        float *__restrict__ lut, int Hkv, int M, int q_bf16, float scale)
+{
+    const int rows_per_head = M * kK;
+    const int blocks_per_head = rows_per_head / 64;          // 4 wavefronts x 16 rows per workgroup
+    const int bg = blockIdx.x / blocks_per_head;             // b * Hkv + g
+    const int g = bg % Hkv;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kg = lane >> 4;
+    const int row = (blockIdx.x % blocks_per_head) * 64 + 16 * wave + n;  // m * K + c
+    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const uint16_t *crow = cb + ((size_t)g * rows_per_head + row) * kD + 8 * kg;
+    const size_t qbase = ((size_t)bg * G + (size_t)n) * kD + 8 * kg;  // head n of the group (rows G .. 15: zero)
+#pragma unroll
+    for (int ks = 0; ks < kD / 32; ++ks) {
+        const uint4 B = *reinterpret_cast<const uint4 *>(crow + 32 * ks);
+        if (q_bf16) {
+            uint4 A = make_uint4(0u, 0u, 0u, 0u);
+            if (n < G) A = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(q) + qbase + 32 * ks);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B), acc, 0, 0, 0);
+        } else {
+            float qf[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[e] = n < G ? static_cast<const float *>(q)[qbase + 32 * ks + e] : 0.f;
+            unsigned part[3][4];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {  // top 16 bits, top 16 bits of the rest, the rest: 8 + 8 + 8 mantissa bits, exact
+                const unsigned u0 = __builtin_bit_cast(unsigned, qf[e]) & 0xffff0000u;
+                const float r1 = qf[e] - __builtin_bit_cast(float, u0);
+                const unsigned u1 = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
+                const float r2 = r1 - __builtin_bit_cast(float, u1);
+                const unsigned u2 = __builtin_bit_cast(unsigned, r2) & 0xffff0000u;
+                if (e & 1) { part[0][e / 2] |= u0; part[1][e / 2] |= u1; part[2][e / 2] |= u2; }
+                else { part[0][e / 2] = u0 >> 16; part[1][e / 2] = u1 >> 16; part[2][e / 2] = u2 >> 16; }
+            }
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) {
+                const uint4 A = make_uint4(part[pc][0], part[pc][1], part[pc][2], part[pc][3]);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B), acc, 0, 0, 0);
+            }
+        }
+    }
+    if (4 * kg < G) {
+        const int m = row / kK, c = row % kK;
+        float4 *dst = reinterpret_cast<float4 *>(lut) + (((size_t)bg * (G / 4) + kg) * (M / 16) + m / 16) * (kK * 16) + (size_t)c * 16 + (m & 15);
+        *dst = make_float4(acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale);
+    }
 }
 
 // k_score_lut: one workgroup per (sequence, KV head, group of HG = min(G, 4) heads, tile of TPT * 1024 tokens); the
@@ -1200,8 +1268,9 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
     constexpr int NGRP = G / HG;
     constexpr int TILE = TPT * kSliceThreads;
     constexpr int NW = kSliceThreads / 64;
-    extern __shared__ __attribute__((aligned(16))) float tabf[];  // [M * 256][HG]
-    __shared__ float2 wstat[NW][HG];
+    // the table at LDS address 0 (no static LDS in this kernel), the per-wavefront statistics behind it
+    extern __shared__ __attribute__((aligned(16))) float tabf[];  // HG < 4: [M * 256][HG]; HG == 4: [M / 16][256][16][4]
+    float2(*wstat)[HG] = reinterpret_cast<float2(*)[HG]>(tabf + M * kK * HG);  // [NW][HG]
     int id = blockIdx.x;
     const int g = id % a.Hkv;
     id /= a.Hkv;
@@ -1215,86 +1284,113 @@ __global__ __launch_bounds__(kSliceThreads) void k_score_lut(const float *__rest
     if (t0 >= L) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint8_t *codes = key_codes + ((size_t)cu0 * a.Hkv + (size_t)g * L) * M;
-    const float *src = lut + ((size_t)b * a.Hkv + g) * (M * kK) * G;
     float *srow = scores + (size_t)cu0 * a.Hq + (size_t)g * G * L;
-    {
-        for (int x = tid; x < M * kK; x += kSliceThreads) {
-            if (HG == 4) {  // one 16-byte piece per table row
-                reinterpret_cast<float4 *>(tabf)[x] = *reinterpret_cast<const float4 *>(src + (size_t)x * G + grp * HG);
-            } else {
+    if (HG == 4) {  // the group's table is contiguous in memory, already in LDS order
+        const float4 *src4 = reinterpret_cast<const float4 *>(lut) + (((size_t)b * a.Hkv + g) * NGRP + grp) * (M * kK);
+        for (int x = tid; x < M * kK; x += kSliceThreads) reinterpret_cast<float4 *>(tabf)[x] = src4[x];
+    } else {
+        const float *src = lut + ((size_t)b * a.Hkv + g) * (M * kK) * G;
+        for (int x = tid; x < M * kK; x += kSliceThreads)
 #pragma unroll
-                for (int h = 0; h < HG; ++h) tabf[x * HG + h] = src[(size_t)x * G + grp * HG + h];
+            for (int h = 0; h < HG; ++h) tabf[x * HG + h] = src[(size_t)x * G + grp * HG + h];
+    }
+    __syncthreads();
+    // HG == 4: every codebook of a block of 16 owns one 16-byte bank column (row = codeword), and lane l walks the
+    // codebooks of a block in the order (rot + k) mod 16 with rot = l % 8 + 8 ((l / 16) % 2): the 16 lanes that a 16-byte
+    // LDS read serves together then fall on 16 different columns whatever their codes (a [codebook][codeword] table
+    // lets random codes collide: 12 clk per wavefront read against 6).  The token's 16 code bytes of the block are rotated
+    // by rot bytes once, so that step k finds its code at byte k; xreg[k]: byte 0 = 16 x column, byte 3 = 1 (the second
+    // 64 KiB block); one byte permute splices the code in as byte 1: address = 65536 block + 256 code + 16 column.
+    const unsigned rot = ((unsigned)lane & 7u) + 8u * (((unsigned)lane >> 4) & 1u);
+    unsigned xreg[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) xreg[k] = (((unsigned)k + rot) & 15u) * 16u | 1u << 24;
+    float mx[HG], sc[TPT][HG];
+#pragma unroll
+    for (int h = 0; h < HG; ++h) mx[h] = -INFINITY;
+    const int tfirst = t0 + tid;
+#pragma unroll
+    for (int k = 0; k < TPT; ++k) {
+        const int tok = tfirst + k * kSliceThreads;
+        const int tc = min(tok, L - 1);
+        float acc[HG];
+        floatx4_t accv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int h = 0; h < HG; ++h) acc[h] = 0.f;
+#pragma unroll
+        for (int v = 0; v < M / 16; ++v) {  // 16 codes at a time, 8 look-ups in flight: keeps registers flat
+            const uint4 c4 = reinterpret_cast<const uint4 *>(codes + (size_t)tc * M)[v];
+            unsigned cw[4] = {c4.x, c4.y, c4.z, c4.w};
+            if (HG == 4) {  // rotate the 16 bytes by rot: dword selects, then a byte-granular funnel shift
+#pragma unroll
+                for (int st = 1; st < 4; st <<= 1) {
+                    unsigned t[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[j] = ((rot >> 2) & (unsigned)st) ? cw[(j + st) % 4] : cw[j];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) cw[j] = t[j];
+                }
+                unsigned rv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) rv[j] = __builtin_amdgcn_alignbyte(cw[(j + 1) % 4], cw[j], rot & 3u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) cw[j] = rv[j];
             }
-        }
-        __syncthreads();
-        float mx[HG], sc[TPT][HG];
 #pragma unroll
-        for (int h = 0; h < HG; ++h) mx[h] = -INFINITY;
-        const int tfirst = t0 + tid;
+            for (int half = 0; half < 2; ++half) {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int k = 0; k < TPT; ++k) {
-            const int tok = tfirst + k * kSliceThreads;
-            const int tc = min(tok, L - 1);
-            float acc[HG];
-            floatx4_t accv = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int h = 0; h < HG; ++h) acc[h] = 0.f;
-#pragma unroll
-            for (int v = 0; v < M / 16; ++v) {  // 16 codes at a time, 8 look-ups in flight: keeps registers flat
-                const uint4 c4 = reinterpret_cast<const uint4 *>(codes + (size_t)tc * M)[v];
-                const unsigned cw[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int x = 0; x < 8; ++x) {
-                        const int m = 16 * v + 8 * half + x;
-                        const unsigned c = (cw[(m % 16) / 4] >> (8 * (m % 4))) & 0xffu;
+                for (int x = 0; x < 8; ++x) {
+                    const int kk = 8 * half + x;
+                    if (HG == 4) {  // one 16-byte read, added as a vector right away
+                        const unsigned sel = 0x0c000000u | (unsigned)(2 + v) << 16 | (unsigned)(4 + kk % 4) << 8;
+                        const unsigned addr = __builtin_amdgcn_perm(cw[kk / 4], xreg[kk], sel);
+                        const uint4_t e = lds_read_b128(addr);
+                        accv += __builtin_bit_cast(floatx4_t, e);
+                    } else {
+                        const int m = 16 * v + kk;
+                        const unsigned c = (cw[kk / 4] >> (8 * (kk % 4))) & 0xffu;
                         const float *e = tabf + ((size_t)m * kK + c) * HG;
-                        if (HG == 4) {  // one 16-byte read, added as a vector right away
-                            accv += *reinterpret_cast<const floatx4_t *>(e);
-                        } else {
 #pragma unroll
-                            for (int h = 0; h < HG; ++h) acc[h] += e[h];
-                        }
+                        for (int h = 0; h < HG; ++h) acc[h] += e[h];
                     }
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
-            if (HG == 4) {
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (HG == 4) {
 #pragma unroll
-                for (int h = 0; h < HG; ++h) acc[h] = accv[h];
-            }
-#pragma unroll
-            for (int h = 0; h < HG; ++h) {
-                sc[k][h] = acc[h];
-                if (tok < L) {
-                    srow[(size_t)(grp * HG + h) * L + tok] = acc[h];
-                    mx[h] = fmaxf(mx[h], acc[h]);
-                }
-            }
+            for (int h = 0; h < HG; ++h) acc[h] = accv[h];
         }
 #pragma unroll
         for (int h = 0; h < HG; ++h) {
-            const float wm = wave_max(mx[h]);
-            float l = 0.f;
-#pragma unroll
-            for (int k = 0; k < TPT; ++k)
-                if (tfirst + k * kSliceThreads < L) l += __builtin_amdgcn_exp2f((sc[k][h] - wm) * kLog2e);
-            l = wave_sum(l);
-            if (lane == 0) wstat[wave][h] = make_float2(wm, l);
-        }
-        __syncthreads();
-        if (tid < HG) {
-            float m = -INFINITY;
-            for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
-            float l = 0.f;
-            for (int w = 0; w < NW; ++w) {
-                const float2 st = wstat[w][tid];
-                if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+            sc[k][h] = acc[h];
+            if (tok < L) {
+                srow[(size_t)(grp * HG + h) * L + tok] = acc[h];
+                mx[h] = fmaxf(mx[h], acc[h]);
             }
-            sstat[((size_t)b * a.Hq + (size_t)g * G + grp * HG + tid) * a.nsplit + tile] = make_float2(m, l);
         }
+    }
+#pragma unroll
+    for (int h = 0; h < HG; ++h) {
+        const float wm = wave_max(mx[h]);
+        float l = 0.f;
+#pragma unroll
+        for (int k = 0; k < TPT; ++k)
+            if (tfirst + k * kSliceThreads < L) l += __builtin_amdgcn_exp2f((sc[k][h] - wm) * kLog2e);
+        l = wave_sum(l);
+        if (lane == 0) wstat[wave][h] = make_float2(wm, l);
+    }
+    __syncthreads();
+    if (tid < HG) {
+        float m = -INFINITY;
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, wstat[w][tid].x);
+        float l = 0.f;
+        for (int w = 0; w < NW; ++w) {
+            const float2 st = wstat[w][tid];
+            if (st.x != -INFINITY) l += st.y * __builtin_amdgcn_exp2f((st.x - m) * kLog2e);
+        }
+        sstat[((size_t)b * a.Hq + (size_t)g * G + grp * HG + tid) * a.nsplit + tile] = make_float2(m, l);
     }
 }
 
@@ -2340,7 +2436,7 @@ template <int M, int G, int TPT>
 hipError_t launch_lut_mgt(const float *lut, const uint8_t *key_codes, const int32_t *cu, float *scores, float2 *sstat,
                           const SliceDims &d, int grid, hipStream_t s)
 {
-    constexpr int lds = M * kK * (G < 4 ? G : 4) * 4;
+    constexpr int lds = M * kK * (G < 4 ? G : 4) * 4 + (kSliceThreads / 64) * (G < 4 ? G : 4) * 8;  // table + per-wavefront statistics
     static std::atomic<uint64_t> lds_ok{0};  // per instantiation and device
     if (hipError_t e = allow_dynamic_lds(&k_score_lut<M, G, TPT>, lds, lds_ok); e != hipSuccess) return e;
     grid *= G < 4 ? 1 : G / 4;  // one workgroup per group of four heads
@@ -2352,7 +2448,10 @@ hipError_t launch_lut_mg(const void *q, const void *key_cb, bool bf16, float *lu
                          float *scores, float2 *sstat, const SliceDims &d, int B, int tpt, int grid, hipStream_t s)
 {
     const int blocks = B * d.Hkv * (M * kK / 256);
-    if (bf16) hipLaunchKernelGGL((k_lut_build<G, true>), dim3(blocks), dim3(256), 0, s, q, key_cb, lut, d.Hkv, M, d.q_bf16, d.scale);
+    if (bf16 && G >= 4)  // the table as a matrix product (16 rows per wavefront, 64 per workgroup)
+        hipLaunchKernelGGL((k_lut_build_mfma<G>), dim3(4 * blocks), dim3(256), 0, s, q, static_cast<const uint16_t *>(key_cb), lut, d.Hkv,
+                           M, d.q_bf16, d.scale);
+    else if (bf16) hipLaunchKernelGGL((k_lut_build<G, true>), dim3(blocks), dim3(256), 0, s, q, key_cb, lut, d.Hkv, M, d.q_bf16, d.scale);
     else hipLaunchKernelGGL((k_lut_build<G, false>), dim3(blocks), dim3(256), 0, s, q, key_cb, lut, d.Hkv, M, d.q_bf16, d.scale);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     switch (tpt) {
