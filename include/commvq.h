@@ -322,9 +322,9 @@ commvq_status commvq_em_step_shared(const float *data, int32_t group, int32_t n_
  *   commvq_stage_bins    Softmax(A) S_V of Eq. optimized_v, unnormalised: exp(score - max)
  *                        accumulated per (head, value codebook, codeword) in 32-bit fixed point
  *                        (unit chosen per context split from its exp-sum; error below
- *                        tokens-per-split * 2^-32 of the split's weight), plus the exp sums.
+ *                        tokens-per-split * 2^-31 of the split's weight), plus the exp sums.
  *                        COMMVQ_VALUES_BINARY: per (head, code bit), as an 8-bit integer matrix product over
- *                        four signed digits of the same fixed-point weights (error below tokens * 2^-31).
+ *                        four signed digits of the same fixed-point weights (error below tokens * 2^-30).
  *   commvq_stage_output  (bins C_V) / sum of Eq. optimized_v -> out.
  */
 commvq_status commvq_stage_scores(commvq_handle *handle, const void *q, const uint8_t *key_codes,

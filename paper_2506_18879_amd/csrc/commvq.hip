@@ -14,7 +14,7 @@
 //               as [K][M_v][G]), one bin set per context split.  The
 //               bins are 32-bit fixed point (integer LDS atomics run ~20x faster than fp32 ones
 //               on gfx950); the scale of each split is chosen from its known exp-sum so that
-//               no bin can overflow and the worst-case error is (tokens per split) * 2^-32.
+//               no bin can overflow and the worst-case error is (tokens per split) * 2^-31.
 //   k_out       (bins C_V): split reduction + bins x value-codebook product, per chunk of rows.
 //   k_out_final sum of the per-chunk products, division by the softmax denominator.
 // Key encoding for cache append lives in commvq_encode.hip, the EM codebook learner in commvq_em.hip.
@@ -1774,7 +1774,7 @@ struct BinsArgs {
 // Softmax(A) S_V).  w is added as round(w * 2^S): the score stage already produced the
 // exp-sum l of this split (relative to the sequence maximum), every bin is bounded by it, so
 // S = 30 - floor(log2 l) keeps every bin below 2^31 while the rounding error of the whole
-// split stays below (tokens in split) * 2^-32 of its weight.  Integer adds commute, so the
+// split stays below (tokens in split) * 2^-31 of its weight (half a unit per token, a unit being at most 2^-30 of the exp-sum).  Integer adds commute, so the
 // result does not depend on the order in which wavefronts arrive.
 template <int M, int G>
 __global__ __launch_bounds__(kBinsThreads) void k_bins(BinsArgs a)

@@ -27,7 +27,7 @@ typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));  // four fl
 // is what v_mfma_i32_16x16x64_i8 multiplies.  The code bits enter as the bytes 2^p in pass p (a mask on the record byte
 // instead of a shift per bit; 2^7 reads as -128), the four digit sums are integers in 32-bit accumulators (|digit| x 128 x
 // tokens of a range <= 2^30), and sum_k (acc_k / +-2^p) 256^k modulo 2^32 is the exact integer sum_i W_i S_V[i][c] whatever
-// the order of additions: results are bit-reproducible and carry a rounding error below (tokens of the range) x 2^-31 of
+// the order of additions: results are bit-reproducible and carry a rounding error below (tokens of the range) x 2^-30 of
 // its weight.
 //
 // Data flow per stage of 128 tokens: the records' 128 bytes that hold the workgroup's code bits are loaded coalesced and
