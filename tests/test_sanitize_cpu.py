@@ -41,3 +41,14 @@ def test_library_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_
     _run([CLANG, "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-I" + os.path.join(ROOT, "include"),
           "-o", exe, os.path.join(SAN, "host_driver.c"), "-L" + str(tmp_path), "-lcommvq_san", "-Wl,-rpath," + str(tmp_path)])
     assert "host_driver: ok" in _run([exe])
+
+
+def test_binary_value_row_order_matches_the_kernel_lane_mapping(tmp_path):
+    """vbits_code_bit (shared by the value kernel, the output kernels and the codebook packing) against the lane
+    mapping written out in the test program: a host-only build of the header."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("no hipcc")
+    exe = str(tmp_path / "vbits_rows")
+    _run([HIPCC, "--offload-arch=gfx950", "-O1", "-std=c++17", "-I" + os.path.join(ROOT, "paper_2506_18879_amd", "csrc"),
+          "-o", exe, os.path.join(SAN, "vbits_rows.hip")])
+    assert "vbits_rows: ok" in _run([exe])
